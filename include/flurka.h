@@ -1,0 +1,165 @@
+/*
+ * flurka.h -- C ABI of the FLuRKA attention library for AMD MI355X (gfx950).
+ *
+ * FLuRKA (Fast Low-Rank & Kernel Attention) first contracts keys and values
+ * along the sequence with two projection matrices, then applies a kernel
+ * feature map and evaluates the attention product in the associative order
+ * that never forms an n x k (or n x n) attention matrix:
+ *
+ *     K' = E K,  V' = F V                                  (n -> k rows)
+ *     out = phi(Q) (phi(K')^T V')  /  phi(Q) (phi(K')^T 1)   (row-wise ratio)
+ *
+ * Source of each piece: the optimised unification, Eq. 2 (low-rank projection
+ * before the kernel map); E, F in R^{k x n}, entries N(0, 1/k) -- Sec. 2,
+ * "Low-rank Methods" (d_k and N there); phi and the product order
+ * phi(Q)(phi(K)^T V) -- Sec. 2, "Kernel Methods"; the row normaliser -- the
+ * ratio form used throughout App. D.  Eq. 2 is printed without the transpose
+ * and the normaliser; both are meant.
+ *
+ * Feature maps:
+ *   FLURKA_PHI_PERFORMER  positive random features,
+ *                         phi(x)_j = exp(omega_j . x - |x|^2/2) / sqrt(m),
+ *                         j = 1..m (Sec. 2: phi = m^{-1/2}[psi_1..psi_m] with
+ *                         E[psi(x) psi(y)] = exp(x . y); Thm. 1 statement).
+ *   FLURKA_PHI_ELU1       phi(x) = elu(x) + 1 elementwise, the non-random map
+ *                         of the RNN variant (Sec. 2); then m must equal d and
+ *                         omega is ignored (may be NULL).
+ * The library applies no 1/sqrt(d) temperature, no mask, no dropout and adds
+ * no epsilon to the denominator.  Exponents are shifted internally by one
+ * constant per (batch, head) on the key side and one per query row on the
+ * query side; both cancel exactly in the ratio.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The
+ *     library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.  Tensors are dense, row-major, innermost index last.
+ *   - Storage type `dtype` applies to Q, K, V, E, F, omega, out, dOut and all
+ *     gradients.  `ctx` and `workspace` are always float32.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); the call returns without synchronising.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed validation launches nothing and touches no memory.
+ *   - Calls that share a ctx or workspace buffer must be ordered on one stream.
+ *   - Results are deterministic: no floating-point atomics are used.
+ */
+#ifndef FLURKA_H
+#define FLURKA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Entry points are the only symbols the shared library exports. */
+#define FLURKA_API __attribute__((visibility("default")))
+
+typedef enum {
+    FLURKA_OK = 0,
+    FLURKA_ERR_NULL = 1,         /* a required pointer is NULL */
+    FLURKA_ERR_SHAPE = 2,        /* a dimension is < 1, too large, or m != d for ELU1 */
+    FLURKA_ERR_DTYPE = 3,        /* unknown dtype / phi / algo value */
+    FLURKA_ERR_UNSUPPORTED = 4,  /* valid problem the selected algo cannot run */
+    FLURKA_ERR_WORKSPACE = 5,    /* ctx or workspace buffer too small */
+    FLURKA_ERR_LAUNCH = 6,       /* the HIP runtime reported a launch error */
+    FLURKA_ERR_ALIGN = 7         /* a pointer is not aligned to its element size (ctx/workspace: 256 B) */
+} flurka_status;
+
+typedef enum { FLURKA_F32 = 0, FLURKA_BF16 = 1 } flurka_dtype;
+typedef enum { FLURKA_PHI_PERFORMER = 0, FLURKA_PHI_ELU1 = 1 } flurka_phi;
+
+/* Kernel family.  AUTO picks the bf16 MFMA kernels when dtype and shape allow
+ * (see flurka_fast_path_supported) and the generic fp32-arithmetic kernels
+ * otherwise.  GENERIC forces the latter; FAST fails with
+ * FLURKA_ERR_UNSUPPORTED instead of falling back. */
+typedef enum { FLURKA_ALGO_AUTO = 0, FLURKA_ALGO_GENERIC = 1, FLURKA_ALGO_FAST = 2 } flurka_algo;
+
+typedef enum { FLURKA_PASS_FWD = 0, FLURKA_PASS_BWD = 1 } flurka_pass;
+
+/* Upper limits accepted by validation (host-checkable, no GPU needed). */
+#define FLURKA_MAX_BATCH_HEADS 65535   /* B*H, one grid-z slot each */
+#define FLURKA_MAX_FEATURE_DIM 4096    /* d, m */
+#define FLURKA_MAX_SEQ (1 << 24)       /* n, k */
+
+/* Library ABI version (major*100 + minor). */
+FLURKA_API int flurka_version(void);
+
+/* Human-readable name of a status code; never NULL. */
+FLURKA_API const char* flurka_status_str(flurka_status s);
+
+/* Bytes of the context buffer that carries the key-side state from the
+ * forward to the backward pass: K', V' (B,H,k,d), phi(K') up to its shift
+ * (B,H,k,mf), S = phi(K')^T V' (B,H,mf,d), z = phi(K')^T 1 (B,H,mf) and the
+ * shift c (B,H); mf = m (performer) or d (elu1).  Returns 0 for an invalid
+ * shape. */
+FLURKA_API size_t flurka_ctx_bytes(int B, int H, int n, int d, int k, int m,
+                        flurka_dtype dtype, flurka_phi phi);
+
+/* Offsets, in float32 elements from the start of ctx, of its six segments in
+ * the order K', V', phi(K'), S, z, c, written to the HOST array `offsets6`
+ * (for inspection and tests).  Returns FLURKA_ERR_NULL / _SHAPE / _DTYPE on
+ * bad arguments. */
+FLURKA_API flurka_status flurka_ctx_layout(int B, int H, int n, int d, int k, int m,
+                                flurka_dtype dtype, flurka_phi phi, size_t* offsets6);
+
+/* Bytes of scratch the given pass needs for `algo` (AUTO = the maximum over
+ * the paths AUTO may take).  Contents need not survive between calls.
+ * Returns 0 for an invalid shape. */
+FLURKA_API size_t flurka_workspace_bytes(int B, int H, int n, int d, int k, int m,
+                              flurka_dtype dtype, flurka_phi phi,
+                              flurka_pass pass, flurka_algo algo);
+
+/* 1 if the bf16 MFMA kernels cover this problem for `pass`, else 0. */
+FLURKA_API int flurka_fast_path_supported(int B, int H, int n, int d, int k, int m,
+                               flurka_dtype dtype, flurka_phi phi, flurka_pass pass);
+
+/*
+ * Forward: out = phi(Q)(phi(EK)^T FV) / phi(Q)(phi(EK)^T 1)   (Eq. 2 with the
+ * App. D normaliser), per (batch, head).
+ *
+ *   Q, K, V   in   (B, H, n, d)
+ *   E, F      in   (k, n)         one pair shared by every batch and head
+ *   omega     in   (H, m, d) if omega_per_head != 0, else (m, d) shared by
+ *                  all heads; ignored (may be NULL) for FLURKA_PHI_ELU1
+ *   out       out  (B, H, n, d)   rounded once to `dtype` at the final store
+ *   ctx       out  flurka_ctx_bytes(...) bytes, 256-byte aligned; holds the
+ *                  key-side state afterwards (input of flurka_attn_bwd)
+ *   workspace      flurka_workspace_bytes(..., FLURKA_PASS_FWD, algo) bytes,
+ *                  256-byte aligned scratch
+ */
+FLURKA_API flurka_status flurka_attn_fwd(const void* Q, const void* K, const void* V,
+                              const void* E, const void* F, const void* omega,
+                              void* out,
+                              void* ctx, size_t ctx_bytes,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int H, int n, int d, int k, int m,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              void* stream);
+
+/*
+ * Backward of the forward above (chain rule; the paper trains through this
+ * layer but prints no backward).  Given dOut = d loss / d out:
+ *
+ *   dQ, dK, dV  out  (B, H, n, d)
+ *   dE, dF      out  (k, n), summed over batch and heads (E, F are shared),
+ *                    overwritten, not accumulated into
+ *   ctx         in   the buffer filled by flurka_attn_fwd for the SAME
+ *                    Q, K, V, E, F, omega and shape, earlier on this stream
+ *
+ * omega is a fixed random draw and gets no gradient.
+ */
+FLURKA_API flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V,
+                              const void* E, const void* F, const void* omega,
+                              const void* dOut, const void* ctx, size_t ctx_bytes,
+                              void* dQ, void* dK, void* dV, void* dE, void* dF,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int H, int n, int d, int k, int m,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLURKA_H */

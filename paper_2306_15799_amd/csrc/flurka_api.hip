@@ -1,0 +1,155 @@
+// C ABI of libflurka: argument validation, buffer sizing and dispatch.
+// The entry points are documented in include/flurka.h.
+#include "flurka_internal.h"
+
+using namespace flurka;
+
+namespace {
+
+constexpr int kVersion = 100;
+
+flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
+                           int dtype, int phi, Problem* out) {
+    if (dtype != FLURKA_F32 && dtype != FLURKA_BF16) return FLURKA_ERR_DTYPE;
+    if (phi != FLURKA_PHI_PERFORMER && phi != FLURKA_PHI_ELU1) return FLURKA_ERR_DTYPE;
+    if (B < 1 || H < 1 || n < 1 || d < 1 || k < 1 || m < 1) return FLURKA_ERR_SHAPE;
+    if ((long)B * (long)H > FLURKA_MAX_BATCH_HEADS) return FLURKA_ERR_SHAPE;
+    if (d > FLURKA_MAX_FEATURE_DIM || m > FLURKA_MAX_FEATURE_DIM) return FLURKA_ERR_SHAPE;
+    if (n > FLURKA_MAX_SEQ || k > FLURKA_MAX_SEQ) return FLURKA_ERR_SHAPE;
+    if (phi == FLURKA_PHI_ELU1 && m != d) return FLURKA_ERR_SHAPE;
+    Problem p;
+    p.B = B; p.H = H; p.n = n; p.d = d; p.k = k; p.m = m;
+    p.elu = (phi == FLURKA_PHI_ELU1);
+    p.mf = p.elu ? d : m;
+    p.BH = B * H;
+    p.omega_per_head = omega_per_head ? 1 : 0;
+    p.bf16 = (dtype == FLURKA_BF16);
+    *out = p;
+    return FLURKA_OK;
+}
+
+bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+bool valid_algo(int a) { return a == FLURKA_ALGO_AUTO || a == FLURKA_ALGO_GENERIC || a == FLURKA_ALGO_FAST; }
+
+}  // namespace
+
+extern "C" {
+
+int flurka_version(void) { return kVersion; }
+
+const char* flurka_status_str(flurka_status s) {
+    switch (s) {
+        case FLURKA_OK: return "ok";
+        case FLURKA_ERR_NULL: return "required pointer is NULL";
+        case FLURKA_ERR_SHAPE: return "invalid shape";
+        case FLURKA_ERR_DTYPE: return "unknown dtype, feature map or algo";
+        case FLURKA_ERR_UNSUPPORTED: return "problem not supported by the selected algo";
+        case FLURKA_ERR_WORKSPACE: return "ctx or workspace buffer too small";
+        case FLURKA_ERR_LAUNCH: return "HIP launch error";
+        case FLURKA_ERR_ALIGN: return "misaligned pointer";
+    }
+    return "unknown status";
+}
+
+size_t flurka_ctx_bytes(int B, int H, int n, int d, int k, int m, flurka_dtype dtype, flurka_phi phi) {
+    Problem p;
+    if (make_problem(B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    return ctx_layout(p).total * sizeof(float);
+}
+
+flurka_status flurka_ctx_layout(int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
+                                flurka_phi phi, size_t* offsets6) {
+    if (!offsets6) return FLURKA_ERR_NULL;
+    Problem p;
+    flurka_status st = make_problem(B, H, n, d, k, m, 1, dtype, phi, &p);
+    if (st != FLURKA_OK) return st;
+    const CtxLayout L = ctx_layout(p);
+    offsets6[0] = L.Kp; offsets6[1] = L.Vp; offsets6[2] = L.PhiK;
+    offsets6[3] = L.S;  offsets6[4] = L.z;  offsets6[5] = L.c + round_up((size_t)p.BH, 64);
+    return FLURKA_OK;
+}
+
+int flurka_fast_path_supported(int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
+                               flurka_phi phi, flurka_pass pass) {
+    Problem p;
+    if (make_problem(B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    if (pass != FLURKA_PASS_FWD && pass != FLURKA_PASS_BWD) return 0;
+    return fast_supported(p, pass == FLURKA_PASS_BWD) ? 1 : 0;
+}
+
+size_t flurka_workspace_bytes(int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
+                              flurka_phi phi, flurka_pass pass, flurka_algo algo) {
+    Problem p;
+    if (make_problem(B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    if (pass != FLURKA_PASS_FWD && pass != FLURKA_PASS_BWD) return 0;
+    if (!valid_algo(algo)) return 0;
+    const int bwd = (pass == FLURKA_PASS_BWD);
+    const size_t gen = generic_ws_layout(p, bwd).total * sizeof(float);
+    const size_t fast = fast_supported(p, bwd) ? fast_ws_bytes(p, bwd) : 0;
+    if (algo == FLURKA_ALGO_GENERIC) return gen;
+    if (algo == FLURKA_ALGO_FAST) return fast;
+    return fast > gen ? fast : gen;
+}
+
+flurka_status flurka_attn_fwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                              const void* omega, void* out, void* ctx, size_t ctx_bytes, void* workspace,
+                              size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                              int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              void* stream) {
+    Problem p;
+    flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
+    if (st != FLURKA_OK) return st;
+    if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
+    if (!Q || !K || !V || !E || !F || !out || !ctx || !workspace) return FLURKA_ERR_NULL;
+    if (!p.elu && !omega) return FLURKA_ERR_NULL;
+    const size_t es = p.bf16 ? 2 : 4;
+    if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
+        misaligned(F, es) || misaligned(out, es) || (omega && misaligned(omega, es)) ||
+        misaligned(ctx, 256) || misaligned(workspace, 256))
+        return FLURKA_ERR_ALIGN;
+    const bool fast_ok = fast_supported(p, 0) && fast_pointers_ok(Q, K, V, E, F, omega, out);
+    if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
+    const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
+    if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
+    const size_t need = use_fast ? fast_ws_bytes(p, 0) : generic_ws_layout(p, 0).total * sizeof(float);
+    if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
+
+    FwdArgs a{Q, K, V, E, F, omega, out, (float*)ctx, (float*)workspace};
+    hipStream_t s = (hipStream_t)stream;
+    return use_fast ? fast_forward(p, a, s) : generic_forward(p, a, s);
+}
+
+flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                              const void* omega, const void* dOut, const void* ctx, size_t ctx_bytes,
+                              void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
+                              size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                              int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              void* stream) {
+    Problem p;
+    flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
+    if (st != FLURKA_OK) return st;
+    if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
+    if (!Q || !K || !V || !E || !F || !dOut || !ctx || !dQ || !dK || !dV || !dE || !dF || !workspace)
+        return FLURKA_ERR_NULL;
+    if (!p.elu && !omega) return FLURKA_ERR_NULL;
+    const size_t es = p.bf16 ? 2 : 4;
+    if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
+        misaligned(F, es) || misaligned(dOut, es) || (omega && misaligned(omega, es)) ||
+        misaligned(dQ, es) || misaligned(dK, es) || misaligned(dV, es) || misaligned(dE, es) ||
+        misaligned(dF, es) || misaligned(ctx, 256) || misaligned(workspace, 256))
+        return FLURKA_ERR_ALIGN;
+    const bool fast_ok = fast_supported(p, 1) && fast_pointers_ok(Q, K, V, E, F, omega, dOut) &&
+                         fast_pointers_ok(dQ, dK, dV, dE, dF, nullptr, dQ);
+    if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
+    const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
+    if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
+    const size_t need = use_fast ? fast_ws_bytes(p, 1) : generic_ws_layout(p, 1).total * sizeof(float);
+    if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
+
+    BwdArgs a{Q, K, V, E, F, omega, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace};
+    hipStream_t s = (hipStream_t)stream;
+    return use_fast ? fast_backward(p, a, s) : generic_backward(p, a, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,146 @@
+// Internal declarations shared by the translation units of libflurka.
+// Nothing here is part of the public ABI (that is include/flurka.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "flurka.h"
+
+namespace flurka {
+
+// Problem description after validation.
+struct Problem {
+    int B, H, n, d, k, m;
+    int mf;              // feature count: m (performer) or d (elu1)
+    int BH;
+    int omega_per_head;
+    int bf16;            // storage type of caller tensors
+    int elu;             // feature map
+};
+
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Context buffer (float32): state carried from forward to backward.
+// Every segment starts on a 256-byte boundary.
+struct CtxLayout {
+    size_t Kp, Vp, PhiK, S, z, c, total;   // offsets / total in floats
+};
+
+static inline CtxLayout ctx_layout(const Problem& p) {
+    CtxLayout L;
+    size_t o = 0;
+    const size_t BH = (size_t)p.BH;
+    L.Kp = o;   o += round_up(BH * p.k * p.d, 64);
+    L.Vp = o;   o += round_up(BH * p.k * p.d, 64);
+    L.PhiK = o; o += round_up(BH * p.k * p.mf, 64);
+    L.S = o;    o += round_up(BH * p.mf * p.d, 64);
+    L.z = o;    o += round_up(BH * p.mf, 64);
+    L.c = o;    o += 2 * round_up(BH, 64);   // order-preserving integer image of c, then c itself
+    L.total = o;
+    return L;
+}
+
+// ---- generic (fp32-arithmetic) path ---------------------------------------
+// Rows of Q handled per chunk so that the (B,H,rows,mf) feature buffer stays
+// near 128 MiB whatever n is.
+static inline int generic_chunk_rows(const Problem& p) {
+    const size_t budget = (size_t)128 << 20;
+    size_t rows = budget / (4 * (size_t)p.BH * (size_t)p.mf);
+    if (rows < 64) rows = 64;
+    rows = rows / 64 * 64;
+    if (rows > (size_t)p.n) rows = (size_t)p.n;
+    return (int)rows;
+}
+
+struct GenericWs {
+    size_t P, T, N, dD, dS, dz, dPhiK, dKp, dVp, rs, total;   // floats
+};
+
+static inline GenericWs generic_ws_layout(const Problem& p, int bwd) {
+    GenericWs W{};
+    const size_t BH = (size_t)p.BH;
+    const size_t nc = (size_t)generic_chunk_rows(p);
+    size_t o = 0;
+    W.P = o; o += round_up(BH * nc * p.mf, 64);
+    W.N = o; o += round_up(BH * nc * p.d, 64);
+    if (bwd) {
+        W.T = o;     o += round_up(BH * nc * p.mf, 64);
+        W.dD = o;    o += round_up(BH * nc, 64);
+        W.dS = o;    o += round_up(BH * p.mf * p.d, 64);
+        W.dz = o;    o += round_up(BH * p.mf, 64);
+        W.dPhiK = o; o += round_up(BH * p.k * p.mf, 64);
+        W.dKp = o;   o += round_up(BH * p.k * p.d, 64);
+        W.dVp = o;   o += round_up(BH * p.k * p.d, 64);
+        W.rs = o;    o += round_up(BH * p.k, 64);
+    }
+    W.total = o;
+    return W;
+}
+
+struct FwdArgs {
+    const void *Q, *K, *V, *E, *F, *omega;
+    void* out;
+    float* ctx;
+    float* ws;
+};
+
+struct BwdArgs {
+    const void *Q, *K, *V, *E, *F, *omega, *dOut;
+    const float* ctx;
+    void *dQ, *dK, *dV, *dE, *dF;
+    float* ws;
+};
+
+// Each returns FLURKA_OK or FLURKA_ERR_LAUNCH.
+flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
+flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s);
+
+// ---- bf16 MFMA path ---------------------------------------------------------
+// Whether the MFMA kernels cover the problem (dtype, feature map, tile multiples).
+bool fast_supported(const Problem& p, int bwd);
+// 16-byte alignment of the caller tensors the vector loads touch (nullptr entries are skipped).
+bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d, const void* e,
+                      const void* f, const void* g);
+size_t fast_ws_bytes(const Problem& p, int bwd);
+flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
+flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s);
+// Key-side state from K', V' already in ctx (used by both paths).
+flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, hipStream_t s);
+
+// ---- device helpers --------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_elem(const void* p, long i, int bf16) {
+    return bf16 ? bf16_to_f32(((const uint16_t*)p)[i]) : ((const float*)p)[i];
+}
+
+__device__ __forceinline__ void store_elem(void* p, long i, float v, int bf16) {
+    if (bf16) ((uint16_t*)p)[i] = f32_to_bf16(v);
+    else ((float*)p)[i] = v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace flurka

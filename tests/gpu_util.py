@@ -1,0 +1,75 @@
+"""Helpers for the GPU parity tests: upload seeded inputs, run the library
+through its binding, compare with the fp64 oracle."""
+import numpy as np
+import torch
+
+from oracle import flurka_oracle as fo
+from paper_2306_15799_amd import binding as fb
+from paper_2306_15799_amd import inputs
+
+# Relative-L2 bars from the benchmark definition: 1e-5 for fp32 storage,
+# 2e-2 for bf16 storage with fp32 accumulation.
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def to_device(t: dict, dtype: str) -> dict:
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    return {k: (None if v is None else torch.from_numpy(v).to("cuda").to(td).contiguous())
+            for k, v in t.items()}
+
+
+def to_host(x: torch.Tensor) -> np.ndarray:
+    return x.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def run_forward(w, t, algo="auto"):
+    g = to_device(t, w.dtype)
+    out, ctx = fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, algo=algo)
+    torch.cuda.synchronize()
+    return g, out, ctx
+
+
+def run_backward(w, g, ctx, algo="auto"):
+    grads = fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], g["dOut"], ctx,
+                               phi=w.phi, algo=algo)
+    torch.cuda.synchronize()
+    return grads
+
+
+def oracle_forward(w, t, rows=None):
+    return fo.flurka_attention(t["Q"], t["K"], t["V"], t["E"], t["F"], t["omega"], w.phi, rows=rows)
+
+
+def oracle_backward(w, t):
+    return fo.flurka_attention_bwd(t["Q"], t["K"], t["V"], t["E"], t["F"], t["omega"], t["dOut"], w.phi)
+
+
+def rel_err(x, ref, floor=0.0):
+    """Relative L2 error; `floor` (per element) keeps a reference that is
+    exactly zero by construction (e.g. dQ when k = 1) from dividing by zero."""
+    x = np.asarray(x, np.float64)
+    ref = np.asarray(ref, np.float64)
+    den = max(float(np.linalg.norm(ref.ravel())), floor * np.sqrt(ref.size))
+    return float(np.linalg.norm((x - ref).ravel())) / den if den > 0 else fo.rel_l2(x, ref)
+
+
+def check_forward(w, seed=0, algo="auto", tol=None):
+    t = inputs.make_inputs(w, seed)
+    _, out, _ = run_forward(w, t, algo)
+    err = fo.rel_l2(to_host(out), oracle_forward(w, t))
+    assert err <= (tol or TOL[w.dtype]), f"{w.name} fwd rel-L2 {err:.3e}"
+    return err
+
+
+def check_forward_backward(w, seed=0, algo="auto", tol=None, floor=0.0):
+    t = inputs.make_inputs(w, seed)
+    g, out, ctx = run_forward(w, t, algo)
+    bar = tol or TOL[w.dtype]
+    errs = {"out": fo.rel_l2(to_host(out), oracle_forward(w, t))}
+    grads = run_backward(w, g, ctx, algo)
+    ref = oracle_backward(w, t)
+    for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], grads, ref):
+        errs[name] = rel_err(to_host(a), b, floor)
+    bad = {k: v for k, v in errs.items() if not v <= bar}
+    assert not bad, f"{w.name} rel-L2 over {bar:g}: {bad} (all: {errs})"
+    return errs

@@ -1,0 +1,115 @@
+"""Host-side checks of the C ABI: the library loads, exports what the header
+declares, sizes its buffers sensibly and rejects bad arguments before any
+launch.  No compute call is made, so this runs without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2306_15799_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000          # 256-byte aligned, never dereferenced: validation fails first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(fb.LIB_PATH):
+        from paper_2306_15799_amd import build
+        build.build()
+    return fb.load_library()
+
+
+def test_every_declared_entry_point_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "flurka.h")).read()
+    declared = set(re.findall(r"FLURKA_API\s+[\w\s\*]+?\b(flurka_\w+)\s*\(", header))
+    assert declared == set(fb.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.flurka_version() == 100
+
+
+def test_status_strings(lib):
+    seen = {fb.status_str(i) for i in range(8)}
+    assert len(seen) == 8 and fb.status_str(0) == "ok"
+    assert fb.status_str(99) == "unknown status"
+
+
+def test_buffer_sizes(lib):
+    # C1: K',V' 2*4096 + PhiK 4096 + S 4096 + z 64 + c 2*64 floats
+    assert fb.ctx_bytes(1, 1, 512, 64, 64, 64, fb.F32, "performer") == 4 * (4 * 4096 + 64 + 128)
+    assert fb.ctx_bytes(1, 1, 512, 64, 64, 63, fb.F32, "elu1") == 0          # m != d
+    assert fb.ctx_bytes(0, 1, 512, 64, 64, 64, fb.F32, "performer") == 0
+    fwd = fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_FWD, "generic")
+    bwd = fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_BWD, "generic")
+    assert 0 < fwd < bwd
+    auto = fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_FWD, "auto")
+    assert auto >= fwd
+    offs = (ctypes.c_size_t * 6)()
+    assert lib.flurka_ctx_layout(1, 1, 512, 64, 64, 64, fb.F32, 0, offs) == fb.OK
+    assert list(offs)[:5] == [0, 4096, 8192, 12288, 16384]
+    assert lib.flurka_ctx_layout(1, 1, 512, 64, 64, 64, fb.F32, 0, None) == fb.ERR_NULL
+
+
+def _fwd(lib, **over):
+    a = dict(Q=FAKE, K=FAKE, V=FAKE, E=FAKE, F=FAKE, omega=FAKE, out=FAKE, ctx=FAKE, ctx_bytes=1 << 40,
+             ws=FAKE, ws_bytes=1 << 40, B=1, H=1, n=512, d=64, k=64, m=64, per_head=1,
+             dtype=fb.F32, phi=fb.PHI_PERFORMER, algo=fb.ALGO_GENERIC)
+    a.update(over)
+    return lib.flurka_attn_fwd(a["Q"], a["K"], a["V"], a["E"], a["F"], a["omega"], a["out"], a["ctx"],
+                               a["ctx_bytes"], a["ws"], a["ws_bytes"], a["B"], a["H"], a["n"], a["d"],
+                               a["k"], a["m"], a["per_head"], a["dtype"], a["phi"], a["algo"], None)
+
+
+def _bwd(lib, **over):
+    a = dict(Q=FAKE, K=FAKE, V=FAKE, E=FAKE, F=FAKE, omega=FAKE, dOut=FAKE, ctx=FAKE, ctx_bytes=1 << 40,
+             dQ=FAKE, dK=FAKE, dV=FAKE, dE=FAKE, dF=FAKE, ws=FAKE, ws_bytes=1 << 40,
+             B=1, H=1, n=512, d=64, k=64, m=64, per_head=1, dtype=fb.F32, phi=fb.PHI_PERFORMER,
+             algo=fb.ALGO_GENERIC)
+    a.update(over)
+    return lib.flurka_attn_bwd(a["Q"], a["K"], a["V"], a["E"], a["F"], a["omega"], a["dOut"], a["ctx"],
+                               a["ctx_bytes"], a["dQ"], a["dK"], a["dV"], a["dE"], a["dF"], a["ws"],
+                               a["ws_bytes"], a["B"], a["H"], a["n"], a["d"], a["k"], a["m"],
+                               a["per_head"], a["dtype"], a["phi"], a["algo"], None)
+
+
+def test_forward_rejects_bad_arguments_before_launching(lib):
+    for name in ["Q", "K", "V", "E", "F", "omega", "out", "ctx", "ws"]:
+        assert _fwd(lib, **{name: None}) == fb.ERR_NULL, name
+    for dim in ["B", "H", "n", "d", "k", "m"]:
+        assert _fwd(lib, **{dim: 0}) == fb.ERR_SHAPE, dim
+        assert _fwd(lib, **{dim: -3}) == fb.ERR_SHAPE, dim
+    assert _fwd(lib, B=256, H=256) == fb.ERR_SHAPE                 # B*H above the grid limit
+    assert _fwd(lib, d=4097) == fb.ERR_SHAPE
+    assert _fwd(lib, n=(1 << 24) + 1) == fb.ERR_SHAPE
+    assert _fwd(lib, phi=fb.PHI_ELU1, m=32) == fb.ERR_SHAPE        # elu1 needs m == d
+    assert _fwd(lib, dtype=7) == fb.ERR_DTYPE
+    assert _fwd(lib, phi=5) == fb.ERR_DTYPE
+    assert _fwd(lib, algo=9) == fb.ERR_DTYPE
+    assert _fwd(lib, Q=FAKE + 2) == fb.ERR_ALIGN
+    assert _fwd(lib, ctx=FAKE + 64) == fb.ERR_ALIGN
+    assert _fwd(lib, ctx_bytes=1000) == fb.ERR_WORKSPACE
+    assert _fwd(lib, ws_bytes=1000) == fb.ERR_WORKSPACE
+    assert _fwd(lib, algo=fb.ALGO_FAST) == fb.ERR_UNSUPPORTED      # fp32 storage has no MFMA path
+    # the elu1 map takes no omega: NULL is fine there, and validation moves on to the next check
+    assert _fwd(lib, phi=fb.PHI_ELU1, omega=None, ws_bytes=8) == fb.ERR_WORKSPACE
+
+
+def test_backward_rejects_bad_arguments_before_launching(lib):
+    for name in ["Q", "K", "V", "E", "F", "omega", "dOut", "ctx", "dQ", "dK", "dV", "dE", "dF", "ws"]:
+        assert _bwd(lib, **{name: None}) == fb.ERR_NULL, name
+    assert _bwd(lib, k=0) == fb.ERR_SHAPE
+    assert _bwd(lib, dtype=2) == fb.ERR_DTYPE
+    assert _bwd(lib, dE=FAKE + 1) == fb.ERR_ALIGN
+    assert _bwd(lib, ctx_bytes=16) == fb.ERR_WORKSPACE
+    assert _bwd(lib, ws_bytes=16) == fb.ERR_WORKSPACE
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    q = torch.zeros(1, 1, 8, 4)
+    e = torch.zeros(2, 8)
+    om = torch.zeros(1, 3, 4)
+    with pytest.raises(ValueError):
+        fb.flurka_attn_fwd(q, q, q, e, e, om)
