@@ -159,6 +159,21 @@ FLURKA_API flurka_status flurka_attn_bwd(const void* Q, const void* K, const voi
                               flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
                               void* stream);
 
+/*
+ * Built-in stage timer (for benchmarks; off by default, not thread-safe).
+ * While enabled, every forward/backward call brackets each of its stages with
+ * HIP events recorded on the call's own stream.  flurka_profile_read waits
+ * for the recorded events, writes up to `capacity` (stage id, milliseconds)
+ * pairs in launch order to the HOST arrays, forgets them and returns how many
+ * it wrote (at most 4096 are kept between reads).  Enabling creates the
+ * events (host-side resources only, no device memory); disabling destroys
+ * them.  Stages: the sequence projections, the key-side state, the query
+ * stream, and the backward stages (see flurka_profile_stage_name).
+ */
+FLURKA_API flurka_status flurka_profile_enable(int on);
+FLURKA_API int flurka_profile_read(int* stage_ids, float* milliseconds, int capacity);
+FLURKA_API const char* flurka_profile_stage_name(int stage_id);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,6 +30,7 @@ _ALGO = {"auto": ALGO_AUTO, "generic": ALGO_GENERIC, "fast": ALGO_FAST,
 EXPORTED_SYMBOLS = (
     "flurka_version", "flurka_status_str", "flurka_ctx_bytes", "flurka_ctx_layout", "flurka_workspace_bytes",
     "flurka_fast_path_supported", "flurka_attn_fwd", "flurka_attn_bwd",
+    "flurka_profile_enable", "flurka_profile_read", "flurka_profile_stage_name",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -70,12 +71,34 @@ def load_library() -> ctypes.CDLL:
     lib.flurka_attn_bwd.restype = c_int
     lib.flurka_attn_bwd.argtypes = ([c_void] * 7 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
+    lib.flurka_profile_enable.restype = c_int
+    lib.flurka_profile_enable.argtypes = [c_int]
+    lib.flurka_profile_read.restype = c_int
+    lib.flurka_profile_read.argtypes = [ctypes.POINTER(c_int), ctypes.POINTER(ctypes.c_float), c_int]
+    lib.flurka_profile_stage_name.restype = ctypes.c_char_p
+    lib.flurka_profile_stage_name.argtypes = [c_int]
     _lib = lib
     return lib
 
 
 def status_str(status: int) -> str:
     return load_library().flurka_status_str(int(status)).decode()
+
+
+def profile_enable(on: bool) -> None:
+    st = load_library().flurka_profile_enable(1 if on else 0)
+    if st != OK:
+        raise FlurkaError(st, "flurka_profile_enable")
+
+
+def profile_read() -> list:
+    """[(stage name, milliseconds), ...] recorded since the last read, in launch order."""
+    lib = load_library()
+    cap = 4096
+    ids = (ctypes.c_int * cap)()
+    ms = (ctypes.c_float * cap)()
+    cnt = lib.flurka_profile_read(ids, ms, cap)
+    return [(lib.flurka_profile_stage_name(ids[i]).decode(), float(ms[i])) for i in range(cnt)]
 
 
 def _dtype_code(t: torch.Tensor) -> int:

@@ -2,7 +2,34 @@
 // The entry points are documented in include/flurka.h.
 #include "flurka_internal.h"
 
+#include <vector>
+
 using namespace flurka;
+
+// ---- stage timer ---------------------------------------------------------------
+namespace flurka {
+namespace {
+constexpr int kMaxIntervals = 4096;
+bool g_prof_on = false;
+std::vector<hipEvent_t> g_events;       // 2 * kMaxIntervals, created on enable
+std::vector<int> g_stage_of;            // stage id per recorded interval
+int g_intervals = 0;
+bool g_open = false;
+}  // namespace
+
+void stage_begin(hipStream_t s) {
+    if (!g_prof_on || g_intervals >= kMaxIntervals) return;
+    if (hipEventRecord(g_events[2 * g_intervals], s) == hipSuccess) g_open = true;
+}
+
+void stage_end(hipStream_t s, Stage id) {
+    if (!g_prof_on || !g_open) return;
+    g_open = false;
+    if (hipEventRecord(g_events[2 * g_intervals + 1], s) != hipSuccess) return;
+    g_stage_of[g_intervals] = (int)id;
+    ++g_intervals;
+}
+}  // namespace flurka
 
 namespace {
 
@@ -150,6 +177,58 @@ flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const
     BwdArgs a{Q, K, V, E, F, omega, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace};
     hipStream_t s = (hipStream_t)stream;
     return use_fast ? fast_backward(p, a, s) : generic_backward(p, a, s);
+}
+
+flurka_status flurka_profile_enable(int on) {
+    if (on && !g_prof_on) {
+        g_events.resize(2 * kMaxIntervals);
+        g_stage_of.assign(kMaxIntervals, 0);
+        for (size_t i = 0; i < g_events.size(); ++i) {
+            if (hipEventCreate(&g_events[i]) != hipSuccess) {
+                for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(g_events[j]);
+                g_events.clear();
+                return FLURKA_ERR_LAUNCH;
+            }
+        }
+        g_intervals = 0;
+        g_open = false;
+        g_prof_on = true;
+    } else if (!on && g_prof_on) {
+        g_prof_on = false;
+        for (hipEvent_t e : g_events) (void)hipEventDestroy(e);
+        g_events.clear();
+        g_intervals = 0;
+    }
+    return FLURKA_OK;
+}
+
+int flurka_profile_read(int* stage_ids, float* milliseconds, int capacity) {
+    if (!g_prof_on || !stage_ids || !milliseconds || capacity < 1) return 0;
+    int written = 0;
+    for (int i = 0; i < g_intervals && written < capacity; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_events[2 * i + 1]) != hipSuccess) break;
+        if (hipEventElapsedTime(&ms, g_events[2 * i], g_events[2 * i + 1]) != hipSuccess) break;
+        stage_ids[written] = g_stage_of[i];
+        milliseconds[written] = ms;
+        ++written;
+    }
+    g_intervals = 0;
+    g_open = false;
+    return written;
+}
+
+const char* flurka_profile_stage_name(int id) {
+    switch (id) {
+        case STAGE_PROJECT: return "project";
+        case STAGE_KEY_STATE: return "key_state";
+        case STAGE_QUERY: return "query_stream";
+        case STAGE_BWD_QUERY: return "bwd_query";
+        case STAGE_BWD_KEY: return "bwd_key";
+        case STAGE_BWD_DKDV: return "bwd_dk_dv";
+        case STAGE_BWD_DEDF: return "bwd_de_df";
+    }
+    return "unknown";
 }
 
 }  // extern "C"

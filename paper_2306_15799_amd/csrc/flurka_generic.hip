@@ -437,12 +437,19 @@ flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s)
     const CtxLayout L = ctx_layout(p);
     const GenericWs W = generic_ws_layout(p, 0);
     flurka_status st;
-    if ((st = project(p, a.E, a.K, a.ctx + L.Kp, s)) != FLURKA_OK) return st;
-    if ((st = project(p, a.F, a.V, a.ctx + L.Vp, s)) != FLURKA_OK) return st;
-    if ((st = generic_key_state(p, a.omega, a.ctx, s)) != FLURKA_OK) return st;
+    {
+        StageScope sc(s, STAGE_PROJECT);
+        if ((st = project(p, a.E, a.K, a.ctx + L.Kp, s)) != FLURKA_OK) return st;
+        if ((st = project(p, a.F, a.V, a.ctx + L.Vp, s)) != FLURKA_OK) return st;
+    }
+    {
+        StageScope sc(s, STAGE_KEY_STATE);
+        if ((st = generic_key_state(p, a.omega, a.ctx, s)) != FLURKA_OK) return st;
+    }
     const int nc = generic_chunk_rows(p);
     float* P = a.ws + W.P;
     float* N = a.ws + W.N;
+    StageScope sc(s, STAGE_QUERY);
     for (int row0 = 0; row0 < p.n; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
         st = query_features_and_numerator(p, a.Q, a.omega, a.ctx + L.S, P, N, row0, nr, s);
@@ -486,6 +493,7 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
     flurka_status st;
     const int nc = generic_chunk_rows(p);
 
+    stage_begin(s);
     for (int row0 = 0; row0 < p.n; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
         const long rows = (long)p.BH * nr;
@@ -544,6 +552,9 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
         }
     }
 
+    stage_end(s, STAGE_BWD_QUERY);
+
+    stage_begin(s);
     const long krows = (long)p.BH * p.k;
     {   // dPhiK = V' dS^T   (k x mf)
         GemmArgs g{};
@@ -587,7 +598,10 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
         FLURKA_CHECK_LAUNCH();
     }
 
+    stage_end(s, STAGE_BWD_KEY);
+
     // dK = E^T dK', dV = F^T dV'   (n x d per head)
+    stage_begin(s);
     for (int which = 0; which < 2; ++which) {
         GemmArgs g{};
         g.A = which ? a.F : a.E; g.B = which ? dVp : dKp; g.C = which ? a.dV : a.dK;
@@ -598,7 +612,9 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
         g.H = p.H; g.a_bf16 = p.bf16; g.c_bf16 = p.bf16;
         if ((st = launch_gemm(g, p.BH, s)) != FLURKA_OK) return st;
     }
+    stage_end(s, STAGE_BWD_DKDV);
     // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T   (k x n); reduction index = (bh, t)
+    stage_begin(s);
     for (int which = 0; which < 2; ++which) {
         GemmArgs g{};
         g.A = which ? dVp : dKp; g.B = which ? a.V : a.K; g.C = which ? a.dF : a.dE;
@@ -609,6 +625,7 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
         g.H = 1; g.b_bf16 = p.bf16; g.c_bf16 = p.bf16;
         if ((st = launch_gemm(g, 1, s)) != FLURKA_OK) return st;
     }
+    stage_end(s, STAGE_BWD_DEDF);
     return FLURKA_OK;
 }
 

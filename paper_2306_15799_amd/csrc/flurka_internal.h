@@ -97,6 +97,27 @@ struct BwdArgs {
 flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
 flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s);
 
+// ---- stage timer -------------------------------------------------------------
+enum Stage {
+    STAGE_PROJECT = 0,     // K' = E K and V' = F V
+    STAGE_KEY_STATE = 1,   // PhiK, S, z
+    STAGE_QUERY = 2,       // phi(Q), numerator, denominator, out
+    STAGE_BWD_QUERY = 3,   // recompute P; dQ, dS, dz
+    STAGE_BWD_KEY = 4,     // dPhiK, dV', dK'
+    STAGE_BWD_DKDV = 5,    // dK = E^T dK', dV = F^T dV'
+    STAGE_BWD_DEDF = 6,    // dE, dF
+    STAGE_COUNT = 7
+};
+// No-ops unless the timer is enabled.  begin/end pairs must not nest.
+void stage_begin(hipStream_t s);
+void stage_end(hipStream_t s, Stage id);
+
+struct StageScope {
+    hipStream_t s; Stage id;
+    StageScope(hipStream_t s_, Stage id_) : s(s_), id(id_) { stage_begin(s); }
+    ~StageScope() { stage_end(s, id); }
+};
+
 // ---- bf16 MFMA path ---------------------------------------------------------
 // Whether the MFMA kernels cover the problem (dtype, feature map, tile multiples).
 bool fast_supported(const Problem& p, int bwd);
