@@ -1,9 +1,431 @@
-// bf16 MFMA path (placeholder until the kernels land): reports nothing as supported.
-#include "flurka_internal.h"
+// bf16 MFMA path of FLuRKA attention for gfx950 (forward).
+//
+//   stage "project"      K' = E K, V' = F V     split-n GEMM on v_mfma_f32_32x32x16_bf16,
+//                                               fp32 partial sums, deterministic second-stage sum
+//   stage "key_state"    PhiK, S, z             fp32 kernels shared with the generic path (K' must stay
+//                                               fp32 into the exponent: exp() turns absolute error in
+//                                               omega.k' - |k'|^2/2 into relative error of the weights)
+//   stage "query_stream" out = (P S) / (P z)    per 32 query rows of a wavefront:
+//                                               U^T = omega Q^T (MFMA) -> running row max -> exp ->
+//                                               bf16 P^T kept in registers as the B operand of
+//                                               N^T = S^T P^T (MFMA); the denominator on the VALU
+// Formulas: Eq. 2 with the App. D row normaliser; feature maps of Sec. 2, "Kernel Methods".
+#include "flurka_mfma.h"
 
 namespace flurka {
 
-bool fast_supported(const Problem&, int) { return false; }
+#define FLURKA_CHECK_LAUNCH()                                   \
+    do {                                                        \
+        if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH; \
+    } while (0)
+
+static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total + block - 1) / block)); }
+
+// ===========================================================================
+// Stage "project": C[k x (BH*d)] = E[k x n] * X[n x (BH*d)] for X in {K, V}
+// ===========================================================================
+constexpr int PBM = 256;              // rows of E per workgroup
+constexpr int PBN = 256;              // columns (whole heads) per workgroup
+constexpr int PBK = 64;               // sequence positions per main-loop step
+constexpr int PA_PITCH = 144;         // bytes per LDS row of the E tile (128 + 16 pad: conflict-free b128 reads)
+constexpr int PB_PITCH = 264;         // dwords per LDS row of the X tile, rows are (position pair) x column
+constexpr int PA_STAGE = PBM * PA_PITCH;
+constexpr int PB_STAGE = (PBK / 2) * PB_PITCH * 4;
+constexpr int P_STAGE = PA_STAGE + PB_STAGE;
+constexpr int P_LDS = 2 * P_STAGE;    // double buffered: 141,312 bytes
+
+struct ProjArgs {
+    const uint16_t* EF[2];    // E, F
+    const uint16_t* X[2];     // K, V
+    float* out[2];            // destination of split 0 for K', V'; split s adds s * split_stride
+    long split_stride;        // floats
+    int n, d, k, BH;
+    int tilesM, tilesN, splits, steps_per_split, total_steps;
+};
+
+__global__ __launch_bounds__(256) void proj_mfma_kernel(ProjArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // workgroup -> (split, which, column tile, row tile); consecutive ids walk the splits first, so
+    // with a split count that is a multiple of 8 every XCD (ids mod 8) keeps to its own n-ranges
+    int id = blockIdx.x;
+    const int split = id % a.splits; id /= a.splits;
+    const int tm = id % a.tilesM;    id /= a.tilesM;
+    const int tn = id % a.tilesN;    id /= a.tilesN;
+    const int which = id;
+    const uint16_t* __restrict__ Eg = a.EF[which];
+    const uint16_t* __restrict__ Xg = a.X[which];
+    const int m0 = tm * PBM;
+    const int heads_per_tile = PBN / a.d;
+    const int bh0 = tn * heads_per_tile;
+    const int step0 = split * a.steps_per_split;
+    int step1 = step0 + a.steps_per_split;
+    if (step1 > a.total_steps) step1 = a.total_steps;
+
+    // global -> register staging maps
+    const int a_chunk = tid & 7;                 // 16-byte chunk within a 128-byte row segment
+    const uint16_t* a_src[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        int r = m0 + (tid >> 3) + 32 * u;
+        if (r > a.k - 1) r = a.k - 1;            // rows past k are computed on clamped data and never stored
+        a_src[u] = Eg + (long)r * a.n + 8 * a_chunk;
+    }
+    const int b_cg = tid & 31;                   // group of 8 columns
+    const int b_col = 8 * b_cg;
+    int b_bh = bh0 + b_col / a.d;
+    if (b_bh > a.BH - 1) b_bh = a.BH - 1;
+    const uint16_t* b_src = Xg + (long)b_bh * a.n * a.d + (b_col % a.d);
+    const int b_pr = tid >> 5;                   // pair-row 0..7 (+8u)
+
+    uint4 ra[8], rb[8];
+    auto load_global = [&](int step) {
+        const long kk0 = (long)step * PBK;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ra[u] = ld16(a_src[u] + kk0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long kk = kk0 + 2 * (b_pr + 8 * u);
+            rb[2 * u] = ld16(b_src + kk * a.d);
+            rb[2 * u + 1] = ld16(b_src + (kk + 1) * a.d);
+        }
+    };
+    auto store_lds = [&](int buf) {
+        unsigned char* As = lds + buf * P_STAGE;
+        uint32_t* Bs = (uint32_t*)(lds + buf * P_STAGE + PA_STAGE);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            *(uint4*)(As + ((tid >> 3) + 32 * u) * PA_PITCH + 16 * a_chunk) = ra[u];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint4 lo = rb[2 * u], hi = rb[2 * u + 1];   // positions 2p and 2p+1, 8 columns each
+            uint4 o0, o1;                                     // column j -> dword {lo[j], hi[j]}
+            o0.x = (lo.x & 0xffffu) | (hi.x << 16);  o0.y = (lo.x >> 16) | (hi.x & 0xffff0000u);
+            o0.z = (lo.y & 0xffffu) | (hi.y << 16);  o0.w = (lo.y >> 16) | (hi.y & 0xffff0000u);
+            o1.x = (lo.z & 0xffffu) | (hi.z << 16);  o1.y = (lo.z >> 16) | (hi.z & 0xffff0000u);
+            o1.z = (lo.w & 0xffffu) | (hi.w << 16);  o1.w = (lo.w >> 16) | (hi.w & 0xffff0000u);
+            uint32_t* dst = Bs + (b_pr + 8 * u) * PB_PITCH + b_col;
+            *(uint4*)dst = o0;
+            *(uint4*)(dst + 4) = o1;
+        }
+    };
+
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = zero16();
+
+    const int half = lane >> 5, l32 = lane & 31;
+    if (step0 < step1) {
+        load_global(step0);
+        store_lds(0);
+    }
+    __syncthreads();
+    for (int step = step0; step < step1; ++step) {
+        const int buf = (step - step0) & 1;
+        const bool more = step + 1 < step1;
+        if (more) load_global(step + 1);
+        const unsigned char* As = lds + buf * P_STAGE;
+        const uint32_t* Bs = (const uint32_t*)(lds + buf * P_STAGE + PA_STAGE);
+#pragma unroll
+        for (int s = 0; s < PBK / 16; ++s) {
+            uint4 fa[4], fb[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                fa[i] = *(const uint4*)(As + (wm * 128 + 32 * i + l32) * PA_PITCH + 32 * s + 16 * half);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t* p = Bs + (8 * s + 4 * half) * PB_PITCH + wn * 128 + 32 * j + l32;
+                fb[j].x = p[0];
+                fb[j].y = p[PB_PITCH];
+                fb[j].z = p[2 * PB_PITCH];
+                fb[j].w = p[3 * PB_PITCH];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
+        }
+        if (more) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: fp32 partial sums in (BH, k, d) layout
+    float* __restrict__ out = a.out[which] + (long)split * a.split_stride;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int c = wn * 128 + 32 * j + l32;
+        const int bh = bh0 + c / a.d;
+        if (bh >= a.BH) continue;
+        float* ob = out + (long)bh * a.k * a.d + (c % a.d);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                const int r = m0 + wm * 128 + 32 * i + 8 * (g >> 2) + 4 * half + (g & 3);
+                if (r < a.k) ob[(long)r * a.d] = acc[i][j][g];
+            }
+        }
+    }
+}
+
+// dst[i] = sum_s src[s * stride + i]
+__global__ void sum_splits_kernel(float* dst, const float* src, long count, long stride, int splits) {
+    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= count) return;
+    if (i + 3 < count) {
+        float4 acc = *(const float4*)(src + i);
+        for (int s = 1; s < splits; ++s) {
+            const float4 v = *(const float4*)(src + (long)s * stride + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *(float4*)(dst + i) = acc;
+    } else {
+        for (long j = i; j < count; ++j) {
+            float acc = src[j];
+            for (int s = 1; s < splits; ++s) acc += src[(long)s * stride + j];
+            dst[j] = acc;
+        }
+    }
+}
+
+struct ProjPlan {
+    int tilesM, tilesN, splits, steps_per_split, total_steps;
+};
+
+static ProjPlan proj_plan(const Problem& p) {
+    ProjPlan q;
+    q.tilesM = (p.k + PBM - 1) / PBM;
+    const int heads_per_tile = PBN / p.d;
+    q.tilesN = (p.BH + heads_per_tile - 1) / heads_per_tile;
+    q.total_steps = p.n / PBK;
+    const int tiles = q.tilesM * q.tilesN * 2;
+    int splits = 256 / tiles;                      // one workgroup per compute unit
+    if (splits < 1) splits = 1;
+    if (splits > 8) splits = splits / 8 * 8;       // keep each XCD on its own n-ranges
+    if (splits > q.total_steps) splits = q.total_steps;
+    q.steps_per_split = (q.total_steps + splits - 1) / splits;
+    q.splits = (q.total_steps + q.steps_per_split - 1) / q.steps_per_split;
+    return q;
+}
+
+// ===========================================================================
+// Stage "query_stream"
+// ===========================================================================
+// Repack S (mf x d fp32) and z (mf fp32) of every head for the query-stream kernel:
+//   St  (d x mf) bf16, St[t][slot] = S[feature(slot)][t]
+//   zp  (mf) fp32,     zp[32*ft + 16*h + g] = z[32*ft + 8*(g/4) + 4*h + g%4]
+// For the performer map the feature order inside each group of 16 slots is the one in which the
+// accumulator of the first MFMA hands P^T to the second MFMA as its B operand:
+//   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4.
+// For elu1 P is built directly in operand order, so St keeps the natural order.
+__global__ void pack_state_kernel(uint16_t* St, float* zp, const float* S, const float* z, int mf, int d,
+                                  int permute, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int slot = (int)(idx % mf);
+    const long rest = idx / mf;
+    const int t = (int)(rest % d);
+    const long bh = rest / d;
+    int f = slot;
+    if (permute) {
+        const int e = slot & 7, h = (slot >> 3) & 1;
+        f = (slot & ~15) + 8 * (e >> 2) + 4 * h + (e & 3);
+    }
+    St[idx] = f32_to_bf16(S[(bh * mf + f) * d + t]);
+    if (t == 0) {
+        // z in accumulator order of a 32-feature tile
+        const int g = slot & 15, h = (slot >> 4) & 1;
+        const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
+        zp[bh * mf + slot] = permute ? z[bh * mf + fz] : z[bh * mf + slot];
+    }
+}
+
+struct QueryArgs {
+    const uint16_t* Q;
+    const uint16_t* omega;     // (H|1, m, d)
+    const uint16_t* St;        // (BH, d, mf) bf16
+    const float* zp;           // (BH, mf)
+    uint16_t* out;
+    int n, H, mf, rows_per_wg, wgs_per_head;
+    long omega_head_stride;    // 0 if shared
+};
+
+template <int D>
+struct QueryLds {
+    static constexpr int w_pitch = (D + 8) * 2;                  // bytes per omega row
+    static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }
+    static __host__ __device__ int w_bytes(int mf) { return mf * w_pitch; }
+    static __host__ __device__ int s_bytes(int mf) { return D * s_pitch(mf); }
+    static __host__ __device__ int total(int mf, int elu) {
+        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + mf * 4;
+    }
+};
+
+// One workgroup = 8 wavefronts sharing the LDS image of omega, S^T and z of one head; each wavefront
+// streams 32 query rows at a time.
+template <int D, bool ELU>
+__global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using L = QueryLds<D>;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int bh = blockIdx.x / a.wgs_per_head;
+    const int chunk = blockIdx.x % a.wgs_per_head;
+    const int mf = a.mf;
+    const int s_pitch = L::s_pitch(mf);
+    unsigned char* lw = lds;
+    unsigned char* ls = lds + (ELU ? 0 : L::w_bytes(mf));
+    float* lz = (float*)(ls + L::s_bytes(mf));
+
+    // fill the LDS image (16-byte chunks, coalesced)
+    if (!ELU) {
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
+        constexpr int cpr = D / 8;                      // chunks per row
+        for (int c = tid; c < mf * cpr; c += 512) {
+            const int r = c / cpr, q = c % cpr;
+            *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
+        }
+    }
+    {
+        const uint16_t* sg = a.St + (long)bh * D * mf;
+        const int cpr = mf / 8;
+        for (int c = tid; c < D * cpr; c += 512) {
+            const int r = c / cpr, q = c % cpr;
+            *(uint4*)(ls + r * s_pitch + 16 * q) = ld16(sg + (long)r * mf + 8 * q);
+        }
+        const float* zg = a.zp + (long)bh * mf;
+        for (int c = tid; c < mf; c += 512) lz[c] = zg[c];
+    }
+    __syncthreads();
+
+    const long head_off = (long)bh * a.n * D;
+    const int row_begin = chunk * a.rows_per_wg;
+    int row_end = row_begin + a.rows_per_wg;
+    if (row_end > a.n) row_end = a.n;
+    constexpr int KS = D / 16;      // reduction steps over d
+    constexpr int TT = D / 32;      // 32-row tiles of N^T
+    constexpr float LOG2E = 1.4426950408889634f;
+
+    for (int row0 = row_begin + 32 * wave; row0 < row_end; row0 += 32 * 8) {
+        // B operand of the first contraction: this lane's query row, 8 consecutive d per step
+        int qrow = row0 + l32;
+        const bool valid = qrow < a.n;
+        if (!valid) qrow = a.n - 1;
+        const uint16_t* qg = a.Q + head_off + (long)qrow * D + 8 * half;
+        uint4 qf[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s] = ld16(qg + 16 * s);
+
+        floatx16 accN[TT];
+#pragma unroll
+        for (int t = 0; t < TT; ++t) accN[t] = zero16();
+        float den = 0.f;
+
+        if (ELU) {
+            // P = elu(q)+1 straight in operand order; features are the d coordinates
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uint32_t w[4] = {qf[s].x, qf[s].y, qf[s].z, qf[s].w};
+                uint32_t pk[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x0 = bf16_to_f32((uint16_t)(w[e] & 0xffffu));
+                    const float x1 = bf16_to_f32((uint16_t)(w[e] >> 16));
+                    const float p0 = x0 > 0.f ? x0 + 1.f : __expf(x0);
+                    const float p1 = x1 > 0.f ? x1 + 1.f : __expf(x1);
+                    pk[e] = pack_bf16(p0, p1);
+                    const int f = 16 * s + 8 * half + 2 * e;
+                    den = fmaf(bf16_to_f32((uint16_t)(pk[e] & 0xffffu)), lz[f], den);
+                    den = fmaf(bf16_to_f32((uint16_t)(pk[e] >> 16)), lz[f + 1], den);
+                }
+                const uint4 pb = {pk[0], pk[1], pk[2], pk[3]};
+#pragma unroll
+                for (int t = 0; t < TT; ++t) {
+                    const uint4 sa = *(const uint4*)(ls + (32 * t + l32) * s_pitch + 32 * s + 16 * half);
+                    accN[t] = mfma32(sa, pb, accN[t]);
+                }
+            }
+        } else {
+            float mu = -INFINITY;     // running row maximum (same value in lanes l and l^32)
+            for (int ft = 0; ft < mf / 32; ++ft) {
+                floatx16 u = zero16();
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    const uint4 wa = *(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half);
+                    u = mfma32(wa, qf[s], u);
+                }
+                float tmax = u[0];
+#pragma unroll
+                for (int g = 1; g < 16; ++g) tmax = fmaxf(tmax, u[g]);
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                if (tmax > mu) {
+                    const float sc = exp2f((mu - tmax) * LOG2E);     // 0 on the first tile
+                    mu = tmax;
+                    den *= sc;
+#pragma unroll
+                    for (int t = 0; t < TT; ++t)
+#pragma unroll
+                        for (int g = 0; g < 16; ++g) accN[t][g] *= sc;
+                }
+                const float shift = mu * LOG2E;
+                const float* zt = lz + 32 * ft + 16 * half;
+                uint32_t pk[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float p0 = exp2f(fmaf(u[2 * e], LOG2E, -shift));
+                    const float p1 = exp2f(fmaf(u[2 * e + 1], LOG2E, -shift));
+                    pk[e] = pack_bf16(p0, p1);
+                    den = fmaf(bf16_to_f32((uint16_t)(pk[e] & 0xffffu)), zt[2 * e], den);
+                    den = fmaf(bf16_to_f32((uint16_t)(pk[e] >> 16)), zt[2 * e + 1], den);
+                }
+                const uint4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
+                const uint4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
+#pragma unroll
+                for (int t = 0; t < TT; ++t) {
+                    const unsigned char* sp = ls + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
+                    accN[t] = mfma32(*(const uint4*)sp, pb0, accN[t]);
+                    accN[t] = mfma32(*(const uint4*)(sp + 32), pb1, accN[t]);
+                }
+            }
+        }
+        den += __shfl_xor(den, 32, 64);
+        const float inv = 1.f / den;
+        if (valid) {
+            uint16_t* og = a.out + head_off + (long)qrow * D;
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 v;
+                    v.x = pack_bf16(accN[t][4 * q] * inv, accN[t][4 * q + 1] * inv);
+                    v.y = pack_bf16(accN[t][4 * q + 2] * inv, accN[t][4 * q + 3] * inv);
+                    *(uint2*)(og + 32 * t + 8 * q + 4 * half) = v;
+                }
+        }
+    }
+}
+
+// ===========================================================================
+// Host side
+// ===========================================================================
+static int query_lds_bytes(const Problem& p) {
+    return p.d == 64 ? QueryLds<64>::total(p.mf, p.elu) : QueryLds<128>::total(p.mf, p.elu);
+}
+
+bool fast_supported(const Problem& p, int bwd) {
+    if (bwd) return false;
+    if (!p.bf16) return false;
+    if (p.d != 64 && p.d != 128) return false;
+    if (p.n % PBK != 0) return false;
+    if (p.mf % 32 != 0) return false;
+    if (query_lds_bytes(p) > 160 * 1024) return false;
+    return true;
+}
 
 bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d, const void* e,
                       const void* f, const void* g) {
@@ -13,9 +435,106 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
     return true;
 }
 
-size_t fast_ws_bytes(const Problem&, int) { return 0; }
+struct FastWs {
+    size_t partial, St, zp, total;    // byte offsets
+    size_t split_stride;              // floats between the partial results of consecutive splits
+};
 
-flurka_status fast_forward(const Problem&, const FwdArgs&, hipStream_t) { return FLURKA_ERR_UNSUPPORTED; }
+static FastWs fast_ws_layout(const Problem& p) {
+    FastWs W{};
+    const CtxLayout L = ctx_layout(p);
+    const ProjPlan q = proj_plan(p);
+    size_t o = 0;
+    W.split_stride = L.PhiK;          // K' and V' segments of ctx, back to back
+    W.partial = o; o += round_up((q.splits > 1 ? (size_t)q.splits : 0) * W.split_stride * 4, 256);
+    W.St = o;      o += round_up((size_t)p.BH * p.d * p.mf * 2, 256);
+    W.zp = o;      o += round_up((size_t)p.BH * p.mf * 4, 256);
+    W.total = o;
+    return W;
+}
+
+size_t fast_ws_bytes(const Problem& p, int bwd) {
+    (void)bwd;
+    return fast_ws_layout(p).total;
+}
+
+template <int D, bool ELU>
+static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int grid, int ldsb, hipStream_t s) {
+    auto kern = query_stream_kernel<D, ELU>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
+        return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ldsb, s, qa);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
+}
+
+flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
+    const CtxLayout L = ctx_layout(p);
+    const FastWs W = fast_ws_layout(p);
+    unsigned char* wsb = (unsigned char*)a.ws;
+    flurka_status st;
+    {
+        StageScope sc(s, STAGE_PROJECT);
+        const ProjPlan q = proj_plan(p);
+        ProjArgs pa{};
+        pa.EF[0] = (const uint16_t*)a.E; pa.EF[1] = (const uint16_t*)a.F;
+        pa.X[0] = (const uint16_t*)a.K;  pa.X[1] = (const uint16_t*)a.V;
+        float* base = q.splits > 1 ? (float*)(wsb + W.partial) : a.ctx;
+        pa.out[0] = base + L.Kp;
+        pa.out[1] = base + L.Vp;
+        pa.split_stride = (long)W.split_stride;
+        pa.n = p.n; pa.d = p.d; pa.k = p.k; pa.BH = p.BH;
+        pa.tilesM = q.tilesM; pa.tilesN = q.tilesN; pa.splits = q.splits;
+        pa.steps_per_split = q.steps_per_split; pa.total_steps = q.total_steps;
+        if (hipFuncSetAttribute((const void*)proj_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                P_LDS) != hipSuccess)
+            return FLURKA_ERR_LAUNCH;
+        const int grid = q.tilesM * q.tilesN * 2 * q.splits;
+        hipLaunchKernelGGL(proj_mfma_kernel, dim3(grid), dim3(256), P_LDS, s, pa);
+        FLURKA_CHECK_LAUNCH();
+        if (q.splits > 1) {
+            const long count = (long)L.PhiK;      // K' and V' segments together
+            hipLaunchKernelGGL(sum_splits_kernel, grid1d((count + 3) / 4, 256), dim3(256), 0, s,
+                               a.ctx + L.Kp, (const float*)(wsb + W.partial), count, (long)W.split_stride,
+                               q.splits);
+            FLURKA_CHECK_LAUNCH();
+        }
+    }
+    {
+        StageScope sc(s, STAGE_KEY_STATE);
+        if ((st = generic_key_state(p, a.omega, a.ctx, s)) != FLURKA_OK) return st;
+        const long total = (long)p.BH * p.d * p.mf;
+        hipLaunchKernelGGL(pack_state_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.St),
+                           (float*)(wsb + W.zp), a.ctx + L.S, a.ctx + L.z, p.mf, p.d, p.elu ? 0 : 1, total);
+        FLURKA_CHECK_LAUNCH();
+    }
+    {
+        StageScope sc(s, STAGE_QUERY);
+        QueryArgs qa{};
+        qa.Q = (const uint16_t*)a.Q;
+        qa.omega = (const uint16_t*)a.omega;
+        qa.St = (const uint16_t*)(wsb + W.St);
+        qa.zp = (const float*)(wsb + W.zp);
+        qa.out = (uint16_t*)a.out;
+        qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
+        qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
+        // about two workgroups per compute unit, each a multiple of 256 rows (8 wavefronts x 32)
+        int wgs_per_head = (512 + p.BH - 1) / p.BH;
+        int rows = (p.n + wgs_per_head - 1) / wgs_per_head;
+        rows = (rows + 255) / 256 * 256;
+        wgs_per_head = (p.n + rows - 1) / rows;
+        qa.rows_per_wg = rows; qa.wgs_per_head = wgs_per_head;
+        const int grid = p.BH * wgs_per_head;
+        const int ldsb = query_lds_bytes(p);
+        if (p.d == 64)
+            st = p.elu ? launch_query<64, true>(p, qa, grid, ldsb, s) : launch_query<64, false>(p, qa, grid, ldsb, s);
+        else
+            st = p.elu ? launch_query<128, true>(p, qa, grid, ldsb, s) : launch_query<128, false>(p, qa, grid, ldsb, s);
+        if (st != FLURKA_OK) return st;
+    }
+    return FLURKA_OK;
+}
+
 flurka_status fast_backward(const Problem&, const BwdArgs&, hipStream_t) { return FLURKA_ERR_UNSUPPORTED; }
 
 }  // namespace flurka

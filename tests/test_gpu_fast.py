@@ -1,0 +1,76 @@
+"""GPU parity of the bf16 MFMA kernels (algo = fast) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flurka_oracle as fo
+from paper_2306_15799_amd import binding as fb
+from paper_2306_15799_amd import inputs
+from paper_2306_15799_amd.inputs import Workload, PHI_ELU1, PHI_PERFORMER
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+# (B, H, n, d, k, m): several 256-wide column tiles, ragged head count per tile, ragged k,
+# a sequence split over several workgroups, both head sizes
+FWD_SHAPES = [
+    (1, 3, 192, 64, 100, 96),
+    (2, 5, 1024, 64, 256, 256),
+    (1, 3, 640, 128, 300, 160),
+    (3, 2, 2048, 128, 512, 32),
+    (1, 1, 64, 64, 1, 32),
+]
+
+
+@pytest.mark.parametrize("shape", FWD_SHAPES)
+def test_forward_performer(shape):
+    B, H, n, d, k, m = shape
+    w = Workload("fast", B, H, n, d, k, m, "bf16", PHI_PERFORMER, False)
+    assert fb.fast_path_supported(B, H, n, d, k, m, fb.BF16, w.phi)
+    err = gu.check_forward(w, seed=7, algo="fast")
+    print(shape, f"rel-L2 {err:.3e}")
+
+
+@pytest.mark.parametrize("shape", [(1, 3, 192, 64, 100), (2, 4, 1024, 64, 256), (1, 2, 320, 128, 64)])
+def test_forward_elu(shape):
+    B, H, n, d, k = shape
+    w = Workload("fast", B, H, n, d, k, d, "bf16", PHI_ELU1, False)
+    err = gu.check_forward(w, seed=8, algo="fast")
+    print(shape, f"rel-L2 {err:.3e}")
+
+
+def test_fast_projection_matches_oracle_projection():
+    w = Workload("proj", 1, 6, 4096, 64, 256, 64, "bf16", PHI_PERFORMER, False)
+    t = inputs.make_inputs(w, 9)
+    _, _, ctx = gu.run_forward(w, t, "fast")
+    v = fb.ctx_views(ctx, w.B, w.H, w.n, w.d, w.k, w.m, fb.BF16, w.phi)
+    Kp = np.matmul(t["E"].astype(np.float64), t["K"].astype(np.float64))
+    Vp = np.matmul(t["F"].astype(np.float64), t["V"].astype(np.float64))
+    # bf16 x bf16 products are exact in fp32; only the fp32 summation order differs
+    assert fo.rel_l2(gu.to_host(v["Kp"]), Kp) < 2e-6
+    assert fo.rel_l2(gu.to_host(v["Vp"]), Vp) < 2e-6
+
+
+def test_shared_omega_and_determinism():
+    w = Workload("shared", 2, 3, 512, 64, 128, 64, "bf16", PHI_PERFORMER, False, omega_per_head=False)
+    t = inputs.make_inputs(w, 10)
+    _, out1, _ = gu.run_forward(w, t, "fast")
+    _, out2, _ = gu.run_forward(w, t, "fast")
+    assert torch.equal(out1, out2)
+    assert fo.rel_l2(gu.to_host(out1), gu.oracle_forward(w, t)) < 2e-2
+
+
+def test_unsupported_shapes_are_refused_not_miscomputed():
+    # n not a multiple of 64, head size other than 64/128, fp32 storage
+    assert not fb.fast_path_supported(1, 1, 100, 64, 8, 32, fb.BF16, "performer")
+    assert not fb.fast_path_supported(1, 1, 128, 48, 8, 32, fb.BF16, "performer")
+    assert not fb.fast_path_supported(1, 1, 128, 64, 8, 32, fb.F32, "performer")
+    w = Workload("odd", 1, 1, 100, 64, 8, 32, "bf16", PHI_PERFORMER, False)
+    t = inputs.make_inputs(w, 11)
+    g = gu.to_device(t, "bf16")
+    with pytest.raises(fb.FlurkaError) as e:
+        fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], algo="fast")
+    assert e.value.status == fb.ERR_UNSUPPORTED
+    # auto falls back to the generic kernels and still matches
+    assert gu.check_forward(w, seed=11, algo="auto") < 2e-2
