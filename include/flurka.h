@@ -26,8 +26,8 @@
  *                         omega is ignored (may be NULL).
  * The library applies no 1/sqrt(d) temperature, no mask, no dropout and adds
  * no epsilon to the denominator.  Exponents are shifted internally by one
- * constant per (batch, head) on the key side and one per query row on the
- * query side; both cancel exactly in the ratio.
+ * constant per (batch, head, feature) on the key side, put back on the query
+ * side, and by one constant per query row; all cancel exactly in the ratio.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The
@@ -88,19 +88,21 @@ FLURKA_API int flurka_version(void);
 FLURKA_API const char* flurka_status_str(flurka_status s);
 
 /* Bytes of the context buffer that carries the key-side state from the
- * forward to the backward pass: K', V' (B,H,k,d), phi(K') up to its shift
- * (B,H,k,mf), S = phi(K')^T V' (B,H,mf,d), z = phi(K')^T 1 (B,H,mf) and the
- * shift c (B,H); mf = m (performer) or d (elu1).  Returns 0 for an invalid
- * shape. */
+ * forward to the backward pass: K', V' (B,H,k,d), S = phi(K')^T V' (B,H,mf,d),
+ * z = phi(K')^T 1 (B,H,mf) and the exponent shifts c (B,H,mf); mf = m
+ * (performer) or d (elu1).  S and z are stored for phi(K') with column j
+ * scaled by exp(-c_j) (c_j = max_r of the key exponent, 0 for elu1); the same
+ * factor is put back on feature j of phi(Q), so the ratio is unchanged.
+ * Returns 0 for an invalid shape. */
 FLURKA_API size_t flurka_ctx_bytes(int B, int H, int n, int d, int k, int m,
                         flurka_dtype dtype, flurka_phi phi);
 
-/* Offsets, in float32 elements from the start of ctx, of its six segments in
- * the order K', V', phi(K'), S, z, c, written to the HOST array `offsets6`
+/* Offsets, in float32 elements from the start of ctx, of its five segments in
+ * the order K', V', S, z, c, written to the HOST array `offsets5`
  * (for inspection and tests).  Returns FLURKA_ERR_NULL / _SHAPE / _DTYPE on
  * bad arguments. */
 FLURKA_API flurka_status flurka_ctx_layout(int B, int H, int n, int d, int k, int m,
-                                flurka_dtype dtype, flurka_phi phi, size_t* offsets6);
+                                flurka_dtype dtype, flurka_phi phi, size_t* offsets5);
 
 /* Bytes of scratch the given pass needs for `algo` (AUTO = the maximum over
  * the paths AUTO may take).  Contents need not survive between calls.

@@ -114,16 +114,15 @@ def ctx_bytes(B, H, n, d, k, m, dtype, phi) -> int:
 
 
 def ctx_views(ctx: torch.Tensor, B, H, n, d, k, m, dtype, phi) -> dict:
-    """float32 views of the context buffer's segments (K', V', PhiK, S, z, c)."""
+    """float32 views of the context buffer's segments (K', V', S, z, c)."""
     lib = load_library()
-    offs = (ctypes.c_size_t * 6)()
+    offs = (ctypes.c_size_t * 5)()
     st = lib.flurka_ctx_layout(B, H, n, d, k, m, dtype, _PHI[phi], offs)
     if st != OK:
         raise FlurkaError(st, "flurka_ctx_layout")
     mf = d if _PHI[phi] == PHI_ELU1 else m
     f = ctx.view(torch.float32)
-    shapes = {"Kp": (B, H, k, d), "Vp": (B, H, k, d), "PhiK": (B, H, k, mf),
-              "S": (B, H, mf, d), "z": (B, H, mf), "c": (B, H)}
+    shapes = {"Kp": (B, H, k, d), "Vp": (B, H, k, d), "S": (B, H, mf, d), "z": (B, H, mf), "c": (B, H, mf)}
     views = {}
     for (name, shape), off in zip(shapes.items(), offs):
         cnt = 1

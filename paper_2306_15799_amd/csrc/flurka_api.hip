@@ -86,14 +86,13 @@ size_t flurka_ctx_bytes(int B, int H, int n, int d, int k, int m, flurka_dtype d
 }
 
 flurka_status flurka_ctx_layout(int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
-                                flurka_phi phi, size_t* offsets6) {
-    if (!offsets6) return FLURKA_ERR_NULL;
+                                flurka_phi phi, size_t* offsets5) {
+    if (!offsets5) return FLURKA_ERR_NULL;
     Problem p;
     flurka_status st = make_problem(B, H, n, d, k, m, 1, dtype, phi, &p);
     if (st != FLURKA_OK) return st;
     const CtxLayout L = ctx_layout(p);
-    offsets6[0] = L.Kp; offsets6[1] = L.Vp; offsets6[2] = L.PhiK;
-    offsets6[3] = L.S;  offsets6[4] = L.z;  offsets6[5] = L.c + round_up((size_t)p.BH, 64);
+    offsets5[0] = L.Kp; offsets5[1] = L.Vp; offsets5[2] = L.S; offsets5[3] = L.z; offsets5[4] = L.c;
     return FLURKA_OK;
 }
 

@@ -218,13 +218,13 @@ static ProjPlan proj_plan(const Problem& p) {
 // ===========================================================================
 // Repack S (mf x d fp32) and z (mf fp32) of every head for the query-stream kernel:
 //   St  (d x mf) bf16, St[t][slot] = S[feature(slot)][t]
-//   zp  (mf) fp32,     zp[32*ft + 16*h + g] = z[32*ft + 8*(g/4) + 4*h + g%4]
+//   zp  (mf) fp32,     zp[32*ft + 16*h + g] = z[32*ft + 8*(g/4) + 4*h + g%4]; cp likewise from c
 // For the performer map the feature order inside each group of 16 slots is the one in which the
 // accumulator of the first MFMA hands P^T to the second MFMA as its B operand:
 //   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4.
 // For elu1 P is built directly in operand order, so St keeps the natural order.
-__global__ void pack_state_kernel(uint16_t* St, float* zp, const float* S, const float* z, int mf, int d,
-                                  int permute, long total) {
+__global__ void pack_state_kernel(uint16_t* St, float* zp, float* cp, const float* S, const float* z,
+                                  const float* c, int mf, int d, int permute, long total) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const int slot = (int)(idx % mf);
@@ -242,6 +242,7 @@ __global__ void pack_state_kernel(uint16_t* St, float* zp, const float* S, const
         const int g = slot & 15, h = (slot >> 4) & 1;
         const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
         zp[bh * mf + slot] = permute ? z[bh * mf + fz] : z[bh * mf + slot];
+        cp[bh * mf + slot] = permute ? c[bh * mf + fz] : c[bh * mf + slot];
     }
 }
 
@@ -250,6 +251,7 @@ struct QueryArgs {
     const uint16_t* omega;     // (H|1, m, d)
     const uint16_t* St;        // (BH, d, mf) bf16
     const float* zp;           // (BH, mf)
+    const float* cp;           // (BH, mf) exponent shifts, same order as zp
     uint16_t* out;
     int n, H, mf, rows_per_wg, wgs_per_head;
     long omega_head_stride;    // 0 if shared
@@ -262,7 +264,7 @@ struct QueryLds {
     static __host__ __device__ int w_bytes(int mf) { return mf * w_pitch; }
     static __host__ __device__ int s_bytes(int mf) { return D * s_pitch(mf); }
     static __host__ __device__ int total(int mf, int elu) {
-        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + mf * 4;
+        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + mf * 8;
     }
 };
 
@@ -281,6 +283,7 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
     unsigned char* lw = lds;
     unsigned char* ls = lds + (ELU ? 0 : L::w_bytes(mf));
     float* lz = (float*)(ls + L::s_bytes(mf));
+    float* lc = lz + mf;
 
     // fill the LDS image (16-byte chunks, coalesced)
     if (!ELU) {
@@ -299,7 +302,8 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
             *(uint4*)(ls + r * s_pitch + 16 * q) = ld16(sg + (long)r * mf + 8 * q);
         }
         const float* zg = a.zp + (long)bh * mf;
-        for (int c = tid; c < mf; c += 512) lz[c] = zg[c];
+        const float* cg = a.cp + (long)bh * mf;
+        for (int c = tid; c < mf; c += 512) { lz[c] = zg[c]; lc[c] = cg[c]; }
     }
     __syncthreads();
 
@@ -359,6 +363,10 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
                     const uint4 wa = *(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half);
                     u = mfma32(wa, qf[s], u);
                 }
+                // put the key side's per-feature shift back: u_j + c_j is the true log-weight
+                const float* ct = lc + 32 * ft + 16 * half;
+#pragma unroll
+                for (int g = 0; g < 16; ++g) u[g] += ct[g];
                 float tmax = u[0];
 #pragma unroll
                 for (int g = 1; g < 16; ++g) tmax = fmaxf(tmax, u[g]);
@@ -436,7 +444,7 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 }
 
 struct FastWs {
-    size_t partial, St, zp, total;    // byte offsets
+    size_t partial, St, zp, cp, PhiK, total;    // byte offsets
     size_t split_stride;              // floats between the partial results of consecutive splits
 };
 
@@ -445,10 +453,12 @@ static FastWs fast_ws_layout(const Problem& p) {
     const CtxLayout L = ctx_layout(p);
     const ProjPlan q = proj_plan(p);
     size_t o = 0;
-    W.split_stride = L.PhiK;          // K' and V' segments of ctx, back to back
+    W.split_stride = L.S;             // K' and V' segments of ctx, back to back
     W.partial = o; o += round_up((q.splits > 1 ? (size_t)q.splits : 0) * W.split_stride * 4, 256);
     W.St = o;      o += round_up((size_t)p.BH * p.d * p.mf * 2, 256);
     W.zp = o;      o += round_up((size_t)p.BH * p.mf * 4, 256);
+    W.cp = o;      o += round_up((size_t)p.BH * p.mf * 4, 256);
+    W.PhiK = o;    o += round_up((size_t)p.BH * p.k * p.mf * 4, 256);
     W.total = o;
     return W;
 }
@@ -493,7 +503,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         hipLaunchKernelGGL(proj_mfma_kernel, dim3(grid), dim3(256), P_LDS, s, pa);
         FLURKA_CHECK_LAUNCH();
         if (q.splits > 1) {
-            const long count = (long)L.PhiK;      // K' and V' segments together
+            const long count = (long)L.S;         // K' and V' segments together
             hipLaunchKernelGGL(sum_splits_kernel, grid1d((count + 3) / 4, 256), dim3(256), 0, s,
                                a.ctx + L.Kp, (const float*)(wsb + W.partial), count, (long)W.split_stride,
                                q.splits);
@@ -502,10 +512,11 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     }
     {
         StageScope sc(s, STAGE_KEY_STATE);
-        if ((st = generic_key_state(p, a.omega, a.ctx, s)) != FLURKA_OK) return st;
+        if ((st = generic_key_state(p, a.omega, a.ctx, (float*)(wsb + W.PhiK), s)) != FLURKA_OK) return st;
         const long total = (long)p.BH * p.d * p.mf;
         hipLaunchKernelGGL(pack_state_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.St),
-                           (float*)(wsb + W.zp), a.ctx + L.S, a.ctx + L.z, p.mf, p.d, p.elu ? 0 : 1, total);
+                           (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S, a.ctx + L.z, a.ctx + L.c,
+                           p.mf, p.d, p.elu ? 0 : 1, total);
         FLURKA_CHECK_LAUNCH();
     }
     {
@@ -515,6 +526,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         qa.omega = (const uint16_t*)a.omega;
         qa.St = (const uint16_t*)(wsb + W.St);
         qa.zp = (const float*)(wsb + W.zp);
+        qa.cp = (const float*)(wsb + W.cp);
         qa.out = (uint16_t*)a.out;
         qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
         qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;

@@ -136,23 +136,8 @@ static flurka_status launch_gemm(GemmArgs g, int batches, hipStream_t s) {
 // ---------------------------------------------------------------------------
 // Row-wise kernels.  One 64-lane wavefront per row, four rows per block.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t float_to_ordered(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float ordered_to_float(uint32_t o) {
-    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
-}
-
-__global__ void fill_u32_kernel(uint32_t* p, uint32_t v, long count) {
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) p[i] = v;
-}
-
-// e_rj <- e_rj - |k'_r|^2 / 2 and the per-head maximum of the result.
-// rows = BH*k rows of length m in e, of length d in Kp.
-__global__ __launch_bounds__(256) void key_exponent_kernel(float* e, const float* Kp, uint32_t* cmax_ord,
-                                                           long rows, int k, int d, int m) {
+// e_rj <- e_rj - |k'_r|^2 / 2.   rows = BH*k rows of length m in e, of length d in Kp.
+__global__ __launch_bounds__(256) void key_exponent_kernel(float* e, const float* Kp, long rows, int d, int m) {
     const int lane = threadIdx.x & 63;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
@@ -161,27 +146,35 @@ __global__ __launch_bounds__(256) void key_exponent_kernel(float* e, const float
     for (int t = lane; t < d; t += 64) sq = fmaf(kr[t], kr[t], sq);
     sq = 0.5f * wave_sum(sq);
     float* er = e + row * m;
-    float mx = -INFINITY;
-    for (int j = lane; j < m; j += 64) {
-        const float v = er[j] - sq;
-        er[j] = v;
-        mx = fmaxf(mx, v);
-    }
-    mx = wave_max(mx);
-    if (lane == 0) atomicMax(cmax_ord + row / k, float_to_ordered(mx));
+    for (int j = lane; j < m; j += 64) er[j] -= sq;
 }
 
-// PhiK <- exp(e - c); also publishes c as a float.
-__global__ __launch_bounds__(256) void key_exp_kernel(float* e, const uint32_t* cmax_ord, float* c_out,
-                                                      long rows, int k, int m) {
+// c[bh, j] = max_r e[bh, r, j]: one exponent shift per feature (any positive rescaling of a
+// feature's column of phi(K') is undone by the same factor on that feature of phi(Q))
+__global__ void column_max_kernel(float* c, const float* e, int k, int m, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const long bh = idx / m;
+    const int j = (int)(idx % m);
+    const float* p = e + bh * (long)k * m + j;
+    float mx = -INFINITY;
+    for (int r = 0; r < k; ++r) mx = fmaxf(mx, p[(long)r * m]);
+    c[idx] = mx;
+}
+
+// PhiK <- exp(e - c_j)
+__global__ __launch_bounds__(256) void key_exp_kernel(float* e, const float* c, long rows, int k, int m) {
     const int lane = threadIdx.x & 63;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const long bh = row / k;
-    const float c = ordered_to_float(cmax_ord[bh]);
-    if (row % k == 0 && lane == 0) c_out[bh] = c;
+    const float* cc = c + (row / k) * m;
     float* er = e + row * m;
-    for (int j = lane; j < m; j += 64) er[j] = expf(er[j] - c);
+    for (int j = lane; j < m; j += 64) er[j] = expf(er[j] - cc[j]);
+}
+
+__global__ void fill_f32_kernel(float* p, float v, long count) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
 }
 
 __device__ __forceinline__ float elu1(float x) { return x > 0.f ? x + 1.f : expf(x); }
@@ -210,16 +203,17 @@ __global__ void column_sum_kernel(float* z, const float* Phi, int k, int m, long
     z[idx] = s;
 }
 
-// P[row, :] <- exp(U[row, :] - max_j U[row, j])
-__global__ __launch_bounds__(256) void row_exp_kernel(float* U, long rows, int m) {
+// P[row, :] <- exp(v - max_j v), v_j = U[row, j] + c[bh, j]   (rows = BH*nr)
+__global__ __launch_bounds__(256) void row_exp_kernel(float* U, const float* c, long rows, int nr, int m) {
     const int lane = threadIdx.x & 63;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     float* u = U + row * m;
+    const float* cc = c + (row / nr) * m;
     float mx = -INFINITY;
-    for (int j = lane; j < m; j += 64) mx = fmaxf(mx, u[j]);
+    for (int j = lane; j < m; j += 64) mx = fmaxf(mx, u[j] + cc[j]);
     mx = wave_max(mx);
-    for (int j = lane; j < m; j += 64) u[j] = expf(u[j] - mx);
+    for (int j = lane; j < m; j += 64) u[j] = expf(u[j] + cc[j] - mx);
 }
 
 // D = P.z ; out = N / D  (rows = BH*nr; output row = bh*n + row0 + i)
@@ -334,7 +328,7 @@ static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total
 // ---------------------------------------------------------------------------
 // P (B,H,nr,mf) <- shifted phi(Q[row0 : row0+nr]);  N (B,H,nr,d) <- P S
 static flurka_status query_features_and_numerator(const Problem& p, const void* Q, const void* omega,
-                                                  const float* S, float* P, float* N,
+                                                  const float* S, const float* c, float* P, float* N,
                                                   int row0, int nr, hipStream_t s) {
     const long rows = (long)p.BH * nr;
     if (!p.elu) {
@@ -348,7 +342,7 @@ static flurka_status query_features_and_numerator(const Problem& p, const void* 
         g.H = p.H; g.a_bf16 = p.bf16; g.b_bf16 = p.bf16;
         flurka_status st = launch_gemm(g, p.BH, s);
         if (st != FLURKA_OK) return st;
-        hipLaunchKernelGGL(row_exp_kernel, grid1d(rows, 4), dim3(256), 0, s, P, rows, p.m);
+        hipLaunchKernelGGL(row_exp_kernel, grid1d(rows, 4), dim3(256), 0, s, P, c, rows, nr, p.m);
         FLURKA_CHECK_LAUNCH();
     } else {
         const long total = rows * p.d;
@@ -378,16 +372,10 @@ static flurka_status project(const Problem& p, const void* E, const void* X, flo
     return launch_gemm(g, p.BH, s);
 }
 
-// PhiK, S, z, c from K', V' (all in ctx)
-flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, hipStream_t s) {
-    const CtxLayout L = ctx_layout(p);
-    float* Kp = ctx + L.Kp;
-    float* Vp = ctx + L.Vp;
-    float* Phi = ctx + L.PhiK;
-    float* S = ctx + L.S;
-    float* z = ctx + L.z;
-    uint32_t* c_ord = (uint32_t*)(ctx + L.c);
-    float* c = ctx + L.c + round_up((size_t)p.BH, 64);
+// PhiK (k x mf, shifted) from K' in ctx.  With `new_shift` the per-feature shifts c are computed
+// and stored; otherwise the stored ones are reused (backward: same PhiK as the forward had).
+static flurka_status key_features(const Problem& p, const void* omega, const float* Kp, float* c,
+                                  float* Phi, int new_shift, hipStream_t s) {
     const long krows = (long)p.BH * p.k;
     if (!p.elu) {
         GemmArgs g{};
@@ -399,21 +387,39 @@ flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx,
         g.H = p.H; g.b_bf16 = p.bf16;
         flurka_status st = launch_gemm(g, p.BH, s);
         if (st != FLURKA_OK) return st;
-        hipLaunchKernelGGL(fill_u32_kernel, grid1d(p.BH, 256), dim3(256), 0, s, c_ord, 0u, (long)p.BH);
+        hipLaunchKernelGGL(key_exponent_kernel, grid1d(krows, 4), dim3(256), 0, s, Phi, Kp, krows, p.d, p.m);
         FLURKA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(key_exponent_kernel, grid1d(krows, 4), dim3(256), 0, s, Phi, Kp, c_ord, krows,
-                           p.k, p.d, p.m);
-        FLURKA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(key_exp_kernel, grid1d(krows, 4), dim3(256), 0, s, Phi, c_ord, c, krows, p.k, p.m);
+        if (new_shift) {
+            const long ct = (long)p.BH * p.m;
+            hipLaunchKernelGGL(column_max_kernel, grid1d(ct, 256), dim3(256), 0, s, c, (const float*)Phi, p.k,
+                               p.m, ct);
+            FLURKA_CHECK_LAUNCH();
+        }
+        hipLaunchKernelGGL(key_exp_kernel, grid1d(krows, 4), dim3(256), 0, s, Phi, (const float*)c, krows,
+                           p.k, p.m);
         FLURKA_CHECK_LAUNCH();
     } else {
         const long total = krows * p.d;
         hipLaunchKernelGGL(elu1_rows_kernel, grid1d(total, 256), dim3(256), 0, s, Phi, (const void*)Kp, 0,
                            total, p.k, p.d, (long)p.k, 0);
         FLURKA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(fill_u32_kernel, grid1d(p.BH, 256), dim3(256), 0, s, (uint32_t*)c, 0u, (long)p.BH);
-        FLURKA_CHECK_LAUNCH();
+        if (new_shift) {
+            const long ct = (long)p.BH * p.d;
+            hipLaunchKernelGGL(fill_f32_kernel, grid1d(ct, 256), dim3(256), 0, s, c, 0.f, ct);
+            FLURKA_CHECK_LAUNCH();
+        }
     }
+    return FLURKA_OK;
+}
+
+// PhiK, S, z, c from K', V' (in ctx)
+flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, float* Phi, hipStream_t s) {
+    const CtxLayout L = ctx_layout(p);
+    float* Vp = ctx + L.Vp;
+    float* S = ctx + L.S;
+    float* z = ctx + L.z;
+    flurka_status st = key_features(p, omega, ctx + L.Kp, ctx + L.c, Phi, 1, s);
+    if (st != FLURKA_OK) return st;
     // S = PhiK^T V'
     GemmArgs g{};
     g.A = Phi; g.B = Vp; g.C = S;
@@ -422,10 +428,10 @@ flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx,
     g.sBn = 1; g.sBki = p.d; g.sBb = (long)p.H * p.k * p.d; g.sBh = (long)p.k * p.d;
     g.sCm = p.d; g.sCn = 1; g.sCb = (long)p.H * p.mf * p.d; g.sCh = (long)p.mf * p.d;
     g.H = p.H;
-    flurka_status st = launch_gemm(g, p.BH, s);
+    st = launch_gemm(g, p.BH, s);
     if (st != FLURKA_OK) return st;
     const long zt = (long)p.BH * p.mf;
-    hipLaunchKernelGGL(column_sum_kernel, grid1d(zt, 256), dim3(256), 0, s, z, Phi, p.k, p.mf, zt);
+    hipLaunchKernelGGL(column_sum_kernel, grid1d(zt, 256), dim3(256), 0, s, z, (const float*)Phi, p.k, p.mf, zt);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
 }
@@ -444,7 +450,7 @@ flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s)
     }
     {
         StageScope sc(s, STAGE_KEY_STATE);
-        if ((st = generic_key_state(p, a.omega, a.ctx, s)) != FLURKA_OK) return st;
+        if ((st = generic_key_state(p, a.omega, a.ctx, a.ws + W.PhiK, s)) != FLURKA_OK) return st;
     }
     const int nc = generic_chunk_rows(p);
     float* P = a.ws + W.P;
@@ -452,7 +458,7 @@ flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s)
     StageScope sc(s, STAGE_QUERY);
     for (int row0 = 0; row0 < p.n; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
-        st = query_features_and_numerator(p, a.Q, a.omega, a.ctx + L.S, P, N, row0, nr, s);
+        st = query_features_and_numerator(p, a.Q, a.omega, a.ctx + L.S, a.ctx + L.c, P, N, row0, nr, s);
         if (st != FLURKA_OK) return st;
         const long rows = (long)p.BH * nr;
         hipLaunchKernelGGL(fwd_finish_kernel, grid1d(rows, 4), dim3(256), 0, s, P, N, a.ctx + L.z, a.out,
@@ -476,8 +482,9 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
     const GenericWs W = generic_ws_layout(p, 1);
     const float* Kp = a.ctx + L.Kp;
     const float* Vp = a.ctx + L.Vp;
-    const float* Phi = a.ctx + L.PhiK;
+    float* Phi = a.ws + W.PhiK;
     const float* S = a.ctx + L.S;
+    const float* cshift = a.ctx + L.c;
     const float* z = a.ctx + L.z;
     float* P = a.ws + W.P;
     float* T = a.ws + W.T;
@@ -497,7 +504,7 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
     for (int row0 = 0; row0 < p.n; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
         const long rows = (long)p.BH * nr;
-        st = query_features_and_numerator(p, a.Q, a.omega, S, P, N, row0, nr, s);
+        st = query_features_and_numerator(p, a.Q, a.omega, S, cshift, P, N, row0, nr, s);
         if (st != FLURKA_OK) return st;
         hipLaunchKernelGGL(bwd_row_prep_kernel, grid1d(rows, 4), dim3(256), 0, s, P, N, z, a.dOut, p.bf16,
                            dD, rows, nr, p.n, row0, p.mf, p.d);
@@ -556,6 +563,8 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
 
     stage_begin(s);
     const long krows = (long)p.BH * p.k;
+    // PhiK exactly as the forward had it (same K', same shifts)
+    if ((st = key_features(p, a.omega, Kp, const_cast<float*>(cshift), Phi, 0, s)) != FLURKA_OK) return st;
     {   // dPhiK = V' dS^T   (k x mf)
         GemmArgs g{};
         g.A = Vp; g.B = dS; g.C = dPhi;

@@ -25,7 +25,7 @@ static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // Context buffer (float32): state carried from forward to backward.
 // Every segment starts on a 256-byte boundary.
 struct CtxLayout {
-    size_t Kp, Vp, PhiK, S, z, c, total;   // offsets / total in floats
+    size_t Kp, Vp, S, z, c, total;   // offsets / total in floats
 };
 
 static inline CtxLayout ctx_layout(const Problem& p) {
@@ -34,10 +34,9 @@ static inline CtxLayout ctx_layout(const Problem& p) {
     const size_t BH = (size_t)p.BH;
     L.Kp = o;   o += round_up(BH * p.k * p.d, 64);
     L.Vp = o;   o += round_up(BH * p.k * p.d, 64);
-    L.PhiK = o; o += round_up(BH * p.k * p.mf, 64);
     L.S = o;    o += round_up(BH * p.mf * p.d, 64);
     L.z = o;    o += round_up(BH * p.mf, 64);
-    L.c = o;    o += 2 * round_up(BH, 64);   // order-preserving integer image of c, then c itself
+    L.c = o;    o += round_up(BH * p.mf, 64);   // exponent shift per (batch, head, feature)
     L.total = o;
     return L;
 }
@@ -55,7 +54,7 @@ static inline int generic_chunk_rows(const Problem& p) {
 }
 
 struct GenericWs {
-    size_t P, T, N, dD, dS, dz, dPhiK, dKp, dVp, rs, total;   // floats
+    size_t P, T, N, PhiK, dD, dS, dz, dPhiK, dKp, dVp, rs, total;   // floats
 };
 
 static inline GenericWs generic_ws_layout(const Problem& p, int bwd) {
@@ -65,6 +64,7 @@ static inline GenericWs generic_ws_layout(const Problem& p, int bwd) {
     size_t o = 0;
     W.P = o; o += round_up(BH * nc * p.mf, 64);
     W.N = o; o += round_up(BH * nc * p.d, 64);
+    W.PhiK = o; o += round_up(BH * p.k * p.mf, 64);
     if (bwd) {
         W.T = o;     o += round_up(BH * nc * p.mf, 64);
         W.dD = o;    o += round_up(BH * nc, 64);
@@ -127,8 +127,8 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 size_t fast_ws_bytes(const Problem& p, int bwd);
 flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
 flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s);
-// Key-side state from K', V' already in ctx (used by both paths).
-flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, hipStream_t s);
+// Key-side state from K', V' already in ctx: PhiK (scratch, BH*k*mf floats), S, z and the shifts c.
+flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, float* PhiK, hipStream_t s);
 
 // ---- device helpers --------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
