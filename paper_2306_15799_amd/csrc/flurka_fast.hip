@@ -10,7 +10,7 @@
 //                                               bf16 P^T kept in registers as the B operand of
 //                                               N^T = S^T P^T (MFMA); the denominator on the VALU
 // Formulas: Eq. 2 with the App. D row normaliser; feature maps of Sec. 2, "Kernel Methods".
-#include "flurka_mfma.h"
+#include "flurka_fast.h"
 
 namespace flurka {
 
@@ -173,26 +173,6 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(ProjArgs a) {
     }
 }
 
-// dst[i] = sum_s src[s * stride + i]
-__global__ void sum_splits_kernel(float* dst, const float* src, long count, long stride, int splits) {
-    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= count) return;
-    if (i + 3 < count) {
-        float4 acc = *(const float4*)(src + i);
-        for (int s = 1; s < splits; ++s) {
-            const float4 v = *(const float4*)(src + (long)s * stride + i);
-            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-        }
-        *(float4*)(dst + i) = acc;
-    } else {
-        for (long j = i; j < count; ++j) {
-            float acc = src[j];
-            for (int s = 1; s < splits; ++s) acc += src[(long)s * stride + j];
-            dst[j] = acc;
-        }
-    }
-}
-
 struct ProjPlan {
     int tilesM, tilesN, splits, steps_per_split, total_steps;
 };
@@ -216,36 +196,6 @@ static ProjPlan proj_plan(const Problem& p) {
 // ===========================================================================
 // Stage "query_stream"
 // ===========================================================================
-// Repack S (mf x d fp32) and z (mf fp32) of every head for the query-stream kernel:
-//   St  (d x mf) bf16, St[t][slot] = S[feature(slot)][t]
-//   zp  (mf) fp32,     zp[32*ft + 16*h + g] = z[32*ft + 8*(g/4) + 4*h + g%4]; cp likewise from c
-// For the performer map the feature order inside each group of 16 slots is the one in which the
-// accumulator of the first MFMA hands P^T to the second MFMA as its B operand:
-//   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4.
-// For elu1 P is built directly in operand order, so St keeps the natural order.
-__global__ void pack_state_kernel(uint16_t* St, float* zp, float* cp, const float* S, const float* z,
-                                  const float* c, int mf, int d, int permute, long total) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int slot = (int)(idx % mf);
-    const long rest = idx / mf;
-    const int t = (int)(rest % d);
-    const long bh = rest / d;
-    int f = slot;
-    if (permute) {
-        const int e = slot & 7, h = (slot >> 3) & 1;
-        f = (slot & ~15) + 8 * (e >> 2) + 4 * h + (e & 3);
-    }
-    St[idx] = f32_to_bf16(S[(bh * mf + f) * d + t]);
-    if (t == 0) {
-        // z in accumulator order of a 32-feature tile
-        const int g = slot & 15, h = (slot >> 4) & 1;
-        const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
-        zp[bh * mf + slot] = permute ? z[bh * mf + fz] : z[bh * mf + slot];
-        cp[bh * mf + slot] = permute ? c[bh * mf + fz] : c[bh * mf + slot];
-    }
-}
-
 struct QueryArgs {
     const uint16_t* Q;
     const uint16_t* omega;     // (H|1, m, d)
@@ -432,6 +382,7 @@ bool fast_supported(const Problem& p, int bwd) {
     if (p.n % PBK != 0) return false;
     if (p.mf % 32 != 0) return false;
     if (query_lds_bytes(p) > 160 * 1024) return false;
+    if (p.elu == 0 && p.m > FLURKA_MAX_FEATURE_DIM) return false;
     return true;
 }
 
@@ -444,7 +395,7 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 }
 
 struct FastWs {
-    size_t partial, St, zp, cp, PhiK, total;    // byte offsets
+    size_t partial, Kimg, Vimg, nrm, Spart, zpart, cpart, St, zp, cp, total;    // byte offsets
     size_t split_stride;              // floats between the partial results of consecutive splits
 };
 
@@ -452,13 +403,20 @@ static FastWs fast_ws_layout(const Problem& p) {
     FastWs W{};
     const CtxLayout L = ctx_layout(p);
     const ProjPlan q = proj_plan(p);
+    const KeyStatePlan ks = key_state_plan(p);
+    const size_t BH = (size_t)p.BH;
     size_t o = 0;
     W.split_stride = L.S;             // K' and V' segments of ctx, back to back
     W.partial = o; o += round_up((q.splits > 1 ? (size_t)q.splits : 0) * W.split_stride * 4, 256);
-    W.St = o;      o += round_up((size_t)p.BH * p.d * p.mf * 2, 256);
-    W.zp = o;      o += round_up((size_t)p.BH * p.mf * 4, 256);
-    W.cp = o;      o += round_up((size_t)p.BH * p.mf * 4, 256);
-    W.PhiK = o;    o += round_up((size_t)p.BH * p.k * p.mf * 4, 256);
+    W.Kimg = o;    o += round_up(p.elu ? 0 : 3 * BH * ks.kpad * p.d * 2, 256);
+    W.Vimg = o;    o += round_up(2 * BH * (ks.kpad / 2) * p.d * 4, 256);
+    W.nrm = o;     o += round_up(BH * ks.kpad * 4, 256);
+    W.Spart = o;   o += round_up(BH * ks.KR * p.mf * p.d * 4, 256);
+    W.zpart = o;   o += round_up(BH * ks.KR * p.mf * 4, 256);
+    W.cpart = o;   o += round_up(BH * ks.KR * p.mf * 4, 256);
+    W.St = o;      o += round_up(BH * p.d * p.mf * 2, 256);
+    W.zp = o;      o += round_up(BH * p.mf * 4, 256);
+    W.cp = o;      o += round_up(BH * p.mf * 4, 256);
     W.total = o;
     return W;
 }
@@ -483,6 +441,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     const FastWs W = fast_ws_layout(p);
     unsigned char* wsb = (unsigned char*)a.ws;
     flurka_status st;
+    int proj_splits = 1;
     {
         StageScope sc(s, STAGE_PROJECT);
         const ProjPlan q = proj_plan(p);
@@ -502,22 +461,17 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         const int grid = q.tilesM * q.tilesN * 2 * q.splits;
         hipLaunchKernelGGL(proj_mfma_kernel, dim3(grid), dim3(256), P_LDS, s, pa);
         FLURKA_CHECK_LAUNCH();
-        if (q.splits > 1) {
-            const long count = (long)L.S;         // K' and V' segments together
-            hipLaunchKernelGGL(sum_splits_kernel, grid1d((count + 3) / 4, 256), dim3(256), 0, s,
-                               a.ctx + L.Kp, (const float*)(wsb + W.partial), count, (long)W.split_stride,
-                               q.splits);
-            FLURKA_CHECK_LAUNCH();
-        }
+        proj_splits = q.splits;
     }
     {
         StageScope sc(s, STAGE_KEY_STATE);
-        if ((st = generic_key_state(p, a.omega, a.ctx, (float*)(wsb + W.PhiK), s)) != FLURKA_OK) return st;
-        const long total = (long)p.BH * p.d * p.mf;
-        hipLaunchKernelGGL(pack_state_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.St),
-                           (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S, a.ctx + L.z, a.ctx + L.c,
-                           p.mf, p.d, p.elu ? 0 : 1, total);
-        FLURKA_CHECK_LAUNCH();
+        KeyStateBuffers kb{};
+        kb.Kimg = (uint16_t*)(wsb + W.Kimg); kb.Vimg = (uint32_t*)(wsb + W.Vimg); kb.nrm = (float*)(wsb + W.nrm);
+        kb.Spart = (float*)(wsb + W.Spart); kb.zpart = (float*)(wsb + W.zpart); kb.cpart = (float*)(wsb + W.cpart);
+        kb.St = (uint16_t*)(wsb + W.St); kb.zp = (float*)(wsb + W.zp); kb.cp = (float*)(wsb + W.cp);
+        const float* partials = proj_splits > 1 ? (const float*)(wsb + W.partial) : a.ctx;
+        st = fast_key_state(p, a.omega, a.ctx, partials, (long)W.split_stride, proj_splits, kb, s);
+        if (st != FLURKA_OK) return st;
     }
     {
         StageScope sc(s, STAGE_QUERY);

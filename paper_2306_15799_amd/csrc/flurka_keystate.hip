@@ -1,0 +1,379 @@
+// Key-side state of FLuRKA attention on MFMA (gfx950):  S = PhiK^T V',  z = PhiK^T 1,  c.
+//
+// PhiK_rj = exp(e_rj - c_j),  e_rj = omega_j . k'_r - |k'_r|^2 / 2  (positive random features, Sec. 2
+// "Kernel Methods"), or PhiK = elu(K') + 1.  exp() turns an absolute error of e into a relative error
+// of the attention weights, and |e| reaches several hundred for long sequences, so e is formed to
+// fp32 accuracy: K' (fp32) is split into three bf16 terms whose products with the bf16 omega are
+// exact in the fp32 accumulator.  PhiK and V' enter the second contraction as two-term bf16 splits.
+//
+// Three kernels:
+//   proj_finish   sums the projection's split-n partials into K', V' (fp32, ctx) and writes the
+//                 operand images: K' as bf16 hi/mid/lo rows, V' as bf16 hi/lo with two consecutive
+//                 keys per dword, and |k'|^2 / 2 per key
+//   key_state     one wavefront per (head, 32 features, key range): first contraction on MFMA, column
+//                 maximum, exp, second contraction on MFMA with PhiK taken from the accumulator
+//                 registers as the A operand; writes per-range partial S, z, c
+//   merge_pack    joins the key ranges (log-sum-exp style), writes S, z, c (fp32, ctx) and the bf16
+//                 images the query-stream kernel loads into LDS
+#include "flurka_fast.h"
+
+namespace flurka {
+
+#define FLURKA_CHECK_LAUNCH()                                   \
+    do {                                                        \
+        if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH; \
+    } while (0)
+
+static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total + block - 1) / block)); }
+
+// x = hi + mid + lo with each term a bf16 (24 mantissa bits in total)
+__device__ __forceinline__ void split3(float x, uint16_t& hi, uint16_t& mid, uint16_t& lo) {
+    hi = f32_to_bf16(x);
+    const float r1 = x - bf16_to_f32(hi);
+    mid = f32_to_bf16(r1);
+    lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+}
+__device__ __forceinline__ void split2(float x, uint16_t& hi, uint16_t& lo) {
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+
+// ---------------------------------------------------------------------------
+// proj_finish: one wavefront per pair of keys (2p, 2p+1) of one head.
+// ---------------------------------------------------------------------------
+struct FinishArgs {
+    const float* part;      // split 0 of [K' segment | V' segment]; split s at + s * split_stride
+    float* ctx;             // K' at ctx + Kp_off, V' at ctx + Vp_off
+    long split_stride, Kp_off, Vp_off;
+    uint16_t* Kimg;         // 3 x (BH, kpad, d) bf16: hi, mid, lo      (nullptr for elu1)
+    uint32_t* Vimg;         // 2 x (BH, kpad/2, d) dwords: hi, lo; low half = even key
+    float* nrm;             // (BH, kpad): |k'|^2/2, +inf for the padding keys (nullptr for elu1)
+    int splits, k, kpad, d, BH;
+};
+
+__global__ __launch_bounds__(256) void proj_finish_kernel(FinishArgs a) {
+    const int lane = threadIdx.x & 63;
+    const long pair = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int pairs_per_head = a.kpad / 2;
+    if (pair >= (long)a.BH * pairs_per_head) return;
+    const int bh = (int)(pair / pairs_per_head);
+    const int p = (int)(pair % pairs_per_head);
+    const long img_plane = (long)a.BH * a.kpad * a.d;          // elements per K image plane
+    const long vimg_plane = (long)a.BH * pairs_per_head * a.d;
+    float sq[2] = {0.f, 0.f};
+    for (int t = lane; t < a.d; t += 64) {
+        float kv[2] = {0.f, 0.f}, vv[2] = {0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int r = 2 * p + e;
+            if (r < a.k) {
+                const long off = ((long)bh * a.k + r) * a.d + t;
+                float ks = 0.f, vs = 0.f;
+                for (int s = 0; s < a.splits; ++s) {
+                    ks += a.part[(long)s * a.split_stride + a.Kp_off + off];
+                    vs += a.part[(long)s * a.split_stride + a.Vp_off + off];
+                }
+                a.ctx[a.Kp_off + off] = ks;
+                a.ctx[a.Vp_off + off] = vs;
+                kv[e] = ks; vv[e] = vs;
+                sq[e] = fmaf(ks, ks, sq[e]);
+            }
+            if (a.Kimg) {
+                uint16_t hi, mid, lo;
+                split3(kv[e], hi, mid, lo);
+                const long io = ((long)bh * a.kpad + r) * a.d + t;
+                a.Kimg[io] = hi;
+                a.Kimg[img_plane + io] = mid;
+                a.Kimg[2 * img_plane + io] = lo;
+            }
+        }
+        uint16_t h0, l0, h1, l1;
+        split2(vv[0], h0, l0);
+        split2(vv[1], h1, l1);
+        const long vo = ((long)bh * pairs_per_head + p) * a.d + t;
+        a.Vimg[vo] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        a.Vimg[vimg_plane + vo] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+    if (a.nrm) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const float tot = wave_sum(sq[e]);
+            const int r = 2 * p + e;
+            if (lane == 0) a.nrm[(long)bh * a.kpad + r] = r < a.k ? 0.5f * tot : INFINITY;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// key_state: one wavefront per (head, feature tile, key range)
+// ---------------------------------------------------------------------------
+struct KeyStateArgs {
+    const uint16_t* Kimg;   // performer
+    const float* Kp;        // elu1: K' fp32 (BH, k, d)
+    const uint32_t* Vimg;
+    const float* nrm;
+    const uint16_t* omega;
+    float* Spart;           // (BH, KR, mf, d)
+    float* zpart;           // (BH, KR, mf)
+    float* cpart;           // (BH, KR, mf)
+    long omega_head_stride;
+    int BH, H, k, kpad, mf, FT, KR, tiles_per_range;
+};
+
+template <int D, bool ELU>
+__global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
+    constexpr int KS = D / 16, TT = D / 32;
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= (long)a.BH * a.FT * a.KR) return;
+    const int kr = (int)(wid % a.KR); wid /= a.KR;
+    const int ft = (int)(wid % a.FT);
+    const int bh = (int)(wid / a.FT);
+    const int KT = a.kpad / 32;
+    const int kt0 = kr * a.tiles_per_range;
+    int kt1 = kt0 + a.tiles_per_range;
+    if (kt1 > KT) kt1 = KT;
+    const long plane = (long)a.BH * a.kpad * D;
+    const long vplane = (long)a.BH * (a.kpad / 2) * D;
+    const uint32_t* vimg = a.Vimg + (long)bh * (a.kpad / 2) * D;
+
+    // B operand of the first contraction: omega rows of this feature tile
+    uint4 wf[KS];
+    if (!ELU) {
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ft + l32) * D + 8 * half;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
+    }
+
+    // exponents (performer) or features (elu1) of one 32-key tile: lane = feature 32*ft + l32,
+    // element g = key 32*kt + 8*(g/4) + 4*half + g%4
+    auto tile_values = [&](int kt) -> floatx16 {
+        floatx16 e = zero16();
+        if (!ELU) {
+            const uint16_t* kg = a.Kimg + ((long)bh * a.kpad + 32 * kt + l32) * D + 8 * half;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                e = mfma32(ld16(kg + 16 * s), wf[s], e);
+                e = mfma32(ld16(kg + plane + 16 * s), wf[s], e);
+                e = mfma32(ld16(kg + 2 * plane + 16 * s), wf[s], e);
+            }
+            const float* ng = a.nrm + (long)bh * a.kpad + 32 * kt + 4 * half;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 nq = *(const float4*)(ng + 8 * q);
+                e[4 * q] -= nq.x; e[4 * q + 1] -= nq.y; e[4 * q + 2] -= nq.z; e[4 * q + 3] -= nq.w;
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                const int r = 32 * kt + 8 * (g >> 2) + 4 * half + (g & 3);
+                float v = 0.f;                                    // padding keys contribute nothing
+                if (r < a.k) {
+                    const float x = a.Kp[((long)bh * a.k + r) * D + 32 * ft + l32];
+                    v = x > 0.f ? x + 1.f : __expf(x);
+                }
+                e[g] = v;
+            }
+        }
+        return e;
+    };
+
+    float c = 0.f;
+    if (!ELU) {
+        c = -INFINITY;
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const floatx16 e = tile_values(kt);
+#pragma unroll
+            for (int g = 0; g < 16; ++g) c = fmaxf(c, e[g]);
+        }
+        c = fmaxf(c, __shfl_xor(c, 32, 64));
+    }
+
+    floatx16 accS[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) accS[t] = zero16();
+    float zsum = 0.f;
+    constexpr float LOG2E = 1.4426950408889634f;
+    for (int kt = kt0; kt < kt1; ++kt) {
+        floatx16 e = tile_values(kt);
+        uint32_t hi[8], lo[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float p0 = e[2 * q], p1 = e[2 * q + 1];
+            if (!ELU) {
+                p0 = exp2f((p0 - c) * LOG2E);
+                p1 = exp2f((p1 - c) * LOG2E);
+            }
+            zsum += p0 + p1;
+            uint16_t h0, l0, h1, l1;
+            split2(p0, h0, l0);
+            split2(p1, h1, l1);
+            hi[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            lo[q] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        // PhiK^T tile as A operand: row = this lane's feature, reduction slots = keys in accumulator order
+        const uint4 ah[2] = {{hi[0], hi[1], hi[2], hi[3]}, {hi[4], hi[5], hi[6], hi[7]}};
+        const uint4 al[2] = {{lo[0], lo[1], lo[2], lo[3]}, {lo[4], lo[5], lo[6], lo[7]}};
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            // B operand: V' columns 32*tt + l32, key pairs in the matching order
+            const uint32_t* vb = vimg + (long)(16 * kt + 8 * sp + 2 * half) * D + l32;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                uint4 bh4, bl4;
+                bh4.x = vb[32 * tt];                 bl4.x = vb[vplane + 32 * tt];
+                bh4.y = vb[32 * tt + D];             bl4.y = vb[vplane + 32 * tt + D];
+                bh4.z = vb[32 * tt + 4 * D];         bl4.z = vb[vplane + 32 * tt + 4 * D];
+                bh4.w = vb[32 * tt + 5 * D];         bl4.w = vb[vplane + 32 * tt + 5 * D];
+                accS[tt] = mfma32(ah[sp], bh4, accS[tt]);
+                accS[tt] = mfma32(al[sp], bh4, accS[tt]);
+                accS[tt] = mfma32(ah[sp], bl4, accS[tt]);
+            }
+        }
+    }
+    zsum += __shfl_xor(zsum, 32, 64);
+
+    const long po = ((long)bh * a.KR + kr) * a.mf;
+    if (half == 0) {
+        a.zpart[po + 32 * ft + l32] = zsum;
+        a.cpart[po + 32 * ft + l32] = c;
+    }
+    float* sp = a.Spart + po * D;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            const int f = 32 * ft + 8 * (g >> 2) + 4 * half + (g & 3);
+            sp[(long)f * D + 32 * tt + l32] = accS[tt][g];
+        }
+}
+
+// ---------------------------------------------------------------------------
+// merge_pack: one workgroup per (head, 32 features).
+//   c_j = max_r c_jr,  S_j = sum_r exp(c_jr - c_j) S_jr,  z_j likewise
+//   St (d x mf) bf16: St[t][slot] = S[feature(slot)][t];  zp, cp: z, c in accumulator order of a tile
+// The slot -> feature order inside each group of 16 is the order in which the first MFMA of the
+// query-stream kernel hands P^T on as the B operand of the second:
+//   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4          (natural order for elu1)
+// ---------------------------------------------------------------------------
+struct MergeArgs {
+    const float* Spart; const float* zpart; const float* cpart;
+    float* S; float* z; float* c;        // ctx
+    uint16_t* St; float* zp; float* cp;  // images for the query stream
+    int KR, mf, d, permute;
+};
+
+__global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
+    __shared__ float w[16][32];          // weights exp(c_jr - c_j), up to 16 ranges
+    __shared__ float tile[32][129];      // merged S tile, padded
+    const int FT = a.mf / 32;
+    const int bh = blockIdx.x / FT, ft = blockIdx.x % FT;
+    const int tid = threadIdx.x;
+    const long pbase = (long)bh * a.KR * a.mf;
+    if (tid < 32) {
+        const int f = 32 * ft + tid;
+        float cm = -INFINITY;
+        for (int r = 0; r < a.KR; ++r) cm = fmaxf(cm, a.cpart[pbase + (long)r * a.mf + f]);
+        float zs = 0.f;
+        for (int r = 0; r < a.KR; ++r) {
+            const float wr = a.permute ? expf(a.cpart[pbase + (long)r * a.mf + f] - cm) : 1.f;
+            w[r][tid] = wr;
+            zs = fmaf(wr, a.zpart[pbase + (long)r * a.mf + f], zs);
+        }
+        a.z[(long)bh * a.mf + f] = zs;
+        a.c[(long)bh * a.mf + f] = cm;
+        // accumulator order of a 32-feature tile: position 16*h + g <-> feature 8*(g/4) + 4*h + g%4
+        int pos = tid;
+        if (a.permute) {
+            const int q = tid >> 3, h = (tid >> 2) & 1, e = tid & 3;
+            pos = 16 * h + 4 * q + e;
+        }
+        a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
+        a.cp[(long)bh * a.mf + 32 * ft + pos] = cm;
+    }
+    __syncthreads();
+    for (int i = tid; i < 32 * a.d; i += 256) {
+        const int fl = i / a.d, t = i % a.d;
+        float s = 0.f;
+        for (int r = 0; r < a.KR; ++r)
+            s = fmaf(w[r][fl], a.Spart[(pbase + (long)r * a.mf + 32 * ft + fl) * a.d + t], s);
+        a.S[((long)bh * a.mf + 32 * ft + fl) * a.d + t] = s;
+        tile[fl][t] = s;
+    }
+    __syncthreads();
+    for (int i = tid; i < 32 * a.d; i += 256) {
+        const int t = i / 32, sl = i % 32;
+        int fl = sl;
+        if (a.permute) {
+            const int e = sl & 7, h = (sl >> 3) & 1;
+            fl = (sl & 16) + 8 * (e >> 2) + 4 * h + (e & 3);
+        }
+        a.St[((long)bh * a.d + t) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl][t]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+KeyStatePlan key_state_plan(const Problem& p) {
+    KeyStatePlan q;
+    q.kpad = (p.k + 31) / 32 * 32;
+    q.FT = p.mf / 32;
+    const int KT = q.kpad / 32;
+    int KR = (1024 + p.BH * q.FT - 1) / (p.BH * q.FT);
+    if (KR > 16) KR = 16;
+    if (KR > KT) KR = KT;
+    if (KR < 1) KR = 1;
+    q.tiles_per_range = (KT + KR - 1) / KR;
+    q.KR = (KT + q.tiles_per_range - 1) / q.tiles_per_range;
+    return q;
+}
+
+template <int D>
+static flurka_status launch_key_state(const Problem& p, const KeyStateArgs& ka, hipStream_t s) {
+    const long waves = (long)p.BH * ka.FT * ka.KR;
+    const dim3 grid((unsigned)((waves + 3) / 4));
+    if (p.elu) hipLaunchKernelGGL((key_state_kernel<D, true>), grid, dim3(256), 0, s, ka);
+    else       hipLaunchKernelGGL((key_state_kernel<D, false>), grid, dim3(256), 0, s, ka);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
+}
+
+flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
+                             long split_stride, int splits, const KeyStateBuffers& b, hipStream_t s) {
+    const CtxLayout L = ctx_layout(p);
+    const KeyStatePlan q = key_state_plan(p);
+    {
+        FinishArgs fa{};
+        fa.part = partials; fa.ctx = ctx; fa.split_stride = split_stride;
+        fa.Kp_off = (long)L.Kp; fa.Vp_off = (long)L.Vp;
+        fa.Kimg = p.elu ? nullptr : b.Kimg; fa.Vimg = b.Vimg; fa.nrm = p.elu ? nullptr : b.nrm;
+        fa.splits = splits; fa.k = p.k; fa.kpad = q.kpad; fa.d = p.d; fa.BH = p.BH;
+        const long pairs = (long)p.BH * (q.kpad / 2);
+        hipLaunchKernelGGL(proj_finish_kernel, grid1d(pairs, 4), dim3(256), 0, s, fa);
+        FLURKA_CHECK_LAUNCH();
+    }
+    {
+        KeyStateArgs ka{};
+        ka.Kimg = b.Kimg; ka.Kp = ctx + L.Kp; ka.Vimg = b.Vimg; ka.nrm = b.nrm;
+        ka.omega = (const uint16_t*)omega;
+        ka.Spart = b.Spart; ka.zpart = b.zpart; ka.cpart = b.cpart;
+        ka.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
+        ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf;
+        ka.FT = q.FT; ka.KR = q.KR; ka.tiles_per_range = q.tiles_per_range;
+        flurka_status st = p.d == 64 ? launch_key_state<64>(p, ka, s) : launch_key_state<128>(p, ka, s);
+        if (st != FLURKA_OK) return st;
+    }
+    {
+        MergeArgs ma{};
+        ma.Spart = b.Spart; ma.zpart = b.zpart; ma.cpart = b.cpart;
+        ma.S = ctx + L.S; ma.z = ctx + L.z; ma.c = ctx + L.c;
+        ma.St = b.St; ma.zp = b.zp; ma.cp = b.cp;
+        ma.KR = q.KR; ma.mf = p.mf; ma.d = p.d; ma.permute = p.elu ? 0 : 1;
+        hipLaunchKernelGGL(merge_pack_kernel, dim3(p.BH * q.FT), dim3(256), 0, s, ma);
+        FLURKA_CHECK_LAUNCH();
+    }
+    return FLURKA_OK;
+}
+
+}  // namespace flurka
