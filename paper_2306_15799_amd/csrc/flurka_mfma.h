@@ -26,10 +26,18 @@ __device__ __forceinline__ floatx16 zero16() {
     return z;
 }
 
-// two floats -> packed bf16 pair (low half = a), round to nearest even
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2;
+
+// two floats -> packed bf16 pair (low half = a), round to nearest even (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+    const floatx2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+
+// 2^x on the transcendental unit, no denormal fix-up (inputs here are <= 0 and results that
+// underflow are meant to be 0)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *(const uint4*)p; }
 
