@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libflurka.so")
 
-SOURCES = ["flurka_api.hip", "flurka_generic.hip", "flurka_fast.hip", "flurka_keystate.hip"]
+SOURCES = ["flurka_api.hip", "flurka_generic.hip", "flurka_fast.hip", "flurka_keystate.hip", "flurka_bwd.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,0 +1,544 @@
+// bf16 MFMA backward of the query side of FLuRKA attention (gfx950): dQ, dS, dz.
+//
+// Chain rule of out = (P S)/(P z) with P_ij = exp(u_ij + c_j - mu_i), u = Q omega^T (positive random
+// features, Sec. 2 "Kernel Methods"; ratio form of App. D).  With the normalised weights
+// W_ij = P_ij / D_i = exp(u_ij + c_j - lambda_i), lambda_i = mu_i + ln D_i, and g_i = G_i . out_i:
+//     dU_ij = W_ij (G_i . S_j - g_i z_j)        dQ = dU omega
+//     dS_j  = sum_i W_ij G_i                    dz_j = - sum_i W_ij g_i
+// (the -rowsum(dU) q term of the feature map's derivative vanishes: sum_j dU_ij = 0 identically).
+//
+// Two kernels, both built on v_mfma_f32_32x32x16_bf16 with operands chained through registers:
+//   bwd_query_x  one wavefront per 32 query rows, lane = query: recomputes the forward (pass 1),
+//                stores lambda_i and g_i, then (pass 2) forms dU^T tile by tile and accumulates dQ^T
+//   bwd_query_y  one wavefront per (head, 32 features, query range), lane = feature: recomputes W with
+//                the stored lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
+#include "flurka_fast.h"
+
+namespace flurka {
+
+#define FLURKA_CHECK_LAUNCH()                                   \
+    do {                                                        \
+        if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH; \
+    } while (0)
+
+static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total + block - 1) / block)); }
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+// position p (0..15) inside a group of 16 operand slots <-> element offset 8*(e/4) + 4*h + e%4 with
+// p = 8*h + e: the order in which a 32x32 accumulator hands 16 consecutive rows to the next MFMA
+__host__ __device__ inline int slot_to_elem16(int p) {
+    const int e = p & 7, h = (p >> 3) & 1;
+    return 8 * (e >> 2) + 4 * h + (e & 3);
+}
+
+// ---------------------------------------------------------------------------
+// Operand images for bwd_query_x, per head (S, z, c from ctx; omega from the caller):
+//   St  (d x mf)   St[t][slot]  = S[feat(slot)][t]        A operand of N^T = S^T P^T
+//   Sp  (mf x d)   Sp[j][slot]  = S[j][t(slot)]           A operand of T'^T = S G^T
+//   Wt  (d x m)    Wt[t][slot]  = omega[feat(slot)][t]    A operand of dQ^T = omega^T dU^T  (per omega head)
+//   zp, cp (mf)    z, c in accumulator order of a 32-feature tile
+// ---------------------------------------------------------------------------
+__global__ void bwd_pack_kernel(uint16_t* St, uint16_t* Sp, float* zp, float* cp, const float* S,
+                                const float* z, const float* c, int mf, int d, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const long bh = idx / ((long)mf * d);
+    const int rem = (int)(idx % ((long)mf * d));
+    {   // St: rem = t * mf + slot
+        const int t = rem / mf, slot = rem % mf;
+        const int f = (slot & ~15) + slot_to_elem16(slot & 15);
+        St[idx] = f32_to_bf16(S[(bh * mf + f) * d + t]);
+        if (t == 0) {
+            const int g = slot & 15, h = (slot >> 4) & 1;
+            const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
+            zp[bh * mf + slot] = z[bh * mf + fz];
+            cp[bh * mf + slot] = c[bh * mf + fz];
+        }
+    }
+    {   // Sp: rem = j * d + slot
+        const int j = rem / d, slot = rem % d;
+        const int t = (slot & ~15) + slot_to_elem16(slot & 15);
+        Sp[idx] = f32_to_bf16(S[(bh * mf + j) * d + t]);
+    }
+}
+
+__global__ void bwd_pack_omega_kernel(uint16_t* Wt, const uint16_t* omega, int m, int d, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const long h = idx / ((long)m * d);
+    const int rem = (int)(idx % ((long)m * d));
+    const int t = rem / m, slot = rem % m;
+    const int f = (slot & ~15) + slot_to_elem16(slot & 15);
+    Wt[idx] = omega[(h * m + f) * d + t];
+}
+
+// ---------------------------------------------------------------------------
+// bwd_query_x
+// ---------------------------------------------------------------------------
+struct BwdXArgs {
+    const uint16_t* Q;
+    const uint16_t* G;         // dOut
+    const uint16_t* omega;     // (H|1, m, d)
+    const uint16_t* St;        // (BH, d, mf)
+    const uint16_t* Sp;        // (BH, mf, d)
+    const uint16_t* Wt;        // (H|1, d, m)
+    const float* zp;
+    const float* cp;
+    uint16_t* dQ;
+    float* lse;                // (BH, n)  lambda_i
+    float* delta;              // (BH, n)  g_i
+    int n, H, mf, rows_per_wg, wgs_per_head;
+    long omega_head_stride;    // 0 if shared
+};
+
+template <int D>
+struct BwdXLds {
+    static constexpr int w_pitch = (D + 8) * 2;                          // rows of length d
+    static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }   // rows of length mf
+    static __host__ __device__ int total(int mf) { return 2 * mf * w_pitch + 2 * D * s_pitch(mf) + mf * 8; }
+};
+
+template <int D>
+__global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using L = BwdXLds<D>;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int bh = blockIdx.x / a.wgs_per_head;
+    const int chunk = blockIdx.x % a.wgs_per_head;
+    const int mf = a.mf;
+    const int s_pitch = L::s_pitch(mf);
+    unsigned char* lw = lds;                              // omega   [feature][d]
+    unsigned char* lsp = lw + mf * L::w_pitch;            // Sp      [feature][t slot]
+    unsigned char* ls = lsp + mf * L::w_pitch;            // St      [t][feature slot]
+    unsigned char* lwt = ls + D * s_pitch;                // Wt      [t][feature slot]
+    float* lz = (float*)(lwt + D * s_pitch);
+    float* lc = lz + mf;
+    {
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
+        const uint16_t* spg = a.Sp + (long)bh * mf * D;
+        constexpr int cpr = D / 8;
+        for (int c = tid; c < mf * cpr; c += 512) {
+            const int r = c / cpr, q = c % cpr;
+            *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
+            *(uint4*)(lsp + r * L::w_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
+        }
+        const uint16_t* sg = a.St + (long)bh * D * mf;
+        const uint16_t* wtg = a.Wt + (long)(bh % a.H) * a.omega_head_stride;
+        const int cps = mf / 8;
+        for (int c = tid; c < D * cps; c += 512) {
+            const int r = c / cps, q = c % cps;
+            *(uint4*)(ls + r * s_pitch + 16 * q) = ld16(sg + (long)r * mf + 8 * q);
+            *(uint4*)(lwt + r * s_pitch + 16 * q) = ld16(wtg + (long)r * mf + 8 * q);
+        }
+        const float* zg = a.zp + (long)bh * mf;
+        const float* cg = a.cp + (long)bh * mf;
+        for (int c = tid; c < mf; c += 512) { lz[c] = zg[c]; lc[c] = cg[c]; }
+    }
+    __syncthreads();
+
+    const long head_off = (long)bh * a.n * D;
+    const int row_begin = chunk * a.rows_per_wg;
+    int row_end = row_begin + a.rows_per_wg;
+    if (row_end > a.n) row_end = a.n;
+    constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
+    constexpr int TT = D / 32;      // 32-row tiles of N^T and dQ^T
+    const int FT = mf / 32;
+
+    for (int row0 = row_begin + 32 * wave; row0 < row_end; row0 += 32 * 8) {
+        int qrow = row0 + l32;
+        const bool valid = qrow < a.n;
+        if (!valid) qrow = a.n - 1;
+        const uint16_t* qg = a.Q + head_off + (long)qrow * D + 8 * half;
+        const uint16_t* gg = a.G + head_off + (long)qrow * D + 4 * half;
+        uint4 qf[KS], gf[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            qf[s] = ld16(qg + 16 * s);
+            // B operand of S G^T: slots (h, j) of step s hold t = 16*s + 8*(j/4) + 4*h + j%4
+            const uint2 g0 = *(const uint2*)(gg + 16 * s);
+            const uint2 g1 = *(const uint2*)(gg + 16 * s + 8);
+            gf[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
+        }
+
+        // ---- pass 1: forward recompute -> D, out, g_i, lambda_i ----------------------------------
+        floatx16 accN[TT];
+#pragma unroll
+        for (int t = 0; t < TT; ++t) accN[t] = zero16();
+        float den = 0.f, mu = -INFINITY;
+        for (int ft = 0; ft < FT; ++ft) {
+            floatx16 u;
+            {
+                const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = ct[q];
+                    u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                u = mfma32(*(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), qf[s], u);
+            float tmax = fmaxf(fmaxf(u[0], u[1]), u[2]);
+#pragma unroll
+            for (int g = 3; g < 15; g += 2) tmax = fmaxf(fmaxf(tmax, u[g]), u[g + 1]);
+            tmax = fmaxf(tmax, u[15]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            if (tmax > mu) {
+                const float sc = fast_exp2((mu - tmax) * LOG2E);
+                mu = tmax;
+                den *= sc;
+#pragma unroll
+                for (int t = 0; t < TT; ++t)
+#pragma unroll
+                    for (int g = 0; g < 16; ++g) accN[t][g] *= sc;
+            }
+            const float nshift = -mu * LOG2E;
+            const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
+            uint32_t pk[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 zv = zt[q];
+                const float p0 = fast_exp2(fmaf(u[4 * q], LOG2E, nshift));
+                const float p1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, nshift));
+                const float p2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, nshift));
+                const float p3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, nshift));
+                pk[2 * q] = pack_bf16(p0, p1);
+                pk[2 * q + 1] = pack_bf16(p2, p3);
+                den = fmaf(p0, zv.x, den); den = fmaf(p1, zv.y, den);
+                den = fmaf(p2, zv.z, den); den = fmaf(p3, zv.w, den);
+            }
+            const uint4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
+            const uint4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
+#pragma unroll
+            for (int t = 0; t < TT; ++t) {
+                const unsigned char* sp = ls + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
+                accN[t] = mfma32(*(const uint4*)sp, pb0, accN[t]);
+                accN[t] = mfma32(*(const uint4*)(sp + 32), pb1, accN[t]);
+            }
+        }
+        den += __shfl_xor(den, 32, 64);
+        const float inv = 1.f / den;
+        // g_i = G_i . out_i ; this lane holds t = 32*tt + 8*(g/4) + 4*half + g%4 of its query,
+        // which are the 8-byte chunks of gf: step s = 2*tt + (g/8), chunk (g/4)%2
+        float gdot = 0.f;
+#pragma unroll
+        for (int t = 0; t < TT; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 gv = gf[2 * t + (q >> 1)];
+                const uint32_t w0 = (q & 1) ? gv.z : gv.x, w1 = (q & 1) ? gv.w : gv.y;
+                gdot = fmaf(bf16_to_f32((uint16_t)(w0 & 0xffffu)), accN[t][4 * q], gdot);
+                gdot = fmaf(bf16_to_f32((uint16_t)(w0 >> 16)), accN[t][4 * q + 1], gdot);
+                gdot = fmaf(bf16_to_f32((uint16_t)(w1 & 0xffffu)), accN[t][4 * q + 2], gdot);
+                gdot = fmaf(bf16_to_f32((uint16_t)(w1 >> 16)), accN[t][4 * q + 3], gdot);
+            }
+        gdot += __shfl_xor(gdot, 32, 64);
+        const float gi = gdot * inv;                         // g_i
+        const float lam = mu + __logf(den);                  // lambda_i
+        if (valid && half == 0) {
+            a.lse[(long)bh * a.n + qrow] = lam;
+            a.delta[(long)bh * a.n + qrow] = gi;
+        }
+
+        // ---- pass 2: dU^T tile by tile, dQ^T = omega^T dU^T ---------------------------------------
+        floatx16 accQ[TT];
+#pragma unroll
+        for (int t = 0; t < TT; ++t) accQ[t] = zero16();
+        const float nlam = -lam * LOG2E;
+        for (int ft = 0; ft < FT; ++ft) {
+            floatx16 u;
+            {
+                const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = ct[q];
+                    u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
+                }
+            }
+            floatx16 tp = zero16();                          // T'^T tile: G_i . S_j
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                u = mfma32(*(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), qf[s], u);
+                tp = mfma32(*(const uint4*)(lsp + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), gf[s], tp);
+            }
+            const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
+            uint32_t pk[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 zv = zt[q];
+                const float w0 = fast_exp2(fmaf(u[4 * q], LOG2E, nlam));
+                const float w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, nlam));
+                const float w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, nlam));
+                const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, nlam));
+                const float d0 = w0 * fmaf(-gi, zv.x, tp[4 * q]);
+                const float d1 = w1 * fmaf(-gi, zv.y, tp[4 * q + 1]);
+                const float d2 = w2 * fmaf(-gi, zv.z, tp[4 * q + 2]);
+                const float d3 = w3 * fmaf(-gi, zv.w, tp[4 * q + 3]);
+                pk[2 * q] = pack_bf16(d0, d1);
+                pk[2 * q + 1] = pack_bf16(d2, d3);
+            }
+            const uint4 db0 = {pk[0], pk[1], pk[2], pk[3]};
+            const uint4 db1 = {pk[4], pk[5], pk[6], pk[7]};
+#pragma unroll
+            for (int t = 0; t < TT; ++t) {
+                const unsigned char* wp = lwt + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
+                accQ[t] = mfma32(*(const uint4*)wp, db0, accQ[t]);
+                accQ[t] = mfma32(*(const uint4*)(wp + 32), db1, accQ[t]);
+            }
+        }
+        if (valid) {
+            uint16_t* og = a.dQ + head_off + (long)qrow * D;
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint2 v;
+                    v.x = pack_bf16(accQ[t][4 * q], accQ[t][4 * q + 1]);
+                    v.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
+                    *(uint2*)(og + 32 * t + 8 * q + 4 * half) = v;
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// bwd_query_y: one wavefront per (head, feature tile, query range)
+// ---------------------------------------------------------------------------
+struct BwdYArgs {
+    const uint16_t* Q;
+    const uint16_t* G;
+    const uint16_t* omega;
+    const float* c;            // ctx shifts, natural order (BH, mf)
+    const float* lse;
+    const float* delta;
+    float* dSpart;             // (BH, R, mf, d)
+    float* dzpart;             // (BH, R, mf)
+    long omega_head_stride;
+    int BH, H, n, mf, FT, R, tiles_per_range;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
+    constexpr int KS = D / 16, TT = D / 32;
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= (long)a.BH * a.FT * a.R) return;
+    const int ft = (int)(wid % a.FT); wid /= a.FT;      // waves of one workgroup share Q and G rows
+    const int r = (int)(wid % a.R);
+    const int bh = (int)(wid / a.R);
+    const int QT = a.n / 32;
+    const int qt0 = r * a.tiles_per_range;
+    int qt1 = qt0 + a.tiles_per_range;
+    if (qt1 > QT) qt1 = QT;
+    const long head_off = (long)bh * a.n * D;
+
+    uint4 wf[KS];
+    {
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ft + l32) * D + 8 * half;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
+    }
+    const float cj = a.c[(long)bh * a.mf + 32 * ft + l32] * LOG2E;
+    floatx16 accS[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) accS[t] = zero16();
+    float dz = 0.f;
+
+    for (int qt = qt0; qt < qt1; ++qt) {
+        // u tile: rows = queries 32*qt + ..., columns = this wavefront's features
+        const uint16_t* qg = a.Q + head_off + (long)(32 * qt + l32) * D + 8 * half;
+        floatx16 u = zero16();
+#pragma unroll
+        for (int s = 0; s < KS; ++s) u = mfma32(ld16(qg + 16 * s), wf[s], u);
+        // element g <-> query 32*qt + 8*(g/4) + 4*half + g%4
+        const float* lg = a.lse + (long)bh * a.n + 32 * qt + 4 * half;
+        const float* dg = a.delta + (long)bh * a.n + 32 * qt + 4 * half;
+        uint32_t wk[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 lv = *(const float4*)(lg + 8 * q);
+            const float4 dv = *(const float4*)(dg + 8 * q);
+            const float w0 = fast_exp2(fmaf(u[4 * q], LOG2E, cj - lv.x * LOG2E));
+            const float w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, cj - lv.y * LOG2E));
+            const float w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, cj - lv.z * LOG2E));
+            const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, cj - lv.w * LOG2E));
+            wk[2 * q] = pack_bf16(w0, w1);
+            wk[2 * q + 1] = pack_bf16(w2, w3);
+            dz = fmaf(-w0, dv.x, dz); dz = fmaf(-w1, dv.y, dz);
+            dz = fmaf(-w2, dv.z, dz); dz = fmaf(-w3, dv.w, dz);
+        }
+        // W^T tile as A operand (row = this lane's feature, slots = queries in accumulator order);
+        // B operand: G columns 32*tt + l32, query pairs in the matching order
+        const uint4 wa[2] = {{wk[0], wk[1], wk[2], wk[3]}, {wk[4], wk[5], wk[6], wk[7]}};
+        const uint16_t* gb = a.G + head_off + (long)(32 * qt) * D + l32;
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            // dword q of the operand = queries 16*sp + 8*(q/2) + 4*half + 2*(q%2) + {0, 1}
+            const uint16_t* g0 = gb + (long)(16 * sp + 4 * half) * D;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const uint16_t* gp = g0 + 32 * tt;
+                uint4 b;
+                b.x = (uint32_t)gp[0] | ((uint32_t)gp[D] << 16);
+                b.y = (uint32_t)gp[2 * D] | ((uint32_t)gp[3 * D] << 16);
+                b.z = (uint32_t)gp[8 * D] | ((uint32_t)gp[9 * D] << 16);
+                b.w = (uint32_t)gp[10 * D] | ((uint32_t)gp[11 * D] << 16);
+                accS[tt] = mfma32(wa[sp], b, accS[tt]);
+            }
+        }
+    }
+    dz += __shfl_xor(dz, 32, 64);
+    const long po = ((long)bh * a.R + r) * a.mf;
+    if (half == 0) a.dzpart[po + 32 * ft + l32] = dz;
+    float* sp = a.dSpart + po * D;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            const int f = 32 * ft + 8 * (g >> 2) + 4 * half + (g & 3);
+            sp[(long)f * D + 32 * tt + l32] = accS[tt][g];
+        }
+}
+
+// dst[bh, i] = sum_r src[bh, r, i]
+__global__ void sum_ranges_kernel(float* dst, const float* src, long per_head, int R, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const long bh = idx / per_head, i = idx % per_head;
+    const float* p = src + bh * R * per_head + i;
+    float s = 0.f;
+    for (int r = 0; r < R; ++r) s += p[(long)r * per_head];
+    dst[idx] = s;
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+static int bwd_x_lds_bytes(const Problem& p) {
+    return p.d == 64 ? BwdXLds<64>::total(p.mf) : BwdXLds<128>::total(p.mf);
+}
+
+bool fast_bwd_supported(const Problem& p) {
+    if (!p.bf16 || p.elu) return false;
+    if (p.d != 64 && p.d != 128) return false;
+    if (p.n % 64 != 0 || p.mf % 32 != 0) return false;
+    if (bwd_x_lds_bytes(p) > 160 * 1024) return false;
+    return true;
+}
+
+struct BwdYPlan { int FT, R, tiles_per_range; };
+
+static BwdYPlan bwd_y_plan(const Problem& p) {
+    BwdYPlan q;
+    q.FT = p.mf / 32;
+    const int QT = p.n / 32;
+    // enough wavefronts to fill the chip several times over, ranges of at least 8 query tiles
+    int R = (4096 + p.BH * q.FT - 1) / (p.BH * q.FT);
+    if (R > QT / 8) R = QT / 8;
+    if (R < 1) R = 1;
+    q.tiles_per_range = (QT + R - 1) / R;
+    q.R = (QT + q.tiles_per_range - 1) / q.tiles_per_range;
+    return q;
+}
+
+struct FastBwdWs {
+    size_t St, Sp, Wt, zp, cp, lse, delta, dSpart, dzpart, generic, total;   // byte offsets
+};
+
+static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
+    FastBwdWs W{};
+    const BwdYPlan y = bwd_y_plan(p);
+    const size_t BH = (size_t)p.BH;
+    size_t o = 0;
+    W.St = o;     o += round_up(BH * p.d * p.mf * 2, 256);
+    W.Sp = o;     o += round_up(BH * p.mf * p.d * 2, 256);
+    W.Wt = o;     o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
+    W.zp = o;     o += round_up(BH * p.mf * 4, 256);
+    W.cp = o;     o += round_up(BH * p.mf * 4, 256);
+    W.lse = o;    o += round_up(BH * p.n * 4, 256);
+    W.delta = o;  o += round_up(BH * p.n * 4, 256);
+    W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
+    W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
+    W.generic = o; o += generic_ws_layout(p, 1).total * sizeof(float);
+    W.total = o;
+    return W;
+}
+
+size_t fast_bwd_ws_bytes(const Problem& p) { return fast_bwd_ws_layout(p).total; }
+
+template <int D>
+static flurka_status launch_bwd_x(const BwdXArgs& xa, int grid, int ldsb, hipStream_t s) {
+    auto kern = bwd_query_x_kernel<D>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
+        return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ldsb, s, xa);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
+}
+
+flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
+    const CtxLayout L = ctx_layout(p);
+    const FastBwdWs W = fast_bwd_ws_layout(p);
+    const GenericWs GW = generic_ws_layout(p, 1);
+    const BwdYPlan y = bwd_y_plan(p);
+    unsigned char* wsb = (unsigned char*)a.ws;
+    float* gws = (float*)(wsb + W.generic);
+    const long omega_stride = p.omega_per_head ? (long)p.m * p.d : 0;
+    flurka_status st;
+    {
+        StageScope sc(s, STAGE_BWD_QUERY);
+        const long total = (long)p.BH * p.mf * p.d;
+        hipLaunchKernelGGL(bwd_pack_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.St),
+                           (uint16_t*)(wsb + W.Sp), (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S,
+                           a.ctx + L.z, a.ctx + L.c, p.mf, p.d, total);
+        FLURKA_CHECK_LAUNCH();
+        const long wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
+        hipLaunchKernelGGL(bwd_pack_omega_kernel, grid1d(wtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Wt),
+                           (const uint16_t*)a.omega, p.m, p.d, wtotal);
+        FLURKA_CHECK_LAUNCH();
+
+        BwdXArgs xa{};
+        xa.Q = (const uint16_t*)a.Q; xa.G = (const uint16_t*)a.dOut; xa.omega = (const uint16_t*)a.omega;
+        xa.St = (const uint16_t*)(wsb + W.St); xa.Sp = (const uint16_t*)(wsb + W.Sp);
+        xa.Wt = (const uint16_t*)(wsb + W.Wt);
+        xa.zp = (const float*)(wsb + W.zp); xa.cp = (const float*)(wsb + W.cp);
+        xa.dQ = (uint16_t*)a.dQ; xa.lse = (float*)(wsb + W.lse); xa.delta = (float*)(wsb + W.delta);
+        xa.n = p.n; xa.H = p.H; xa.mf = p.mf; xa.omega_head_stride = omega_stride;
+        int wgs_per_head = (512 + p.BH - 1) / p.BH;
+        int rows = (p.n + wgs_per_head - 1) / wgs_per_head;
+        rows = (rows + 255) / 256 * 256;
+        wgs_per_head = (p.n + rows - 1) / rows;
+        xa.rows_per_wg = rows; xa.wgs_per_head = wgs_per_head;
+        const int ldsb = bwd_x_lds_bytes(p);
+        st = p.d == 64 ? launch_bwd_x<64>(xa, p.BH * wgs_per_head, ldsb, s)
+                       : launch_bwd_x<128>(xa, p.BH * wgs_per_head, ldsb, s);
+        if (st != FLURKA_OK) return st;
+
+        BwdYArgs ya{};
+        ya.Q = xa.Q; ya.G = xa.G; ya.omega = xa.omega; ya.c = a.ctx + L.c;
+        ya.lse = xa.lse; ya.delta = xa.delta;
+        ya.dSpart = (float*)(wsb + W.dSpart); ya.dzpart = (float*)(wsb + W.dzpart);
+        ya.omega_head_stride = omega_stride;
+        ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
+        ya.tiles_per_range = y.tiles_per_range;
+        const long waves = (long)p.BH * y.FT * y.R;
+        if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, grid1d(waves, 4), dim3(256), 0, s, ya);
+        else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, grid1d(waves, 4), dim3(256), 0, s, ya);
+        FLURKA_CHECK_LAUNCH();
+        const long st_total = (long)p.BH * p.mf * p.d, z_total = (long)p.BH * p.mf;
+        hipLaunchKernelGGL(sum_ranges_kernel, grid1d(st_total, 256), dim3(256), 0, s, gws + GW.dS,
+                           (const float*)ya.dSpart, (long)p.mf * p.d, y.R, st_total);
+        FLURKA_CHECK_LAUNCH();
+        hipLaunchKernelGGL(sum_ranges_kernel, grid1d(z_total, 256), dim3(256), 0, s, gws + GW.dz,
+                           (const float*)ya.dzpart, (long)p.mf, y.R, z_total);
+        FLURKA_CHECK_LAUNCH();
+    }
+    // key side and the sequence-length GEMMs
+    BwdArgs rest = a;
+    rest.ws = gws;
+    return generic_backward_from(p, rest, s, 1);
+}
+
+}  // namespace flurka

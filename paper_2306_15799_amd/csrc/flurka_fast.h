@@ -31,4 +31,8 @@ struct KeyStateBuffers {
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
                              long split_stride, int splits, const KeyStateBuffers& b, hipStream_t s);
 
+// Backward (flurka_bwd.hip)
+bool fast_bwd_supported(const Problem& p);
+size_t fast_bwd_ws_bytes(const Problem& p);
+
 }  // namespace flurka

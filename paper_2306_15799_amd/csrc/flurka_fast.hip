@@ -458,7 +458,7 @@ static int query_lds_bytes(const Problem& p) {
 }
 
 bool fast_supported(const Problem& p, int bwd) {
-    if (bwd) return false;
+    if (bwd) return fast_bwd_supported(p);
     if (!p.bf16) return false;
     if (p.d != 64 && p.d != 128) return false;
     if (p.n % PBK != 0) return false;
@@ -506,8 +506,7 @@ static FastWs fast_ws_layout(const Problem& p) {
 }
 
 size_t fast_ws_bytes(const Problem& p, int bwd) {
-    (void)bwd;
-    return fast_ws_layout(p).total;
+    return bwd ? fast_bwd_ws_bytes(p) : fast_ws_layout(p).total;
 }
 
 template <int D, bool ELU>
@@ -586,6 +585,5 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     return FLURKA_OK;
 }
 
-flurka_status fast_backward(const Problem&, const BwdArgs&, hipStream_t) { return FLURKA_ERR_UNSUPPORTED; }
 
 }  // namespace flurka

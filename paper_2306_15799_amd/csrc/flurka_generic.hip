@@ -478,6 +478,12 @@ flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s)
 //   dK = E^T dK', dV = F^T dV', dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
 // ---------------------------------------------------------------------------
 flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
+    return generic_backward_from(p, a, s, 0);
+}
+
+// With `query_done` the caller has already written dQ and left dS, dz in the workspace slots of
+// the generic layout; only the key side and the four sequence-length GEMMs remain.
+flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStream_t s, int query_done) {
     const CtxLayout L = ctx_layout(p);
     const GenericWs W = generic_ws_layout(p, 1);
     const float* Kp = a.ctx + L.Kp;
@@ -500,8 +506,8 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
     flurka_status st;
     const int nc = generic_chunk_rows(p);
 
-    stage_begin(s);
-    for (int row0 = 0; row0 < p.n; row0 += nc) {
+    if (!query_done) stage_begin(s);
+    for (int row0 = 0; row0 < p.n && !query_done; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
         const long rows = (long)p.BH * nr;
         st = query_features_and_numerator(p, a.Q, a.omega, S, cshift, P, N, row0, nr, s);
@@ -559,7 +565,7 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
         }
     }
 
-    stage_end(s, STAGE_BWD_QUERY);
+    if (!query_done) stage_end(s, STAGE_BWD_QUERY);
 
     stage_begin(s);
     const long krows = (long)p.BH * p.k;

@@ -96,6 +96,7 @@ struct BwdArgs {
 // Each returns FLURKA_OK or FLURKA_ERR_LAUNCH.
 flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
 flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s);
+flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStream_t s, int query_done);
 
 // ---- stage timer -------------------------------------------------------------
 enum Stage {

@@ -74,3 +74,42 @@ def test_unsupported_shapes_are_refused_not_miscomputed():
     assert e.value.status == fb.ERR_UNSUPPORTED
     # auto falls back to the generic kernels and still matches
     assert gu.check_forward(w, seed=11, algo="auto") < 2e-2
+
+
+# ---- backward ------------------------------------------------------------------------------
+BWD_SHAPES = [
+    (1, 3, 192, 64, 100, 96),
+    (2, 5, 1024, 64, 256, 256),
+    (2, 2, 2048, 64, 64, 32),
+]
+
+
+@pytest.mark.parametrize("shape", BWD_SHAPES)
+def test_forward_backward_performer(shape):
+    B, H, n, d, k, m = shape
+    w = Workload("fastbwd", B, H, n, d, k, m, "bf16", PHI_PERFORMER, True)
+    assert fb.fast_path_supported(B, H, n, d, k, m, fb.BF16, w.phi, fb.PASS_BWD)
+    errs = gu.check_forward_backward(w, seed=12, algo="fast")
+    print(shape, {k_: f"{v:.2e}" for k_, v in errs.items()})
+
+
+def test_backward_matches_generic_kernels_closely():
+    """Same inputs through both kernel families: they differ only by bf16 rounding of operands."""
+    w = Workload("cmp", 1, 2, 512, 64, 128, 64, "bf16", PHI_PERFORMER, True)
+    t = inputs.make_inputs(w, 13)
+    g, _, ctx = gu.run_forward(w, t, "fast")
+    fast = gu.run_backward(w, g, ctx, "fast")
+    g2, _, ctx2 = gu.run_forward(w, t, "generic")
+    gen = gu.run_backward(w, g2, ctx2, "generic")
+    for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], fast, gen):
+        assert fo.rel_l2(gu.to_host(a), gu.to_host(b)) < 2e-2, name
+
+
+def test_backward_is_deterministic():
+    w = Workload("det", 2, 2, 512, 64, 96, 64, "bf16", PHI_PERFORMER, True)
+    t = inputs.make_inputs(w, 14)
+    g, _, ctx = gu.run_forward(w, t, "fast")
+    a = gu.run_backward(w, g, ctx, "fast")
+    b = gu.run_backward(w, g, ctx, "fast")
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
