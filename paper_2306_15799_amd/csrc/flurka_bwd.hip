@@ -13,6 +13,7 @@
 //   bwd_query_y  one wavefront per (head, 32 features, query range), lane = feature: recomputes W with
 //                the stored lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
 #include "flurka_fast.h"
+#include "flurka_gemm.h"
 
 namespace flurka {
 
@@ -413,6 +414,35 @@ __global__ void sum_ranges_kernel(float* dst, const float* src, long per_head, i
     dst[idx] = s;
 }
 
+// dK', dV' (fp32, (BH, k, d)) -> bf16 operand images of the two gradient GEMMs, zero padded to kp rows:
+//   img  (BH, kp, d)      rows = projected slots               (A operand of dE = sum dK' K^T)
+//   imgT (BH * d, kp)     rows = (head, t), slots contiguous   (A operand of dK = E^T dK')
+__global__ void grad_images_kernel(uint16_t* img, uint16_t* imgT, const float* dXp, int k, int kp, int d,
+                                   long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int t = (int)(idx % d);
+    const long rest = idx / d;
+    const int r = (int)(rest % kp);
+    const long bh = rest / kp;
+    const uint16_t v = r < k ? f32_to_bf16(dXp[(bh * k + r) * d + t]) : (uint16_t)0;
+    img[idx] = v;
+    imgT[(bh * d + t) * kp + r] = v;
+}
+
+// dst (bf16) = sum over splits of src (fp32)
+__global__ void sum_splits_bf16_kernel(uint16_t* dst, const float* src, long count, long stride, int splits) {
+    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 2;
+    if (i >= count) return;
+    float a0 = 0.f, a1 = 0.f;
+    for (int s = 0; s < splits; ++s) {
+        a0 += src[(long)s * stride + i];
+        if (i + 1 < count) a1 += src[(long)s * stride + i + 1];
+    }
+    if (i + 1 < count) *(uint32_t*)(dst + i) = pack_bf16(a0, a1);
+    else dst[i] = f32_to_bf16(a0);
+}
+
 // ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
@@ -425,7 +455,25 @@ bool fast_bwd_supported(const Problem& p) {
     if (p.d != 64 && p.d != 128) return false;
     if (p.n % 64 != 0 || p.mf % 32 != 0) return false;
     if (bwd_x_lds_bytes(p) > 160 * 1024) return false;
+    // 32-bit byte offsets inside the gradient GEMMs' buffer descriptors
+    if ((size_t)p.BH * p.n * p.d * 2 >= ((size_t)1 << 31)) return false;
+    if (((size_t)p.k + GBM) * (size_t)p.n * 2 >= ((size_t)1 << 31)) return false;
     return true;
+}
+
+struct GradEPlan { int tilesM, tilesN, total_steps, splits, steps_per_split; };
+
+static GradEPlan grad_e_plan(const Problem& p) {
+    GradEPlan q;
+    q.tilesM = (p.k + GBM - 1) / GBM;
+    q.tilesN = (p.n + GBN - 1) / GBN;
+    q.total_steps = p.BH * p.d / GBK;
+    int splits = 256 / (q.tilesM * q.tilesN * 2);
+    if (splits < 1) splits = 1;
+    if (splits > q.total_steps) splits = q.total_steps;
+    q.steps_per_split = (q.total_steps + splits - 1) / splits;
+    q.splits = (q.total_steps + q.steps_per_split - 1) / q.steps_per_split;
+    return q;
 }
 
 struct BwdYPlan { int FT, R, tiles_per_range; };
@@ -444,7 +492,8 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
 }
 
 struct FastBwdWs {
-    size_t St, Sp, Wt, zp, cp, lse, delta, dSpart, dzpart, generic, total;   // byte offsets
+    size_t St, Sp, Wt, zp, cp, lse, delta, dSpart, dzpart, img, imgT, epart, generic, total;   // byte offsets
+    int kp;
 };
 
 static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
@@ -461,6 +510,11 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
     W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
+    W.kp = (p.k + 63) / 64 * 64;
+    const GradEPlan e = grad_e_plan(p);
+    W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);        // dK' then dV'
+    W.imgT = o;   o += round_up(2 * BH * W.kp * p.d * 2, 256);
+    W.epart = o;  o += round_up(2 * (size_t)e.splits * p.k * p.n * 4, 256);   // dE then dF partials
     W.generic = o; o += generic_ws_layout(p, 1).total * sizeof(float);
     W.total = o;
     return W;
@@ -535,10 +589,55 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
                            (const float*)ya.dzpart, (long)p.mf, y.R, z_total);
         FLURKA_CHECK_LAUNCH();
     }
-    // key side and the sequence-length GEMMs
+    // key side (generic kernels): dK', dV' in fp32
     BwdArgs rest = a;
     rest.ws = gws;
-    return generic_backward_from(p, rest, s, 1);
+    if ((st = generic_backward_from(p, rest, s, 3)) != FLURKA_OK) return st;
+
+    const size_t img_elems = (size_t)p.BH * W.kp * p.d;
+    uint16_t* img = (uint16_t*)(wsb + W.img);
+    uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
+    {
+        StageScope sc(s, STAGE_BWD_DKDV);
+        hipLaunchKernelGGL(grad_images_kernel, grid1d((long)img_elems, 256), dim3(256), 0, s, img, imgT,
+                           (const float*)(gws + GW.dKp), p.k, W.kp, p.d, (long)img_elems);
+        FLURKA_CHECK_LAUNCH();
+        hipLaunchKernelGGL(grad_images_kernel, grid1d((long)img_elems, 256), dim3(256), 0, s, img + img_elems,
+                           imgT + img_elems, (const float*)(gws + GW.dVp), p.k, W.kp, p.d, (long)img_elems);
+        FLURKA_CHECK_LAUNCH();
+        GemmParams gp{};       // dK = E^T dK', dV = F^T dV'
+        gp.A[0] = imgT; gp.A[1] = imgT + img_elems;
+        gp.B[0] = (const uint16_t*)a.E; gp.B[1] = (const uint16_t*)a.F;
+        gp.C[0] = a.dK; gp.C[1] = a.dV;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
+        gp.tilesM = (p.BH * p.d + GBM - 1) / GBM; gp.tilesN = (p.n + GBN - 1) / GBN;
+        gp.splits = 1; gp.total_steps = W.kp / GBK; gp.steps_per_split = gp.total_steps;
+        st = p.d == 64 ? launch_gemm_mfma<GradXPolicy<64>>(gp, s) : launch_gemm_mfma<GradXPolicy<128>>(gp, s);
+        if (st != FLURKA_OK) return st;
+    }
+    {
+        StageScope sc(s, STAGE_BWD_DEDF);
+        const GradEPlan e = grad_e_plan(p);
+        float* part = (float*)(wsb + W.epart);
+        const long kn = (long)p.k * p.n;
+        GemmParams gp{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
+        gp.A[0] = img; gp.A[1] = img + img_elems;
+        gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
+        gp.C[0] = part; gp.C[1] = part + (long)e.splits * kn;
+        gp.c_split_stride = kn;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
+        gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
+        gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
+        st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64>>(gp, s) : launch_gemm_mfma<GradEPolicy<128>>(gp, s);
+        if (st != FLURKA_OK) return st;
+        hipLaunchKernelGGL(sum_splits_bf16_kernel, grid1d((kn + 1) / 2, 256), dim3(256), 0, s, (uint16_t*)a.dE,
+                           (const float*)part, kn, kn, e.splits);
+        FLURKA_CHECK_LAUNCH();
+        hipLaunchKernelGGL(sum_splits_bf16_kernel, grid1d((kn + 1) / 2, 256), dim3(256), 0, s, (uint16_t*)a.dF,
+                           (const float*)(part + (long)e.splits * kn), kn, kn, e.splits);
+        FLURKA_CHECK_LAUNCH();
+    }
+    return FLURKA_OK;
 }
 
 }  // namespace flurka

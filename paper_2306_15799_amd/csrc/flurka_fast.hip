@@ -11,6 +11,7 @@
 //                                               N^T = S^T P^T (MFMA); the denominator on the VALU
 // Formulas: Eq. 2 with the App. D row normaliser; feature maps of Sec. 2, "Kernel Methods".
 #include "flurka_fast.h"
+#include "flurka_gemm.h"
 
 namespace flurka {
 
@@ -24,223 +25,7 @@ static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total
 // ===========================================================================
 // Stage "project": C[k x (BH*d)] = E[k x n] * X[n x (BH*d)] for X in {K, V}
 // ===========================================================================
-constexpr int PBM = 256;              // rows of E per workgroup
-constexpr int PBN = 256;              // columns (whole heads) per workgroup
-constexpr int PBK = 64;               // sequence positions per main-loop step
-constexpr int PA_PITCH = 144;         // bytes per LDS row of the E tile (128 + 16 pad: conflict-free b128 reads)
-constexpr int PA_STAGE = PBM * PA_PITCH;
-// X tile in LDS: [group of 8 positions][column][8 positions] bf16, i.e. every column's 8 consecutive
-// positions form one 16-byte MFMA operand chunk.  Within a plane the chunk of column c sits at
-// position c ^ ((c >> 4) & 15): a thread writes columns 8*cg + j for j = 0..7 one instruction at a
-// time, so without the swizzle the lanes of one write would be 128 bytes apart and hit two banks
-constexpr int PB_STAGE = (PBK / 8) * PBN * 16;
-constexpr int P_STAGE = PA_STAGE + PB_STAGE;
-constexpr int P_LDS = 2 * P_STAGE;    // double buffered: 139,264 bytes
-
-struct ProjArgs {
-    const uint16_t* EF[2];    // E, F
-    const uint16_t* X[2];     // K, V
-    float* out[2];            // destination of split 0 for K', V'; split s adds s * split_stride
-    long split_stride;        // floats
-    int n, d, k, BH;
-    int tilesM, tilesN, splits, steps_per_split, total_steps;
-};
-
-template <int N>
-struct IC { static constexpr int value = N; };
-
-// Main loop structure (one wavefront per SIMD, so every latency has to be hidden inside the
-// instruction stream of that one wavefront): a 64-position step is four 16-position sub-steps of
-// 16 MFMAs each.  While sub-step s multiplies, the operand fragments of sub-step s+1 are read from
-// LDS into the other register set; the global loads of the next step are issued during sub-step 0,
-// transposed and written to the other LDS buffer during sub-step 2, the single barrier of the step
-// sits between sub-steps 2 and 3, and sub-step 3 already prefetches from the next buffer.
-// sched_barrier(0) after every "2 MFMA + 1..4 other" group keeps the compiler from undoing this.
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// 16-byte load through a buffer descriptor: per-thread byte offset + wave-uniform byte offset;
-// addresses past the descriptor's range read as zero
-__device__ __forceinline__ uint4 buf_ld16(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
-    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
-template <int D>
-__global__ __launch_bounds__(256) void proj_mfma_kernel(ProjArgs a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int half = lane >> 5, l32 = lane & 31;
-
-    // workgroup -> (split, row tile, column tile, which); consecutive ids walk the splits first, so
-    // with a split count that is a multiple of 8 every XCD (ids mod 8) keeps to its own n-ranges
-    int id = blockIdx.x;
-    const int split = id % a.splits; id /= a.splits;
-    const int tm = id % a.tilesM;    id /= a.tilesM;
-    const int tn = id % a.tilesN;    id /= a.tilesN;
-    const int which = id;
-    const uint16_t* __restrict__ Eg = a.EF[which];
-    const uint16_t* __restrict__ Xg = a.X[which];
-    const int m0 = tm * PBM;
-    constexpr int heads_per_tile = PBN / D;
-    const int bh0 = tn * heads_per_tile;
-    const int step0 = split * a.steps_per_split;
-    int step1 = step0 + a.steps_per_split;
-    if (step1 > a.total_steps) step1 = a.total_steps;
-
-    // Global reads go through buffer descriptors: rows of E past k and heads past BH fall outside the
-    // descriptor and read as zero (such rows/columns are computed but never stored).
-    const __amdgpu_buffer_rsrc_t rsA =
-        __builtin_amdgcn_make_buffer_rsrc((void*)Eg, 0, (int)((unsigned)a.k * (unsigned)a.n * 2u), 0x00020000);
-    int tile_heads = a.BH - bh0;
-    if (tile_heads > heads_per_tile) tile_heads = heads_per_tile;
-    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(Xg + (long)bh0 * a.n * D), 0, (int)((unsigned)tile_heads * (unsigned)a.n * (unsigned)(D * 2)),
-        0x00020000);
-    const int a_chunk = tid & 7;                 // 16-byte chunk within a 128-byte row segment
-    const int voffA = ((m0 + (tid >> 3)) * a.n + 8 * a_chunk) * 2;      // + q * 32 rows (uniform), + step
-    const int rowsA = 64 * a.n;                                          // bytes between rows r and r + 32
-    const int b_cg = tid & 31;                   // group of 8 columns
-    const int b_kg = tid >> 5;                   // group of 8 positions
-    const int b_col = 8 * b_cg;
-    const int voffB = (((b_col / D) * a.n + 8 * b_kg) * D + (b_col % D)) * 2;   // + q rows (immediate), + step
-
-    // LDS addresses of this thread's writes and of this lane's operand reads (per buffer: + P_STAGE)
-    unsigned char* const a_dst = lds + (tid >> 3) * PA_PITCH + 16 * a_chunk;                 // + 32*u rows
-    const int b_dst0 = PA_STAGE + (b_kg * PBN + (b_col & ~15) + ((8 * (b_cg & 1)) ^ ((b_cg >> 1) & 15))) * 16;  // ^ 16*c
-    const unsigned char* const fa_src = lds + (wm * 128 + l32) * PA_PITCH + 16 * half;       // + 32*i rows, + 32*s
-    const unsigned char* fb_src[4];                                                          // + 2*s planes
-    {
-        const int c0 = wn * 128 + (l32 & 16) + ((l32 & 15) ^ ((8 * wn + (l32 >> 4)) & 15));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fb_src[j] = lds + PA_STAGE + (half * PBN + ((c0 ^ (2 * j)) + 32 * j)) * 16;
-    }
-
-    // Staging registers: two whole steps of global data are in flight per workgroup (2 x 64 KB),
-    // which is what it takes to cover HBM latency with one workgroup per compute unit.
-    uint4 RA[2][8], RB[2][8];
-    uint4 FA[2][4], FB[2][4];
-    floatx16 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = zero16();
-
-#define PROJ_SB() __builtin_amdgcn_sched_barrier(0)
-#define PROJ_MMA(set, i, j) acc[i][j] = mfma32(FA[set][i], FB[set][j], acc[i][j])
-#define PROJ_LDA(set, buf, s, i) \
-    FA[set][i] = *(const uint4*)(fa_src + (buf) * P_STAGE + (32 * (i)) * PA_PITCH + 32 * (s))
-#define PROJ_LDB(set, buf, s, j) \
-    FB[set][j] = *(const uint4*)(fb_src[j] + (buf) * P_STAGE + ((2 * (s)) * PBN) * 16)
-
-    // transposes 8 positions x 8 columns held in rb[0..7] and stores column c as one 16-byte chunk
-    auto store_b_col = [&](const uint4 (&rb)[8], int buf, int c) {
-        const unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
-        const int w = c >> 1;
-        auto dw = [&](const uint4& v) -> uint32_t { return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w)); };
-        uint4 o;
-        o.x = __builtin_amdgcn_perm(dw(rb[1]), dw(rb[0]), sel);
-        o.y = __builtin_amdgcn_perm(dw(rb[3]), dw(rb[2]), sel);
-        o.z = __builtin_amdgcn_perm(dw(rb[5]), dw(rb[4]), sel);
-        o.w = __builtin_amdgcn_perm(dw(rb[7]), dw(rb[6]), sel);
-        *(uint4*)(lds + ((b_dst0 ^ (16 * c)) + buf * P_STAGE)) = o;
-    };
-
-    // One 64-position step on LDS buffer PAR: sub-step 0 also fetches step + 2 into staging set PAR,
-    // sub-step 2 writes step + 1 (staging set PAR ^ 1) into LDS buffer PAR ^ 1; then the barrier, and
-    // sub-step 3 prefetches its fragments from that buffer.  The last two steps of a workgroup fetch
-    // and store tiles nobody uses (reads past the tensors return zero through the descriptors); that
-    // keeps the loop body free of branches, which the accumulator registers do not survive well.
-    auto run_step = [&](auto par_c, int kk_load) {
-        constexpr int PAR = decltype(par_c)::value;
-#define PROJ_CHUNK(PH, q, i0, j0, i1, j1, LD)                                                   \
-        {                                                                                       \
-            constexpr int cur = (PH) & 1, nxt = cur ^ 1, ns = ((PH) + 1) & 3;                   \
-            constexpr int pbuf = (PH) == 3 ? (PAR ^ 1) : PAR;                                   \
-            PROJ_MMA(cur, i0, j0); PROJ_MMA(cur, i1, j1);                                       \
-            LD(nxt, pbuf, ns, (q) >> 1);                                                        \
-            if ((PH) == 0) {                                                                    \
-                RA[PAR][q] = buf_ld16(rsA, voffA, kk_load * 2 + (q) * rowsA);                   \
-                RB[PAR][q] = buf_ld16(rsB, voffB + (q) * (D * 2), kk_load * (D * 2));           \
-            }                                                                                   \
-            if ((PH) == 2) {                                                                    \
-                *(uint4*)(a_dst + (PAR ^ 1) * P_STAGE + (32 * (q)) * PA_PITCH) = RA[PAR ^ 1][q]; \
-                store_b_col(RB[PAR ^ 1], PAR ^ 1, q);                                           \
-            }                                                                                   \
-            PROJ_SB();                                                                          \
-        }
-#define PROJ_PHASE(PH)                                  \
-        PROJ_CHUNK(PH, 0, 0, 0, 0, 1, PROJ_LDA)         \
-        PROJ_CHUNK(PH, 1, 1, 0, 1, 1, PROJ_LDB)         \
-        PROJ_CHUNK(PH, 2, 0, 2, 1, 2, PROJ_LDA)         \
-        PROJ_CHUNK(PH, 3, 0, 3, 1, 3, PROJ_LDB)         \
-        PROJ_CHUNK(PH, 4, 2, 0, 2, 1, PROJ_LDA)         \
-        PROJ_CHUNK(PH, 5, 3, 0, 3, 1, PROJ_LDB)         \
-        PROJ_CHUNK(PH, 6, 2, 2, 3, 2, PROJ_LDA)         \
-        PROJ_CHUNK(PH, 7, 2, 3, 3, 3, PROJ_LDB)
-        PROJ_PHASE(0)
-        PROJ_PHASE(1)
-        PROJ_PHASE(2)
-        __syncthreads();              // next buffer complete; nobody still reads it
-        PROJ_SB();
-        PROJ_PHASE(3)
-#undef PROJ_PHASE
-#undef PROJ_CHUNK
-    };
-
-    if (step0 < step1) {
-        // prologue: step0 through registers into buffer 0, step0 + 1 into staging set 1
-        const int kk0 = step0 * PBK;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            RA[0][q] = buf_ld16(rsA, voffA, kk0 * 2 + q * rowsA);
-            RB[0][q] = buf_ld16(rsB, voffB + q * (D * 2), kk0 * (D * 2));
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            RA[1][q] = buf_ld16(rsA, voffA, (kk0 + PBK) * 2 + q * rowsA);
-            RB[1][q] = buf_ld16(rsB, voffB + q * (D * 2), (kk0 + PBK) * (D * 2));
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            *(uint4*)(a_dst + (32 * q) * PA_PITCH) = RA[0][q];
-            store_b_col(RB[0], 0, q);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { PROJ_LDA(0, 0, 0, i); PROJ_LDB(0, 0, 0, i); }
-        PROJ_SB();
-        int step = step0;
-        for (; step + 1 < step1; step += 2) {
-            run_step(IC<0>{}, (step + 2) * PBK);
-            run_step(IC<1>{}, (step + 3) * PBK);
-        }
-        if (step < step1) run_step(IC<0>{}, (step + 2) * PBK);
-    }
-#undef PROJ_SB
-#undef PROJ_MMA
-#undef PROJ_LDA
-#undef PROJ_LDB
-
-    // epilogue: fp32 partial sums in (BH, k, d) layout
-    float* __restrict__ out = a.out[which] + (long)split * a.split_stride;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int c = wn * 128 + 32 * j + l32;
-        const int bh = bh0 + c / D;
-        if (bh >= a.BH) continue;
-        float* ob = out + (long)bh * a.k * D + (c % D);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-#pragma unroll
-            for (int g = 0; g < 16; ++g) {
-                const int r = m0 + wm * 128 + 32 * i + 8 * (g >> 2) + 4 * half + (g & 3);
-                if (r < a.k) ob[(long)r * D] = acc[i][j][g];
-            }
-        }
-    }
-}
+constexpr int PBM = GBM, PBN = GBN, PBK = GBK;   // tile of the shared GEMM main loop (flurka_gemm.h)
 
 struct ProjPlan {
     int tilesM, tilesN, splits, steps_per_split, total_steps;
@@ -528,23 +313,18 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     {
         StageScope sc(s, STAGE_PROJECT);
         const ProjPlan q = proj_plan(p);
-        ProjArgs pa{};
-        pa.EF[0] = (const uint16_t*)a.E; pa.EF[1] = (const uint16_t*)a.F;
-        pa.X[0] = (const uint16_t*)a.K;  pa.X[1] = (const uint16_t*)a.V;
+        GemmParams gp{};
+        gp.A[0] = (const uint16_t*)a.E; gp.A[1] = (const uint16_t*)a.F;
+        gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
         float* base = q.splits > 1 ? (float*)(wsb + W.partial) : a.ctx;
-        pa.out[0] = base + L.Kp;
-        pa.out[1] = base + L.Vp;
-        pa.split_stride = (long)W.split_stride;
-        pa.n = p.n; pa.d = p.d; pa.k = p.k; pa.BH = p.BH;
-        pa.tilesM = q.tilesM; pa.tilesN = q.tilesN; pa.splits = q.splits;
-        pa.steps_per_split = q.steps_per_split; pa.total_steps = q.total_steps;
-        const void* kern = p.d == 64 ? (const void*)proj_mfma_kernel<64> : (const void*)proj_mfma_kernel<128>;
-        if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS) != hipSuccess)
-            return FLURKA_ERR_LAUNCH;
-        const int grid = q.tilesM * q.tilesN * 2 * q.splits;
-        if (p.d == 64) hipLaunchKernelGGL(proj_mfma_kernel<64>, dim3(grid), dim3(256), P_LDS, s, pa);
-        else           hipLaunchKernelGGL(proj_mfma_kernel<128>, dim3(grid), dim3(256), P_LDS, s, pa);
-        FLURKA_CHECK_LAUNCH();
+        gp.C[0] = base + L.Kp;
+        gp.C[1] = base + L.Vp;
+        gp.c_split_stride = (long)W.split_stride;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = p.k;
+        gp.tilesM = q.tilesM; gp.tilesN = q.tilesN; gp.splits = q.splits;
+        gp.steps_per_split = q.steps_per_split; gp.total_steps = q.total_steps;
+        st = p.d == 64 ? launch_gemm_mfma<ProjPolicy<64>>(gp, s) : launch_gemm_mfma<ProjPolicy<128>>(gp, s);
+        if (st != FLURKA_OK) return st;
         proj_splits = q.splits;
     }
     {

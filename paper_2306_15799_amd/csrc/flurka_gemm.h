@@ -1,0 +1,355 @@
+// One 256 x 256 x 64 bf16 MFMA GEMM main loop for gfx950, shared by the three large contractions
+// of FLuRKA attention.  What differs between them (where the operands live, how a reduction step
+// maps to addresses, where the result goes) is supplied by a policy type:
+//
+//   ProjPolicy<D>   K' = E K, V' = F V          A = E rows, B = X (positions x columns, transposed on
+//                                               the way into LDS), fp32 split partials
+//   GradXPolicy<D>  dK = E^T dK', dV = F^T dV'  A = (dK')^T image rows, B = E (same transposing path),
+//                                               bf16 result stored transposed into (B,H,n,d)
+//   GradEPolicy<D>  dE = sum_bh dK' K^T         A = dK' image rows, B = K rows (both contiguous along
+//                                               the reduction), fp32 split partials
+//
+// Structure (one wavefront per SIMD, 4 per workgroup, wave tile 128 x 128 = 4 x 4 MFMA tiles, so all
+// latency hiding happens inside one instruction stream): a 64-deep step is four 16-deep sub-steps of
+// 16 MFMAs.  While sub-step s multiplies, the fragments of sub-step s+1 are read from LDS into the
+// other register set.  Global data runs two steps ahead in registers: sub-step 0 issues the loads of
+// step + 2, sub-step 2 writes step + 1 into the other LDS buffer, then the single barrier of the step,
+// and sub-step 3 already prefetches from that buffer.  sched_barrier(0) after each "2 MFMA + few
+// others" group pins this order.  The last two steps fetch and store tiles nobody uses (reads past a
+// descriptor return zero); that keeps the loop body free of branches, which the 256 accumulator
+// registers do not survive well.
+#pragma once
+
+#include "flurka_mfma.h"
+
+namespace flurka {
+
+constexpr int GBM = 256, GBN = 256, GBK = 64;
+constexpr int GA_PITCH = 144;                       // bytes per LDS row of a row-major tile (128 + 16)
+constexpr int GA_STAGE = GBM * GA_PITCH;            // 36,864
+constexpr int GB_STAGE_T = (GBK / 8) * GBN * 16;    // transposed tile: [8-position group][column][8]
+constexpr int GB_STAGE_D = GBN * GA_PITCH;          // direct tile: like A
+constexpr int G_STAGE = GA_STAGE + GB_STAGE_D;      // 73,728 (the larger of the two layouts)
+constexpr int G_LDS = 2 * G_STAGE;                  // 147,456
+
+struct GemmParams {
+    const uint16_t* A[2];
+    const uint16_t* B[2];
+    void* C[2];
+    long c_split_stride;     // elements between the outputs of consecutive splits
+    int tilesM, tilesN, splits, steps_per_split, total_steps;
+    int n, d, k, BH, kp;     // problem sizes the policies need (kp: padded k of an image)
+};
+
+template <int N>
+struct IC { static constexpr int value = N; };
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load through a buffer descriptor: per-thread byte offset + wave-uniform byte offset;
+// addresses past the descriptor's range read as zero
+__device__ __forceinline__ uint4 buf_ld16(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+template <class Pol>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    constexpr bool BT = Pol::B_TRANSPOSE;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int half = lane >> 5, l32 = lane & 31;
+
+    // workgroup -> (split, row tile, column tile, which); consecutive ids walk the splits first, so
+    // with a split count that is a multiple of 8 every XCD (ids mod 8) keeps to its own reduction range
+    int id = blockIdx.x;
+    const int split = id % g.splits; id /= g.splits;
+    const int tm = id % g.tilesM;    id /= g.tilesM;
+    const int tn = id % g.tilesN;    id /= g.tilesN;
+    const int which = id;
+    const int m0 = tm * GBM, n0 = tn * GBN;
+    const int step0 = split * g.steps_per_split;
+    int step1 = step0 + g.steps_per_split;
+    if (step1 > g.total_steps) step1 = g.total_steps;
+
+    const typename Pol::Ctx pc = Pol::make(g, which, m0, n0, tid);
+    const __amdgpu_buffer_rsrc_t rsA = pc.rsA, rsB = pc.rsB;
+    const int voffA = pc.voffA, voffB = pc.voffB;
+
+    // LDS addresses of this thread's writes and of this lane's fragment reads (per buffer: + G_STAGE)
+    unsigned char* const a_dst = lds + (tid >> 3) * GA_PITCH + 16 * (tid & 7);                    // + 32*q rows
+    const unsigned char* const fa_src = lds + (wm * 128 + l32) * GA_PITCH + 16 * half;           // + 32*i rows, + 32*s
+    // transposed B: thread = (8 positions b_kg, 8 columns b_cg); chunk of column c at c ^ ((c >> 4) & 15)
+    const int b_cg = tid & 31, b_kg = tid >> 5;
+    const int bt_dst0 = GA_STAGE + (b_kg * GBN + ((8 * b_cg) & ~15) + ((8 * (b_cg & 1)) ^ ((b_cg >> 1) & 15))) * 16;
+    unsigned char* const bd_dst = lds + GA_STAGE + (tid >> 3) * GA_PITCH + 16 * (tid & 7);       // direct B
+    const unsigned char* fb_src[4];
+    if (BT) {
+        const int c0 = wn * 128 + (l32 & 16) + ((l32 & 15) ^ ((8 * wn + (l32 >> 4)) & 15));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fb_src[j] = lds + GA_STAGE + (half * GBN + ((c0 ^ (2 * j)) + 32 * j)) * 16;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fb_src[j] = lds + GA_STAGE + (wn * 128 + 32 * j + l32) * GA_PITCH + 16 * half;
+    }
+
+    uint4 RA[2][8], RB[2][8];
+    uint4 FA[2][4], FB[2][4];
+    floatx16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = zero16();
+
+#define G_SB() __builtin_amdgcn_sched_barrier(0)
+#define G_MMA(set, i, j) acc[i][j] = mfma32(FA[set][i], FB[set][j], acc[i][j])
+#define G_LDA(set, buf, s, i) \
+    FA[set][i] = *(const uint4*)(fa_src + (buf) * G_STAGE + (32 * (i)) * GA_PITCH + 32 * (s))
+#define G_LDB(set, buf, s, j) \
+    FB[set][j] = *(const uint4*)(fb_src[j] + (buf) * G_STAGE + (BT ? ((2 * (s)) * GBN) * 16 : 32 * (s)))
+
+    // store B row q of the staging set into LDS buffer `buf`
+    auto store_b = [&](const uint4 (&rb)[8], int buf, int q) {
+        if (BT) {
+            // transpose 8 positions x 8 columns held in rb[0..7]; column q becomes one 16-byte chunk
+            const unsigned sel = (q & 1) ? 0x07060302u : 0x05040100u;
+            const int w = q >> 1;
+            auto dw = [&](const uint4& v) -> uint32_t { return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w)); };
+            uint4 o;
+            o.x = __builtin_amdgcn_perm(dw(rb[1]), dw(rb[0]), sel);
+            o.y = __builtin_amdgcn_perm(dw(rb[3]), dw(rb[2]), sel);
+            o.z = __builtin_amdgcn_perm(dw(rb[5]), dw(rb[4]), sel);
+            o.w = __builtin_amdgcn_perm(dw(rb[7]), dw(rb[6]), sel);
+            *(uint4*)(lds + ((bt_dst0 ^ (16 * q)) + buf * G_STAGE)) = o;
+        } else {
+            *(uint4*)(bd_dst + buf * G_STAGE + (32 * q) * GA_PITCH) = rb[q];
+        }
+    };
+
+    auto run_step = [&](auto par_c, int step_load) {
+        constexpr int PAR = decltype(par_c)::value;
+        const int sA = Pol::a_soff(pc, step_load), sB = Pol::b_soff(pc, step_load);
+#define G_CHUNK(PH, q, i0, j0, i1, j1, LD)                                                      \
+        {                                                                                       \
+            constexpr int cur = (PH) & 1, nxt = cur ^ 1, ns = ((PH) + 1) & 3;                   \
+            constexpr int pbuf = (PH) == 3 ? (PAR ^ 1) : PAR;                                   \
+            G_MMA(cur, i0, j0); G_MMA(cur, i1, j1);                                             \
+            LD(nxt, pbuf, ns, (q) >> 1);                                                        \
+            if ((PH) == 0) {                                                                    \
+                RA[PAR][q] = buf_ld16(rsA, voffA, sA + (q) * pc.a_qstride);                     \
+                RB[PAR][q] = buf_ld16(rsB, voffB, sB + (q) * pc.b_qstride);                     \
+            }                                                                                   \
+            if ((PH) == 2) {                                                                    \
+                *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * (q)) * GA_PITCH) = RA[PAR ^ 1][q]; \
+                store_b(RB[PAR ^ 1], PAR ^ 1, q);                                               \
+            }                                                                                   \
+            G_SB();                                                                             \
+        }
+#define G_PHASE(PH)                               \
+        G_CHUNK(PH, 0, 0, 0, 0, 1, G_LDA)         \
+        G_CHUNK(PH, 1, 1, 0, 1, 1, G_LDB)         \
+        G_CHUNK(PH, 2, 0, 2, 1, 2, G_LDA)         \
+        G_CHUNK(PH, 3, 0, 3, 1, 3, G_LDB)         \
+        G_CHUNK(PH, 4, 2, 0, 2, 1, G_LDA)         \
+        G_CHUNK(PH, 5, 3, 0, 3, 1, G_LDB)         \
+        G_CHUNK(PH, 6, 2, 2, 3, 2, G_LDA)         \
+        G_CHUNK(PH, 7, 2, 3, 3, 3, G_LDB)
+        G_PHASE(0)
+        G_PHASE(1)
+        G_PHASE(2)
+        __syncthreads();              // next buffer complete; nobody still reads it
+        G_SB();
+        G_PHASE(3)
+#undef G_PHASE
+#undef G_CHUNK
+    };
+
+    if (step0 < step1) {
+        // prologue: step0 through registers into buffer 0, step0 + 1 into staging set 1
+        {
+            const int sA = Pol::a_soff(pc, step0), sB = Pol::b_soff(pc, step0);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                RA[0][q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
+                RB[0][q] = buf_ld16(rsB, voffB, sB + q * pc.b_qstride);
+            }
+        }
+        {
+            const int sA = Pol::a_soff(pc, step0 + 1), sB = Pol::b_soff(pc, step0 + 1);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                RA[1][q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
+                RB[1][q] = buf_ld16(rsB, voffB, sB + q * pc.b_qstride);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            *(uint4*)(a_dst + (32 * q) * GA_PITCH) = RA[0][q];
+            store_b(RB[0], 0, q);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { G_LDA(0, 0, 0, i); G_LDB(0, 0, 0, i); }
+        G_SB();
+        int step = step0;
+        for (; step + 1 < step1; step += 2) {
+            run_step(IC<0>{}, step + 2);
+            run_step(IC<1>{}, step + 3);
+        }
+        if (step < step1) run_step(IC<0>{}, step + 2);
+    }
+#undef G_SB
+#undef G_MMA
+#undef G_LDA
+#undef G_LDB
+
+    // epilogue: this lane holds, for every 32 x 32 tile (i, j), column 32*j + l32 and rows
+    // 32*i + 8*(e/4) + 4*half + e%4, e = 0..15, in groups of four consecutive rows
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int col = n0 + wn * 128 + 32 * j + l32;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = m0 + wm * 128 + 32 * i + 8 * q + 4 * half;
+                Pol::store4(g, pc, which, split, row, col, acc[i][j][4 * q], acc[i][j][4 * q + 1],
+                            acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Policies.  Common contract:
+//   Ctx make(g, which, m0, n0, tid)   descriptors and this thread's byte offsets
+//   a_soff / b_soff (ctx, step)       wave-uniform byte offset of a reduction step
+//   a_qstride / b_qstride             byte offset between the 8 loads (q = 0..7) of one step
+//   store4(..., row, col, v0..v3)     result rows row..row+3 of column col
+// A tile: thread loads 16-byte chunk (tid & 7) of rows (tid >> 3) + 32*q.
+// B transposed: thread loads columns 8*(tid & 31).. of positions 8*(tid >> 5) + q.
+// B direct: like A, rows being the columns of the result.
+// ---------------------------------------------------------------------------
+struct PolicyCtxBase {
+    __amdgpu_buffer_rsrc_t rsA, rsB;
+    int voffA, voffB, a_qstride, b_qstride;
+};
+
+// K' = E K: rows = k projected slots, columns = (head, t), reduction = sequence positions.
+template <int D>
+struct ProjPolicy {
+    static constexpr bool B_TRANSPOSE = true;
+    struct Ctx : PolicyCtxBase { int bh0; };
+    static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
+        Ctx c;
+        constexpr int hpt = GBN / D;
+        c.bh0 = (n0 / GBN) * hpt;
+        int tile_heads = g.BH - c.bh0;
+        if (tile_heads > hpt) tile_heads = hpt;
+        c.rsA = make_rsrc(g.A[which], (unsigned)g.k * (unsigned)g.n * 2u);
+        c.rsB = make_rsrc(g.B[which] + (long)c.bh0 * g.n * D, (unsigned)tile_heads * (unsigned)g.n * (unsigned)(D * 2));
+        c.voffA = ((m0 + (tid >> 3)) * g.n + 8 * (tid & 7)) * 2;
+        c.a_qstride = 64 * g.n;
+        const int b_col = 8 * (tid & 31), b_kg = tid >> 5;
+        c.voffB = (((b_col / D) * g.n + 8 * b_kg) * D + (b_col % D)) * 2;
+        c.b_qstride = D * 2;
+        return c;
+    }
+    static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
+    static __device__ __forceinline__ int b_soff(const Ctx&, int step) { return step * (GBK * D * 2); }
+    static __device__ __forceinline__ void store4(const GemmParams& g, const Ctx& c, int which, int split, int row,
+                                                  int col, float v0, float v1, float v2, float v3) {
+        const int cl = col % GBN;
+        const int bh = c.bh0 + cl / D;
+        if (bh >= g.BH) return;
+        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + ((long)bh * g.k + row) * D + (cl % D);
+        if (row < g.k) o[0] = v0;
+        if (row + 1 < g.k) o[D] = v1;
+        if (row + 2 < g.k) o[2 * D] = v2;
+        if (row + 3 < g.k) o[3 * D] = v3;
+    }
+};
+
+// dX = E^T dX': rows = (head, t) of the (BH*D x kp) image of (dX')^T, columns = sequence positions,
+// reduction = projected slots (kp = k rounded up to 64, image zero-padded; rows of E past k read 0).
+template <int D>
+struct GradXPolicy {
+    static constexpr bool B_TRANSPOSE = true;
+    struct Ctx : PolicyCtxBase {};
+    static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
+        Ctx c;
+        c.rsA = make_rsrc(g.A[which], (unsigned)(g.BH * D) * (unsigned)g.kp * 2u);
+        c.rsB = make_rsrc(g.B[which], (unsigned)g.k * (unsigned)g.n * 2u);
+        c.voffA = ((m0 + (tid >> 3)) * g.kp + 8 * (tid & 7)) * 2;
+        c.a_qstride = 64 * g.kp;
+        c.voffB = ((8 * (tid >> 5)) * g.n + n0 + 8 * (tid & 31)) * 2;
+        c.b_qstride = g.n * 2;
+        return c;
+    }
+    static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
+    static __device__ __forceinline__ int b_soff(const Ctx& c, int step) { return step * GBK * c.b_qstride; }
+    static __device__ __forceinline__ void store4(const GemmParams& g, const Ctx&, int which, int, int row, int col,
+                                                  float v0, float v1, float v2, float v3) {
+        if (col >= g.n || row >= g.BH * D) return;      // rows come in aligned groups of 4 inside one head
+        const int bh = row / D, t = row % D;
+        uint2 v;
+        v.x = pack_bf16(v0, v1);
+        v.y = pack_bf16(v2, v3);
+        *(uint2*)((uint16_t*)g.C[which] + ((long)bh * g.n + col) * D + t) = v;
+    }
+};
+
+// dE = sum_bh dX' X^T: rows = projected slots of the (BH, kp, D) image of dX', columns = sequence
+// positions, reduction = (head, t) pairs, 64 of them per step.
+template <int D>
+struct GradEPolicy {
+    static constexpr bool B_TRANSPOSE = false;
+    struct Ctx : PolicyCtxBase { int a_batch, b_batch; };
+    static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
+        Ctx c;
+        c.rsA = make_rsrc(g.A[which], (unsigned)g.BH * (unsigned)g.kp * (unsigned)(D * 2));
+        c.rsB = make_rsrc(g.B[which], (unsigned)g.BH * (unsigned)g.n * (unsigned)(D * 2));
+        c.voffA = ((m0 + (tid >> 3)) * D + 8 * (tid & 7)) * 2;
+        c.a_qstride = 32 * D * 2;
+        c.voffB = ((n0 + (tid >> 3)) * D + 8 * (tid & 7)) * 2;
+        c.b_qstride = 32 * D * 2;
+        c.a_batch = g.kp * D * 2;
+        c.b_batch = g.n * D * 2;
+        return c;
+    }
+    static __device__ __forceinline__ int a_soff(const Ctx& c, int step) {
+        constexpr int spb = D / GBK;           // steps per head
+        return (step / spb) * c.a_batch + (step % spb) * (GBK * 2);
+    }
+    static __device__ __forceinline__ int b_soff(const Ctx& c, int step) {
+        constexpr int spb = D / GBK;
+        return (step / spb) * c.b_batch + (step % spb) * (GBK * 2);
+    }
+    static __device__ __forceinline__ void store4(const GemmParams& g, const Ctx&, int which, int split, int row,
+                                                  int col, float v0, float v1, float v2, float v3) {
+        if (col >= g.n) return;
+        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + (long)row * g.n + col;
+        if (row < g.k) o[0] = v0;
+        if (row + 1 < g.k) o[g.n] = v1;
+        if (row + 2 < g.k) o[2 * (long)g.n] = v2;
+        if (row + 3 < g.k) o[3 * (long)g.n] = v3;
+    }
+};
+
+template <class Pol>
+static inline flurka_status launch_gemm_mfma(const GemmParams& g, hipStream_t s) {
+    auto kern = gemm_mfma_kernel<Pol>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS) != hipSuccess)
+        return FLURKA_ERR_LAUNCH;
+    const int grid = g.tilesM * g.tilesN * 2 * g.splits;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G_LDS, s, g);
+    if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH;
+    return FLURKA_OK;
+}
+
+}  // namespace flurka

@@ -481,9 +481,11 @@ flurka_status generic_backward(const Problem& p, const BwdArgs& a, hipStream_t s
     return generic_backward_from(p, a, s, 0);
 }
 
-// With `query_done` the caller has already written dQ and left dS, dz in the workspace slots of
-// the generic layout; only the key side and the four sequence-length GEMMs remain.
-flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStream_t s, int query_done) {
+// `done` bit 0: the caller has already written dQ and left dS, dz in the workspace slots of the
+// generic layout.  Bit 1: stop after the key side (dK', dV' in the workspace); the caller runs the
+// four sequence-length GEMMs itself.
+flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStream_t s, int done) {
+    const int query_done = done & 1;
     const CtxLayout L = ctx_layout(p);
     const GenericWs W = generic_ws_layout(p, 1);
     const float* Kp = a.ctx + L.Kp;
@@ -614,6 +616,7 @@ flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStrea
     }
 
     stage_end(s, STAGE_BWD_KEY);
+    if (done & 2) return FLURKA_OK;
 
     // dK = E^T dK', dV = F^T dV'   (n x d per head)
     stage_begin(s);
