@@ -64,14 +64,23 @@ __global__ void bwd_pack_kernel(uint16_t* St, uint16_t* Sp, float* zp, float* cp
     }
 }
 
-__global__ void bwd_pack_omega_kernel(uint16_t* Wt, const uint16_t* omega, int m, int d, long total) {
+//   Wpair (m/2 x d) dwords: {omega[2p][t], omega[2p+1][t]}   B operand of dK' = dUk omega
+__global__ void bwd_pack_omega_kernel(uint16_t* Wt, uint32_t* Wpair, const uint16_t* omega, int m, int d,
+                                      long total) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const long h = idx / ((long)m * d);
     const int rem = (int)(idx % ((long)m * d));
-    const int t = rem / m, slot = rem % m;
-    const int f = (slot & ~15) + slot_to_elem16(slot & 15);
-    Wt[idx] = omega[(h * m + f) * d + t];
+    {
+        const int t = rem / m, slot = rem % m;
+        const int f = (slot & ~15) + slot_to_elem16(slot & 15);
+        Wt[idx] = omega[(h * m + f) * d + t];
+    }
+    if (rem < (m / 2) * d) {
+        const int pr = rem / d, t = rem % d;
+        Wpair[h * (m / 2) * d + rem] =
+            (uint32_t)omega[(h * m + 2 * pr) * d + t] | ((uint32_t)omega[(h * m + 2 * pr + 1) * d + t] << 16);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -403,31 +412,238 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
         }
 }
 
-// dst[bh, i] = sum_r src[bh, r, i]
-__global__ void sum_ranges_kernel(float* dst, const float* src, long per_head, int R, long total) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const long bh = idx / per_head, i = idx % per_head;
-    const float* p = src + bh * R * per_head + i;
-    float s = 0.f;
-    for (int r = 0; r < R; ++r) s += p[(long)r * per_head];
-    dst[idx] = s;
+// x = hi + lo, both bf16
+__device__ __forceinline__ void bsplit2(float x, uint16_t& hi, uint16_t& lo) {
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
 
-// dK', dV' (fp32, (BH, k, d)) -> bf16 operand images of the two gradient GEMMs, zero padded to kp rows:
-//   img  (BH, kp, d)      rows = projected slots               (A operand of dE = sum dK' K^T)
-//   imgT (BH * d, kp)     rows = (head, t), slots contiguous   (A operand of dK = E^T dK')
-__global__ void grad_images_kernel(uint16_t* img, uint16_t* imgT, const float* dXp, int k, int kp, int d,
-                                   long total) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+// Sums the query ranges of dS, dz and writes the operand images of the key-side kernel:
+//   dSimg  2 x (BH, mf, d) bf16 (hi, lo)              A operand of dPhiK^T = dS V'^T
+//   dSpair 2 x (BH, mf/2, d) dwords (hi, lo)          B operand of dV' = PhiK dS, two features per dword
+//   dz     (BH, mf) fp32
+__global__ void bwd_merge_kernel(uint16_t* dSimg, uint32_t* dSpair, float* dz, const float* dSpart,
+                                 const float* dzpart, int R, int mf, int d, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;    // (bh, feature pair, t)
     if (idx >= total) return;
     const int t = (int)(idx % d);
     const long rest = idx / d;
-    const int r = (int)(rest % kp);
-    const long bh = rest / kp;
-    const uint16_t v = r < k ? f32_to_bf16(dXp[(bh * k + r) * d + t]) : (uint16_t)0;
-    img[idx] = v;
-    imgT[(bh * d + t) * kp + r] = v;
+    const int pr = (int)(rest % (mf / 2));
+    const long bh = rest / (mf / 2);
+    float s0 = 0.f, s1 = 0.f;
+    for (int r = 0; r < R; ++r) {
+        const float* p = dSpart + ((bh * R + r) * mf + 2 * pr) * d + t;
+        s0 += p[0];
+        s1 += p[d];
+    }
+    uint16_t h0, l0, h1, l1;
+    bsplit2(s0, h0, l0);
+    bsplit2(s1, h1, l1);
+    const long plane = total * 2;                     // BH * mf * d
+    const long i0 = (bh * mf + 2 * pr) * d + t;
+    dSimg[i0] = h0; dSimg[i0 + d] = h1;
+    dSimg[plane + i0] = l0; dSimg[plane + i0 + d] = l1;
+    dSpair[idx] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    dSpair[total + idx] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    if (t == 0) {
+        float z0 = 0.f, z1 = 0.f;
+        for (int r = 0; r < R; ++r) {
+            z0 += dzpart[(bh * R + r) * mf + 2 * pr];
+            z1 += dzpart[(bh * R + r) * mf + 2 * pr + 1];
+        }
+        dz[bh * mf + 2 * pr] = z0;
+        dz[bh * mf + 2 * pr + 1] = z1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// bwd_key: one wavefront per (head, 32 keys), lane = key.  Recomputes PhiK^T = exp(e^T - c) tile by
+// tile with the forward's split-precision exponent, then
+//     dPhiK^T = dS V'^T + dz 1^T       dUk = dPhiK * PhiK       rs_r = sum_j dUk_rj
+//     dV' = PhiK dS                    dK' = dUk omega - rs_r k'_r
+// with PhiK and dUk taken from the accumulator registers as A operands.  Every operand that enters a
+// product whose result is later differenced is a two- or three-term bf16 split (fp32-level accuracy);
+// the results leave as the bf16 images the two gradient GEMMs read.
+// ---------------------------------------------------------------------------
+struct BwdKeyArgs {
+    const float* Kp; const float* Vp; const float* c;      // ctx
+    const uint16_t* omega; const uint32_t* Wpair;
+    const uint16_t* dSimg; const uint32_t* dSpair; const float* dz;
+    uint16_t* img;     // 2 x (BH, kp, d): dK' then dV'
+    uint16_t* imgT;    // 2 x (BH * d, kp)
+    long omega_head_stride;
+    int BH, H, k, kp, mf;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
+    constexpr int KS = D / 16, TT = D / 32;
+    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int KT = a.kp / 32;
+    const long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (wid >= (long)a.BH * KT) return;
+    const int kt = (int)(wid % KT);
+    const int bh = (int)(wid / KT);
+    const int FT = a.mf / 32;
+    const int key = 32 * kt + l32;
+    const bool live = key < a.k;
+    const int krow = live ? key : a.k - 1;
+    const long img_plane = (long)a.BH * a.kp * D;
+    const long ds_plane = (long)a.BH * a.mf * D;
+    const long pair_plane = ds_plane / 2;
+
+    // this key's k' and v' (8 consecutive coordinates per step), split into bf16 terms: B operands
+    uint4 kb[3][KS], vb[2][KS];
+    float nrm = 0.f;
+    {
+        const float* kg = a.Kp + ((long)bh * a.k + krow) * D + 8 * half;
+        const float* vg = a.Vp + ((long)bh * a.k + krow) * D + 8 * half;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            float kv[8], vv[8];
+            *(float4*)&kv[0] = *(const float4*)(kg + 16 * s);
+            *(float4*)&kv[4] = *(const float4*)(kg + 16 * s + 4);
+            *(float4*)&vv[0] = *(const float4*)(vg + 16 * s);
+            *(float4*)&vv[4] = *(const float4*)(vg + 16 * s + 4);
+            uint32_t kh[4], km[4], kl[4], vh[4], vl[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint16_t h0, m0, l0, h1, m1, l1;
+                h0 = f32_to_bf16(kv[2 * e]);     { const float r = kv[2 * e] - bf16_to_f32(h0);         m0 = f32_to_bf16(r); l0 = f32_to_bf16(r - bf16_to_f32(m0)); }
+                h1 = f32_to_bf16(kv[2 * e + 1]); { const float r = kv[2 * e + 1] - bf16_to_f32(h1);     m1 = f32_to_bf16(r); l1 = f32_to_bf16(r - bf16_to_f32(m1)); }
+                kh[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                km[e] = (uint32_t)m0 | ((uint32_t)m1 << 16);
+                kl[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+                nrm = fmaf(kv[2 * e], kv[2 * e], nrm);
+                nrm = fmaf(kv[2 * e + 1], kv[2 * e + 1], nrm);
+                uint16_t a0, b0, a1, b1;
+                bsplit2(vv[2 * e], a0, b0);
+                bsplit2(vv[2 * e + 1], a1, b1);
+                vh[e] = (uint32_t)a0 | ((uint32_t)a1 << 16);
+                vl[e] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+            }
+            kb[0][s] = make_uint4(kh[0], kh[1], kh[2], kh[3]);
+            kb[1][s] = make_uint4(km[0], km[1], km[2], km[3]);
+            kb[2][s] = make_uint4(kl[0], kl[1], kl[2], kl[3]);
+            vb[0][s] = make_uint4(vh[0], vh[1], vh[2], vh[3]);
+            vb[1][s] = make_uint4(vl[0], vl[1], vl[2], vl[3]);
+        }
+        nrm += __shfl_xor(nrm, 32, 64);
+        nrm = live ? 0.5f * nrm : INFINITY;       // padding keys: exponent -inf, PhiK = 0
+    }
+
+    floatx16 accV[TT], accK[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) { accV[t] = zero16(); accK[t] = zero16(); }
+    float rs = 0.f;
+    const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)l32 * D + 8 * half;
+    const uint16_t* dsg = a.dSimg + ((long)bh * a.mf + l32) * D + 8 * half;
+    const uint32_t* dpg = a.dSpair + (long)bh * (a.mf / 2) * D + l32;
+    const uint32_t* wpg = a.Wpair + (long)(bh % a.H) * (a.omega_head_stride / 2) + l32;
+    const float* cg = a.c + (long)bh * a.mf + 4 * half;
+    const float* zg = a.dz + (long)bh * a.mf + 4 * half;
+
+    for (int ft = 0; ft < FT; ++ft) {
+        // e^T tile (features x keys) and dPhiK^T tile; element g <-> feature 32*ft + 8*(g/4) + 4*half + g%4
+        floatx16 e = zero16(), dp;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 zv = *(const float4*)(zg + 32 * ft + 8 * q);
+            dp[4 * q] = zv.x; dp[4 * q + 1] = zv.y; dp[4 * q + 2] = zv.z; dp[4 * q + 3] = zv.w;
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const uint4 wa = ld16(og + (long)(32 * ft) * D + 16 * s);
+            e = mfma32(wa, kb[0][s], e);
+            e = mfma32(wa, kb[1][s], e);
+            e = mfma32(wa, kb[2][s], e);
+            const uint4 dh = ld16(dsg + (long)(32 * ft) * D + 16 * s);
+            const uint4 dl = ld16(dsg + ds_plane + (long)(32 * ft) * D + 16 * s);
+            dp = mfma32(dh, vb[0][s], dp);
+            dp = mfma32(dl, vb[0][s], dp);
+            dp = mfma32(dh, vb[1][s], dp);
+        }
+        uint32_t ph[8], pl[8], uh[8], ul[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 cv = *(const float4*)(cg + 32 * ft + 8 * q);
+            const float cc[4] = {cv.x, cv.y, cv.z, cv.w};
+            float phi[4], du[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                phi[i] = fast_exp2((e[4 * q + i] - nrm - cc[i]) * LOG2E);
+                du[i] = dp[4 * q + i] * phi[i];
+                rs += du[i];
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint16_t h0, l0, h1, l1;
+                bsplit2(phi[2 * i], h0, l0);
+                bsplit2(phi[2 * i + 1], h1, l1);
+                ph[2 * q + i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                pl[2 * q + i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+                bsplit2(du[2 * i], h0, l0);
+                bsplit2(du[2 * i + 1], h1, l1);
+                uh[2 * q + i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                ul[2 * q + i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            }
+        }
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            const uint4 pah = {ph[4 * sp], ph[4 * sp + 1], ph[4 * sp + 2], ph[4 * sp + 3]};
+            const uint4 pal = {pl[4 * sp], pl[4 * sp + 1], pl[4 * sp + 2], pl[4 * sp + 3]};
+            const uint4 uah = {uh[4 * sp], uh[4 * sp + 1], uh[4 * sp + 2], uh[4 * sp + 3]};
+            const uint4 ual = {ul[4 * sp], ul[4 * sp + 1], ul[4 * sp + 2], ul[4 * sp + 3]};
+            // B operands: columns t = 32*tt + l32, feature pairs 16*ft + 8*sp + {0,1,4,5} + 2*half
+            const long prow = (long)(16 * ft + 8 * sp + 2 * half) * D;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const uint32_t* dq = dpg + prow + 32 * tt;
+                const uint32_t* wq = wpg + prow + 32 * tt;
+                const uint4 bh4 = {dq[0], dq[D], dq[4 * D], dq[5 * D]};
+                const uint4 bl4 = {dq[pair_plane], dq[pair_plane + D], dq[pair_plane + 4 * D], dq[pair_plane + 5 * D]};
+                const uint4 bw4 = {wq[0], wq[D], wq[4 * D], wq[5 * D]};
+                accV[tt] = mfma32(pah, bh4, accV[tt]);
+                accV[tt] = mfma32(pal, bh4, accV[tt]);
+                accV[tt] = mfma32(pah, bl4, accV[tt]);
+                accK[tt] = mfma32(uah, bw4, accK[tt]);
+                accK[tt] = mfma32(ual, bw4, accK[tt]);
+            }
+        }
+    }
+    rs += __shfl_xor(rs, 32, 64);
+
+    // results: this lane holds column t = 32*tt + l32 and rows (keys) 32*kt + 8*(g/4) + 4*half + g%4
+    uint16_t* imgK = a.img;
+    uint16_t* imgV = a.img + img_plane;
+    uint16_t* imgTK = a.imgT;
+    uint16_t* imgTV = a.imgT + img_plane;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r0 = 32 * kt + 8 * q + 4 * half;               // four consecutive keys r0..r0+3
+        float rsq[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rsq[i] = __shfl(rs, 8 * q + 4 * half + i, 64);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const int t = 32 * tt + l32;
+            float dk[4], dv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = r0 + i;
+                const float kprt = r < a.k ? a.Kp[((long)bh * a.k + r) * D + t] : 0.f;
+                dk[i] = accK[tt][4 * q + i] - rsq[i] * kprt;
+                dv[i] = accV[tt][4 * q + i];
+                imgK[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dk[i]);
+                imgV[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dv[i]);
+            }
+            uint2 pk, pv;
+            pk.x = pack_bf16(dk[0], dk[1]); pk.y = pack_bf16(dk[2], dk[3]);
+            pv.x = pack_bf16(dv[0], dv[1]); pv.y = pack_bf16(dv[2], dv[3]);
+            *(uint2*)(imgTK + ((long)bh * D + t) * a.kp + r0) = pk;
+            *(uint2*)(imgTV + ((long)bh * D + t) * a.kp + r0) = pv;
+        }
+    }
 }
 
 // dst (bf16) = sum over splits of src (fp32)
@@ -492,8 +708,8 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
 }
 
 struct FastBwdWs {
-    size_t St, Sp, Wt, zp, cp, lse, delta, dSpart, dzpart, img, imgT, epart, generic, total;   // byte offsets
-    int kp;
+    size_t St, Sp, Wt, Wpair, zp, cp, lse, delta, dSpart, dzpart, dSimg, dSpair, dz, img, imgT, epart, total;
+    int kp;      // k rounded up to whole 64-slot reduction steps of the gradient GEMMs
 };
 
 static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
@@ -504,18 +720,21 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     W.St = o;     o += round_up(BH * p.d * p.mf * 2, 256);
     W.Sp = o;     o += round_up(BH * p.mf * p.d * 2, 256);
     W.Wt = o;     o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
+    W.Wpair = o;  o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
     W.zp = o;     o += round_up(BH * p.mf * 4, 256);
     W.cp = o;     o += round_up(BH * p.mf * 4, 256);
     W.lse = o;    o += round_up(BH * p.n * 4, 256);
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
     W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
+    W.dSimg = o;  o += round_up(2 * BH * p.mf * p.d * 2, 256);
+    W.dSpair = o; o += round_up(2 * BH * p.mf * p.d * 2, 256);
+    W.dz = o;     o += round_up(BH * p.mf * 4, 256);
     W.kp = (p.k + 63) / 64 * 64;
     const GradEPlan e = grad_e_plan(p);
     W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);        // dK' then dV'
     W.imgT = o;   o += round_up(2 * BH * W.kp * p.d * 2, 256);
     W.epart = o;  o += round_up(2 * (size_t)e.splits * p.k * p.n * 4, 256);   // dE then dF partials
-    W.generic = o; o += generic_ws_layout(p, 1).total * sizeof(float);
     W.total = o;
     return W;
 }
@@ -535,10 +754,8 @@ static flurka_status launch_bwd_x(const BwdXArgs& xa, int grid, int ldsb, hipStr
 flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     const CtxLayout L = ctx_layout(p);
     const FastBwdWs W = fast_bwd_ws_layout(p);
-    const GenericWs GW = generic_ws_layout(p, 1);
     const BwdYPlan y = bwd_y_plan(p);
     unsigned char* wsb = (unsigned char*)a.ws;
-    float* gws = (float*)(wsb + W.generic);
     const long omega_stride = p.omega_per_head ? (long)p.m * p.d : 0;
     flurka_status st;
     {
@@ -550,7 +767,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         FLURKA_CHECK_LAUNCH();
         const long wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
         hipLaunchKernelGGL(bwd_pack_omega_kernel, grid1d(wtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Wt),
-                           (const uint16_t*)a.omega, p.m, p.d, wtotal);
+                           (uint32_t*)(wsb + W.Wpair), (const uint16_t*)a.omega, p.m, p.d, wtotal);
         FLURKA_CHECK_LAUNCH();
 
         BwdXArgs xa{};
@@ -581,30 +798,32 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, grid1d(waves, 4), dim3(256), 0, s, ya);
         else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, grid1d(waves, 4), dim3(256), 0, s, ya);
         FLURKA_CHECK_LAUNCH();
-        const long st_total = (long)p.BH * p.mf * p.d, z_total = (long)p.BH * p.mf;
-        hipLaunchKernelGGL(sum_ranges_kernel, grid1d(st_total, 256), dim3(256), 0, s, gws + GW.dS,
-                           (const float*)ya.dSpart, (long)p.mf * p.d, y.R, st_total);
-        FLURKA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(sum_ranges_kernel, grid1d(z_total, 256), dim3(256), 0, s, gws + GW.dz,
-                           (const float*)ya.dzpart, (long)p.mf, y.R, z_total);
-        FLURKA_CHECK_LAUNCH();
     }
-    // key side (generic kernels): dK', dV' in fp32
-    BwdArgs rest = a;
-    rest.ws = gws;
-    if ((st = generic_backward_from(p, rest, s, 3)) != FLURKA_OK) return st;
-
     const size_t img_elems = (size_t)p.BH * W.kp * p.d;
     uint16_t* img = (uint16_t*)(wsb + W.img);
     uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
     {
+        StageScope sc(s, STAGE_BWD_KEY);
+        const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
+        hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.dSimg),
+                           (uint32_t*)(wsb + W.dSpair), (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
+                           (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
+        FLURKA_CHECK_LAUNCH();
+        BwdKeyArgs ka{};
+        ka.Kp = a.ctx + L.Kp; ka.Vp = a.ctx + L.Vp; ka.c = a.ctx + L.c;
+        ka.omega = (const uint16_t*)a.omega; ka.Wpair = (const uint32_t*)(wsb + W.Wpair);
+        ka.dSimg = (const uint16_t*)(wsb + W.dSimg); ka.dSpair = (const uint32_t*)(wsb + W.dSpair);
+        ka.dz = (const float*)(wsb + W.dz);
+        ka.img = img; ka.imgT = imgT;
+        ka.omega_head_stride = omega_stride;
+        ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kp = W.kp; ka.mf = p.mf;
+        const long kwaves = (long)p.BH * (W.kp / 32);
+        if (p.d == 64) hipLaunchKernelGGL(bwd_key_kernel<64>, grid1d(kwaves, 4), dim3(256), 0, s, ka);
+        else           hipLaunchKernelGGL(bwd_key_kernel<128>, grid1d(kwaves, 4), dim3(256), 0, s, ka);
+        FLURKA_CHECK_LAUNCH();
+    }
+    {
         StageScope sc(s, STAGE_BWD_DKDV);
-        hipLaunchKernelGGL(grad_images_kernel, grid1d((long)img_elems, 256), dim3(256), 0, s, img, imgT,
-                           (const float*)(gws + GW.dKp), p.k, W.kp, p.d, (long)img_elems);
-        FLURKA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(grad_images_kernel, grid1d((long)img_elems, 256), dim3(256), 0, s, img + img_elems,
-                           imgT + img_elems, (const float*)(gws + GW.dVp), p.k, W.kp, p.d, (long)img_elems);
-        FLURKA_CHECK_LAUNCH();
         GemmParams gp{};       // dK = E^T dK', dV = F^T dV'
         gp.A[0] = imgT; gp.A[1] = imgT + img_elems;
         gp.B[0] = (const uint16_t*)a.E; gp.B[1] = (const uint16_t*)a.F;
