@@ -24,7 +24,7 @@ namespace flurka {
 
 static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total + block - 1) / block)); }
 
-constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LOG2E = FLURKA_LOG2E;
 
 // position p (0..15) inside a group of 16 operand slots <-> element offset 8*(e/4) + 4*h + e%4 with
 // p = 8*h + e: the order in which a 32x32 accumulator hands 16 consecutive rows to the next MFMA
@@ -177,58 +177,8 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
 #pragma unroll
         for (int t = 0; t < TT; ++t) accN[t] = zero16();
         float den = 0.f, mu = -INFINITY;
-        for (int ft = 0; ft < FT; ++ft) {
-            floatx16 u;
-            {
-                const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = ct[q];
-                    u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
-                }
-            }
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-                u = mfma32(*(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), qf[s], u);
-            float tmax = fmaxf(fmaxf(u[0], u[1]), u[2]);
-#pragma unroll
-            for (int g = 3; g < 15; g += 2) tmax = fmaxf(fmaxf(tmax, u[g]), u[g + 1]);
-            tmax = fmaxf(tmax, u[15]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            if (tmax > mu) {
-                const float sc = fast_exp2((mu - tmax) * LOG2E);
-                mu = tmax;
-                den *= sc;
-#pragma unroll
-                for (int t = 0; t < TT; ++t)
-#pragma unroll
-                    for (int g = 0; g < 16; ++g) accN[t][g] *= sc;
-            }
-            const float nshift = -mu * LOG2E;
-            const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
-            uint32_t pk[8];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 zv = zt[q];
-                const float p0 = fast_exp2(fmaf(u[4 * q], LOG2E, nshift));
-                const float p1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, nshift));
-                const float p2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, nshift));
-                const float p3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, nshift));
-                pk[2 * q] = pack_bf16(p0, p1);
-                pk[2 * q + 1] = pack_bf16(p2, p3);
-                den = fmaf(p0, zv.x, den); den = fmaf(p1, zv.y, den);
-                den = fmaf(p2, zv.z, den); den = fmaf(p3, zv.w, den);
-            }
-            const uint4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
-            const uint4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
-#pragma unroll
-            for (int t = 0; t < TT; ++t) {
-                const unsigned char* sp = ls + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
-                accN[t] = mfma32(*(const uint4*)sp, pb0, accN[t]);
-                accN[t] = mfma32(*(const uint4*)(sp + 32), pb1, accN[t]);
-            }
-        }
-        den += __shfl_xor(den, 32, 64);
+        forward_feature_pass<D>(lw, L::w_pitch, ls, s_pitch, lz, lc, FT, l32, half, qf, accN, den, mu);
+        den = half_sum(den);
         const float inv = 1.f / den;
         // g_i = G_i . out_i ; this lane holds t = 32*tt + 8*(g/4) + 4*half + g%4 of its query,
         // which are the 8-byte chunks of gf: step s = 2*tt + (g/8), chunk (g/4)%2
@@ -244,7 +194,7 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
                 gdot = fmaf(bf16_to_f32((uint16_t)(w1 & 0xffffu)), accN[t][4 * q + 2], gdot);
                 gdot = fmaf(bf16_to_f32((uint16_t)(w1 >> 16)), accN[t][4 * q + 3], gdot);
             }
-        gdot += __shfl_xor(gdot, 32, 64);
+        gdot = half_sum(gdot);
         const float gi = gdot * inv;                         // g_i
         const float lam = mu + __logf(den);                  // lambda_i
         if (valid && half == 0) {
@@ -399,7 +349,7 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
             }
         }
     }
-    dz += __shfl_xor(dz, 32, 64);
+    dz = half_sum(dz);
     const long po = ((long)bh * a.R + r) * a.mf;
     if (half == 0) a.dzpart[po + 32 * ft + l32] = dz;
     float* sp = a.dSpart + po * D;
@@ -528,7 +478,7 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
             vb[0][s] = make_uint4(vh[0], vh[1], vh[2], vh[3]);
             vb[1][s] = make_uint4(vl[0], vl[1], vl[2], vl[3]);
         }
-        nrm += __shfl_xor(nrm, 32, 64);
+        nrm = half_sum(nrm);
         nrm = live ? 0.5f * nrm : INFINITY;       // padding keys: exponent -inf, PhiK = 0
     }
 
@@ -611,7 +561,7 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
             }
         }
     }
-    rs += __shfl_xor(rs, 32, 64);
+    rs = half_sum(rs);
 
     // results: this lane holds column t = 32*tt + l32 and rows (keys) 32*kt + 8*(g/4) + 4*half + g%4
     uint16_t* imgK = a.img;

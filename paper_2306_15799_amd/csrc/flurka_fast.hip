@@ -117,7 +117,6 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
     if (row_end > a.n) row_end = a.n;
     constexpr int KS = D / 16;      // reduction steps over d
     constexpr int TT = D / 32;      // 32-row tiles of N^T
-    constexpr float LOG2E = 1.4426950408889634f;
 
     for (int row0 = row_begin + 32 * wave; row0 < row_end; row0 += 32 * 8) {
         // B operand of the first contraction: this lane's query row, 8 consecutive d per step
@@ -160,65 +159,9 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
             }
         } else {
             float mu = -INFINITY;     // running row maximum (same value in lanes l and l^32)
-            for (int ft = 0; ft < mf / 32; ++ft) {
-                // accumulator starts at the key side's per-feature shift: u_j + c_j is the true
-                // log-weight, and the add costs nothing
-                floatx16 u;
-                {
-                    const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 v = ct[q];
-                        u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
-                    }
-                }
-#pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const uint4 wa = *(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half);
-                    u = mfma32(wa, qf[s], u);
-                }
-                float tmax = fmaxf(fmaxf(u[0], u[1]), u[2]);
-#pragma unroll
-                for (int g = 3; g < 15; g += 2) tmax = fmaxf(fmaxf(tmax, u[g]), u[g + 1]);
-                tmax = fmaxf(tmax, u[15]);
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-                if (tmax > mu) {
-                    const float sc = fast_exp2((mu - tmax) * LOG2E);     // 0 on the first tile
-                    mu = tmax;
-                    den *= sc;
-#pragma unroll
-                    for (int t = 0; t < TT; ++t)
-#pragma unroll
-                        for (int g = 0; g < 16; ++g) accN[t][g] *= sc;
-                }
-                const float nshift = -mu * LOG2E;
-                const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
-                uint32_t pk[8];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 zv = zt[q];
-                    const float p0 = fast_exp2(fmaf(u[4 * q], LOG2E, nshift));
-                    const float p1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, nshift));
-                    const float p2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, nshift));
-                    const float p3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, nshift));
-                    pk[2 * q] = pack_bf16(p0, p1);
-                    pk[2 * q + 1] = pack_bf16(p2, p3);
-                    den = fmaf(p0, zv.x, den);
-                    den = fmaf(p1, zv.y, den);
-                    den = fmaf(p2, zv.z, den);
-                    den = fmaf(p3, zv.w, den);
-                }
-                const uint4 pb0 = {pk[0], pk[1], pk[2], pk[3]};
-                const uint4 pb1 = {pk[4], pk[5], pk[6], pk[7]};
-#pragma unroll
-                for (int t = 0; t < TT; ++t) {
-                    const unsigned char* sp = ls + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
-                    accN[t] = mfma32(*(const uint4*)sp, pb0, accN[t]);
-                    accN[t] = mfma32(*(const uint4*)(sp + 32), pb1, accN[t]);
-                }
-            }
+            forward_feature_pass<D>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu);
         }
-        den += __shfl_xor(den, 32, 64);
+        den = half_sum(den);
         const float inv = 1.f / den;
         if (valid) {
             uint16_t* og = a.out + head_off + (long)qrow * D;

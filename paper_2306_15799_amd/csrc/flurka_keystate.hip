@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
 #pragma unroll
             for (int g = 0; g < 16; ++g) c = fmaxf(c, e[g]);
         }
-        c = fmaxf(c, __shfl_xor(c, 32, 64));
+        c = half_max(c);
     }
 
     floatx16 accS[TT];
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
             }
         }
     }
-    zsum += __shfl_xor(zsum, 32, 64);
+    zsum = half_sum(zsum);
 
     const long po = ((long)bh * a.KR + kr) * a.mf;
     if (half == 0) {

@@ -41,4 +41,144 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *(const uint4*)p; }
 
+// Combine the values that lanes l and l ^ 32 hold (the two halves of a wavefront carry the two
+// halves of an MFMA reduction).  v_permlane32_swap exchanges the upper half of one register with the
+// lower half of another, so two copies of x become {lo, lo} and {hi, hi}: no LDS round trip.
+__device__ __forceinline__ float half_max(float x) {
+    const unsigned xi = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+    const unsigned xi = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+constexpr float FLURKA_LOG2E = 1.4426950408889634f;
+// The running row maximum is only raised when a tile exceeds it by more than this (natural log
+// units): weights may then be as large as exp(5) instead of 1, which costs nothing in fp32 or bf16
+// range, and almost every tile skips the rescaling of the accumulators.
+constexpr float FLURKA_LAZY_MAX = 5.0f;
+
+// Forward pass over all feature tiles for the 32 query rows of one wavefront (lane = query):
+//   u^T = omega q^T (accumulator starts at the key side's shift c_j) -> running max mu -> P^T = exp ->
+//   N^T += S^T P^T (P^T goes from the accumulator registers straight into the B operand),
+//   den += P z on the VALU.
+// An in-order wavefront overlaps its matrix and vector pipes only if the two kinds of instruction
+// alternate in program order, so the loop is software-pipelined by hand: iteration ft runs the exp
+// work of tile ft, and between those VALU groups issues the (dependent) MFMAs of u^T for tile ft + 1
+// and the MFMAs of N^T for tile ft; the maximum of tile ft + 1 is taken in the shadow of the last
+// N^T MFMAs.  sched_barrier(0) after each group pins the order.  The only branch is the (rare, see
+// FLURKA_LAZY_MAX) rescaling between iterations.
+// lw: omega [feature][D] (pitch w_pitch), ls: S^T [t][feature slot] (pitch s_pitch), lz, lc: z, c in
+// accumulator order; all in LDS.
+template <int D>
+__device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, int w_pitch, const unsigned char* ls,
+                                                     int s_pitch, const float* lz, const float* lc, int FT,
+                                                     int l32, int half, const uint4 (&qf)[D / 16],
+                                                     floatx16 (&accN)[D / 32], float& den, float& mu) {
+    constexpr int KS = D / 16, TT = D / 32;
+    constexpr int EPC = 16 / KS;                 // accumulator elements handled per group
+    const unsigned char* wrow = lw + l32 * w_pitch + 16 * half;        // + 32*ft rows, + 32*s
+    const unsigned char* srow = ls + l32 * s_pitch + 16 * half;        // + 32*t rows, + 64*ft (+32)
+
+    auto load_c = [&](int ft) -> floatx16 {
+        floatx16 u;
+        const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = ct[q];
+            u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
+        }
+        return u;
+    };
+    auto tile_max = [&](const floatx16& u) -> float {
+        float tmax = fmaxf(fmaxf(u[0], u[1]), u[2]);
+#pragma unroll
+        for (int g = 3; g < 15; g += 2) tmax = fmaxf(fmaxf(tmax, u[g]), u[g + 1]);
+        return half_max(fmaxf(tmax, u[15]));
+    };
+    auto maybe_rescale = [&](float tmax) {
+        if (tmax > mu + FLURKA_LAZY_MAX) {
+            const float sc = fast_exp2((mu - tmax) * FLURKA_LOG2E);     // 0 on the first tile
+            mu = tmax;
+            den *= sc;
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+#pragma unroll
+                for (int g = 0; g < 16; ++g) accN[t][g] *= sc;
+        }
+    };
+
+    // prologue: tile 0
+    floatx16 u = load_c(0);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) u = mfma32(*(const uint4*)(wrow + 32 * s), qf[s], u);
+    maybe_rescale(tile_max(u));
+
+    for (int ft = 0; ft < FT; ++ft) {
+        const int nft = ft + 1 < FT ? ft + 1 : ft;            // last iteration recomputes its own tile, unused
+        const float nshift = -mu * FLURKA_LOG2E;
+        floatx16 un = load_c(nft);
+        float zv[16];
+        {
+            const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = zt[q];
+                zv[4 * q] = v.x; zv[4 * q + 1] = v.y; zv[4 * q + 2] = v.z; zv[4 * q + 3] = v.w;
+            }
+        }
+        uint4 wa[KS], sa[2 * TT];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) wa[s] = *(const uint4*)(wrow + (32 * nft) * w_pitch + 32 * s);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            sa[2 * t] = *(const uint4*)(srow + (32 * t) * s_pitch + 64 * ft);
+            sa[2 * t + 1] = *(const uint4*)(srow + (32 * t) * s_pitch + 64 * ft + 32);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float p[16];
+        uint32_t pk[8];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            // one dependent MFMA of the next tile's u^T ...
+            un = mfma32(wa[s], qf[s], un);
+            // ... over the exp work of EPC elements of this tile
+#pragma unroll
+            for (int e = s * EPC; e < (s + 1) * EPC; ++e) {
+                p[e] = fast_exp2(fmaf(u[e], FLURKA_LOG2E, nshift));
+                den = fmaf(p[e], zv[e], den);
+            }
+#pragma unroll
+            for (int e = s * EPC; e < (s + 1) * EPC; e += 2) pk[e / 2] = pack_bf16(p[e], p[e + 1]);
+            // second half of the groups: N^T MFMAs with the first half of P^T (elements 0..7)
+            if (s >= KS / 2) {
+                constexpr int per = (TT + KS / 2 - 1) / (KS / 2);
+#pragma unroll
+                for (int j = 0; j < per; ++j) {
+                    const int t = (s - KS / 2) * per + j;
+                    if (t < TT) accN[t] = mfma32(sa[2 * t], make_uint4(pk[0], pk[1], pk[2], pk[3]), accN[t]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // N^T MFMAs with the second half of P^T, over the maximum of the next tile
+        const uint4 pb1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+        float tmax = fmaxf(fmaxf(un[0], un[1]), un[2]);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            accN[t] = mfma32(sa[2 * t + 1], pb1, accN[t]);
+            constexpr int per = (12 + TT - 1) / TT;          // elements 3..14 spread over the TT groups
+#pragma unroll
+            for (int g = 3 + t * per; g < 3 + (t + 1) * per && g < 15; ++g) tmax = fmaxf(tmax, un[g]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        tmax = half_max(fmaxf(tmax, un[15]));
+        if (ft + 1 < FT) maybe_rescale(tmax);
+        u = un;
+    }
+}
+
 }  // namespace flurka
