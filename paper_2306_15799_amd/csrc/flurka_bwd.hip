@@ -162,7 +162,8 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
         if (!valid) qrow = a.n - 1;
         const uint16_t* qg = a.Q + head_off + (long)qrow * D + 8 * half;
         const uint16_t* gg = a.G + head_off + (long)qrow * D + 4 * half;
-        uint4 qf[KS], gf[KS];
+        uint4 qf1[1][KS], gf[KS];
+        uint4 (&qf)[KS] = qf1[0];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             qf[s] = ld16(qg + 16 * s);
@@ -173,12 +174,14 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
         }
 
         // ---- pass 1: forward recompute -> D, out, g_i, lambda_i ----------------------------------
-        floatx16 accN[TT];
+        floatx16 accN1[1][TT];
+        floatx16 (&accN)[TT] = accN1[0];
 #pragma unroll
         for (int t = 0; t < TT; ++t) accN[t] = zero16();
-        float den = 0.f, mu = -INFINITY;
-        forward_feature_pass<D>(lw, L::w_pitch, ls, s_pitch, lz, lc, FT, l32, half, qf, accN, den, mu);
-        den = half_sum(den);
+        float den1[1] = {0.f}, mu1[1] = {-INFINITY};
+        forward_feature_pass<D, 1>(lw, L::w_pitch, ls, s_pitch, lz, lc, FT, l32, half, qf1, accN1, den1, mu1);
+        float den = half_sum(den1[0]);
+        const float mu = mu1[0];
         const float inv = 1.f / den;
         // g_i = G_i . out_i ; this lane holds t = 32*tt + 8*(g/4) + 4*half + g%4 of its query,
         // which are the 8-byte chunks of gf: step s = 2*tt + (g/8), chunk (g/4)%2
@@ -279,39 +282,93 @@ struct BwdYArgs {
     int BH, H, n, mf, FT, R, tiles_per_range;
 };
 
+// A workgroup is four wavefronts = four feature tiles of one (head, query range).  They need the same
+// Q rows (A operand) and the same dOut rows (B operand, contraction over queries), so each 32-query
+// tile is loaded once per workgroup with 16-byte loads and staged in LDS, double buffered: Q row-major,
+// dOut transposed to [t][query slot] with the 32 queries of the tile in accumulator-slot order, so that
+// a lane's B operand is one 16-byte read.
 template <int D>
 __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
-    const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wid >= (long)a.BH * a.FT * a.R) return;
-    const int ft = (int)(wid % a.FT); wid /= a.FT;      // waves of one workgroup share Q and G rows
-    const int r = (int)(wid % a.R);
-    const int bh = (int)(wid / a.R);
-    const int QT = a.n / 32;
+    constexpr int QP = (D + 8) * 2;            // LDS pitch of a Q row
+    constexpr int GP = 80;                     // LDS pitch of a dOut^T row: 32 queries + 16 bytes pad
+    constexpr int QB = 32 * QP, GB = D * GP;
+    constexpr int LPT = D / 64;                // 16-byte loads per thread per tensor per tile
+    __shared__ __attribute__((aligned(16))) unsigned char sm[2 * (QB + GB)];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int FG = (a.FT + 3) / 4;
+    int id = blockIdx.x;
+    const int fg = id % FG; id /= FG;
+    const int r = id % a.R;
+    const int bh = id / a.R;
+    const int ft = 4 * fg + wave;
+    const bool active = ft < a.FT;
+    const int ftc = active ? ft : a.FT - 1;
+    const int QTn = a.n / 32;
     const int qt0 = r * a.tiles_per_range;
     int qt1 = qt0 + a.tiles_per_range;
-    if (qt1 > QT) qt1 = QT;
+    if (qt1 > QTn) qt1 = QTn;
     const long head_off = (long)bh * a.n * D;
 
     uint4 wf[KS];
     {
-        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ft + l32) * D + 8 * half;
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ftc + l32) * D + 8 * half;
 #pragma unroll
         for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
     }
-    const float cj = a.c[(long)bh * a.mf + 32 * ft + l32] * LOG2E;
+    const float cj = a.c[(long)bh * a.mf + 32 * ftc + l32] * LOG2E;
     floatx16 accS[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) accS[t] = zero16();
     float dz = 0.f;
 
+    // loader map: 16-byte chunk c of row lr (+ 256/(D/8) rows per extra load)
+    constexpr int CPR = D / 8;                 // chunks per row
+    const int lr = tid / CPR, lc8 = tid % CPR;
+    // slot of query q inside the tile: q = 16*sp + 8*j4 + 4*h + j0  ->  16*h + 8*sp + 4*j4 + j0
+    auto slot_of = [](int q) { return 16 * ((q >> 2) & 1) + 8 * (q >> 4) + 4 * ((q >> 3) & 1) + (q & 3); };
+    uint4 rq[LPT], rg[LPT];
+    auto load_tile = [&](int qt) {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            const long off = head_off + (long)(32 * qt + lr + u * (256 / CPR)) * D + 8 * lc8;
+            rq[u] = ld16(a.Q + off);
+            rg[u] = ld16(a.G + off);
+        }
+    };
+    auto store_tile = [&](int buf) {
+        unsigned char* qs = sm + buf * (QB + GB);
+        unsigned char* gs = qs + QB;
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            const int row = lr + u * (256 / CPR);
+            *(uint4*)(qs + row * QP + 16 * lc8) = rq[u];
+            const int sl = slot_of(row);
+            const uint32_t w[4] = {rg[u].x, rg[u].y, rg[u].z, rg[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                *(uint16_t*)(gs + (8 * lc8 + 2 * e) * GP + 2 * sl) = (uint16_t)(w[e] & 0xffffu);
+                *(uint16_t*)(gs + (8 * lc8 + 2 * e + 1) * GP + 2 * sl) = (uint16_t)(w[e] >> 16);
+            }
+        }
+    };
+
+    if (qt0 < qt1) {
+        load_tile(qt0);
+        store_tile(0);
+    }
+    __syncthreads();
     for (int qt = qt0; qt < qt1; ++qt) {
+        const int buf = (qt - qt0) & 1;
+        const bool more = qt + 1 < qt1;
+        if (more) load_tile(qt + 1);
+        const unsigned char* qs = sm + buf * (QB + GB);
+        const unsigned char* gs = qs + QB;
         // u tile: rows = queries 32*qt + ..., columns = this wavefront's features
-        const uint16_t* qg = a.Q + head_off + (long)(32 * qt + l32) * D + 8 * half;
         floatx16 u = zero16();
 #pragma unroll
-        for (int s = 0; s < KS; ++s) u = mfma32(ld16(qg + 16 * s), wf[s], u);
+        for (int s = 0; s < KS; ++s) u = mfma32(*(const uint4*)(qs + l32 * QP + 32 * s + 16 * half), wf[s], u);
         // element g <-> query 32*qt + 8*(g/4) + 4*half + g%4
         const float* lg = a.lse + (long)bh * a.n + 32 * qt + 4 * half;
         const float* dg = a.delta + (long)bh * a.n + 32 * qt + 4 * half;
@@ -330,25 +387,19 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
             dz = fmaf(-w2, dv.z, dz); dz = fmaf(-w3, dv.w, dz);
         }
         // W^T tile as A operand (row = this lane's feature, slots = queries in accumulator order);
-        // B operand: G columns 32*tt + l32, query pairs in the matching order
+        // B operand: dOut^T row t = 32*tt + l32, the 8 query slots of (half, sp)
         const uint4 wa[2] = {{wk[0], wk[1], wk[2], wk[3]}, {wk[4], wk[5], wk[6], wk[7]}};
-        const uint16_t* gb = a.G + head_off + (long)(32 * qt) * D + l32;
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-            // dword q of the operand = queries 16*sp + 8*(q/2) + 4*half + 2*(q%2) + {0, 1}
-            const uint16_t* g0 = gb + (long)(16 * sp + 4 * half) * D;
+        for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                const uint16_t* gp = g0 + 32 * tt;
-                uint4 b;
-                b.x = (uint32_t)gp[0] | ((uint32_t)gp[D] << 16);
-                b.y = (uint32_t)gp[2 * D] | ((uint32_t)gp[3 * D] << 16);
-                b.z = (uint32_t)gp[8 * D] | ((uint32_t)gp[9 * D] << 16);
-                b.w = (uint32_t)gp[10 * D] | ((uint32_t)gp[11 * D] << 16);
+                const uint4 b = *(const uint4*)(gs + (32 * tt + l32) * GP + 32 * half + 16 * sp);
                 accS[tt] = mfma32(wa[sp], b, accS[tt]);
             }
-        }
+        if (more) store_tile(buf ^ 1);
+        __syncthreads();
     }
+    if (!active) return;
     dz = half_sum(dz);
     const long po = ((long)bh * a.R + r) * a.mf;
     if (half == 0) a.dzpart[po + 32 * ft + l32] = dz;
@@ -744,9 +795,9 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ya.omega_head_stride = omega_stride;
         ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
         ya.tiles_per_range = y.tiles_per_range;
-        const long waves = (long)p.BH * y.FT * y.R;
-        if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, grid1d(waves, 4), dim3(256), 0, s, ya);
-        else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, grid1d(waves, 4), dim3(256), 0, s, ya);
+        const unsigned ygrid = (unsigned)((long)p.BH * y.R * ((y.FT + 3) / 4));
+        if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, dim3(ygrid), dim3(256), 0, s, ya);
+        else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, dim3(ygrid), dim3(256), 0, s, ya);
         FLURKA_CHECK_LAUNCH();
     }
     const size_t img_elems = (size_t)p.BH * W.kp * p.d;

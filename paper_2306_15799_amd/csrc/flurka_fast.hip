@@ -72,10 +72,11 @@ struct QueryLds {
     }
 };
 
-// One workgroup = 8 wavefronts sharing the LDS image of omega, S^T and z of one head; each wavefront
-// streams 32 query rows at a time.
-template <int D, bool ELU>
-__global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
+// One workgroup = NW wavefronts sharing the LDS image of omega, S^T and z of one head; each wavefront
+// streams QT tiles of 32 query rows at a time.  With QT = 2 every operand fragment read from LDS
+// feeds two MFMAs, which halves the LDS traffic per flop (the limiter at one tile per wavefront).
+template <int D, bool ELU, int NW, int QT>
+__global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     using L = QueryLds<D>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
     if (!ELU) {
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
         constexpr int cpr = D / 8;                      // chunks per row
-        for (int c = tid; c < mf * cpr; c += 512) {
+        for (int c = tid; c < mf * cpr; c += NW * 64) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
         }
@@ -101,13 +102,13 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
     {
         const uint16_t* sg = a.St + (long)bh * D * mf;
         const int cpr = mf / 8;
-        for (int c = tid; c < D * cpr; c += 512) {
+        for (int c = tid; c < D * cpr; c += NW * 64) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(ls + r * s_pitch + 16 * q) = ld16(sg + (long)r * mf + 8 * q);
         }
         const float* zg = a.zp + (long)bh * mf;
         const float* cg = a.cp + (long)bh * mf;
-        for (int c = tid; c < mf; c += 512) { lz[c] = zg[c]; lc[c] = cg[c]; }
+        for (int c = tid; c < mf; c += NW * 64) { lz[c] = zg[c]; lc[c] = cg[c]; }
     }
     __syncthreads();
 
@@ -118,62 +119,76 @@ __global__ __launch_bounds__(512) void query_stream_kernel(QueryArgs a) {
     constexpr int KS = D / 16;      // reduction steps over d
     constexpr int TT = D / 32;      // 32-row tiles of N^T
 
-    for (int row0 = row_begin + 32 * wave; row0 < row_end; row0 += 32 * 8) {
+    for (int row0 = row_begin + 32 * QT * wave; row0 < row_end; row0 += 32 * QT * NW) {
         // B operand of the first contraction: this lane's query row, 8 consecutive d per step
-        int qrow = row0 + l32;
-        const bool valid = qrow < a.n;
-        if (!valid) qrow = a.n - 1;
-        const uint16_t* qg = a.Q + head_off + (long)qrow * D + 8 * half;
-        uint4 qf[KS];
+        int qrow[QT];
+        bool valid[QT];
+        uint4 qf[QT][KS];
+        floatx16 accN[QT][TT];
+        float den[QT];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qf[s] = ld16(qg + 16 * s);
-
-        floatx16 accN[TT];
+        for (int i = 0; i < QT; ++i) {
+            qrow[i] = row0 + 32 * i + l32;
+            valid[i] = qrow[i] < a.n;
+            if (!valid[i]) qrow[i] = a.n - 1;
+            const uint16_t* qg = a.Q + head_off + (long)qrow[i] * D + 8 * half;
 #pragma unroll
-        for (int t = 0; t < TT; ++t) accN[t] = zero16();
-        float den = 0.f;
+            for (int s = 0; s < KS; ++s) qf[i][s] = ld16(qg + 16 * s);
+#pragma unroll
+            for (int t = 0; t < TT; ++t) accN[i][t] = zero16();
+            den[i] = 0.f;
+        }
 
         if (ELU) {
             // P = elu(q)+1 straight in operand order; features are the d coordinates
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                const uint32_t w[4] = {qf[s].x, qf[s].y, qf[s].z, qf[s].w};
-                uint32_t pk[4];
+                uint4 pb[QT];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x0 = bf16_to_f32((uint16_t)(w[e] & 0xffffu));
-                    const float x1 = bf16_to_f32((uint16_t)(w[e] >> 16));
-                    const float p0 = x0 > 0.f ? x0 + 1.f : __expf(x0);
-                    const float p1 = x1 > 0.f ? x1 + 1.f : __expf(x1);
-                    pk[e] = pack_bf16(p0, p1);
-                    const int f = 16 * s + 8 * half + 2 * e;
-                    den = fmaf(p0, lz[f], den);
-                    den = fmaf(p1, lz[f + 1], den);
+                for (int i = 0; i < QT; ++i) {
+                    const uint32_t w[4] = {qf[i][s].x, qf[i][s].y, qf[i][s].z, qf[i][s].w};
+                    uint32_t pk[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float x0 = bf16_to_f32((uint16_t)(w[e] & 0xffffu));
+                        const float x1 = bf16_to_f32((uint16_t)(w[e] >> 16));
+                        const float p0 = x0 > 0.f ? x0 + 1.f : __expf(x0);
+                        const float p1 = x1 > 0.f ? x1 + 1.f : __expf(x1);
+                        pk[e] = pack_bf16(p0, p1);
+                        const int f = 16 * s + 8 * half + 2 * e;
+                        den[i] = fmaf(p0, lz[f], den[i]);
+                        den[i] = fmaf(p1, lz[f + 1], den[i]);
+                    }
+                    pb[i] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
                 }
-                const uint4 pb = {pk[0], pk[1], pk[2], pk[3]};
 #pragma unroll
                 for (int t = 0; t < TT; ++t) {
                     const uint4 sa = *(const uint4*)(ls + (32 * t + l32) * s_pitch + 32 * s + 16 * half);
-                    accN[t] = mfma32(sa, pb, accN[t]);
+#pragma unroll
+                    for (int i = 0; i < QT; ++i) accN[i][t] = mfma32(sa, pb[i], accN[i][t]);
                 }
             }
         } else {
-            float mu = -INFINITY;     // running row maximum (same value in lanes l and l^32)
-            forward_feature_pass<D>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu);
+            float mu[QT];     // running row maxima (same value in lanes l and l^32)
+#pragma unroll
+            for (int i = 0; i < QT; ++i) mu[i] = -INFINITY;
+            forward_feature_pass<D, QT>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu);
         }
-        den = half_sum(den);
-        const float inv = 1.f / den;
-        if (valid) {
-            uint16_t* og = a.out + head_off + (long)qrow * D;
 #pragma unroll
-            for (int t = 0; t < TT; ++t)
+        for (int i = 0; i < QT; ++i) {
+            const float inv = 1.f / half_sum(den[i]);
+            if (valid[i]) {
+                uint16_t* og = a.out + head_off + (long)qrow[i] * D;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint2 v;
-                    v.x = pack_bf16(accN[t][4 * q] * inv, accN[t][4 * q + 1] * inv);
-                    v.y = pack_bf16(accN[t][4 * q + 2] * inv, accN[t][4 * q + 3] * inv);
-                    *(uint2*)(og + 32 * t + 8 * q + 4 * half) = v;
-                }
+                for (int t = 0; t < TT; ++t)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint2 v;
+                        v.x = pack_bf16(accN[i][t][4 * q] * inv, accN[i][t][4 * q + 1] * inv);
+                        v.y = pack_bf16(accN[i][t][4 * q + 2] * inv, accN[i][t][4 * q + 3] * inv);
+                        *(uint2*)(og + 32 * t + 8 * q + 4 * half) = v;
+                    }
+            }
         }
     }
 }
@@ -237,12 +252,14 @@ size_t fast_ws_bytes(const Problem& p, int bwd) {
     return bwd ? fast_bwd_ws_bytes(p) : fast_ws_layout(p).total;
 }
 
+constexpr int QS_NW = 8, QS_QT = 1;      // wavefronts per workgroup, 32-row tiles per wavefront
+
 template <int D, bool ELU>
 static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int grid, int ldsb, hipStream_t s) {
-    auto kern = query_stream_kernel<D, ELU>;
+    auto kern = query_stream_kernel<D, ELU, QS_NW, QS_QT>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ldsb, s, qa);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(QS_NW * 64), ldsb, s, qa);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
 }
@@ -291,10 +308,11 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         qa.out = (uint16_t*)a.out;
         qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
         qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
-        // about two workgroups per compute unit, each a multiple of 256 rows (8 wavefronts x 32)
+        // about two workgroups per compute unit, each a multiple of the rows one pass of a workgroup covers
+        constexpr int pass_rows = QS_NW * QS_QT * 32;
         int wgs_per_head = (512 + p.BH - 1) / p.BH;
         int rows = (p.n + wgs_per_head - 1) / wgs_per_head;
-        rows = (rows + 255) / 256 * 256;
+        rows = (rows + pass_rows - 1) / pass_rows * pass_rows;
         wgs_per_head = (p.n + rows - 1) / rows;
         qa.rows_per_wg = rows; qa.wgs_per_head = wgs_per_head;
         const int grid = p.BH * wgs_per_head;

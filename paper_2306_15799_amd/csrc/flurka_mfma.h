@@ -73,11 +73,12 @@ constexpr float FLURKA_LAZY_MAX = 5.0f;
 // FLURKA_LAZY_MAX) rescaling between iterations.
 // lw: omega [feature][D] (pitch w_pitch), ls: S^T [t][feature slot] (pitch s_pitch), lz, lc: z, c in
 // accumulator order; all in LDS.
-template <int D>
+template <int D, int QT>
 __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, int w_pitch, const unsigned char* ls,
                                                      int s_pitch, const float* lz, const float* lc, int FT,
-                                                     int l32, int half, const uint4 (&qf)[D / 16],
-                                                     floatx16 (&accN)[D / 32], float& den, float& mu) {
+                                                     int l32, int half, const uint4 (&qf)[QT][D / 16],
+                                                     floatx16 (&accN)[QT][D / 32], float (&den)[QT],
+                                                     float (&mu)[QT]) {
     constexpr int KS = D / 16, TT = D / 32;
     constexpr int EPC = 16 / KS;                 // accumulator elements handled per group
     const unsigned char* wrow = lw + l32 * w_pitch + 16 * half;        // + 32*ft rows, + 32*s
@@ -99,28 +100,43 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         for (int g = 3; g < 15; g += 2) tmax = fmaxf(fmaxf(tmax, u[g]), u[g + 1]);
         return half_max(fmaxf(tmax, u[15]));
     };
-    auto maybe_rescale = [&](float tmax) {
-        if (tmax > mu + FLURKA_LAZY_MAX) {
-            const float sc = fast_exp2((mu - tmax) * FLURKA_LOG2E);     // 0 on the first tile
-            mu = tmax;
-            den *= sc;
+    auto maybe_rescale = [&](int i, float tmax) {
+        if (tmax > mu[i] + FLURKA_LAZY_MAX) {
+            const float sc = fast_exp2((mu[i] - tmax) * FLURKA_LOG2E);     // 0 on the first tile
+            mu[i] = tmax;
+            den[i] *= sc;
 #pragma unroll
             for (int t = 0; t < TT; ++t)
 #pragma unroll
-                for (int g = 0; g < 16; ++g) accN[t][g] *= sc;
+                for (int g = 0; g < 16; ++g) accN[i][t][g] *= sc;
         }
     };
 
     // prologue: tile 0
-    floatx16 u = load_c(0);
+    floatx16 u[QT];
+    {
+        const floatx16 c0 = load_c(0);
 #pragma unroll
-    for (int s = 0; s < KS; ++s) u = mfma32(*(const uint4*)(wrow + 32 * s), qf[s], u);
-    maybe_rescale(tile_max(u));
+        for (int i = 0; i < QT; ++i) u[i] = c0;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const uint4 wa = *(const uint4*)(wrow + 32 * s);
+#pragma unroll
+            for (int i = 0; i < QT; ++i) u[i] = mfma32(wa, qf[i][s], u[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < QT; ++i) maybe_rescale(i, tile_max(u[i]));
+    }
 
     for (int ft = 0; ft < FT; ++ft) {
         const int nft = ft + 1 < FT ? ft + 1 : ft;            // last iteration recomputes its own tile, unused
-        const float nshift = -mu * FLURKA_LOG2E;
-        floatx16 un = load_c(nft);
+        float nshift[QT];
+        floatx16 un[QT];
+        {
+            const floatx16 cn = load_c(nft);
+#pragma unroll
+            for (int i = 0; i < QT; ++i) { un[i] = cn; nshift[i] = -mu[i] * FLURKA_LOG2E; }
+        }
         float zv[16];
         {
             const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
@@ -139,45 +155,60 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
             sa[2 * t + 1] = *(const uint4*)(srow + (32 * t) * s_pitch + 64 * ft + 32);
         }
         __builtin_amdgcn_sched_barrier(0);
-        float p[16];
-        uint32_t pk[8];
+        uint32_t pk[QT][8];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            // one dependent MFMA of the next tile's u^T ...
-            un = mfma32(wa[s], qf[s], un);
+            // dependent MFMAs of the next tile's u^T (one per query tile) ...
+#pragma unroll
+            for (int i = 0; i < QT; ++i) un[i] = mfma32(wa[s], qf[i][s], un[i]);
             // ... over the exp work of EPC elements of this tile
 #pragma unroll
-            for (int e = s * EPC; e < (s + 1) * EPC; ++e) {
-                p[e] = fast_exp2(fmaf(u[e], FLURKA_LOG2E, nshift));
-                den = fmaf(p[e], zv[e], den);
-            }
+            for (int i = 0; i < QT; ++i) {
+                float p[EPC];
 #pragma unroll
-            for (int e = s * EPC; e < (s + 1) * EPC; e += 2) pk[e / 2] = pack_bf16(p[e], p[e + 1]);
+                for (int e = 0; e < EPC; ++e) {
+                    p[e] = fast_exp2(fmaf(u[i][s * EPC + e], FLURKA_LOG2E, nshift[i]));
+                    den[i] = fmaf(p[e], zv[s * EPC + e], den[i]);
+                }
+#pragma unroll
+                for (int e = 0; e < EPC; e += 2) pk[i][(s * EPC + e) / 2] = pack_bf16(p[e], p[e + 1]);
+            }
             // second half of the groups: N^T MFMAs with the first half of P^T (elements 0..7)
             if (s >= KS / 2) {
                 constexpr int per = (TT + KS / 2 - 1) / (KS / 2);
 #pragma unroll
                 for (int j = 0; j < per; ++j) {
                     const int t = (s - KS / 2) * per + j;
-                    if (t < TT) accN[t] = mfma32(sa[2 * t], make_uint4(pk[0], pk[1], pk[2], pk[3]), accN[t]);
+                    if (t < TT) {
+#pragma unroll
+                        for (int i = 0; i < QT; ++i)
+                            accN[i][t] = mfma32(sa[2 * t], make_uint4(pk[i][0], pk[i][1], pk[i][2], pk[i][3]), accN[i][t]);
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
         // N^T MFMAs with the second half of P^T, over the maximum of the next tile
-        const uint4 pb1 = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        float tmax = fmaxf(fmaxf(un[0], un[1]), un[2]);
+        float tmax[QT];
+#pragma unroll
+        for (int i = 0; i < QT; ++i) tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
-            accN[t] = mfma32(sa[2 * t + 1], pb1, accN[t]);
             constexpr int per = (12 + TT - 1) / TT;          // elements 3..14 spread over the TT groups
 #pragma unroll
-            for (int g = 3 + t * per; g < 3 + (t + 1) * per && g < 15; ++g) tmax = fmaxf(tmax, un[g]);
+            for (int i = 0; i < QT; ++i) {
+                accN[i][t] = mfma32(sa[2 * t + 1], make_uint4(pk[i][4], pk[i][5], pk[i][6], pk[i][7]), accN[i][t]);
+#pragma unroll
+                for (int g = 3 + t * per; g < 3 + (t + 1) * per && g < 15; ++g) tmax[i] = fmaxf(tmax[i], un[i][g]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        tmax = half_max(fmaxf(tmax, un[15]));
-        if (ft + 1 < FT) maybe_rescale(tmax);
-        u = un;
+#pragma unroll
+        for (int i = 0; i < QT; ++i) {
+            tmax[i] = half_max(fmaxf(tmax[i], un[i][15]));
+            if (ft + 1 < FT) maybe_rescale(i, tmax[i]);
+            u[i] = un[i];
+        }
     }
 }
 
