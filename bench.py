@@ -62,6 +62,51 @@ def stage_model(w, stage: str):
     raise KeyError(stage)
 
 
+# timer name of an MFMA-path kernel -> (name in rocprofv3 traces, stage it belongs to)
+KERNEL_TRACE_NAME = {
+    "gemm_mfma_proj": "gemm_mfma_kernel<ProjPolicy<{d}> >",
+    "proj_finish": "proj_finish_kernel",
+    "key_state": "key_state_kernel<{d}, false>",
+    "merge_pack": "merge_pack_kernel",
+    "query_stream": "query_stream_kernel<{d}, {elu}, 8, 1>",
+    "bwd_pack": "bwd_pack_kernel",
+    "bwd_query_x": "bwd_query_x_kernel<{d}>",
+    "bwd_query_y": "bwd_query_y_kernel<{d}>",
+    "bwd_merge": "bwd_merge_kernel",
+    "bwd_key": "bwd_key_kernel<{d}>",
+    "gemm_mfma_gradx": "gemm_mfma_kernel<GradXPolicy<{d}> >",
+    "gemm_mfma_grade": "gemm_mfma_kernel<GradEPolicy<{d}> >",
+    "sum_splits": "sum_splits_bf16_kernel",
+}
+
+
+def kernel_model(w, kernel: str):
+    """Algorithmic (flops, bytes) of one kernel of the MFMA path (recomputation is not counted:
+    the backward's five n*m*d contractions are split 4 : 1 between bwd_query_x and bwd_query_y)."""
+    es = 2 if w.dtype == "bf16" else 4
+    BH, n, d, k = w.B * w.H, w.n, w.d, w.k
+    mf = w.d if w.phi == "elu1" else w.m
+    if kernel == "gemm_mfma_proj":
+        return stage_model(w, "project")
+    if kernel == "query_stream":
+        return stage_model(w, "query_stream")
+    if kernel == "key_state":
+        return stage_model(w, "key_state")
+    if kernel == "bwd_query_x":
+        return 8.0 * n * mf * d * BH, es * 3 * BH * n * d + 8 * BH * n
+    if kernel == "bwd_query_y":
+        return 2.0 * n * mf * d * BH, es * 2 * BH * n * d + 8 * BH * n + 4 * BH * mf * d
+    if kernel == "bwd_key":
+        return stage_model(w, "bwd_key")
+    if kernel == "gemm_mfma_gradx":
+        return stage_model(w, "bwd_dk_dv")
+    if kernel == "gemm_mfma_grade":
+        return stage_model(w, "bwd_de_df")
+    # small helper kernels: data movement only
+    small = 4 * BH * (2 * k * d + mf * d + mf)
+    return 0.0, float(small)
+
+
 def whole_model(w):
     stages = ["project", "key_state", "query_stream"]
     if w.backward:
@@ -76,8 +121,8 @@ def whole_model(w):
     return fl, by
 
 
-def roofline_entry(w, stage, avg_ms, launches_note):
-    fl, by = stage_model(w, stage)
+def roofline_entry(w, stage, avg_ms, launches_note, model=None):
+    fl, by = (model or stage_model)(w, stage)
     sec = avg_ms * 1e-3
     peak_fl = PEAK_MFMA_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
     t_fl = fl / (peak_fl * 1e12)
@@ -167,17 +212,41 @@ def main():
     torch.cuda.synchronize()
     rec = fb.profile_read()
     fb.profile_enable(False)
-    stage_ms = {}
+    # timer entries are "stage" (generic kernels) or "stage:kernel" (MFMA path, one kernel each)
+    steps_seen = max(1, args.steps)
+    stage_tot, kernel_tot, kernel_cnt = {}, {}, {}
     for name, ms in rec:
-        stage_ms.setdefault(name, []).append(ms)
-    stage_avg = {k: sum(v) / len(v) for k, v in stage_ms.items()}
-    dominant = max(stage_avg, key=stage_avg.get)
-    roof = roofline_entry(w, dominant, stage_avg[dominant],
-                          "stage time = HIP events around the stage's launches on their stream")
+        stage, _, kern = name.partition(":")
+        stage_tot[stage] = stage_tot.get(stage, 0.0) + ms
+        if kern:
+            kernel_tot[kern] = kernel_tot.get(kern, 0.0) + ms
+            kernel_cnt[kern] = kernel_cnt.get(kern, 0) + 1
+    stage_avg = {k: v / steps_seen for k, v in stage_tot.items()}
     stages_out = {}
     for name, ms in stage_avg.items():
         fl, by = stage_model(w, name)
         stages_out[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 2), "gbs": round(by / ms / 1e6, 1)}
+    kernels_out = {k: {"avg_ms": round(kernel_tot[k] / kernel_cnt[k], 5), "launches_per_step": kernel_cnt[k] / steps_seen}
+                   for k in kernel_tot}
+    if kernel_tot:
+        # dominant kernel = largest time per step; its average launch duration from the HIP events
+        dominant = max(kernel_tot, key=kernel_tot.get)
+        avg_launch = kernel_tot[dominant] / kernel_cnt[dominant]
+        roof = roofline_entry(w, dominant, avg_launch,
+                              "HIP events around each launch of this kernel, on the stream it runs on",
+                              model=kernel_model)
+        trace = KERNEL_TRACE_NAME[dominant].format(d=w.d, elu="true" if w.phi == "elu1" else "false")
+        roof["kernel_in_trace"] = trace
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            tr = json.load(open(tpath)).get(w.name, {}).get("kernels", {}).get(trace)
+            if tr:
+                roof["traffic"] = tr["read_bytes"] + tr["write_bytes"]
+                roof["traffic_note"] = "HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE runs (profiles/hbm_traffic_%s.txt)" % w.name
+    else:
+        dominant = max(stage_avg, key=stage_avg.get)
+        roof = roofline_entry(w, dominant, stage_avg[dominant],
+                              "stage time = HIP events around the stage's launches on their stream")
 
     fl_all, by_all = whole_model(w)
     sec = ms_per_step * 1e-3
@@ -197,6 +266,7 @@ def main():
                        "frac_of_binding_roof": round(max(fl_all / (PEAK_MFMA_BF16_TFLOPS * 1e12 if w.dtype == "bf16" else PEAK_FP32_TFLOPS * 1e12),
                                                          by_all / (PEAK_HBM_GBS * 1e9)) / sec, 4)},
         "stages": stages_out,
+        "kernels": kernels_out,
         "roofline": roof,
     }
 

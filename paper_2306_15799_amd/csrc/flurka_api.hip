@@ -226,6 +226,19 @@ const char* flurka_profile_stage_name(int id) {
         case STAGE_BWD_KEY: return "bwd_key";
         case STAGE_BWD_DKDV: return "bwd_dk_dv";
         case STAGE_BWD_DEDF: return "bwd_de_df";
+        case STAGE_K_PROJ_GEMM: return "project:gemm_mfma_proj";
+        case STAGE_K_PROJ_FINISH: return "key_state:proj_finish";
+        case STAGE_K_KEY_STATE: return "key_state:key_state";
+        case STAGE_K_MERGE_PACK: return "key_state:merge_pack";
+        case STAGE_K_QUERY_STREAM: return "query_stream:query_stream";
+        case STAGE_K_BWD_PACK: return "bwd_query:bwd_pack";
+        case STAGE_K_BWD_X: return "bwd_query:bwd_query_x";
+        case STAGE_K_BWD_Y: return "bwd_query:bwd_query_y";
+        case STAGE_K_BWD_MERGE: return "bwd_key:bwd_merge";
+        case STAGE_K_BWD_KEY: return "bwd_key:bwd_key";
+        case STAGE_K_GRAD_X: return "bwd_dk_dv:gemm_mfma_gradx";
+        case STAGE_K_GRAD_E: return "bwd_de_df:gemm_mfma_grade";
+        case STAGE_K_SUM_SPLITS: return "bwd_de_df:sum_splits";
     }
     return "unknown";
 }

@@ -760,7 +760,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     const long omega_stride = p.omega_per_head ? (long)p.m * p.d : 0;
     flurka_status st;
     {
-        StageScope sc(s, STAGE_BWD_QUERY);
+        stage_begin(s);
         const long total = (long)p.BH * p.mf * p.d;
         hipLaunchKernelGGL(bwd_pack_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.St),
                            (uint16_t*)(wsb + W.Sp), (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S,
@@ -770,6 +770,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         hipLaunchKernelGGL(bwd_pack_omega_kernel, grid1d(wtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Wt),
                            (uint32_t*)(wsb + W.Wpair), (const uint16_t*)a.omega, p.m, p.d, wtotal);
         FLURKA_CHECK_LAUNCH();
+        stage_end(s, STAGE_K_BWD_PACK);
 
         BwdXArgs xa{};
         xa.Q = (const uint16_t*)a.Q; xa.G = (const uint16_t*)a.dOut; xa.omega = (const uint16_t*)a.omega;
@@ -784,9 +785,11 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         wgs_per_head = (p.n + rows - 1) / rows;
         xa.rows_per_wg = rows; xa.wgs_per_head = wgs_per_head;
         const int ldsb = bwd_x_lds_bytes(p);
+        stage_begin(s);
         st = p.d == 64 ? launch_bwd_x<64>(xa, p.BH * wgs_per_head, ldsb, s)
                        : launch_bwd_x<128>(xa, p.BH * wgs_per_head, ldsb, s);
         if (st != FLURKA_OK) return st;
+        stage_end(s, STAGE_K_BWD_X);
 
         BwdYArgs ya{};
         ya.Q = xa.Q; ya.G = xa.G; ya.omega = xa.omega; ya.c = a.ctx + L.c;
@@ -796,20 +799,24 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
         ya.tiles_per_range = y.tiles_per_range;
         const unsigned ygrid = (unsigned)((long)p.BH * y.R * ((y.FT + 3) / 4));
+        stage_begin(s);
         if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, dim3(ygrid), dim3(256), 0, s, ya);
         else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, dim3(ygrid), dim3(256), 0, s, ya);
         FLURKA_CHECK_LAUNCH();
+        stage_end(s, STAGE_K_BWD_Y);
     }
     const size_t img_elems = (size_t)p.BH * W.kp * p.d;
     uint16_t* img = (uint16_t*)(wsb + W.img);
     uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
     {
-        StageScope sc(s, STAGE_BWD_KEY);
+        stage_begin(s);
         const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
         hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.dSimg),
                            (uint32_t*)(wsb + W.dSpair), (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
                            (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
         FLURKA_CHECK_LAUNCH();
+        stage_end(s, STAGE_K_BWD_MERGE);
+        StageScope sc(s, STAGE_K_BWD_KEY);
         BwdKeyArgs ka{};
         ka.Kp = a.ctx + L.Kp; ka.Vp = a.ctx + L.Vp; ka.c = a.ctx + L.c;
         ka.omega = (const uint16_t*)a.omega; ka.Wpair = (const uint32_t*)(wsb + W.Wpair);
@@ -824,7 +831,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         FLURKA_CHECK_LAUNCH();
     }
     {
-        StageScope sc(s, STAGE_BWD_DKDV);
+        StageScope sc(s, STAGE_K_GRAD_X);
         GemmParams gp{};       // dK = E^T dK', dV = F^T dV'
         gp.A[0] = imgT; gp.A[1] = imgT + img_elems;
         gp.B[0] = (const uint16_t*)a.E; gp.B[1] = (const uint16_t*)a.F;
@@ -836,7 +843,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         if (st != FLURKA_OK) return st;
     }
     {
-        StageScope sc(s, STAGE_BWD_DEDF);
+        stage_begin(s);
         const GradEPlan e = grad_e_plan(p);
         float* part = (float*)(wsb + W.epart);
         const long kn = (long)p.k * p.n;
@@ -850,6 +857,8 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
         st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64>>(gp, s) : launch_gemm_mfma<GradEPolicy<128>>(gp, s);
         if (st != FLURKA_OK) return st;
+        stage_end(s, STAGE_K_GRAD_E);
+        StageScope sc(s, STAGE_K_SUM_SPLITS);
         hipLaunchKernelGGL(sum_splits_bf16_kernel, grid1d((kn + 1) / 2, 256), dim3(256), 0, s, (uint16_t*)a.dE,
                            (const float*)part, kn, kn, e.splits);
         FLURKA_CHECK_LAUNCH();

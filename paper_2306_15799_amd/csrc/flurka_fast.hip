@@ -271,7 +271,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     flurka_status st;
     int proj_splits = 1;
     {
-        StageScope sc(s, STAGE_PROJECT);
+        StageScope sc(s, STAGE_K_PROJ_GEMM);
         const ProjPlan q = proj_plan(p);
         GemmParams gp{};
         gp.A[0] = (const uint16_t*)a.E; gp.A[1] = (const uint16_t*)a.F;
@@ -288,7 +288,6 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         proj_splits = q.splits;
     }
     {
-        StageScope sc(s, STAGE_KEY_STATE);
         KeyStateBuffers kb{};
         kb.Kimg = (uint16_t*)(wsb + W.Kimg); kb.Vimg = (uint32_t*)(wsb + W.Vimg); kb.nrm = (float*)(wsb + W.nrm);
         kb.Spart = (float*)(wsb + W.Spart); kb.zpart = (float*)(wsb + W.zpart); kb.cpart = (float*)(wsb + W.cpart);
@@ -298,7 +297,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         if (st != FLURKA_OK) return st;
     }
     {
-        StageScope sc(s, STAGE_QUERY);
+        StageScope sc(s, STAGE_K_QUERY_STREAM);
         QueryArgs qa{};
         qa.Q = (const uint16_t*)a.Q;
         qa.omega = (const uint16_t*)a.omega;

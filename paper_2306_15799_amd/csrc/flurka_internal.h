@@ -107,7 +107,21 @@ enum Stage {
     STAGE_BWD_KEY = 4,     // dPhiK, dV', dK'
     STAGE_BWD_DKDV = 5,    // dK = E^T dK', dV = F^T dV'
     STAGE_BWD_DEDF = 6,    // dE, dF
-    STAGE_COUNT = 7
+    // single kernels of the MFMA path (reported as "stage:kernel")
+    STAGE_K_PROJ_GEMM = 7,
+    STAGE_K_PROJ_FINISH = 8,
+    STAGE_K_KEY_STATE = 9,
+    STAGE_K_MERGE_PACK = 10,
+    STAGE_K_QUERY_STREAM = 11,
+    STAGE_K_BWD_PACK = 12,
+    STAGE_K_BWD_X = 13,
+    STAGE_K_BWD_Y = 14,
+    STAGE_K_BWD_MERGE = 15,
+    STAGE_K_BWD_KEY = 16,
+    STAGE_K_GRAD_X = 17,
+    STAGE_K_GRAD_E = 18,
+    STAGE_K_SUM_SPLITS = 19,
+    STAGE_COUNT = 20
 };
 // No-ops unless the timer is enabled.  begin/end pairs must not nest.
 void stage_begin(hipStream_t s);

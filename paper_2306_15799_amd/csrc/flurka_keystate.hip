@@ -344,6 +344,7 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
     const CtxLayout L = ctx_layout(p);
     const KeyStatePlan q = key_state_plan(p);
     {
+        StageScope sc(s, STAGE_K_PROJ_FINISH);
         FinishArgs fa{};
         fa.part = partials; fa.ctx = ctx; fa.split_stride = split_stride;
         fa.Kp_off = (long)L.Kp; fa.Vp_off = (long)L.Vp;
@@ -354,6 +355,7 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         FLURKA_CHECK_LAUNCH();
     }
     {
+        StageScope sc(s, STAGE_K_KEY_STATE);
         KeyStateArgs ka{};
         ka.Kimg = b.Kimg; ka.Kp = ctx + L.Kp; ka.Vimg = b.Vimg; ka.nrm = b.nrm;
         ka.omega = (const uint16_t*)omega;
@@ -365,6 +367,7 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         if (st != FLURKA_OK) return st;
     }
     {
+        StageScope sc(s, STAGE_K_MERGE_PACK);
         MergeArgs ma{};
         ma.Spart = b.Spart; ma.zpart = b.zpart; ma.cpart = b.cpart;
         ma.S = ctx + L.S; ma.z = ctx + L.z; ma.c = ctx + L.c;
