@@ -256,11 +256,13 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
 #pragma unroll
             for (int t = 0; t < TT; ++t)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint2 v;
-                    v.x = pack_bf16(accQ[t][4 * q], accQ[t][4 * q + 1]);
-                    v.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
-                    *(uint2*)(og + 32 * t + 8 * q + 4 * half) = v;
+                for (int q = 0; q < 4; q += 2) {
+                    uint2 ev, od;
+                    ev.x = pack_bf16(accQ[t][4 * q], accQ[t][4 * q + 1]);
+                    ev.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
+                    od.x = pack_bf16(accQ[t][4 * q + 4], accQ[t][4 * q + 5]);
+                    od.y = pack_bf16(accQ[t][4 * q + 6], accQ[t][4 * q + 7]);
+                    *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
                 }
         }
     }

@@ -182,11 +182,13 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
 #pragma unroll
                 for (int t = 0; t < TT; ++t)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        uint2 v;
-                        v.x = pack_bf16(accN[i][t][4 * q] * inv, accN[i][t][4 * q + 1] * inv);
-                        v.y = pack_bf16(accN[i][t][4 * q + 2] * inv, accN[i][t][4 * q + 3] * inv);
-                        *(uint2*)(og + 32 * t + 8 * q + 4 * half) = v;
+                    for (int q = 0; q < 4; q += 2) {
+                        uint2 ev, od;
+                        ev.x = pack_bf16(accN[i][t][4 * q] * inv, accN[i][t][4 * q + 1] * inv);
+                        ev.y = pack_bf16(accN[i][t][4 * q + 2] * inv, accN[i][t][4 * q + 3] * inv);
+                        od.x = pack_bf16(accN[i][t][4 * q + 4] * inv, accN[i][t][4 * q + 5] * inv);
+                        od.y = pack_bf16(accN[i][t][4 * q + 6] * inv, accN[i][t][4 * q + 7] * inv);
+                        *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
                     }
             }
         }

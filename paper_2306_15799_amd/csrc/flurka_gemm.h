@@ -210,17 +210,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 #undef G_LDB
 
     // epilogue: this lane holds, for every 32 x 32 tile (i, j), column 32*j + l32 and rows
-    // 32*i + 8*(e/4) + 4*half + e%4, e = 0..15, in groups of four consecutive rows
+    // 32*i + 8*q + 4*half + {0..3}, q = 0..3; groups q and q + 1 are handed over together so that a
+    // policy may join the two halves of a wavefront into 8 consecutive rows per lane
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int col = n0 + wn * 128 + 32 * j + l32;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int row = m0 + wm * 128 + 32 * i + 8 * q + 4 * half;
-                Pol::store4(g, pc, which, split, row, col, acc[i][j][4 * q], acc[i][j][4 * q + 1],
-                            acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            for (int q = 0; q < 4; q += 2) {
+                const int row = m0 + wm * 128 + 32 * i + 8 * q;
+                const float ev[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                const float od[4] = {acc[i][j][4 * q + 4], acc[i][j][4 * q + 5], acc[i][j][4 * q + 6], acc[i][j][4 * q + 7]};
+                Pol::store_groups(g, pc, which, split, row, half, col, ev, od);
             }
     }
 }
@@ -230,7 +232,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 //   Ctx make(g, which, m0, n0, tid)   descriptors and this thread's byte offsets
 //   a_soff / b_soff (ctx, step)       wave-uniform byte offset of a reduction step
 //   a_qstride / b_qstride             byte offset between the 8 loads (q = 0..7) of one step
-//   store4(..., row, col, v0..v3)     result rows row..row+3 of column col
+//   store_groups(..., row, half, col, ev, od)   this lane's rows row + 4*half + {0..3} (ev) and
+//                                     row + 8 + 4*half + {0..3} (od) of column col
 // A tile: thread loads 16-byte chunk (tid & 7) of rows (tid >> 3) + 32*q.
 // B transposed: thread loads columns 8*(tid & 31).. of positions 8*(tid >> 5) + q.
 // B direct: like A, rows being the columns of the result.
@@ -262,16 +265,19 @@ struct ProjPolicy {
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
     static __device__ __forceinline__ int b_soff(const Ctx&, int step) { return step * (GBK * D * 2); }
-    static __device__ __forceinline__ void store4(const GemmParams& g, const Ctx& c, int which, int split, int row,
-                                                  int col, float v0, float v1, float v2, float v3) {
+    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx& c, int which, int split,
+                                                        int row, int half, int col, const float (&ev)[4],
+                                                        const float (&od)[4]) {
         const int cl = col % GBN;
         const int bh = c.bh0 + cl / D;
         if (bh >= g.BH) return;
-        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + ((long)bh * g.k + row) * D + (cl % D);
-        if (row < g.k) o[0] = v0;
-        if (row + 1 < g.k) o[D] = v1;
-        if (row + 2 < g.k) o[2 * D] = v2;
-        if (row + 3 < g.k) o[3 * D] = v3;
+        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + ((long)bh * g.k) * D + (cl % D);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r0 = row + 4 * half + e, r1 = r0 + 8;
+            if (r0 < g.k) o[(long)r0 * D] = ev[e];
+            if (r1 < g.k) o[(long)r1 * D] = od[e];
+        }
     }
 };
 
@@ -293,14 +299,18 @@ struct GradXPolicy {
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
     static __device__ __forceinline__ int b_soff(const Ctx& c, int step) { return step * GBK * c.b_qstride; }
-    static __device__ __forceinline__ void store4(const GemmParams& g, const Ctx&, int which, int, int row, int col,
-                                                  float v0, float v1, float v2, float v3) {
-        if (col >= g.n || row >= g.BH * D) return;      // rows come in aligned groups of 4 inside one head
-        const int bh = row / D, t = row % D;
-        uint2 v;
-        v.x = pack_bf16(v0, v1);
-        v.y = pack_bf16(v2, v3);
-        *(uint2*)((uint16_t*)g.C[which] + ((long)bh * g.n + col) * D + t) = v;
+    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx&, int which, int, int row,
+                                                        int half, int col, const float (&ev)[4],
+                                                        const float (&od)[4]) {
+        // join the two halves: this lane ends up with the 8 consecutive t of group row + 8*half
+        uint2 e2, o2;
+        e2.x = pack_bf16(ev[0], ev[1]); e2.y = pack_bf16(ev[2], ev[3]);
+        o2.x = pack_bf16(od[0], od[1]); o2.y = pack_bf16(od[2], od[3]);
+        const uint4 v = join_halves(e2, o2);
+        const int r = row + 8 * half;                   // aligned group of 8 rows inside one head
+        if (col >= g.n || r >= g.BH * D) return;
+        const int bh = r / D, t = r % D;
+        *(uint4*)((uint16_t*)g.C[which] + ((long)bh * g.n + col) * D + t) = v;
     }
 };
 
@@ -330,14 +340,17 @@ struct GradEPolicy {
         constexpr int spb = D / GBK;
         return (step / spb) * c.b_batch + (step % spb) * (GBK * 2);
     }
-    static __device__ __forceinline__ void store4(const GemmParams& g, const Ctx&, int which, int split, int row,
-                                                  int col, float v0, float v1, float v2, float v3) {
+    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx&, int which, int split,
+                                                        int row, int half, int col, const float (&ev)[4],
+                                                        const float (&od)[4]) {
         if (col >= g.n) return;
-        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + (long)row * g.n + col;
-        if (row < g.k) o[0] = v0;
-        if (row + 1 < g.k) o[g.n] = v1;
-        if (row + 2 < g.k) o[2 * (long)g.n] = v2;
-        if (row + 3 < g.k) o[3 * (long)g.n] = v3;
+        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + col;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r0 = row + 4 * half + e, r1 = r0 + 8;
+            if (r0 < g.k) o[(long)r0 * g.n] = ev[e];
+            if (r1 < g.k) o[(long)r1 * g.n] = od[e];
+        }
     }
 };
 

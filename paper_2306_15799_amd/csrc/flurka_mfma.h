@@ -55,6 +55,16 @@ __device__ __forceinline__ float half_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// A 32x32 accumulator gives lane l rows 8q + 4*(l/32) + {0..3} of its column: lanes l and l ^ 32
+// hold the two 8-byte halves of every 8-row group.  Given the packed halves of groups 2i (`even`)
+// and 2i + 1 (`odd`), one v_permlane32_swap per dword leaves each lane with ONE complete group --
+// group 2i + (l/32) -- so results can be stored 16 bytes at a time.
+__device__ __forceinline__ uint4 join_halves(uint2 even, uint2 odd) {
+    const auto x = __builtin_amdgcn_permlane32_swap(even.x, odd.x, false, false);
+    const auto y = __builtin_amdgcn_permlane32_swap(even.y, odd.y, false, false);
+    return make_uint4(x[0], y[0], x[1], y[1]);
+}
+
 constexpr float FLURKA_LOG2E = 1.4426950408889634f;
 // The running row maximum is only raised when a tile exceeds it by more than this (natural log
 // units): weights may then be as large as exp(5) instead of 1, which costs nothing in fp32 or bf16
