@@ -478,15 +478,17 @@ struct BwdKeyArgs {
     int BH, H, k, kp, mf;
 };
 
+// One workgroup per (head, 32 keys); its four wavefronts take every fourth feature tile and add their
+// partial dV', dK', rs through LDS (fixed order, so the result does not depend on timing).
 template <int D>
 __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
+    const int wave = threadIdx.x >> 6;
     const int KT = a.kp / 32;
-    const long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wid >= (long)a.BH * KT) return;
-    const int kt = (int)(wid % KT);
-    const int bh = (int)(wid / KT);
+    const int kt = blockIdx.x % KT;
+    const int bh = blockIdx.x / KT;
     const int FT = a.mf / 32;
     const int key = 32 * kt + l32;
     const bool live = key < a.k;
@@ -546,7 +548,7 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     const float* cg = a.c + (long)bh * a.mf + 4 * half;
     const float* zg = a.dz + (long)bh * a.mf + 4 * half;
 
-    for (int ft = 0; ft < FT; ++ft) {
+    for (int ft = wave; ft < FT; ft += 4) {
         // e^T tile (features x keys) and dPhiK^T tile; element g <-> feature 32*ft + 8*(g/4) + 4*half + g%4
         floatx16 e = zero16(), dp;
 #pragma unroll
@@ -616,36 +618,61 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     }
     rs = half_sum(rs);
 
-    // results: this lane holds column t = 32*tt + l32 and rows (keys) 32*kt + 8*(g/4) + 4*half + g%4
+    // add the four wavefronts' partial results: slot w = [dV' | dK'][tt][g][lane], then rs[lane]
+    float* slots = (float*)lds;
+    constexpr int SLOT = 2 * TT * 16 * 64 + 64;
+    {
+        float* my = slots + wave * SLOT;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                my[(tt * 16 + g) * 64 + lane] = accV[tt][g];
+                my[((TT + tt) * 16 + g) * 64 + lane] = accK[tt][g];
+            }
+        my[2 * TT * 16 * 64 + lane] = rs;
+    }
+    __syncthreads();
+
+    // wavefront w finishes key group q = w: rows (keys) 32*kt + 8*w + 4*half + {0..3}, column t = 32*tt + l32
     uint16_t* imgK = a.img;
     uint16_t* imgV = a.img + img_plane;
     uint16_t* imgTK = a.imgT;
     uint16_t* imgTV = a.imgT + img_plane;
+    const int q = wave;
+    const int r0 = 32 * kt + 8 * q + 4 * half;
+    float rsq[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r0 = 32 * kt + 8 * q + 4 * half;               // four consecutive keys r0..r0+3
-        float rsq[4];
+    for (int i = 0; i < 4; ++i) {
+        const int src = 8 * q + 4 * half + i;                // lane that holds this key's row sum
+        rsq[i] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rsq[i] = __shfl(rs, 8 * q + 4 * half + i, 64);
+        for (int w = 0; w < 4; ++w) rsq[i] += slots[w * SLOT + 2 * TT * 16 * 64 + src];
+    }
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            const int t = 32 * tt + l32;
-            float dk[4], dv[4];
+    for (int tt = 0; tt < TT; ++tt) {
+        const int t = 32 * tt + l32;
+        float dk[4], dv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = r0 + i;
-                const float kprt = r < a.k ? a.Kp[((long)bh * a.k + r) * D + t] : 0.f;
-                dk[i] = accK[tt][4 * q + i] - rsq[i] * kprt;
-                dv[i] = accV[tt][4 * q + i];
-                imgK[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dk[i]);
-                imgV[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dv[i]);
+        for (int i = 0; i < 4; ++i) {
+            float sv = 0.f, sk = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                sv += slots[w * SLOT + (tt * 16 + 4 * q + i) * 64 + lane];
+                sk += slots[w * SLOT + ((TT + tt) * 16 + 4 * q + i) * 64 + lane];
             }
-            uint2 pk, pv;
-            pk.x = pack_bf16(dk[0], dk[1]); pk.y = pack_bf16(dk[2], dk[3]);
-            pv.x = pack_bf16(dv[0], dv[1]); pv.y = pack_bf16(dv[2], dv[3]);
-            *(uint2*)(imgTK + ((long)bh * D + t) * a.kp + r0) = pk;
-            *(uint2*)(imgTV + ((long)bh * D + t) * a.kp + r0) = pv;
+            const int r = r0 + i;
+            const float kprt = r < a.k ? a.Kp[((long)bh * a.k + r) * D + t] : 0.f;
+            dk[i] = sk - rsq[i] * kprt;
+            dv[i] = sv;
+            imgK[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dk[i]);
+            imgV[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dv[i]);
         }
+        uint2 pk, pv;
+        pk.x = pack_bf16(dk[0], dk[1]); pk.y = pack_bf16(dk[2], dk[3]);
+        pv.x = pack_bf16(dv[0], dv[1]); pv.y = pack_bf16(dv[2], dv[3]);
+        *(uint2*)(imgTK + ((long)bh * D + t) * a.kp + r0) = pk;
+        *(uint2*)(imgTV + ((long)bh * D + t) * a.kp + r0) = pv;
     }
 }
 
@@ -827,9 +854,13 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ka.img = img; ka.imgT = imgT;
         ka.omega_head_stride = omega_stride;
         ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kp = W.kp; ka.mf = p.mf;
-        const long kwaves = (long)p.BH * (W.kp / 32);
-        if (p.d == 64) hipLaunchKernelGGL(bwd_key_kernel<64>, grid1d(kwaves, 4), dim3(256), 0, s, ka);
-        else           hipLaunchKernelGGL(bwd_key_kernel<128>, grid1d(kwaves, 4), dim3(256), 0, s, ka);
+        const unsigned kgrid = (unsigned)(p.BH * (W.kp / 32));
+        const int klds = 4 * (2 * (p.d / 32) * 16 * 64 + 64) * 4;
+        const void* kk = p.d == 64 ? (const void*)bwd_key_kernel<64> : (const void*)bwd_key_kernel<128>;
+        if (hipFuncSetAttribute(kk, hipFuncAttributeMaxDynamicSharedMemorySize, klds) != hipSuccess)
+            return FLURKA_ERR_LAUNCH;
+        if (p.d == 64) hipLaunchKernelGGL(bwd_key_kernel<64>, dim3(kgrid), dim3(256), klds, s, ka);
+        else           hipLaunchKernelGGL(bwd_key_kernel<128>, dim3(kgrid), dim3(256), klds, s, ka);
         FLURKA_CHECK_LAUNCH();
     }
     {
