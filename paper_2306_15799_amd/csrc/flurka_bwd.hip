@@ -179,7 +179,7 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
 #pragma unroll
         for (int t = 0; t < TT; ++t) accN[t] = zero16();
         float den1[1] = {0.f}, mu1[1] = {-INFINITY};
-        forward_feature_pass<D, 1>(lw, L::w_pitch, ls, s_pitch, lz, lc, FT, l32, half, qf1, accN1, den1, mu1);
+        forward_feature_pass<D, 1>(lw, L::w_pitch, ls, s_pitch, lz, lc, FT, l32, half, qf1, accN1, den1, mu1, [] {});
         float den = half_sum(den1[0]);
         const float mu = mu1[0];
         const float inv = 1.f / den;

@@ -119,21 +119,33 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     constexpr int KS = D / 16;      // reduction steps over d
     constexpr int TT = D / 32;      // 32-row tiles of N^T
 
-    for (int row0 = row_begin + 32 * QT * wave; row0 < row_end; row0 += 32 * QT * NW) {
-        // B operand of the first contraction: this lane's query row, 8 consecutive d per step
-        int qrow[QT];
-        bool valid[QT];
-        uint4 qf[QT][KS];
+    // this lane's query rows (B operand of the first contraction: 8 consecutive d per step); the
+    // rows of the next tile are requested while the current tile is still being worked on
+    int qrow[QT];
+    bool valid[QT];
+    uint4 qf[QT][KS];
+    auto load_queries = [&](int row0, uint4 (&dst)[QT][KS]) {
+#pragma unroll
+        for (int i = 0; i < QT; ++i) {
+            int r = row0 + 32 * i + l32;
+            if (r >= a.n) r = a.n - 1;
+            const uint16_t* qg = a.Q + head_off + (long)r * D + 8 * half;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) dst[i][s] = ld16(qg + 16 * s);
+        }
+    };
+    const int row_first = row_begin + 32 * QT * wave;
+    if (row_first < row_end) load_queries(row_first, qf);
+
+    for (int row0 = row_first; row0 < row_end; row0 += 32 * QT * NW) {
         floatx16 accN[QT][TT];
         float den[QT];
+        const int row_next = row0 + 32 * QT * NW;
 #pragma unroll
         for (int i = 0; i < QT; ++i) {
             qrow[i] = row0 + 32 * i + l32;
             valid[i] = qrow[i] < a.n;
             if (!valid[i]) qrow[i] = a.n - 1;
-            const uint16_t* qg = a.Q + head_off + (long)qrow[i] * D + 8 * half;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) qf[i][s] = ld16(qg + 16 * s);
 #pragma unroll
             for (int t = 0; t < TT; ++t) accN[i][t] = zero16();
             den[i] = 0.f;
@@ -167,12 +179,15 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
 #pragma unroll
                     for (int i = 0; i < QT; ++i) accN[i][t] = mfma32(sa, pb[i], accN[i][t]);
                 }
+                __builtin_amdgcn_sched_barrier(0);        // keeps the unrolled steps from piling up loads
             }
+            if (row_next < row_end) load_queries(row_next, qf);
         } else {
             float mu[QT];     // running row maxima (same value in lanes l and l^32)
 #pragma unroll
             for (int i = 0; i < QT; ++i) mu[i] = -INFINITY;
-            forward_feature_pass<D, QT>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu);
+            forward_feature_pass<D, QT>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu,
+                                        [&] { if (row_next < row_end) load_queries(row_next, qf); });
         }
 #pragma unroll
         for (int i = 0; i < QT; ++i) {

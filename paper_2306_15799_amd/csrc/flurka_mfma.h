@@ -83,12 +83,16 @@ constexpr float FLURKA_LAZY_MAX = 5.0f;
 // FLURKA_LAZY_MAX) rescaling between iterations.
 // lw: omega [feature][D] (pitch w_pitch), ls: S^T [t][feature slot] (pitch s_pitch), lz, lc: z, c in
 // accumulator order; all in LDS.
-template <int D, int QT>
+// `last_hook()` runs at the start of the last iteration, which no longer needs qf: a caller that
+// streams over query tiles issues the loads of its next tile there (it may overwrite qf).
+template <int N> struct IterTag { static constexpr int value = N; };
+
+template <int D, int QT, class LastHook>
 __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, int w_pitch, const unsigned char* ls,
                                                      int s_pitch, const float* lz, const float* lc, int FT,
-                                                     int l32, int half, const uint4 (&qf)[QT][D / 16],
+                                                     int l32, int half, uint4 (&qf)[QT][D / 16],
                                                      floatx16 (&accN)[QT][D / 32], float (&den)[QT],
-                                                     float (&mu)[QT]) {
+                                                     float (&mu)[QT], LastHook&& last_hook) {
     constexpr int KS = D / 16, TT = D / 32;
     constexpr int EPC = 16 / KS;                 // accumulator elements handled per group
     const unsigned char* wrow = lw + l32 * w_pitch + 16 * half;        // + 32*ft rows, + 32*s
@@ -138,14 +142,18 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         for (int i = 0; i < QT; ++i) maybe_rescale(i, tile_max(u[i]));
     }
 
-    for (int ft = 0; ft < FT; ++ft) {
-        const int nft = ft + 1 < FT ? ft + 1 : ft;            // last iteration recomputes its own tile, unused
+    auto iteration = [&](int ft, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value != 0;
+        const int nft = LAST ? ft : ft + 1;
         float nshift[QT];
         floatx16 un[QT];
-        {
+        if constexpr (LAST) last_hook();
+#pragma unroll
+        for (int i = 0; i < QT; ++i) nshift[i] = -mu[i] * FLURKA_LOG2E;
+        if constexpr (!LAST) {
             const floatx16 cn = load_c(nft);
 #pragma unroll
-            for (int i = 0; i < QT; ++i) { un[i] = cn; nshift[i] = -mu[i] * FLURKA_LOG2E; }
+            for (int i = 0; i < QT; ++i) un[i] = cn;
         }
         float zv[16];
         {
@@ -157,8 +165,10 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
             }
         }
         uint4 wa[KS], sa[2 * TT];
+        if constexpr (!LAST) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wa[s] = *(const uint4*)(wrow + (32 * nft) * w_pitch + 32 * s);
+            for (int s = 0; s < KS; ++s) wa[s] = *(const uint4*)(wrow + (32 * nft) * w_pitch + 32 * s);
+        }
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
             sa[2 * t] = *(const uint4*)(srow + (32 * t) * s_pitch + 64 * ft);
@@ -169,8 +179,10 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             // dependent MFMAs of the next tile's u^T (one per query tile) ...
+            if constexpr (!LAST) {
 #pragma unroll
-            for (int i = 0; i < QT; ++i) un[i] = mfma32(wa[s], qf[i][s], un[i]);
+                for (int i = 0; i < QT; ++i) un[i] = mfma32(wa[s], qf[i][s], un[i]);
+            }
             // ... over the exp work of EPC elements of this tile
 #pragma unroll
             for (int i = 0; i < QT; ++i) {
@@ -200,26 +212,34 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         }
         // N^T MFMAs with the second half of P^T, over the maximum of the next tile
         float tmax[QT];
+        if constexpr (!LAST) {
 #pragma unroll
-        for (int i = 0; i < QT; ++i) tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
+            for (int i = 0; i < QT; ++i) tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
+        }
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
             constexpr int per = (12 + TT - 1) / TT;          // elements 3..14 spread over the TT groups
 #pragma unroll
             for (int i = 0; i < QT; ++i) {
                 accN[i][t] = mfma32(sa[2 * t + 1], make_uint4(pk[i][4], pk[i][5], pk[i][6], pk[i][7]), accN[i][t]);
+                if constexpr (!LAST) {
 #pragma unroll
-                for (int g = 3 + t * per; g < 3 + (t + 1) * per && g < 15; ++g) tmax[i] = fmaxf(tmax[i], un[i][g]);
+                    for (int g = 3 + t * per; g < 3 + (t + 1) * per && g < 15; ++g) tmax[i] = fmaxf(tmax[i], un[i][g]);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (!LAST) {
 #pragma unroll
-        for (int i = 0; i < QT; ++i) {
-            tmax[i] = half_max(fmaxf(tmax[i], un[i][15]));
-            if (ft + 1 < FT) maybe_rescale(i, tmax[i]);
-            u[i] = un[i];
+            for (int i = 0; i < QT; ++i) {
+                tmax[i] = half_max(fmaxf(tmax[i], un[i][15]));
+                maybe_rescale(i, tmax[i]);
+                u[i] = un[i];
+            }
         }
-    }
+    };
+    for (int ft = 0; ft + 1 < FT; ++ft) iteration(ft, IterTag<0>{});
+    iteration(FT - 1, IterTag<1>{});
 }
 
 }  // namespace flurka
