@@ -189,7 +189,7 @@ def main():
         fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, algo=args.algo,
                            out=out, ctx=ctx, workspace=ws_f)
         if w.backward:
-            fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], g["dOut"], ctx,
+            fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, g["dOut"], ctx,
                                phi=w.phi, algo=args.algo, workspace=ws_b, grads=grads)
 
     for _ in range(args.warmup):

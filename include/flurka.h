@@ -87,22 +87,24 @@ FLURKA_API int flurka_version(void);
 /* Human-readable name of a status code; never NULL. */
 FLURKA_API const char* flurka_status_str(flurka_status s);
 
-/* Bytes of the context buffer that carries the key-side state from the
- * forward to the backward pass: K', V' (B,H,k,d), S = phi(K')^T V' (B,H,mf,d),
- * z = phi(K')^T 1 (B,H,mf) and the exponent shifts c (B,H,mf); mf = m
- * (performer) or d (elu1).  S and z are stored for phi(K') with column j
+/* Bytes of the context buffer that carries state from the forward to the
+ * backward pass: K', V' (B,H,k,d), S = phi(K')^T V' (B,H,mf,d),
+ * z = phi(K')^T 1 (B,H,mf), the exponent shifts c (B,H,mf) and, per query row,
+ * lse (B,H,n) = ln of the denominator phi(Q) z as the library scales it (below);
+ * mf = m (performer) or d (elu1).  S and z are stored for phi(K') with column j
  * scaled by exp(-c_j) (c_j = max_r of the key exponent, 0 for elu1); the same
- * factor is put back on feature j of phi(Q), so the ratio is unchanged.
+ * factor is put back on feature j of phi(Q), so the ratio is unchanged:
+ * lse_i = ln sum_j exp(omega_j . q_i + c_j) z_j  (elu1: ln sum_j phi(q_i)_j z_j).
  * Returns 0 for an invalid shape. */
 FLURKA_API size_t flurka_ctx_bytes(int B, int H, int n, int d, int k, int m,
                         flurka_dtype dtype, flurka_phi phi);
 
-/* Offsets, in float32 elements from the start of ctx, of its five segments in
- * the order K', V', S, z, c, written to the HOST array `offsets5`
+/* Offsets, in float32 elements from the start of ctx, of its six segments in
+ * the order K', V', S, z, c, lse, written to the HOST array `offsets6`
  * (for inspection and tests).  Returns FLURKA_ERR_NULL / _SHAPE / _DTYPE on
  * bad arguments. */
 FLURKA_API flurka_status flurka_ctx_layout(int B, int H, int n, int d, int k, int m,
-                                flurka_dtype dtype, flurka_phi phi, size_t* offsets5);
+                                flurka_dtype dtype, flurka_phi phi, size_t* offsets6);
 
 /* Bytes of scratch the given pass needs for `algo` (AUTO = the maximum over
  * the paths AUTO may take).  Contents need not survive between calls.
@@ -125,7 +127,7 @@ FLURKA_API int flurka_fast_path_supported(int B, int H, int n, int d, int k, int
  *                  all heads; ignored (may be NULL) for FLURKA_PHI_ELU1
  *   out       out  (B, H, n, d)   rounded once to `dtype` at the final store
  *   ctx       out  flurka_ctx_bytes(...) bytes, 256-byte aligned; holds the
- *                  key-side state afterwards (input of flurka_attn_bwd)
+ *                  key-side state and lse afterwards (input of flurka_attn_bwd)
  *   workspace      flurka_workspace_bytes(..., FLURKA_PASS_FWD, algo) bytes,
  *                  256-byte aligned scratch
  */
@@ -143,6 +145,9 @@ FLURKA_API flurka_status flurka_attn_fwd(const void* Q, const void* K, const voi
  * Backward of the forward above (chain rule; the paper trains through this
  * layer but prints no backward).  Given dOut = d loss / d out:
  *
+ *   out         in   (B, H, n, d), the forward's result for the same inputs
+ *                    (the row sums of dOut * out enter every gradient; the
+ *                    generic kernels recompute them and only check the pointer)
  *   dQ, dK, dV  out  (B, H, n, d)
  *   dE, dF      out  (k, n), summed over batch and heads (E, F are shared),
  *                    overwritten, not accumulated into
@@ -153,7 +158,8 @@ FLURKA_API flurka_status flurka_attn_fwd(const void* Q, const void* K, const voi
  */
 FLURKA_API flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V,
                               const void* E, const void* F, const void* omega,
-                              const void* dOut, const void* ctx, size_t ctx_bytes,
+                              const void* out, const void* dOut,
+                              const void* ctx, size_t ctx_bytes,
                               void* dQ, void* dK, void* dV, void* dE, void* dF,
                               void* workspace, size_t workspace_bytes,
                               int B, int H, int n, int d, int k, int m,

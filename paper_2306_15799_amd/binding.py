@@ -69,7 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.flurka_attn_fwd.argtypes = ([c_void] * 7 + [c_void, c_size, c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
     lib.flurka_attn_bwd.restype = c_int
-    lib.flurka_attn_bwd.argtypes = ([c_void] * 7 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
+    lib.flurka_attn_bwd.argtypes = ([c_void] * 8 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
     lib.flurka_profile_enable.restype = c_int
     lib.flurka_profile_enable.argtypes = [c_int]
@@ -114,15 +114,16 @@ def ctx_bytes(B, H, n, d, k, m, dtype, phi) -> int:
 
 
 def ctx_views(ctx: torch.Tensor, B, H, n, d, k, m, dtype, phi) -> dict:
-    """float32 views of the context buffer's segments (K', V', S, z, c)."""
+    """float32 views of the context buffer's segments (K', V', S, z, c, lse)."""
     lib = load_library()
-    offs = (ctypes.c_size_t * 5)()
+    offs = (ctypes.c_size_t * 6)()
     st = lib.flurka_ctx_layout(B, H, n, d, k, m, dtype, _PHI[phi], offs)
     if st != OK:
         raise FlurkaError(st, "flurka_ctx_layout")
     mf = d if _PHI[phi] == PHI_ELU1 else m
     f = ctx.view(torch.float32)
-    shapes = {"Kp": (B, H, k, d), "Vp": (B, H, k, d), "S": (B, H, mf, d), "z": (B, H, mf), "c": (B, H, mf)}
+    shapes = {"Kp": (B, H, k, d), "Vp": (B, H, k, d), "S": (B, H, mf, d), "z": (B, H, mf), "c": (B, H, mf),
+              "lse": (B, H, n)}
     views = {}
     for (name, shape), off in zip(shapes.items(), offs):
         cnt = 1
@@ -213,14 +214,14 @@ def flurka_attn_fwd(Q, K, V, E, F, omega, phi="performer", algo="auto", out=None
     return out, ctx
 
 
-def flurka_attn_bwd(Q, K, V, E, F, omega, dOut, ctx, phi="performer", algo="auto", workspace=None,
+def flurka_attn_bwd(Q, K, V, E, F, omega, out, dOut, ctx, phi="performer", algo="auto", workspace=None,
                     stream=None, grads=None):
-    """dQ, dK, dV, dE, dF given dOut and the ctx returned by flurka_attn_fwd."""
+    """dQ, dK, dV, dE, dF given dOut and the (out, ctx) returned by flurka_attn_fwd."""
     lib = load_library()
     B, H, n, d, k, m, per_head, omega_shape = _shapes(Q, E, omega, phi)
     dt, dev = Q.dtype, Q.device
     code = _dtype_code(Q)
-    for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (dOut, "dOut")):
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (out, "out"), (dOut, "dOut")):
         _check(t, name, (B, H, n, d), dt, dev)
     for t, name in ((E, "E"), (F, "F")):
         _check(t, name, (k, n), dt, dev)
@@ -239,7 +240,7 @@ def flurka_attn_bwd(Q, K, V, E, F, omega, dOut, ctx, phi="performer", algo="auto
         workspace = alloc_buffer(wb, dev)
     s = stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
     st = lib.flurka_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(E), _ptr(F),
-                             _ptr(omega) if omega_shape is not None else None, _ptr(dOut),
+                             _ptr(omega) if omega_shape is not None else None, _ptr(out), _ptr(dOut),
                              _ptr(ctx), ctx.numel() * ctx.element_size(),
                              _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dE), _ptr(dF),
                              _ptr(workspace), workspace.numel() * workspace.element_size(),

@@ -33,7 +33,7 @@ void stage_end(hipStream_t s, Stage id) {
 
 namespace {
 
-constexpr int kVersion = 100;
+constexpr int kVersion = 110;
 
 flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
                            int dtype, int phi, Problem* out) {
@@ -86,13 +86,14 @@ size_t flurka_ctx_bytes(int B, int H, int n, int d, int k, int m, flurka_dtype d
 }
 
 flurka_status flurka_ctx_layout(int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
-                                flurka_phi phi, size_t* offsets5) {
-    if (!offsets5) return FLURKA_ERR_NULL;
+                                flurka_phi phi, size_t* offsets6) {
+    if (!offsets6) return FLURKA_ERR_NULL;
     Problem p;
     flurka_status st = make_problem(B, H, n, d, k, m, 1, dtype, phi, &p);
     if (st != FLURKA_OK) return st;
     const CtxLayout L = ctx_layout(p);
-    offsets5[0] = L.Kp; offsets5[1] = L.Vp; offsets5[2] = L.S; offsets5[3] = L.z; offsets5[4] = L.c;
+    offsets6[0] = L.Kp; offsets6[1] = L.Vp; offsets6[2] = L.S; offsets6[3] = L.z; offsets6[4] = L.c;
+    offsets6[5] = L.lse;
     return FLURKA_OK;
 }
 
@@ -147,8 +148,8 @@ flurka_status flurka_attn_fwd(const void* Q, const void* K, const void* V, const
 }
 
 flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
-                              const void* omega, const void* dOut, const void* ctx, size_t ctx_bytes,
-                              void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
+                              const void* omega, const void* out, const void* dOut, const void* ctx,
+                              size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
                               size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
                               int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
                               void* stream) {
@@ -156,24 +157,24 @@ flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const
     flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
     if (st != FLURKA_OK) return st;
     if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
-    if (!Q || !K || !V || !E || !F || !dOut || !ctx || !dQ || !dK || !dV || !dE || !dF || !workspace)
+    if (!Q || !K || !V || !E || !F || !out || !dOut || !ctx || !dQ || !dK || !dV || !dE || !dF || !workspace)
         return FLURKA_ERR_NULL;
     if (!p.elu && !omega) return FLURKA_ERR_NULL;
     const size_t es = p.bf16 ? 2 : 4;
     if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
-        misaligned(F, es) || misaligned(dOut, es) || (omega && misaligned(omega, es)) ||
+        misaligned(F, es) || misaligned(out, es) || misaligned(dOut, es) || (omega && misaligned(omega, es)) ||
         misaligned(dQ, es) || misaligned(dK, es) || misaligned(dV, es) || misaligned(dE, es) ||
         misaligned(dF, es) || misaligned(ctx, 256) || misaligned(workspace, 256))
         return FLURKA_ERR_ALIGN;
     const bool fast_ok = fast_supported(p, 1) && fast_pointers_ok(Q, K, V, E, F, omega, dOut) &&
-                         fast_pointers_ok(dQ, dK, dV, dE, dF, nullptr, dQ);
+                         fast_pointers_ok(dQ, dK, dV, dE, dF, nullptr, out);
     if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
     const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
     if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
     const size_t need = use_fast ? fast_ws_bytes(p, 1) : generic_ws_layout(p, 1).total * sizeof(float);
     if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
 
-    BwdArgs a{Q, K, V, E, F, omega, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace};
+    BwdArgs a{Q, K, V, E, F, omega, out, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace};
     hipStream_t s = (hipStream_t)stream;
     return use_fast ? fast_backward(p, a, s) : generic_backward(p, a, s);
 }

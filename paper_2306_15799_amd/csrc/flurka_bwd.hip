@@ -8,10 +8,10 @@
 // (the -rowsum(dU) q term of the feature map's derivative vanishes: sum_j dU_ij = 0 identically).
 //
 // Two kernels, both built on v_mfma_f32_32x32x16_bf16 with operands chained through registers:
-//   bwd_query_x  one wavefront per 32 query rows, lane = query: recomputes the forward (pass 1),
-//                stores lambda_i and g_i, then (pass 2) forms dU^T tile by tile and accumulates dQ^T
+//   bwd_query_x  one wavefront per 32 query rows, lane = query: lambda_i comes from the forward (ctx),
+//                g_i from the rows of dOut and out; forms dU^T tile by tile and accumulates dQ^T
 //   bwd_query_y  one wavefront per (head, 32 features, query range), lane = feature: recomputes W with
-//                the stored lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
+//                the same lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
 #include "flurka_fast.h"
 #include "flurka_gemm.h"
 
@@ -35,27 +35,22 @@ __host__ __device__ inline int slot_to_elem16(int p) {
 
 // ---------------------------------------------------------------------------
 // Operand images for bwd_query_x, per head (S, z, c from ctx; omega from the caller):
-//   St  (d x mf)   St[t][slot]  = S[feat(slot)][t]        A operand of N^T = S^T P^T
 //   Sp  (mf x d)   Sp[j][slot]  = S[j][t(slot)]           A operand of T'^T = S G^T
 //   Wt  (d x m)    Wt[t][slot]  = omega[feat(slot)][t]    A operand of dQ^T = omega^T dU^T  (per omega head)
 //   zp, cp (mf)    z, c in accumulator order of a 32-feature tile
 // ---------------------------------------------------------------------------
-__global__ void bwd_pack_kernel(uint16_t* St, uint16_t* Sp, float* zp, float* cp, const float* S,
-                                const float* z, const float* c, int mf, int d, long total) {
+__global__ void bwd_pack_kernel(uint16_t* Sp, float* zp, float* cp, const float* S, const float* z,
+                                const float* c, int mf, int d, long total) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const long bh = idx / ((long)mf * d);
     const int rem = (int)(idx % ((long)mf * d));
-    {   // St: rem = t * mf + slot
-        const int t = rem / mf, slot = rem % mf;
-        const int f = (slot & ~15) + slot_to_elem16(slot & 15);
-        St[idx] = f32_to_bf16(S[(bh * mf + f) * d + t]);
-        if (t == 0) {
-            const int g = slot & 15, h = (slot >> 4) & 1;
-            const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
-            zp[bh * mf + slot] = z[bh * mf + fz];
-            cp[bh * mf + slot] = c[bh * mf + fz];
-        }
+    if (rem < mf) {
+        const int slot = rem;
+        const int g = slot & 15, h = (slot >> 4) & 1;
+        const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
+        zp[bh * mf + slot] = z[bh * mf + fz];
+        cp[bh * mf + slot] = c[bh * mf + fz];
     }
     {   // Sp: rem = j * d + slot
         const int j = rem / d, slot = rem % d;
@@ -89,14 +84,14 @@ __global__ void bwd_pack_omega_kernel(uint16_t* Wt, uint32_t* Wpair, const uint1
 struct BwdXArgs {
     const uint16_t* Q;
     const uint16_t* G;         // dOut
+    const uint16_t* O;         // out
     const uint16_t* omega;     // (H|1, m, d)
-    const uint16_t* St;        // (BH, d, mf)
     const uint16_t* Sp;        // (BH, mf, d)
     const uint16_t* Wt;        // (H|1, d, m)
     const float* zp;
     const float* cp;
+    const float* lse;          // (BH, n)  lambda_i, written by the forward
     uint16_t* dQ;
-    float* lse;                // (BH, n)  lambda_i
     float* delta;              // (BH, n)  g_i
     int n, H, mf, rows_per_wg, wgs_per_head;
     long omega_head_stride;    // 0 if shared
@@ -106,7 +101,7 @@ template <int D>
 struct BwdXLds {
     static constexpr int w_pitch = (D + 8) * 2;                          // rows of length d
     static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }   // rows of length mf
-    static __host__ __device__ int total(int mf) { return 2 * mf * w_pitch + 2 * D * s_pitch(mf) + mf * 8; }
+    static __host__ __device__ int total(int mf) { return 2 * mf * w_pitch + D * s_pitch(mf) + mf * 8; }
 };
 
 template <int D>
@@ -121,8 +116,7 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
     const int s_pitch = L::s_pitch(mf);
     unsigned char* lw = lds;                              // omega   [feature][d]
     unsigned char* lsp = lw + mf * L::w_pitch;            // Sp      [feature][t slot]
-    unsigned char* ls = lsp + mf * L::w_pitch;            // St      [t][feature slot]
-    unsigned char* lwt = ls + D * s_pitch;                // Wt      [t][feature slot]
+    unsigned char* lwt = lsp + mf * L::w_pitch;           // Wt      [t][feature slot]
     float* lz = (float*)(lwt + D * s_pitch);
     float* lc = lz + mf;
     {
@@ -134,12 +128,10 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
             *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
             *(uint4*)(lsp + r * L::w_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
         }
-        const uint16_t* sg = a.St + (long)bh * D * mf;
         const uint16_t* wtg = a.Wt + (long)(bh % a.H) * a.omega_head_stride;
         const int cps = mf / 8;
         for (int c = tid; c < D * cps; c += 512) {
             const int r = c / cps, q = c % cps;
-            *(uint4*)(ls + r * s_pitch + 16 * q) = ld16(sg + (long)r * mf + 8 * q);
             *(uint4*)(lwt + r * s_pitch + 16 * q) = ld16(wtg + (long)r * mf + 8 * q);
         }
         const float* zg = a.zp + (long)bh * mf;
@@ -153,63 +145,61 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
     int row_end = row_begin + a.rows_per_wg;
     if (row_end > a.n) row_end = a.n;
     constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
-    constexpr int TT = D / 32;      // 32-row tiles of N^T and dQ^T
+    constexpr int TT = D / 32;      // 32-row tiles of dQ^T
     const int FT = mf / 32;
 
-    for (int row0 = row_begin + 32 * wave; row0 < row_end; row0 += 32 * 8) {
-        int qrow = row0 + l32;
-        const bool valid = qrow < a.n;
-        if (!valid) qrow = a.n - 1;
-        const uint16_t* qg = a.Q + head_off + (long)qrow * D + 8 * half;
-        const uint16_t* gg = a.G + head_off + (long)qrow * D + 4 * half;
-        uint4 qf1[1][KS], gf[KS];
-        uint4 (&qf)[KS] = qf1[0];
+    // One tile = this lane's query row: Q as the B operand of u^T (8 consecutive d per step), dOut as
+    // the B operand of S G^T (slots (h, j) of step s hold t = 16*s + 8*(j/4) + 4*h + j%4), the same
+    // elements of out (for g_i) and lambda_i.  The next tile is requested before this one is worked on.
+    struct Tile { uint4 q[KS], g[KS], o[KS]; float lam; };
+    auto load_tile = [&](int row0, Tile& t) {
+        int r = row0 + l32;
+        if (r >= a.n) r = a.n - 1;
+        const uint16_t* qg = a.Q + head_off + (long)r * D + 8 * half;
+        const uint16_t* gg = a.G + head_off + (long)r * D + 4 * half;
+        const uint16_t* og = a.O + head_off + (long)r * D + 4 * half;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            qf[s] = ld16(qg + 16 * s);
-            // B operand of S G^T: slots (h, j) of step s hold t = 16*s + 8*(j/4) + 4*h + j%4
+            t.q[s] = ld16(qg + 16 * s);
             const uint2 g0 = *(const uint2*)(gg + 16 * s);
             const uint2 g1 = *(const uint2*)(gg + 16 * s + 8);
-            gf[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
+            t.g[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
+            const uint2 o0 = *(const uint2*)(og + 16 * s);
+            const uint2 o1 = *(const uint2*)(og + 16 * s + 8);
+            t.o[s] = make_uint4(o0.x, o0.y, o1.x, o1.y);
         }
+        t.lam = a.lse[(long)bh * a.n + r];
+    };
+    auto dot2 = [](uint32_t x, uint32_t y, float acc) {
+        acc = fmaf(bf16_to_f32((uint16_t)(x & 0xffffu)), bf16_to_f32((uint16_t)(y & 0xffffu)), acc);
+        return fmaf(bf16_to_f32((uint16_t)(x >> 16)), bf16_to_f32((uint16_t)(y >> 16)), acc);
+    };
 
-        // ---- pass 1: forward recompute -> D, out, g_i, lambda_i ----------------------------------
-        floatx16 accN1[1][TT];
-        floatx16 (&accN)[TT] = accN1[0];
-#pragma unroll
-        for (int t = 0; t < TT; ++t) accN[t] = zero16();
-        float den1[1] = {0.f}, mu1[1] = {-INFINITY};
-        forward_feature_pass<D, 1>(lw, L::w_pitch, ls, s_pitch, lz, lc, FT, l32, half, qf1, accN1, den1, mu1, [] {});
-        float den = half_sum(den1[0]);
-        const float mu = mu1[0];
-        const float inv = 1.f / den;
-        // g_i = G_i . out_i ; this lane holds t = 32*tt + 8*(g/4) + 4*half + g%4 of its query,
-        // which are the 8-byte chunks of gf: step s = 2*tt + (g/8), chunk (g/4)%2
+    const int row_first = row_begin + 32 * wave;
+    Tile cur, nxt;
+    if (row_first < row_end) load_tile(row_first, cur);
+    for (int row0 = row_first; row0 < row_end; row0 += 32 * 8) {
+        const int qrow = row0 + l32;
+        const bool valid = qrow < a.n;
+        if (row0 + 32 * 8 < row_end) load_tile(row0 + 32 * 8, nxt);
+
+        // g_i = G_i . out_i: the two halves of the wavefront hold complementary elements of the row
         float gdot = 0.f;
 #pragma unroll
-        for (int t = 0; t < TT; ++t)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint4 gv = gf[2 * t + (q >> 1)];
-                const uint32_t w0 = (q & 1) ? gv.z : gv.x, w1 = (q & 1) ? gv.w : gv.y;
-                gdot = fmaf(bf16_to_f32((uint16_t)(w0 & 0xffffu)), accN[t][4 * q], gdot);
-                gdot = fmaf(bf16_to_f32((uint16_t)(w0 >> 16)), accN[t][4 * q + 1], gdot);
-                gdot = fmaf(bf16_to_f32((uint16_t)(w1 & 0xffffu)), accN[t][4 * q + 2], gdot);
-                gdot = fmaf(bf16_to_f32((uint16_t)(w1 >> 16)), accN[t][4 * q + 3], gdot);
-            }
-        gdot = half_sum(gdot);
-        const float gi = gdot * inv;                         // g_i
-        const float lam = mu + __logf(den);                  // lambda_i
-        if (valid && half == 0) {
-            a.lse[(long)bh * a.n + qrow] = lam;
-            a.delta[(long)bh * a.n + qrow] = gi;
+        for (int s = 0; s < KS; ++s) {
+            gdot = dot2(cur.g[s].x, cur.o[s].x, gdot);
+            gdot = dot2(cur.g[s].y, cur.o[s].y, gdot);
+            gdot = dot2(cur.g[s].z, cur.o[s].z, gdot);
+            gdot = dot2(cur.g[s].w, cur.o[s].w, gdot);
         }
+        const float gi = half_sum(gdot);
+        if (valid && half == 0) a.delta[(long)bh * a.n + qrow] = gi;
 
-        // ---- pass 2: dU^T tile by tile, dQ^T = omega^T dU^T ---------------------------------------
+        // dU^T tile by tile, dQ^T = omega^T dU^T
         floatx16 accQ[TT];
 #pragma unroll
         for (int t = 0; t < TT; ++t) accQ[t] = zero16();
-        const float nlam = -lam * LOG2E;
+        const float nlam = -cur.lam * LOG2E;
         for (int ft = 0; ft < FT; ++ft) {
             floatx16 u;
             {
@@ -223,8 +213,8 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
             floatx16 tp = zero16();                          // T'^T tile: G_i . S_j
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                u = mfma32(*(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), qf[s], u);
-                tp = mfma32(*(const uint4*)(lsp + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), gf[s], tp);
+                u = mfma32(*(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), cur.q[s], u);
+                tp = mfma32(*(const uint4*)(lsp + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), cur.g[s], tp);
             }
             const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
             uint32_t pk[8];
@@ -265,6 +255,7 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
                     *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
                 }
         }
+        cur = nxt;
     }
 }
 
@@ -738,7 +729,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
 }
 
 struct FastBwdWs {
-    size_t St, Sp, Wt, Wpair, zp, cp, lse, delta, dSpart, dzpart, dSimg, dSpair, dz, img, imgT, epart, total;
+    size_t Sp, Wt, Wpair, zp, cp, delta, dSpart, dzpart, dSimg, dSpair, dz, img, imgT, epart, total;
     int kp;      // k rounded up to whole 64-slot reduction steps of the gradient GEMMs
 };
 
@@ -747,13 +738,11 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     const BwdYPlan y = bwd_y_plan(p);
     const size_t BH = (size_t)p.BH;
     size_t o = 0;
-    W.St = o;     o += round_up(BH * p.d * p.mf * 2, 256);
     W.Sp = o;     o += round_up(BH * p.mf * p.d * 2, 256);
     W.Wt = o;     o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
     W.Wpair = o;  o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
     W.zp = o;     o += round_up(BH * p.mf * 4, 256);
     W.cp = o;     o += round_up(BH * p.mf * 4, 256);
-    W.lse = o;    o += round_up(BH * p.n * 4, 256);
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
     W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
@@ -791,8 +780,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     {
         stage_begin(s);
         const long total = (long)p.BH * p.mf * p.d;
-        hipLaunchKernelGGL(bwd_pack_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.St),
-                           (uint16_t*)(wsb + W.Sp), (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S,
+        hipLaunchKernelGGL(bwd_pack_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Sp), (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S,
                            a.ctx + L.z, a.ctx + L.c, p.mf, p.d, total);
         FLURKA_CHECK_LAUNCH();
         const long wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
@@ -803,10 +791,10 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
 
         BwdXArgs xa{};
         xa.Q = (const uint16_t*)a.Q; xa.G = (const uint16_t*)a.dOut; xa.omega = (const uint16_t*)a.omega;
-        xa.St = (const uint16_t*)(wsb + W.St); xa.Sp = (const uint16_t*)(wsb + W.Sp);
+        xa.O = (const uint16_t*)a.out; xa.Sp = (const uint16_t*)(wsb + W.Sp);
         xa.Wt = (const uint16_t*)(wsb + W.Wt);
         xa.zp = (const float*)(wsb + W.zp); xa.cp = (const float*)(wsb + W.cp);
-        xa.dQ = (uint16_t*)a.dQ; xa.lse = (float*)(wsb + W.lse); xa.delta = (float*)(wsb + W.delta);
+        xa.dQ = (uint16_t*)a.dQ; xa.lse = a.ctx + L.lse; xa.delta = (float*)(wsb + W.delta);
         xa.n = p.n; xa.H = p.H; xa.mf = p.mf; xa.omega_head_stride = omega_stride;
         int wgs_per_head = (512 + p.BH - 1) / p.BH;
         int rows = (p.n + wgs_per_head - 1) / wgs_per_head;

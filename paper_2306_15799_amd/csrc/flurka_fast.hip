@@ -57,6 +57,7 @@ struct QueryArgs {
     const float* zp;           // (BH, mf)
     const float* cp;           // (BH, mf) exponent shifts, same order as zp
     uint16_t* out;
+    float* lse;                // (BH, n) log of the denominator, kept for the backward pass
     int n, H, mf, rows_per_wg, wgs_per_head;
     long omega_head_stride;    // 0 if shared
 };
@@ -151,6 +152,9 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
             den[i] = 0.f;
         }
 
+        float mu[QT];     // running row maxima (same value in lanes l and l^32); 0 for elu1
+#pragma unroll
+        for (int i = 0; i < QT; ++i) mu[i] = ELU ? 0.f : -INFINITY;
         if (ELU) {
             // P = elu(q)+1 straight in operand order; features are the d coordinates
 #pragma unroll
@@ -183,16 +187,15 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
             }
             if (row_next < row_end) load_queries(row_next, qf);
         } else {
-            float mu[QT];     // running row maxima (same value in lanes l and l^32)
-#pragma unroll
-            for (int i = 0; i < QT; ++i) mu[i] = -INFINITY;
             forward_feature_pass<D, QT>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu,
                                         [&] { if (row_next < row_end) load_queries(row_next, qf); });
         }
 #pragma unroll
         for (int i = 0; i < QT; ++i) {
-            const float inv = 1.f / half_sum(den[i]);
+            const float dsum = half_sum(den[i]);
+            const float inv = 1.f / dsum;
             if (valid[i]) {
+                if (half == 0) a.lse[(long)bh * a.n + qrow[i]] = mu[i] + __logf(dsum);
                 uint16_t* og = a.out + head_off + (long)qrow[i] * D;
 #pragma unroll
                 for (int t = 0; t < TT; ++t)
@@ -322,6 +325,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         qa.zp = (const float*)(wsb + W.zp);
         qa.cp = (const float*)(wsb + W.cp);
         qa.out = (uint16_t*)a.out;
+        qa.lse = a.ctx + L.lse;
         qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
         qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
         // about two workgroups per compute unit, each a multiple of the rows one pass of a workgroup covers

@@ -203,8 +203,10 @@ __global__ void column_sum_kernel(float* z, const float* Phi, int k, int m, long
     z[idx] = s;
 }
 
-// P[row, :] <- exp(v - max_j v), v_j = U[row, j] + c[bh, j]   (rows = BH*nr)
-__global__ __launch_bounds__(256) void row_exp_kernel(float* U, const float* c, long rows, int nr, int m) {
+// P[row, :] <- exp(v - max_j v), v_j = U[row, j] + c[bh, j]   (rows = BH*nr).  With `rowmax` (the
+// lse segment, forward only) the maximum of row (bh, row0 + i) is left there for fwd_finish_kernel.
+__global__ __launch_bounds__(256) void row_exp_kernel(float* U, const float* c, long rows, int nr, int m,
+                                                      float* rowmax, int n, int row0) {
     const int lane = threadIdx.x & 63;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
@@ -214,12 +216,15 @@ __global__ __launch_bounds__(256) void row_exp_kernel(float* U, const float* c, 
     for (int j = lane; j < m; j += 64) mx = fmaxf(mx, u[j] + cc[j]);
     mx = wave_max(mx);
     for (int j = lane; j < m; j += 64) u[j] = expf(u[j] + cc[j] - mx);
+    if (rowmax && lane == 0) rowmax[(row / nr) * n + row0 + row % nr] = mx;
 }
 
-// D = P.z ; out = N / D  (rows = BH*nr; output row = bh*n + row0 + i)
+// D = P.z ; out = N / D  (rows = BH*nr; output row = bh*n + row0 + i); lse = row maximum + ln D
+// (`has_max`: row_exp_kernel left the maximum in lse; otherwise it is 0)
 __global__ __launch_bounds__(256) void fwd_finish_kernel(const float* P, const float* N, const float* z,
                                                          void* out, int out_bf16, long rows, int nr,
-                                                         int n, int row0, int mf, int d) {
+                                                         int n, int row0, int mf, int d, float* lse,
+                                                         int has_max) {
     const int lane = threadIdx.x & 63;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
@@ -232,6 +237,10 @@ __global__ __launch_bounds__(256) void fwd_finish_kernel(const float* P, const f
     const float* nrow = N + row * d;
     const long o = (bh * n + row0 + i) * d;
     for (int t = lane; t < d; t += 64) store_elem(out, o + t, nrow[t] / D, out_bf16);
+    if (lane == 0) {
+        float* l = lse + bh * n + row0 + i;
+        *l = (has_max ? *l : 0.f) + logf(D);
+    }
 }
 
 // Backward row preparation:  D = P.z, out = N/D, dD = -(G.out)/D, N <- dN = G/D.
@@ -329,7 +338,7 @@ static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total
 // P (B,H,nr,mf) <- shifted phi(Q[row0 : row0+nr]);  N (B,H,nr,d) <- P S
 static flurka_status query_features_and_numerator(const Problem& p, const void* Q, const void* omega,
                                                   const float* S, const float* c, float* P, float* N,
-                                                  int row0, int nr, hipStream_t s) {
+                                                  int row0, int nr, float* rowmax, hipStream_t s) {
     const long rows = (long)p.BH * nr;
     if (!p.elu) {
         GemmArgs g{};
@@ -342,7 +351,7 @@ static flurka_status query_features_and_numerator(const Problem& p, const void* 
         g.H = p.H; g.a_bf16 = p.bf16; g.b_bf16 = p.bf16;
         flurka_status st = launch_gemm(g, p.BH, s);
         if (st != FLURKA_OK) return st;
-        hipLaunchKernelGGL(row_exp_kernel, grid1d(rows, 4), dim3(256), 0, s, P, c, rows, nr, p.m);
+        hipLaunchKernelGGL(row_exp_kernel, grid1d(rows, 4), dim3(256), 0, s, P, c, rows, nr, p.m, rowmax, p.n, row0);
         FLURKA_CHECK_LAUNCH();
     } else {
         const long total = rows * p.d;
@@ -458,11 +467,11 @@ flurka_status generic_forward(const Problem& p, const FwdArgs& a, hipStream_t s)
     StageScope sc(s, STAGE_QUERY);
     for (int row0 = 0; row0 < p.n; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
-        st = query_features_and_numerator(p, a.Q, a.omega, a.ctx + L.S, a.ctx + L.c, P, N, row0, nr, s);
+        st = query_features_and_numerator(p, a.Q, a.omega, a.ctx + L.S, a.ctx + L.c, P, N, row0, nr, a.ctx + L.lse, s);
         if (st != FLURKA_OK) return st;
         const long rows = (long)p.BH * nr;
         hipLaunchKernelGGL(fwd_finish_kernel, grid1d(rows, 4), dim3(256), 0, s, P, N, a.ctx + L.z, a.out,
-                           p.bf16, rows, nr, p.n, row0, p.mf, p.d);
+                           p.bf16, rows, nr, p.n, row0, p.mf, p.d, a.ctx + L.lse, p.elu ? 0 : 1);
         FLURKA_CHECK_LAUNCH();
     }
     return FLURKA_OK;
@@ -512,7 +521,7 @@ flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStrea
     for (int row0 = 0; row0 < p.n && !query_done; row0 += nc) {
         const int nr = (p.n - row0 < nc) ? (p.n - row0) : nc;
         const long rows = (long)p.BH * nr;
-        st = query_features_and_numerator(p, a.Q, a.omega, S, cshift, P, N, row0, nr, s);
+        st = query_features_and_numerator(p, a.Q, a.omega, S, cshift, P, N, row0, nr, nullptr, s);
         if (st != FLURKA_OK) return st;
         hipLaunchKernelGGL(bwd_row_prep_kernel, grid1d(rows, 4), dim3(256), 0, s, P, N, z, a.dOut, p.bf16,
                            dD, rows, nr, p.n, row0, p.mf, p.d);

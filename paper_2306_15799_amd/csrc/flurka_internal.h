@@ -25,7 +25,7 @@ static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // Context buffer (float32): state carried from forward to backward.
 // Every segment starts on a 256-byte boundary.
 struct CtxLayout {
-    size_t Kp, Vp, S, z, c, total;   // offsets / total in floats
+    size_t Kp, Vp, S, z, c, lse, total;   // offsets / total in floats
 };
 
 static inline CtxLayout ctx_layout(const Problem& p) {
@@ -37,6 +37,7 @@ static inline CtxLayout ctx_layout(const Problem& p) {
     L.S = o;    o += round_up(BH * p.mf * p.d, 64);
     L.z = o;    o += round_up(BH * p.mf, 64);
     L.c = o;    o += round_up(BH * p.mf, 64);   // exponent shift per (batch, head, feature)
+    L.lse = o;  o += round_up(BH * p.n, 64);    // log of the denominator per query row
     L.total = o;
     return L;
 }
@@ -87,7 +88,7 @@ struct FwdArgs {
 };
 
 struct BwdArgs {
-    const void *Q, *K, *V, *E, *F, *omega, *dOut;
+    const void *Q, *K, *V, *E, *F, *omega, *out, *dOut;
     const float* ctx;
     void *dQ, *dK, *dV, *dE, *dF;
     float* ws;

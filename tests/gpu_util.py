@@ -29,11 +29,20 @@ def run_forward(w, t, algo="auto"):
     return g, out, ctx
 
 
-def run_backward(w, g, ctx, algo="auto"):
-    grads = fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], g["dOut"], ctx,
+def run_backward(w, g, out, ctx, algo="auto"):
+    grads = fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, g["dOut"], ctx,
                                phi=w.phi, algo=algo)
     torch.cuda.synchronize()
     return grads
+
+
+def log_denominator(Q, omega, e):
+    """ln sum_j exp(omega_j . q_i) sum_r exp(e[r, j]) per query row, in fp64 and range-safe
+    (e: the key exponents omega_j . k'_r - |k'_r|^2 / 2, shape (k, m))."""
+    u = np.asarray(Q, np.float64) @ np.asarray(omega, np.float64).T
+    lz = e.max(axis=0) + np.log(np.exp(e - e.max(axis=0)).sum(axis=0))
+    v = u + lz[None, :]
+    return v.max(axis=1) + np.log(np.exp(v - v.max(axis=1, keepdims=True)).sum(axis=1))
 
 
 def oracle_forward(w, t, rows=None):
@@ -66,7 +75,7 @@ def check_forward_backward(w, seed=0, algo="auto", tol=None, floor=0.0):
     g, out, ctx = run_forward(w, t, algo)
     bar = tol or TOL[w.dtype]
     errs = {"out": fo.rel_l2(to_host(out), oracle_forward(w, t))}
-    grads = run_backward(w, g, ctx, algo)
+    grads = run_backward(w, g, out, ctx, algo)
     ref = oracle_backward(w, t)
     for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], grads, ref):
         errs[name] = rel_err(to_host(a), b, floor)

@@ -27,7 +27,7 @@ def test_every_declared_entry_point_is_exported(lib):
     assert declared == set(fb.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.flurka_version() == 100
+    assert lib.flurka_version() == 110
 
 
 def test_status_strings(lib):
@@ -37,8 +37,8 @@ def test_status_strings(lib):
 
 
 def test_buffer_sizes(lib):
-    # C1: K',V' 2*4096 + S 4096 + z 64 + c 64 floats
-    assert fb.ctx_bytes(1, 1, 512, 64, 64, 64, fb.F32, "performer") == 4 * (3 * 4096 + 64 + 64)
+    # C1: K',V' 2*4096 + S 4096 + z 64 + c 64 + lse 512 floats
+    assert fb.ctx_bytes(1, 1, 512, 64, 64, 64, fb.F32, "performer") == 4 * (3 * 4096 + 64 + 64 + 512)
     assert fb.ctx_bytes(1, 1, 512, 64, 64, 63, fb.F32, "elu1") == 0          # m != d
     assert fb.ctx_bytes(0, 1, 512, 64, 64, 64, fb.F32, "performer") == 0
     fwd = fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_FWD, "generic")
@@ -46,9 +46,9 @@ def test_buffer_sizes(lib):
     assert 0 < fwd < bwd
     auto = fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_FWD, "auto")
     assert auto >= fwd
-    offs = (ctypes.c_size_t * 5)()
+    offs = (ctypes.c_size_t * 6)()
     assert lib.flurka_ctx_layout(1, 1, 512, 64, 64, 64, fb.F32, 0, offs) == fb.OK
-    assert list(offs) == [0, 4096, 8192, 12288, 12352]
+    assert list(offs) == [0, 4096, 8192, 12288, 12352, 12416]
     assert lib.flurka_ctx_layout(1, 1, 512, 64, 64, 64, fb.F32, 0, None) == fb.ERR_NULL
 
 
@@ -63,13 +63,13 @@ def _fwd(lib, **over):
 
 
 def _bwd(lib, **over):
-    a = dict(Q=FAKE, K=FAKE, V=FAKE, E=FAKE, F=FAKE, omega=FAKE, dOut=FAKE, ctx=FAKE, ctx_bytes=1 << 40,
-             dQ=FAKE, dK=FAKE, dV=FAKE, dE=FAKE, dF=FAKE, ws=FAKE, ws_bytes=1 << 40,
+    a = dict(Q=FAKE, K=FAKE, V=FAKE, E=FAKE, F=FAKE, omega=FAKE, out=FAKE, dOut=FAKE, ctx=FAKE,
+             ctx_bytes=1 << 40, dQ=FAKE, dK=FAKE, dV=FAKE, dE=FAKE, dF=FAKE, ws=FAKE, ws_bytes=1 << 40,
              B=1, H=1, n=512, d=64, k=64, m=64, per_head=1, dtype=fb.F32, phi=fb.PHI_PERFORMER,
              algo=fb.ALGO_GENERIC)
     a.update(over)
-    return lib.flurka_attn_bwd(a["Q"], a["K"], a["V"], a["E"], a["F"], a["omega"], a["dOut"], a["ctx"],
-                               a["ctx_bytes"], a["dQ"], a["dK"], a["dV"], a["dE"], a["dF"], a["ws"],
+    return lib.flurka_attn_bwd(a["Q"], a["K"], a["V"], a["E"], a["F"], a["omega"], a["out"], a["dOut"],
+                               a["ctx"], a["ctx_bytes"], a["dQ"], a["dK"], a["dV"], a["dE"], a["dF"], a["ws"],
                                a["ws_bytes"], a["B"], a["H"], a["n"], a["d"], a["k"], a["m"],
                                a["per_head"], a["dtype"], a["phi"], a["algo"], None)
 
@@ -97,7 +97,7 @@ def test_forward_rejects_bad_arguments_before_launching(lib):
 
 
 def test_backward_rejects_bad_arguments_before_launching(lib):
-    for name in ["Q", "K", "V", "E", "F", "omega", "dOut", "ctx", "dQ", "dK", "dV", "dE", "dF", "ws"]:
+    for name in ["Q", "K", "V", "E", "F", "omega", "out", "dOut", "ctx", "dQ", "dK", "dV", "dE", "dF", "ws"]:
         assert _bwd(lib, **{name: None}) == fb.ERR_NULL, name
     assert _bwd(lib, k=0) == fb.ERR_SHAPE
     assert _bwd(lib, dtype=2) == fb.ERR_DTYPE

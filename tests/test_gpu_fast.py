@@ -50,6 +50,12 @@ def test_fast_projection_matches_oracle_projection():
     # bf16 x bf16 products are exact in fp32; only the fp32 summation order differs
     assert fo.rel_l2(gu.to_host(v["Kp"]), Kp) < 2e-6
     assert fo.rel_l2(gu.to_host(v["Vp"]), Vp) < 2e-6
+    # the forward also leaves the log of every row's denominator for the backward pass
+    for h in range(w.H):
+        om = t["omega"][h].astype(np.float64)
+        e = Kp[0, h] @ om.T - 0.5 * np.sum(Kp[0, h] ** 2, axis=1, keepdims=True)
+        lse = gu.log_denominator(t["Q"][0, h], om, e)
+        assert np.max(np.abs(gu.to_host(v["lse"][0, h]) - lse)) < 2e-3 * max(1.0, np.abs(lse).max())
 
 
 def test_shared_omega_and_determinism():
@@ -97,10 +103,10 @@ def test_backward_matches_generic_kernels_closely():
     """Same inputs through both kernel families: they differ only by bf16 rounding of operands."""
     w = Workload("cmp", 1, 2, 512, 64, 128, 64, "bf16", PHI_PERFORMER, True)
     t = inputs.make_inputs(w, 13)
-    g, _, ctx = gu.run_forward(w, t, "fast")
-    fast = gu.run_backward(w, g, ctx, "fast")
-    g2, _, ctx2 = gu.run_forward(w, t, "generic")
-    gen = gu.run_backward(w, g2, ctx2, "generic")
+    g, out, ctx = gu.run_forward(w, t, "fast")
+    fast = gu.run_backward(w, g, out, ctx, "fast")
+    g2, out2, ctx2 = gu.run_forward(w, t, "generic")
+    gen = gu.run_backward(w, g2, out2, ctx2, "generic")
     for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], fast, gen):
         assert fo.rel_l2(gu.to_host(a), gu.to_host(b)) < 2e-2, name
 
@@ -108,8 +114,8 @@ def test_backward_matches_generic_kernels_closely():
 def test_backward_is_deterministic():
     w = Workload("det", 2, 2, 512, 64, 96, 64, "bf16", PHI_PERFORMER, True)
     t = inputs.make_inputs(w, 14)
-    g, _, ctx = gu.run_forward(w, t, "fast")
-    a = gu.run_backward(w, g, ctx, "fast")
-    b = gu.run_backward(w, g, ctx, "fast")
+    g, out, ctx = gu.run_forward(w, t, "fast")
+    a = gu.run_backward(w, g, out, ctx, "fast")
+    b = gu.run_backward(w, g, out, ctx, "fast")
     for x, y in zip(a, b):
         assert torch.equal(x, y)

@@ -74,6 +74,9 @@ def test_context_holds_the_key_side_state():
         gS, gz = gu.to_host(v["S"][0, h]), gu.to_host(v["z"][0, h])
         assert fo.rel_l2(gS / gz[:, None], S / z[:, None]) < 1e-5
         assert fo.rel_l2(np.log(gz) + gc, np.log(z) + c) < 1e-5
+        # lse_i = ln sum_j exp(omega_j . q_i) sum_r exp(e_rj): the denominator without any shift
+        lse = gu.log_denominator(t["Q"][0, h], om, e)
+        assert np.max(np.abs(gu.to_host(v["lse"][0, h]) - lse)) < 1e-4 * max(1.0, np.abs(lse).max())
 
 
 def test_large_exponent_scale_stays_finite():
@@ -90,9 +93,9 @@ def test_results_are_deterministic():
     w = Workload("det", 2, 2, 300, 32, 50, 70, "bf16", PHI_PERFORMER, True)
     t = inputs.make_inputs(w, 6)
     g, out1, ctx = gu.run_forward(w, t, "generic")
-    grads1 = gu.run_backward(w, g, ctx, "generic")
+    grads1 = gu.run_backward(w, g, out1, ctx, "generic")
     _, out2, ctx2 = gu.run_forward(w, t, "generic")
-    grads2 = gu.run_backward(w, g, ctx2, "generic")
+    grads2 = gu.run_backward(w, g, out2, ctx2, "generic")
     assert torch.equal(out1, out2)
     for a, b in zip(grads1, grads2):
         assert torch.equal(a, b)
