@@ -276,18 +276,43 @@ struct BwdYArgs {
 };
 
 // A workgroup is four wavefronts = four feature tiles of one (head, query range).  They need the same
-// Q rows (A operand) and the same dOut rows (B operand, contraction over queries), so each 32-query
-// tile is loaded once per workgroup with 16-byte loads and staged in LDS, double buffered: Q row-major,
-// dOut transposed to [t][query slot] with the 32 queries of the tile in accumulator-slot order, so that
-// a lane's B operand is one 16-byte read.
+// Q rows (A operand of u = Q omega^T) and the same dOut rows (B operand of dS = W^T dOut, contraction
+// over queries), so blocks of Y_ST 32-query tiles are loaded once per workgroup with 16-byte loads and
+// kept in LDS row-major.  The B operand needs, per lane, one column t of dOut for 8 query rows: that is
+// what ds_read_b64_tr_b16 delivers from a row-major tile.  Layout of that instruction (checked on
+// hardware): in each group of 16 lanes, lane s supplies the address of 4 consecutive 16-bit elements
+// M[s][0..3]; lane i receives M[4j + i/4][i%4], j = 0..3.  With lane s pointing at row s/4, columns
+// 4*(s%4).. of a 4 x 16 block, lane i receives column i of the block's four rows.
+// The next block is requested into registers while the current one is worked on.
+constexpr int Y_ST = 4;
+
+template <int D>
+struct BwdYLds {
+    static constexpr int rows = 32 * Y_ST;
+    static constexpr int q_pitch = (D + 8) * 2;      // conflict-free 16-byte reads down a column of rows
+    static constexpr int g_pitch = D * 2 + 64;       // 4 consecutive rows fall into 4 distinct bank groups
+    static constexpr int total = rows * (q_pitch + g_pitch) + 2 * rows * 4;
+};
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p) {
+    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+    return __builtin_bit_cast(uint2, v);
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
-    constexpr int QP = (D + 8) * 2;            // LDS pitch of a Q row
-    constexpr int GP = 80;                     // LDS pitch of a dOut^T row: 32 queries + 16 bytes pad
-    constexpr int QB = 32 * QP, GB = D * GP;
-    constexpr int LPT = D / 64;                // 16-byte loads per thread per tensor per tile
-    __shared__ __attribute__((aligned(16))) unsigned char sm[2 * (QB + GB)];
+    using L = BwdYLds<D>;
+    constexpr int QP = L::q_pitch, GP = L::g_pitch, ROWS = L::rows;
+    constexpr int CPR = D / 8;                 // 16-byte chunks per row
+    constexpr int LPT = ROWS * CPR / 256;      // 16-byte loads per thread per tensor per block
+    static_assert(2 * ROWS <= 256 && (ROWS * CPR) % 256 == 0, "one lambda or g value per thread");
+    extern __shared__ __attribute__((aligned(16))) unsigned char sm[];
+    unsigned char* qs = sm;
+    unsigned char* gs = sm + ROWS * QP;
+    float* ll = (float*)(gs + ROWS * GP);      // lambda_i * log2(e); +inf past the end of the range
+    float* ld = ll + ROWS;                     // g_i
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int FG = (a.FT + 3) / 4;
@@ -302,7 +327,9 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     const int qt0 = r * a.tiles_per_range;
     int qt1 = qt0 + a.tiles_per_range;
     if (qt1 > QTn) qt1 = QTn;
+    const int row_last = 32 * qt1 - 1;
     const long head_off = (long)bh * a.n * D;
+    const long vec_off = (long)bh * a.n;
 
     uint4 wf[KS];
     {
@@ -316,80 +343,80 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     for (int t = 0; t < TT; ++t) accS[t] = zero16();
     float dz = 0.f;
 
-    // loader map: 16-byte chunk c of row lr (+ 256/(D/8) rows per extra load)
-    constexpr int CPR = D / 8;                 // chunks per row
-    const int lr = tid / CPR, lc8 = tid % CPR;
-    // slot of query q inside the tile: q = 16*sp + 8*j4 + 4*h + j0  ->  16*h + 8*sp + 4*j4 + j0
-    auto slot_of = [](int q) { return 16 * ((q >> 2) & 1) + 8 * (q >> 4) + 4 * ((q >> 3) & 1) + (q & 3); };
     uint4 rq[LPT], rg[LPT];
-    auto load_tile = [&](int qt) {
+    float rv = 0.f;                            // threads 0..ROWS-1: lambda, ROWS..2*ROWS-1: g
+    auto load_block = [&](int qt) {
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
-            const long off = head_off + (long)(32 * qt + lr + u * (256 / CPR)) * D + 8 * lc8;
+            const int chunk = tid + 256 * u;
+            int row = 32 * qt + chunk / CPR;
+            if (row > row_last) row = row_last;
+            const long off = head_off + (long)row * D + 8 * (chunk % CPR);
             rq[u] = ld16(a.Q + off);
             rg[u] = ld16(a.G + off);
         }
+        if (tid < 2 * ROWS) {
+            const int row = 32 * qt + (tid % ROWS);
+            if (tid < ROWS) rv = row <= row_last ? a.lse[vec_off + row] * LOG2E : INFINITY;
+            else            rv = row <= row_last ? a.delta[vec_off + row] : 0.f;
+        }
     };
-    auto store_tile = [&](int buf) {
-        unsigned char* qs = sm + buf * (QB + GB);
-        unsigned char* gs = qs + QB;
+    auto store_block = [&]() {
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
-            const int row = lr + u * (256 / CPR);
-            *(uint4*)(qs + row * QP + 16 * lc8) = rq[u];
-            const int sl = slot_of(row);
-            const uint32_t w[4] = {rg[u].x, rg[u].y, rg[u].z, rg[u].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                *(uint16_t*)(gs + (8 * lc8 + 2 * e) * GP + 2 * sl) = (uint16_t)(w[e] & 0xffffu);
-                *(uint16_t*)(gs + (8 * lc8 + 2 * e + 1) * GP + 2 * sl) = (uint16_t)(w[e] >> 16);
-            }
+            const int chunk = tid + 256 * u;
+            const int row = chunk / CPR, c = chunk % CPR;
+            *(uint4*)(qs + row * QP + 16 * c) = rq[u];
+            *(uint4*)(gs + row * GP + 16 * c) = rg[u];
         }
+        if (tid < 2 * ROWS) ll[tid] = rv;       // ld follows ll
     };
 
-    if (qt0 < qt1) {
-        load_tile(qt0);
-        store_tile(0);
-    }
-    __syncthreads();
-    for (int qt = qt0; qt < qt1; ++qt) {
-        const int buf = (qt - qt0) & 1;
-        const bool more = qt + 1 < qt1;
-        if (more) load_tile(qt + 1);
-        const unsigned char* qs = sm + buf * (QB + GB);
-        const unsigned char* gs = qs + QB;
-        // u tile: rows = queries 32*qt + ..., columns = this wavefront's features
-        floatx16 u = zero16();
+    // this lane's part of the transposing reads: row s/4 (+ 4*half) of a 4-row group, columns 4*(s%4)..
+    // of the 16-column group (l32/16); see the layout note above
+    const int s16 = lane & 15;
+    const unsigned char* gtr = gs + (4 * half + (s16 >> 2)) * GP + 2 * (16 * ((lane >> 4) & 1) + 4 * (s16 & 3));
+
+    if (qt0 < qt1) load_block(qt0);
+    for (int qt = qt0; qt < qt1; qt += Y_ST) {
+        store_block();
+        __syncthreads();
+        if (qt + Y_ST < qt1) load_block(qt + Y_ST);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) u = mfma32(*(const uint4*)(qs + l32 * QP + 32 * s + 16 * half), wf[s], u);
-        // element g <-> query 32*qt + 8*(g/4) + 4*half + g%4
-        const float* lg = a.lse + (long)bh * a.n + 32 * qt + 4 * half;
-        const float* dg = a.delta + (long)bh * a.n + 32 * qt + 4 * half;
-        uint32_t wk[8];
+        for (int i = 0; i < Y_ST; ++i) {
+            // u tile: rows = queries of tile i, columns = this wavefront's features
+            floatx16 u = zero16();
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 lv = *(const float4*)(lg + 8 * q);
-            const float4 dv = *(const float4*)(dg + 8 * q);
-            const float w0 = fast_exp2(fmaf(u[4 * q], LOG2E, cj - lv.x * LOG2E));
-            const float w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, cj - lv.y * LOG2E));
-            const float w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, cj - lv.z * LOG2E));
-            const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, cj - lv.w * LOG2E));
-            wk[2 * q] = pack_bf16(w0, w1);
-            wk[2 * q + 1] = pack_bf16(w2, w3);
-            dz = fmaf(-w0, dv.x, dz); dz = fmaf(-w1, dv.y, dz);
-            dz = fmaf(-w2, dv.z, dz); dz = fmaf(-w3, dv.w, dz);
-        }
-        // W^T tile as A operand (row = this lane's feature, slots = queries in accumulator order);
-        // B operand: dOut^T row t = 32*tt + l32, the 8 query slots of (half, sp)
-        const uint4 wa[2] = {{wk[0], wk[1], wk[2], wk[3]}, {wk[4], wk[5], wk[6], wk[7]}};
+            for (int s = 0; s < KS; ++s)
+                u = mfma32(*(const uint4*)(qs + (32 * i + l32) * QP + 32 * s + 16 * half), wf[s], u);
+            // element g <-> query 32*i + 8*(g/4) + 4*half + g%4
+            uint32_t wk[8];
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp)
-#pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                const uint4 b = *(const uint4*)(gs + (32 * tt + l32) * GP + 32 * half + 16 * sp);
-                accS[tt] = mfma32(wa[sp], b, accS[tt]);
+            for (int q = 0; q < 4; ++q) {
+                const float4 lv = *(const float4*)(ll + 32 * i + 8 * q + 4 * half);
+                const float4 dv = *(const float4*)(ld + 32 * i + 8 * q + 4 * half);
+                const float w0 = fast_exp2(fmaf(u[4 * q], LOG2E, cj - lv.x));
+                const float w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, cj - lv.y));
+                const float w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, cj - lv.z));
+                const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, cj - lv.w));
+                wk[2 * q] = pack_bf16(w0, w1);
+                wk[2 * q + 1] = pack_bf16(w2, w3);
+                dz = fmaf(-w0, dv.x, dz); dz = fmaf(-w1, dv.y, dz);
+                dz = fmaf(-w2, dv.z, dz); dz = fmaf(-w3, dv.w, dz);
             }
-        if (more) store_tile(buf ^ 1);
+            // W^T tile as A operand (row = this lane's feature; slot 8h + e of step sp <-> query
+            // 16*sp + 8*(e/4) + 4*h + e%4).  B operand: column t = 32*tt + l32 of the same queries.
+            const uint4 wa[2] = {{wk[0], wk[1], wk[2], wk[3]}, {wk[4], wk[5], wk[6], wk[7]}};
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const unsigned char* bp = gtr + (32 * i + 16 * sp) * GP + 64 * tt;
+                    const uint2 b0 = lds_read_tr16(bp);
+                    const uint2 b1 = lds_read_tr16(bp + 8 * GP);
+                    accS[tt] = mfma32(wa[sp], make_uint4(b0.x, b0.y, b1.x, b1.y), accS[tt]);
+                }
+        }
         __syncthreads();
     }
     if (!active) return;
@@ -723,7 +750,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
     int R = (4096 + p.BH * q.FT - 1) / (p.BH * q.FT);
     if (R > QT / 8) R = QT / 8;
     if (R < 1) R = 1;
-    q.tiles_per_range = (QT + R - 1) / R;
+    q.tiles_per_range = ((QT + R - 1) / R + Y_ST - 1) / Y_ST * Y_ST;     // whole staged blocks
     q.R = (QT + q.tiles_per_range - 1) / q.tiles_per_range;
     return q;
 }
@@ -817,8 +844,12 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ya.tiles_per_range = y.tiles_per_range;
         const unsigned ygrid = (unsigned)((long)p.BH * y.R * ((y.FT + 3) / 4));
         stage_begin(s);
-        if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, dim3(ygrid), dim3(256), 0, s, ya);
-        else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, dim3(ygrid), dim3(256), 0, s, ya);
+        const int ylds = p.d == 64 ? BwdYLds<64>::total : BwdYLds<128>::total;
+        const void* yk = p.d == 64 ? (const void*)bwd_query_y_kernel<64> : (const void*)bwd_query_y_kernel<128>;
+        if (hipFuncSetAttribute(yk, hipFuncAttributeMaxDynamicSharedMemorySize, ylds) != hipSuccess)
+            return FLURKA_ERR_LAUNCH;
+        if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, dim3(ygrid), dim3(256), ylds, s, ya);
+        else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, dim3(ygrid), dim3(256), ylds, s, ya);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_Y);
     }
