@@ -93,7 +93,8 @@ struct BwdXArgs {
     const float* lse;          // (BH, n)  lambda_i, written by the forward
     uint16_t* dQ;
     float* delta;              // (BH, n)  g_i
-    int n, H, mf, rows_per_wg, wgs_per_head;
+    int n, H, mf, tiles_per_head;   // tiles of 32 rows
+    long total_tiles;               // BH * tiles_per_head
     long omega_head_stride;    // 0 if shared
 };
 
@@ -104,14 +105,15 @@ struct BwdXLds {
     static __host__ __device__ int total(int mf) { return 2 * mf * w_pitch + D * s_pitch(mf) + mf * 8; }
 };
 
+constexpr int X_NW = 12;                 // wavefronts per workgroup (three per SIMD)
+constexpr bool X_PREFETCH = false;       // request the next tile's rows a whole tile ahead
+
 template <int D>
-__global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
+__global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     using L = BwdXLds<D>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int bh = blockIdx.x / a.wgs_per_head;
-    const int chunk = blockIdx.x % a.wgs_per_head;
     const int mf = a.mf;
     const int s_pitch = L::s_pitch(mf);
     unsigned char* lw = lds;                              // omega   [feature][d]
@@ -119,34 +121,45 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
     unsigned char* lwt = lsp + mf * L::w_pitch;           // Wt      [t][feature slot]
     float* lz = (float*)(lwt + D * s_pitch);
     float* lc = lz + mf;
+    constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
+    constexpr int TT = D / 32;      // 32-row tiles of dQ^T
+    const int FT = mf / 32;
+
+    // Resident grid: each workgroup takes an equal, contiguous share of all (head, 32-row tile) pairs
+    // and walks it head by head, refilling the LDS image when the head changes.
+    const long tile_begin = a.total_tiles * blockIdx.x / gridDim.x;
+    const long tile_end = a.total_tiles * (blockIdx.x + 1) / gridDim.x;
+    for (long seg = tile_begin; seg < tile_end;) {
+    const int bh = (int)(seg / a.tiles_per_head);
+    long seg_end = (long)(bh + 1) * a.tiles_per_head;
+    if (seg_end > tile_end) seg_end = tile_end;
+    if (seg != tile_begin) __syncthreads();          // every wavefront is done with the previous image
     {
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
         const uint16_t* spg = a.Sp + (long)bh * mf * D;
         constexpr int cpr = D / 8;
-        for (int c = tid; c < mf * cpr; c += 512) {
+        for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
             *(uint4*)(lsp + r * L::w_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
         }
         const uint16_t* wtg = a.Wt + (long)(bh % a.H) * a.omega_head_stride;
         const int cps = mf / 8;
-        for (int c = tid; c < D * cps; c += 512) {
+        for (int c = tid; c < D * cps; c += X_NW * 64) {
             const int r = c / cps, q = c % cps;
             *(uint4*)(lwt + r * s_pitch + 16 * q) = ld16(wtg + (long)r * mf + 8 * q);
         }
         const float* zg = a.zp + (long)bh * mf;
         const float* cg = a.cp + (long)bh * mf;
-        for (int c = tid; c < mf; c += 512) { lz[c] = zg[c]; lc[c] = cg[c]; }
+        for (int c = tid; c < mf; c += X_NW * 64) { lz[c] = zg[c]; lc[c] = cg[c]; }
     }
     __syncthreads();
 
     const long head_off = (long)bh * a.n * D;
-    const int row_begin = chunk * a.rows_per_wg;
-    int row_end = row_begin + a.rows_per_wg;
+    const int row_begin = (int)(seg - (long)bh * a.tiles_per_head) * 32;
+    int row_end = (int)(seg_end - (long)bh * a.tiles_per_head) * 32;
     if (row_end > a.n) row_end = a.n;
-    constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
-    constexpr int TT = D / 32;      // 32-row tiles of dQ^T
-    const int FT = mf / 32;
+    seg = seg_end;
 
     // One tile = this lane's query row: Q as the B operand of u^T (8 consecutive d per step), dOut as
     // the B operand of S G^T (slots (h, j) of step s hold t = 16*s + 8*(j/4) + 4*h + j%4), the same
@@ -177,11 +190,12 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
 
     const int row_first = row_begin + 32 * wave;
     Tile cur, nxt;
-    if (row_first < row_end) load_tile(row_first, cur);
-    for (int row0 = row_first; row0 < row_end; row0 += 32 * 8) {
+    if (X_PREFETCH && row_first < row_end) load_tile(row_first, cur);
+    for (int row0 = row_first; row0 < row_end; row0 += 32 * X_NW) {
         const int qrow = row0 + l32;
         const bool valid = qrow < a.n;
-        if (row0 + 32 * 8 < row_end) load_tile(row0 + 32 * 8, nxt);
+        if (!X_PREFETCH) load_tile(row0, cur);
+        else if (row0 + 32 * X_NW < row_end) load_tile(row0 + 32 * X_NW, nxt);
 
         // g_i = G_i . out_i: the two halves of the wavefront hold complementary elements of the row
         float gdot = 0.f;
@@ -255,8 +269,9 @@ __global__ __launch_bounds__(512) void bwd_query_x_kernel(BwdXArgs a) {
                     *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
                 }
         }
-        cur = nxt;
+        if (X_PREFETCH) cur = nxt;
     }
+    }   // head segments
 }
 
 // ---------------------------------------------------------------------------
@@ -788,11 +803,13 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
 size_t fast_bwd_ws_bytes(const Problem& p) { return fast_bwd_ws_layout(p).total; }
 
 template <int D>
-static flurka_status launch_bwd_x(const BwdXArgs& xa, int grid, int ldsb, hipStream_t s) {
+static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
     auto kern = bwd_query_x_kernel<D>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ldsb, s, xa);
+    const int grid = resident_grid((const void*)kern, X_NW * 64, ldsb, xa.total_tiles);
+    if (grid < 1) return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(X_NW * 64), ldsb, s, xa);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
 }
@@ -823,15 +840,11 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         xa.zp = (const float*)(wsb + W.zp); xa.cp = (const float*)(wsb + W.cp);
         xa.dQ = (uint16_t*)a.dQ; xa.lse = a.ctx + L.lse; xa.delta = (float*)(wsb + W.delta);
         xa.n = p.n; xa.H = p.H; xa.mf = p.mf; xa.omega_head_stride = omega_stride;
-        int wgs_per_head = (512 + p.BH - 1) / p.BH;
-        int rows = (p.n + wgs_per_head - 1) / wgs_per_head;
-        rows = (rows + 255) / 256 * 256;
-        wgs_per_head = (p.n + rows - 1) / rows;
-        xa.rows_per_wg = rows; xa.wgs_per_head = wgs_per_head;
+        xa.tiles_per_head = (p.n + 31) / 32;
+        xa.total_tiles = (long)p.BH * xa.tiles_per_head;
         const int ldsb = bwd_x_lds_bytes(p);
         stage_begin(s);
-        st = p.d == 64 ? launch_bwd_x<64>(xa, p.BH * wgs_per_head, ldsb, s)
-                       : launch_bwd_x<128>(xa, p.BH * wgs_per_head, ldsb, s);
+        st = p.d == 64 ? launch_bwd_x<64>(xa, ldsb, s) : launch_bwd_x<128>(xa, ldsb, s);
         if (st != FLURKA_OK) return st;
         stage_end(s, STAGE_K_BWD_X);
 

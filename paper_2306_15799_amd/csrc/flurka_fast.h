@@ -31,6 +31,20 @@ struct KeyStateBuffers {
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
                              long split_stride, int splits, const KeyStateBuffers& b, hipStream_t s);
 
+// Grid of a kernel whose workgroups split `items` evenly among themselves: as many workgroups as the
+// device keeps resident at once for this block size and LDS use (one round, no tail), at most `items`.
+// Returns 0 if the runtime cannot place the kernel.
+inline int resident_grid(const void* kernel, int threads, int lds_bytes, long items) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, (size_t)lds_bytes) != hipSuccess)
+        return 0;
+    long grid = (long)cus * per_cu;
+    if (grid > items) grid = items;
+    return (int)grid;
+}
+
 // Backward (flurka_bwd.hip)
 bool fast_bwd_supported(const Problem& p);
 size_t fast_bwd_ws_bytes(const Problem& p);

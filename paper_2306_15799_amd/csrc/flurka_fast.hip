@@ -58,7 +58,8 @@ struct QueryArgs {
     const float* cp;           // (BH, mf) exponent shifts, same order as zp
     uint16_t* out;
     float* lse;                // (BH, n) log of the denominator, kept for the backward pass
-    int n, H, mf, rows_per_wg, wgs_per_head;
+    int n, H, mf, tiles_per_head;   // tiles of 32*QT rows
+    long total_tiles;               // BH * tiles_per_head
     long omega_head_stride;    // 0 if shared
 };
 
@@ -82,14 +83,25 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     using L = QueryLds<D>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int bh = blockIdx.x / a.wgs_per_head;
-    const int chunk = blockIdx.x % a.wgs_per_head;
     const int mf = a.mf;
     const int s_pitch = L::s_pitch(mf);
     unsigned char* lw = lds;
     unsigned char* ls = lds + (ELU ? 0 : L::w_bytes(mf));
     float* lz = (float*)(ls + L::s_bytes(mf));
     float* lc = lz + mf;
+    constexpr int KS = D / 16;      // reduction steps over d
+    constexpr int TT = D / 32;      // 32-row tiles of N^T
+
+    // The grid is as many workgroups as the chip holds at once; each takes an equal, contiguous share
+    // of all (head, 32*QT-row tile) pairs and walks it head by head, refilling the LDS image when the
+    // head changes.
+    const long tile_begin = a.total_tiles * blockIdx.x / gridDim.x;
+    const long tile_end = a.total_tiles * (blockIdx.x + 1) / gridDim.x;
+    for (long seg = tile_begin; seg < tile_end;) {
+    const int bh = (int)(seg / a.tiles_per_head);
+    long seg_end = (long)(bh + 1) * a.tiles_per_head;
+    if (seg_end > tile_end) seg_end = tile_end;
+    if (seg != tile_begin) __syncthreads();          // every wavefront is done with the previous image
 
     // fill the LDS image (16-byte chunks, coalesced)
     if (!ELU) {
@@ -114,11 +126,10 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     __syncthreads();
 
     const long head_off = (long)bh * a.n * D;
-    const int row_begin = chunk * a.rows_per_wg;
-    int row_end = row_begin + a.rows_per_wg;
+    const int row_begin = (int)(seg - (long)bh * a.tiles_per_head) * (32 * QT);
+    int row_end = (int)(seg_end - (long)bh * a.tiles_per_head) * (32 * QT);
     if (row_end > a.n) row_end = a.n;
-    constexpr int KS = D / 16;      // reduction steps over d
-    constexpr int TT = D / 32;      // 32-row tiles of N^T
+    seg = seg_end;
 
     // this lane's query rows (B operand of the first contraction: 8 consecutive d per step); the
     // rows of the next tile are requested while the current tile is still being worked on
@@ -211,6 +222,7 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
             }
         }
     }
+    }   // head segments
 }
 
 // ===========================================================================
@@ -275,10 +287,12 @@ size_t fast_ws_bytes(const Problem& p, int bwd) {
 constexpr int QS_NW = 8, QS_QT = 1;      // wavefronts per workgroup, 32-row tiles per wavefront
 
 template <int D, bool ELU>
-static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int grid, int ldsb, hipStream_t s) {
+static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int ldsb, hipStream_t s) {
     auto kern = query_stream_kernel<D, ELU, QS_NW, QS_QT>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
+    const int grid = resident_grid((const void*)kern, QS_NW * 64, ldsb, qa.total_tiles);
+    if (grid < 1) return FLURKA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(QS_NW * 64), ldsb, s, qa);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
@@ -328,19 +342,13 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         qa.lse = a.ctx + L.lse;
         qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
         qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
-        // about two workgroups per compute unit, each a multiple of the rows one pass of a workgroup covers
-        constexpr int pass_rows = QS_NW * QS_QT * 32;
-        int wgs_per_head = (512 + p.BH - 1) / p.BH;
-        int rows = (p.n + wgs_per_head - 1) / wgs_per_head;
-        rows = (rows + pass_rows - 1) / pass_rows * pass_rows;
-        wgs_per_head = (p.n + rows - 1) / rows;
-        qa.rows_per_wg = rows; qa.wgs_per_head = wgs_per_head;
-        const int grid = p.BH * wgs_per_head;
+        qa.tiles_per_head = (p.n + 32 * QS_QT - 1) / (32 * QS_QT);
+        qa.total_tiles = (long)p.BH * qa.tiles_per_head;
         const int ldsb = query_lds_bytes(p);
         if (p.d == 64)
-            st = p.elu ? launch_query<64, true>(p, qa, grid, ldsb, s) : launch_query<64, false>(p, qa, grid, ldsb, s);
+            st = p.elu ? launch_query<64, true>(p, qa, ldsb, s) : launch_query<64, false>(p, qa, ldsb, s);
         else
-            st = p.elu ? launch_query<128, true>(p, qa, grid, ldsb, s) : launch_query<128, false>(p, qa, grid, ldsb, s);
+            st = p.elu ? launch_query<128, true>(p, qa, ldsb, s) : launch_query<128, false>(p, qa, ldsb, s);
         if (st != FLURKA_OK) return st;
     }
     return FLURKA_OK;
