@@ -284,10 +284,13 @@ size_t fast_ws_bytes(const Problem& p, int bwd) {
     return bwd ? fast_bwd_ws_bytes(p) : fast_ws_layout(p).total;
 }
 
-constexpr int QS_NW = 8, QS_QT = 1;      // wavefronts per workgroup, 32-row tiles per wavefront
+constexpr int QS_QT = 1;                  // 32-row tiles per wavefront
+// wavefronts per workgroup: as many per SIMD as the register budget of the kernel allows
+template <int D> struct QsWaves { static constexpr int value = D == 64 ? 12 : 8; };
 
 template <int D, bool ELU>
 static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int ldsb, hipStream_t s) {
+    constexpr int QS_NW = QsWaves<D>::value;
     auto kern = query_stream_kernel<D, ELU, QS_NW, QS_QT>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
