@@ -141,14 +141,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
             constexpr int pbuf = (PH) == 3 ? (PAR ^ 1) : PAR;                                   \
             G_MMA(cur, i0, j0); G_MMA(cur, i1, j1);                                             \
             LD(nxt, pbuf, ns, (q) >> 1);                                                        \
-            if ((PH) == 0) {                                                                    \
-                RA[PAR][q] = buf_ld16(rsA, voffA, sA + (q) * pc.a_qstride);                     \
-                RB[PAR][q] = buf_ld16(rsB, voffB, sB + (q) * pc.b_qstride);                     \
-            }                                                                                   \
-            if ((PH) == 2) {                                                                    \
-                *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * (q)) * GA_PITCH) = RA[PAR ^ 1][q]; \
-                store_b(RB[PAR ^ 1], PAR ^ 1, q);                                               \
-            }                                                                                   \
+            constexpr int pos = 8 * (PH) + (q);      /* 0..31 within the step */                \
+            /* requests two steps ahead: B in the first 8 chunks, A in every other chunk after */  \
+            if (pos < 8) RB[PAR][pos] = buf_ld16(rsB, voffB, sB + pos * pc.b_qstride);          \
+            if (pos >= 8 && pos < 24 && (pos & 1) == 0)                                         \
+                RA[PAR][(pos - 8) / 2] = buf_ld16(rsA, voffA, sA + ((pos - 8) / 2) * pc.a_qstride); \
+            /* the step after this one goes to LDS: A early, B (needs all 8 of its loads) late */ \
+            if (pos < 16 && (pos & 1) == 0)                                                     \
+                *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * (pos / 2)) * GA_PITCH) = RA[PAR ^ 1][pos / 2]; \
+            if (pos >= 16 && pos < 24) store_b(RB[PAR ^ 1], PAR ^ 1, pos - 16);                 \
             G_SB();                                                                             \
         }
 #define G_PHASE(PH)                               \
