@@ -142,10 +142,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
             G_MMA(cur, i0, j0); G_MMA(cur, i1, j1);                                             \
             LD(nxt, pbuf, ns, (q) >> 1);                                                        \
             constexpr int pos = 8 * (PH) + (q);      /* 0..31 within the step */                \
-            /* requests two steps ahead: B in the first 8 chunks, A in every other chunk after */  \
-            if (pos < 8) RB[PAR][pos] = buf_ld16(rsB, voffB, sB + pos * pc.b_qstride);          \
-            if (pos >= 8 && pos < 24 && (pos & 1) == 0)                                         \
-                RA[PAR][(pos - 8) / 2] = buf_ld16(rsA, voffA, sA + ((pos - 8) / 2) * pc.a_qstride); \
+            /* requests two steps ahead, at most one per chunk: B in even chunks 0..14, A in odd 9..23 */ \
+            if (pos < 16 && (pos & 1) == 0) RB[PAR][pos / 2] = buf_ld16(rsB, voffB, sB + (pos / 2) * pc.b_qstride); \
+            if (pos >= 9 && pos < 24 && (pos & 1) == 1)                                         \
+                RA[PAR][(pos - 9) / 2] = buf_ld16(rsA, voffA, sA + ((pos - 9) / 2) * pc.a_qstride); \
             /* the step after this one goes to LDS: A early, B (needs all 8 of its loads) late */ \
             if (pos < 16 && (pos & 1) == 0)                                                     \
                 *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * (pos / 2)) * GA_PITCH) = RA[PAR ^ 1][pos / 2]; \
