@@ -142,14 +142,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
             G_MMA(cur, i0, j0); G_MMA(cur, i1, j1);                                             \
             LD(nxt, pbuf, ns, (q) >> 1);                                                        \
             constexpr int pos = 8 * (PH) + (q);      /* 0..31 within the step */                \
-            /* requests two steps ahead, at most one per chunk: B in even chunks 0..14, A in odd 9..23 */ \
+            /* requests two steps ahead, one every other chunk: B in chunks 0..14, A in 16..30 */ \
             if (pos < 16 && (pos & 1) == 0) RB[PAR][pos / 2] = buf_ld16(rsB, voffB, sB + (pos / 2) * pc.b_qstride); \
-            if (pos >= 9 && pos < 24 && (pos & 1) == 1)                                         \
-                RA[PAR][(pos - 9) / 2] = buf_ld16(rsA, voffA, sA + ((pos - 9) / 2) * pc.a_qstride); \
-            /* the step after this one goes to LDS: A early, B (needs all 8 of its loads) late */ \
-            if (pos < 16 && (pos & 1) == 0)                                                     \
-                *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * (pos / 2)) * GA_PITCH) = RA[PAR ^ 1][pos / 2]; \
-            if (pos >= 16 && pos < 24) store_b(RB[PAR ^ 1], PAR ^ 1, pos - 16);                 \
+            if (pos >= 16 && (pos & 1) == 0)                                                    \
+                RA[PAR][(pos - 16) / 2] = buf_ld16(rsA, voffA, sA + ((pos - 16) / 2) * pc.a_qstride); \
+            /* the step after this one goes to LDS, one store per chunk in 8..23: A in the even */ \
+            /* chunks, B (which needs all 8 of its loads) in the odd ones */                     \
+            if (pos >= 8 && pos < 24 && (pos & 1) == 0)                                         \
+                *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * ((pos - 8) / 2)) * GA_PITCH) = RA[PAR ^ 1][(pos - 8) / 2]; \
+            if (pos >= 9 && pos < 24 && (pos & 1) == 1) store_b(RB[PAR ^ 1], PAR ^ 1, (pos - 9) / 2); \
             G_SB();                                                                             \
         }
 #define G_PHASE(PH)                               \
