@@ -65,6 +65,16 @@ __device__ __forceinline__ uint4 join_halves(uint2 even, uint2 odd) {
     return make_uint4(x[0], y[0], x[1], y[1]);
 }
 
+// Value that lane G of this lane's row of 16 lanes holds (DPP row_newbcast, no LDS traffic).  With
+// one register per 32-feature tile loaded so that lane 16*r + n holds the entry for accumulator
+// element n of half r/2, bcast16<g>(reg) is the entry that belongs to accumulator element g.
+template <int G>
+__device__ __forceinline__ float bcast16(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + G, 0xf, 0xf, false));
+}
+// lane's position in a per-tile vector stored in accumulator order (slot 16*half + g)
+__device__ __forceinline__ int acc_order_slot(int lane) { return 16 * (lane >> 5) + (lane & 15); }
+
 constexpr float FLURKA_LOG2E = 1.4426950408889634f;
 // The running row maximum is only raised when a tile exceeds it by more than this (natural log
 // units): weights may then be as large as exp(5) instead of 1, which costs nothing in fp32 or bf16
@@ -98,15 +108,23 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
     const unsigned char* wrow = lw + l32 * w_pitch + 16 * half;        // + 32*ft rows, + 32*s
     const unsigned char* srow = ls + l32 * s_pitch + 16 * half;        // + 32*t rows, + 64*ft (+32)
 
-    auto load_c = [&](int ft) -> floatx16 {
-        floatx16 u;
-        const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 v = ct[q];
-            u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
+    const int slot = acc_order_slot(32 * half + l32);
+    // u <- u + c, element g taking the shift of its own feature
+    auto add_shift = [&](floatx16& u, float cr) {
+        u[0] += bcast16<0>(cr);   u[1] += bcast16<1>(cr);   u[2] += bcast16<2>(cr);   u[3] += bcast16<3>(cr);
+        u[4] += bcast16<4>(cr);   u[5] += bcast16<5>(cr);   u[6] += bcast16<6>(cr);   u[7] += bcast16<7>(cr);
+        u[8] += bcast16<8>(cr);   u[9] += bcast16<9>(cr);   u[10] += bcast16<10>(cr); u[11] += bcast16<11>(cr);
+        u[12] += bcast16<12>(cr); u[13] += bcast16<13>(cr); u[14] += bcast16<14>(cr); u[15] += bcast16<15>(cr);
+    };
+    auto z_of = [&](float zr, int g) -> float {
+        switch (g) {
+            case 0: return bcast16<0>(zr);   case 1: return bcast16<1>(zr);   case 2: return bcast16<2>(zr);
+            case 3: return bcast16<3>(zr);   case 4: return bcast16<4>(zr);   case 5: return bcast16<5>(zr);
+            case 6: return bcast16<6>(zr);   case 7: return bcast16<7>(zr);   case 8: return bcast16<8>(zr);
+            case 9: return bcast16<9>(zr);   case 10: return bcast16<10>(zr); case 11: return bcast16<11>(zr);
+            case 12: return bcast16<12>(zr); case 13: return bcast16<13>(zr); case 14: return bcast16<14>(zr);
+            default: return bcast16<15>(zr);
         }
-        return u;
     };
     auto tile_max = [&](const floatx16& u) -> float {
         float tmax = fmaxf(fmaxf(u[0], u[1]), u[2]);
@@ -129,9 +147,9 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
     // prologue: tile 0
     floatx16 u[QT];
     {
-        const floatx16 c0 = load_c(0);
+        const float c0 = lc[slot];
 #pragma unroll
-        for (int i = 0; i < QT; ++i) u[i] = c0;
+        for (int i = 0; i < QT; ++i) u[i] = zero16();
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const uint4 wa = *(const uint4*)(wrow + 32 * s);
@@ -139,7 +157,10 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
             for (int i = 0; i < QT; ++i) u[i] = mfma32(wa, qf[i][s], u[i]);
         }
 #pragma unroll
-        for (int i = 0; i < QT; ++i) maybe_rescale(i, tile_max(u[i]));
+        for (int i = 0; i < QT; ++i) {
+            add_shift(u[i], c0);
+            maybe_rescale(i, tile_max(u[i]));
+        }
     }
 
     auto iteration = [&](int ft, auto last_tag) {
@@ -150,20 +171,13 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         if constexpr (LAST) last_hook();
 #pragma unroll
         for (int i = 0; i < QT; ++i) nshift[i] = -mu[i] * FLURKA_LOG2E;
+        float cn = 0.f;
         if constexpr (!LAST) {
-            const floatx16 cn = load_c(nft);
+            cn = lc[32 * nft + slot];
 #pragma unroll
-            for (int i = 0; i < QT; ++i) un[i] = cn;
+            for (int i = 0; i < QT; ++i) un[i] = zero16();
         }
-        float zv[16];
-        {
-            const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = zt[q];
-                zv[4 * q] = v.x; zv[4 * q + 1] = v.y; zv[4 * q + 2] = v.z; zv[4 * q + 3] = v.w;
-            }
-        }
+        const float zr = lz[32 * ft + slot];
         uint4 wa[KS], sa[2 * TT];
         if constexpr (!LAST) {
 #pragma unroll
@@ -190,7 +204,7 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
 #pragma unroll
                 for (int e = 0; e < EPC; ++e) {
                     p[e] = fast_exp2(fmaf(u[i][s * EPC + e], FLURKA_LOG2E, nshift[i]));
-                    den[i] = fmaf(p[e], zv[s * EPC + e], den[i]);
+                    den[i] = fmaf(z_of(zr, s * EPC + e), p[e], den[i]);
                 }
 #pragma unroll
                 for (int e = 0; e < EPC; e += 2) pk[i][(s * EPC + e) / 2] = pack_bf16(p[e], p[e + 1]);
@@ -214,7 +228,10 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         float tmax[QT];
         if constexpr (!LAST) {
 #pragma unroll
-            for (int i = 0; i < QT; ++i) tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
+            for (int i = 0; i < QT; ++i) {
+                add_shift(un[i], cn);
+                tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
+            }
         }
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
