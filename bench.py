@@ -51,8 +51,9 @@ def stage_model(w, stage: str):
         fl = (2 * n * d * mf + 2 * n * mf * d + 2 * n * mf) * BH if perf else (2 * n * d * d + 2 * n * d) * BH
         return float(fl), es * 2 * BH * n * d + om + 4 * BH * (mf * d + mf)
     if stage == "bwd_query":
-        gemms = 5 if perf else 3
-        return 2.0 * gemms * n * mf * d * BH, es * 3 * BH * n * d + om + 4 * BH * 2 * (mf * d + mf)
+        # with the forward's log-denominators and out at hand: u, G S^T, dQ, dS (performer)
+        gemms = 4 if perf else 3
+        return 2.0 * gemms * n * mf * d * BH, es * 4 * BH * n * d + om + 4 * BH * 2 * (mf * d + mf)
     if stage == "bwd_key":
         return float((4 * k * mf * d + (2 * k * mf * d if perf else 0)) * BH), 2 * small
     if stage == "bwd_dk_dv":
@@ -68,7 +69,7 @@ KERNEL_TRACE_NAME = {
     "proj_finish": "proj_finish_kernel",
     "key_state": "key_state_kernel<{d}, false>",
     "merge_pack": "merge_pack_kernel",
-    "query_stream": "query_stream_kernel<{d}, {elu}, 8, 1>",
+    "query_stream": "query_stream_kernel<{d}, {elu}, {qs_waves}, 1>",
     "bwd_pack": "bwd_pack_kernel",
     "bwd_query_x": "bwd_query_x_kernel<{d}>",
     "bwd_query_y": "bwd_query_y_kernel<{d}>",
@@ -81,8 +82,9 @@ KERNEL_TRACE_NAME = {
 
 
 def kernel_model(w, kernel: str):
-    """Algorithmic (flops, bytes) of one kernel of the MFMA path (recomputation is not counted:
-    the backward's five n*m*d contractions are split 4 : 1 between bwd_query_x and bwd_query_y)."""
+    """Algorithmic (flops, bytes) of one kernel of the MFMA path (recomputation is not counted: the
+    backward's four n*m*d contractions are split 3 : 1 between bwd_query_x, which forms u, G S^T and
+    dQ, and bwd_query_y, whose second evaluation of u is not counted)."""
     es = 2 if w.dtype == "bf16" else 4
     BH, n, d, k = w.B * w.H, w.n, w.d, w.k
     mf = w.d if w.phi == "elu1" else w.m
@@ -93,7 +95,7 @@ def kernel_model(w, kernel: str):
     if kernel == "key_state":
         return stage_model(w, "key_state")
     if kernel == "bwd_query_x":
-        return 8.0 * n * mf * d * BH, es * 3 * BH * n * d + 8 * BH * n
+        return 6.0 * n * mf * d * BH, es * 4 * BH * n * d + 8 * BH * n
     if kernel == "bwd_query_y":
         return 2.0 * n * mf * d * BH, es * 2 * BH * n * d + 8 * BH * n + 4 * BH * mf * d
     if kernel == "bwd_key":
@@ -117,7 +119,8 @@ def whole_model(w):
     om = (w.H if w.omega_per_head else 1) * w.m * d * es if w.phi != "elu1" else 0
     by = es * (4 * BH * n * d + 2 * k * n) + om                       # forward: Q,K,V,E,F,omega in, out out
     if w.backward:
-        by += es * (4 * BH * n * d + 2 * k * n) + om + es * (3 * BH * n * d + 2 * k * n)
+        # backward: Q, K, V, out, dOut, E, F, omega in; dQ, dK, dV, dE, dF out
+        by += es * (5 * BH * n * d + 2 * k * n) + om + es * (3 * BH * n * d + 2 * k * n)
     return fl, by
 
 
@@ -235,7 +238,8 @@ def main():
         roof = roofline_entry(w, dominant, avg_launch,
                               "HIP events around each launch of this kernel, on the stream it runs on",
                               model=kernel_model)
-        trace = KERNEL_TRACE_NAME[dominant].format(d=w.d, elu="true" if w.phi == "elu1" else "false")
+        trace = KERNEL_TRACE_NAME[dominant].format(d=w.d, elu="true" if w.phi == "elu1" else "false",
+                                                   qs_waves=12 if w.d == 64 else 8)
         roof["kernel_in_trace"] = trace
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
