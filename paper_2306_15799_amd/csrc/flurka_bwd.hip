@@ -59,23 +59,14 @@ __global__ void bwd_pack_kernel(uint16_t* Sp, float* zp, float* cp, const float*
     }
 }
 
-//   Wpair (m/2 x d) dwords: {omega[2p][t], omega[2p+1][t]}   B operand of dK' = dUk omega
-__global__ void bwd_pack_omega_kernel(uint16_t* Wt, uint32_t* Wpair, const uint16_t* omega, int m, int d,
-                                      long total) {
+__global__ void bwd_pack_omega_kernel(uint16_t* Wt, const uint16_t* omega, int m, int d, long total) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const long h = idx / ((long)m * d);
     const int rem = (int)(idx % ((long)m * d));
-    {
-        const int t = rem / m, slot = rem % m;
-        const int f = (slot & ~15) + slot_to_elem16(slot & 15);
-        Wt[idx] = omega[(h * m + f) * d + t];
-    }
-    if (rem < (m / 2) * d) {
-        const int pr = rem / d, t = rem % d;
-        Wpair[h * (m / 2) * d + rem] =
-            (uint32_t)omega[(h * m + 2 * pr) * d + t] | ((uint32_t)omega[(h * m + 2 * pr + 1) * d + t] << 16);
-    }
+    const int t = rem / m, slot = rem % m;
+    const int f = (slot & ~15) + slot_to_elem16(slot & 15);
+    Wt[idx] = omega[(h * m + f) * d + t];
 }
 
 // ---------------------------------------------------------------------------
@@ -455,10 +446,10 @@ __device__ __forceinline__ void bsplit2(float x, uint16_t& hi, uint16_t& lo) {
 }
 
 // Sums the query ranges of dS, dz and writes the operand images of the key-side kernel:
-//   dSimg  2 x (BH, mf, d) bf16 (hi, lo)              A operand of dPhiK^T = dS V'^T
-//   dSpair 2 x (BH, mf/2, d) dwords (hi, lo)          B operand of dV' = PhiK dS, two features per dword
+//   dSimg  2 x (BH, mf, d) bf16 (hi, lo)    A operand of dPhiK^T = dS V'^T, and (through transposing
+//                                           LDS reads) B operand of dV' = PhiK dS
 //   dz     (BH, mf) fp32
-__global__ void bwd_merge_kernel(uint16_t* dSimg, uint32_t* dSpair, float* dz, const float* dSpart,
+__global__ void bwd_merge_kernel(uint16_t* dSimg, float* dz, const float* dSpart,
                                  const float* dzpart, int R, int mf, int d, long total) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;    // (bh, feature pair, t)
     if (idx >= total) return;
@@ -479,8 +470,6 @@ __global__ void bwd_merge_kernel(uint16_t* dSimg, uint32_t* dSpair, float* dz, c
     const long i0 = (bh * mf + 2 * pr) * d + t;
     dSimg[i0] = h0; dSimg[i0 + d] = h1;
     dSimg[plane + i0] = l0; dSimg[plane + i0 + d] = l1;
-    dSpair[idx] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-    dSpair[total + idx] = (uint32_t)l0 | ((uint32_t)l1 << 16);
     if (t == 0) {
         float z0 = 0.f, z1 = 0.f;
         for (int r = 0; r < R; ++r) {
@@ -503,8 +492,8 @@ __global__ void bwd_merge_kernel(uint16_t* dSimg, uint32_t* dSpair, float* dz, c
 // ---------------------------------------------------------------------------
 struct BwdKeyArgs {
     const float* Kp; const float* Vp; const float* c;      // ctx
-    const uint16_t* omega; const uint32_t* Wpair;
-    const uint16_t* dSimg; const uint32_t* dSpair; const float* dz;
+    const uint16_t* omega;
+    const uint16_t* dSimg; const float* dz;
     uint16_t* img;     // 2 x (BH, kp, d): dK' then dV'
     uint16_t* imgT;    // 2 x (BH * d, kp)
     long omega_head_stride;
@@ -513,6 +502,18 @@ struct BwdKeyArgs {
 
 // One workgroup per (head, 32 keys); its four wavefronts take every fourth feature tile and add their
 // partial dV', dK', rs through LDS (fixed order, so the result does not depend on timing).
+// The B operands of dV' = PhiK dS and dK' = dUk omega need, per lane, one column t for 8 features:
+// each wavefront copies the 32 x d tiles of omega and dS (hi, lo) of its feature tile into its own
+// LDS area with 16-byte loads and takes them out with ds_read_b64_tr_b16 (see bwd_query_y).
+template <int D>
+struct BwdKeyLds {
+    static constexpr int pitch = D * 2 + 64;                       // as the dOut tile of bwd_query_y
+    static constexpr int tile = 32 * pitch;
+    static constexpr int tiles = 4 * 3 * tile;                     // per wavefront: omega, dS hi, dS lo
+    static constexpr int slots = 4 * (2 * (D / 32) * 16 * 64 + 64) * 4;
+    static constexpr int total = tiles > slots ? tiles : slots;    // the sums reuse the tile area
+};
+
 template <int D>
 __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
@@ -528,7 +529,10 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     const int krow = live ? key : a.k - 1;
     const long img_plane = (long)a.BH * a.kp * D;
     const long ds_plane = (long)a.BH * a.mf * D;
-    const long pair_plane = ds_plane / 2;
+    constexpr int P = BwdKeyLds<D>::pitch;
+    unsigned char* tw = lds + wave * 3 * BwdKeyLds<D>::tile;       // omega | dS hi | dS lo
+    const int s16 = lane & 15;
+    const int tr_off = (4 * half + (s16 >> 2)) * P + 2 * (16 * ((lane >> 4) & 1) + 4 * (s16 & 3));
 
     // this key's k' and v' (8 consecutive coordinates per step), split into bf16 terms: B operands
     uint4 kb[3][KS], vb[2][KS];
@@ -576,12 +580,26 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     float rs = 0.f;
     const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)l32 * D + 8 * half;
     const uint16_t* dsg = a.dSimg + ((long)bh * a.mf + l32) * D + 8 * half;
-    const uint32_t* dpg = a.dSpair + (long)bh * (a.mf / 2) * D + l32;
-    const uint32_t* wpg = a.Wpair + (long)(bh % a.H) * (a.omega_head_stride / 2) + l32;
     const float* cg = a.c + (long)bh * a.mf + 4 * half;
     const float* zg = a.dz + (long)bh * a.mf + 4 * half;
 
     for (int ft = wave; ft < FT; ft += 4) {
+        {   // this feature tile's rows of omega and dS, row-major, into the wavefront's LDS area
+            constexpr int CPR = D / 8, LPT = 32 * CPR / 64;
+            const uint16_t* ob = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ft) * D;
+            const uint16_t* sb = a.dSimg + ((long)bh * a.mf + 32 * ft) * D;
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) {
+                const int chunk = lane + 64 * u, row = chunk / CPR, c = chunk % CPR;
+                const uint4 x0 = ld16(ob + row * D + 8 * c);
+                const uint4 x1 = ld16(sb + row * D + 8 * c);
+                const uint4 x2 = ld16(sb + ds_plane + row * D + 8 * c);
+                unsigned char* dst = tw + row * P + 16 * c;
+                *(uint4*)dst = x0;
+                *(uint4*)(dst + BwdKeyLds<D>::tile) = x1;
+                *(uint4*)(dst + 2 * BwdKeyLds<D>::tile) = x2;
+            }
+        }
         // e^T tile (features x keys) and dPhiK^T tile; element g <-> feature 32*ft + 8*(g/4) + 4*half + g%4
         floatx16 e = zero16(), dp;
 #pragma unroll
@@ -632,15 +650,16 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
             const uint4 pal = {pl[4 * sp], pl[4 * sp + 1], pl[4 * sp + 2], pl[4 * sp + 3]};
             const uint4 uah = {uh[4 * sp], uh[4 * sp + 1], uh[4 * sp + 2], uh[4 * sp + 3]};
             const uint4 ual = {ul[4 * sp], ul[4 * sp + 1], ul[4 * sp + 2], ul[4 * sp + 3]};
-            // B operands: columns t = 32*tt + l32, feature pairs 16*ft + 8*sp + {0,1,4,5} + 2*half
-            const long prow = (long)(16 * ft + 8 * sp + 2 * half) * D;
+            // B operands: column t = 32*tt + l32 of features 32*ft + 16*sp + 4*half + {0..3, 8..11}
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                const uint32_t* dq = dpg + prow + 32 * tt;
-                const uint32_t* wq = wpg + prow + 32 * tt;
-                const uint4 bh4 = {dq[0], dq[D], dq[4 * D], dq[5 * D]};
-                const uint4 bl4 = {dq[pair_plane], dq[pair_plane + D], dq[pair_plane + 4 * D], dq[pair_plane + 5 * D]};
-                const uint4 bw4 = {wq[0], wq[D], wq[4 * D], wq[5 * D]};
+                const unsigned char* bp = tw + tr_off + (16 * sp) * P + 64 * tt;
+                const uint2 w0 = lds_read_tr16(bp), w1 = lds_read_tr16(bp + 8 * P);
+                const uint2 h0 = lds_read_tr16(bp + BwdKeyLds<D>::tile), h1 = lds_read_tr16(bp + BwdKeyLds<D>::tile + 8 * P);
+                const uint2 l0 = lds_read_tr16(bp + 2 * BwdKeyLds<D>::tile), l1 = lds_read_tr16(bp + 2 * BwdKeyLds<D>::tile + 8 * P);
+                const uint4 bw4 = {w0.x, w0.y, w1.x, w1.y};
+                const uint4 bh4 = {h0.x, h0.y, h1.x, h1.y};
+                const uint4 bl4 = {l0.x, l0.y, l1.x, l1.y};
                 accV[tt] = mfma32(pah, bh4, accV[tt]);
                 accV[tt] = mfma32(pal, bh4, accV[tt]);
                 accV[tt] = mfma32(pah, bl4, accV[tt]);
@@ -652,6 +671,7 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     rs = half_sum(rs);
 
     // add the four wavefronts' partial results: slot w = [dV' | dK'][tt][g][lane], then rs[lane]
+    __syncthreads();                    // the slots reuse the tile area
     float* slots = (float*)lds;
     constexpr int SLOT = 2 * TT * 16 * 64 + 64;
     {
@@ -771,7 +791,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
 }
 
 struct FastBwdWs {
-    size_t Sp, Wt, Wpair, zp, cp, delta, dSpart, dzpart, dSimg, dSpair, dz, img, imgT, epart, total;
+    size_t Sp, Wt, zp, cp, delta, dSpart, dzpart, dSimg, dz, img, imgT, epart, total;
     int kp;      // k rounded up to whole 64-slot reduction steps of the gradient GEMMs
 };
 
@@ -782,14 +802,12 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     size_t o = 0;
     W.Sp = o;     o += round_up(BH * p.mf * p.d * 2, 256);
     W.Wt = o;     o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
-    W.Wpair = o;  o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
     W.zp = o;     o += round_up(BH * p.mf * 4, 256);
     W.cp = o;     o += round_up(BH * p.mf * 4, 256);
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
     W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
     W.dSimg = o;  o += round_up(2 * BH * p.mf * p.d * 2, 256);
-    W.dSpair = o; o += round_up(2 * BH * p.mf * p.d * 2, 256);
     W.dz = o;     o += round_up(BH * p.mf * 4, 256);
     W.kp = (p.k + 63) / 64 * 64;
     const GradEPlan e = grad_e_plan(p);
@@ -829,7 +847,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         FLURKA_CHECK_LAUNCH();
         const long wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
         hipLaunchKernelGGL(bwd_pack_omega_kernel, grid1d(wtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Wt),
-                           (uint32_t*)(wsb + W.Wpair), (const uint16_t*)a.omega, p.m, p.d, wtotal);
+                           (const uint16_t*)a.omega, p.m, p.d, wtotal);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_PACK);
 
@@ -873,21 +891,21 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         stage_begin(s);
         const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
         hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.dSimg),
-                           (uint32_t*)(wsb + W.dSpair), (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
+                           (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
                            (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_MERGE);
         StageScope sc(s, STAGE_K_BWD_KEY);
         BwdKeyArgs ka{};
         ka.Kp = a.ctx + L.Kp; ka.Vp = a.ctx + L.Vp; ka.c = a.ctx + L.c;
-        ka.omega = (const uint16_t*)a.omega; ka.Wpair = (const uint32_t*)(wsb + W.Wpair);
-        ka.dSimg = (const uint16_t*)(wsb + W.dSimg); ka.dSpair = (const uint32_t*)(wsb + W.dSpair);
+        ka.omega = (const uint16_t*)a.omega;
+        ka.dSimg = (const uint16_t*)(wsb + W.dSimg);
         ka.dz = (const float*)(wsb + W.dz);
         ka.img = img; ka.imgT = imgT;
         ka.omega_head_stride = omega_stride;
         ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kp = W.kp; ka.mf = p.mf;
         const unsigned kgrid = (unsigned)(p.BH * (W.kp / 32));
-        const int klds = 4 * (2 * (p.d / 32) * 16 * 64 + 64) * 4;
+        const int klds = p.d == 64 ? BwdKeyLds<64>::total : BwdKeyLds<128>::total;
         const void* kk = p.d == 64 ? (const void*)bwd_key_kernel<64> : (const void*)bwd_key_kernel<128>;
         if (hipFuncSetAttribute(kk, hipFuncAttributeMaxDynamicSharedMemorySize, klds) != hipSuccess)
             return FLURKA_ERR_LAUNCH;
