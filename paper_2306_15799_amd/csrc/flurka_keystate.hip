@@ -120,6 +120,8 @@ struct KeyStateArgs {
     int BH, H, k, kpad, mf, FT, KR, tiles_per_range;
 };
 
+constexpr int KS_MT = 4;       // key tiles of a range that stay in registers
+
 template <int D, bool ELU>
 __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
@@ -178,13 +180,33 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
         return e;
     };
 
+    // Up to KS_MT tiles per range (what the plan aims for) are evaluated once, all their loads in flight
+    // together, and kept in registers between the maximum and the accumulation; longer ranges are
+    // evaluated twice.
+    const int nt = kt1 - kt0;
+    const bool keep = nt <= KS_MT;
+    floatx16 ev[KS_MT];
+    if (keep) {
+#pragma unroll
+        for (int i = 0; i < KS_MT; ++i)
+            if (i < nt) ev[i] = tile_values(kt0 + i);
+    }
     float c = 0.f;
     if (!ELU) {
         c = -INFINITY;
-        for (int kt = kt0; kt < kt1; ++kt) {
-            const floatx16 e = tile_values(kt);
+        if (keep) {
 #pragma unroll
-            for (int g = 0; g < 16; ++g) c = fmaxf(c, e[g]);
+            for (int i = 0; i < KS_MT; ++i)
+                if (i < nt) {
+#pragma unroll
+                    for (int g = 0; g < 16; ++g) c = fmaxf(c, ev[i][g]);
+                }
+        } else {
+            for (int kt = kt0; kt < kt1; ++kt) {
+                const floatx16 e = tile_values(kt);
+#pragma unroll
+                for (int g = 0; g < 16; ++g) c = fmaxf(c, e[g]);
+            }
         }
         c = half_max(c);
     }
@@ -194,8 +216,7 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
     for (int t = 0; t < TT; ++t) accS[t] = zero16();
     float zsum = 0.f;
     constexpr float LOG2E = 1.4426950408889634f;
-    for (int kt = kt0; kt < kt1; ++kt) {
-        floatx16 e = tile_values(kt);
+    auto accumulate = [&](int kt, const floatx16& e) {
         uint32_t hi[8], lo[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -230,6 +251,13 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
                 accS[tt] = mfma32(ah[sp], bl4, accS[tt]);
             }
         }
+    };
+    if (keep) {
+#pragma unroll
+        for (int i = 0; i < KS_MT; ++i)
+            if (i < nt) accumulate(kt0 + i, ev[i]);
+    } else {
+        for (int kt = kt0; kt < kt1; ++kt) accumulate(kt, tile_values(kt));
     }
     zsum = half_sum(zsum);
 
@@ -263,11 +291,13 @@ struct MergeArgs {
     int KR, mf, d, permute;
 };
 
+// Grid: (head, 32 features) x chunks of 32 coordinates t, so that even a few heads fill the chip.
 __global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
-    __shared__ float w[16][32];          // weights exp(c_jr - c_j), up to 16 ranges
-    __shared__ float tile[32][129];      // merged S tile, padded
+    __shared__ float w[32][32];          // weights exp(c_jr - c_j) per range and feature
+    __shared__ float tile[32][33];       // merged S tile (features x 32 t), padded
     const int FT = a.mf / 32;
     const int bh = blockIdx.x / FT, ft = blockIdx.x % FT;
+    const int t0 = 32 * blockIdx.y;
     const int tid = threadIdx.x;
     const long pbase = (long)bh * a.KR * a.mf;
     if (tid < 32) {
@@ -280,35 +310,37 @@ __global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
             w[r][tid] = wr;
             zs = fmaf(wr, a.zpart[pbase + (long)r * a.mf + f], zs);
         }
-        a.z[(long)bh * a.mf + f] = zs;
-        a.c[(long)bh * a.mf + f] = cm;
-        // accumulator order of a 32-feature tile: position 16*h + g <-> feature 8*(g/4) + 4*h + g%4
-        int pos = tid;
-        if (a.permute) {
-            const int q = tid >> 3, h = (tid >> 2) & 1, e = tid & 3;
-            pos = 16 * h + 4 * q + e;
+        if (blockIdx.y == 0) {
+            a.z[(long)bh * a.mf + f] = zs;
+            a.c[(long)bh * a.mf + f] = cm;
+            // accumulator order of a 32-feature tile: position 16*h + g <-> feature 8*(g/4) + 4*h + g%4
+            int pos = tid;
+            if (a.permute) {
+                const int q = tid >> 3, h = (tid >> 2) & 1, e = tid & 3;
+                pos = 16 * h + 4 * q + e;
+            }
+            a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
+            a.cp[(long)bh * a.mf + 32 * ft + pos] = cm;
         }
-        a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
-        a.cp[(long)bh * a.mf + 32 * ft + pos] = cm;
     }
     __syncthreads();
-    for (int i = tid; i < 32 * a.d; i += 256) {
-        const int fl = i / a.d, t = i % a.d;
+    for (int i = tid; i < 32 * 32; i += 256) {
+        const int fl = i / 32, t = t0 + i % 32;
         float s = 0.f;
         for (int r = 0; r < a.KR; ++r)
             s = fmaf(w[r][fl], a.Spart[(pbase + (long)r * a.mf + 32 * ft + fl) * a.d + t], s);
         a.S[((long)bh * a.mf + 32 * ft + fl) * a.d + t] = s;
-        tile[fl][t] = s;
+        tile[fl][i % 32] = s;
     }
     __syncthreads();
-    for (int i = tid; i < 32 * a.d; i += 256) {
-        const int t = i / 32, sl = i % 32;
+    for (int i = tid; i < 32 * 32; i += 256) {
+        const int tl = i / 32, sl = i % 32;
         int fl = sl;
         if (a.permute) {
             const int e = sl & 7, h = (sl >> 3) & 1;
             fl = (sl & 16) + 8 * (e >> 2) + 4 * h + (e & 3);
         }
-        a.St[((long)bh * a.d + t) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl][t]);
+        a.St[((long)bh * a.d + t0 + tl) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl][tl]);
     }
 }
 
@@ -320,8 +352,9 @@ KeyStatePlan key_state_plan(const Problem& p) {
     q.kpad = (p.k + 31) / 32 * 32;
     q.FT = p.mf / 32;
     const int KT = q.kpad / 32;
-    int KR = (1024 + p.BH * q.FT - 1) / (p.BH * q.FT);
-    if (KR > 16) KR = 16;
+    int KR = (1024 + p.BH * q.FT - 1) / (p.BH * q.FT);          // about 1024 wavefronts ...
+    if (KR < (KT + KS_MT - 1) / KS_MT) KR = (KT + KS_MT - 1) / KS_MT;   // ... of at most KS_MT key tiles
+    if (KR > 32) KR = 32;
     if (KR > KT) KR = KT;
     if (KR < 1) KR = 1;
     q.tiles_per_range = (KT + KR - 1) / KR;
@@ -373,7 +406,7 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         ma.S = ctx + L.S; ma.z = ctx + L.z; ma.c = ctx + L.c;
         ma.St = b.St; ma.zp = b.zp; ma.cp = b.cp;
         ma.KR = q.KR; ma.mf = p.mf; ma.d = p.d; ma.permute = p.elu ? 0 : 1;
-        hipLaunchKernelGGL(merge_pack_kernel, dim3(p.BH * q.FT), dim3(256), 0, s, ma);
+        hipLaunchKernelGGL(merge_pack_kernel, dim3(p.BH * q.FT, p.d / 32), dim3(256), 0, s, ma);
         FLURKA_CHECK_LAUNCH();
     }
     return FLURKA_OK;
