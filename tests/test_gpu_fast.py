@@ -14,12 +14,16 @@ pytestmark = pytest.mark.gpu
 
 # (B, H, n, d, k, m): several 256-wide column tiles, ragged head count per tile, ragged k,
 # a sequence split over several workgroups, both head sizes
+# the last two: more (head, tile) pairs than resident workgroups, so one workgroup's share crosses
+# from one head into the next and refills its LDS image; many heads with few tiles each
 FWD_SHAPES = [
     (1, 3, 192, 64, 100, 96),
     (2, 5, 1024, 64, 256, 256),
     (1, 3, 640, 128, 300, 160),
     (3, 2, 2048, 128, 512, 32),
     (1, 1, 64, 64, 1, 32),
+    (3, 5, 1088, 64, 96, 128),
+    (8, 16, 128, 128, 40, 64),
 ]
 
 
@@ -83,10 +87,14 @@ def test_unsupported_shapes_are_refused_not_miscomputed():
 
 
 # ---- backward ------------------------------------------------------------------------------
+# (3, 5, 1088, ...): 34 query tiles per head -- shares of the resident grid cross head boundaries, and
+# the last 128-query block of each range of the dS kernel is only half filled
 BWD_SHAPES = [
     (1, 3, 192, 64, 100, 96),
     (2, 5, 1024, 64, 256, 256),
     (2, 2, 2048, 64, 64, 32),
+    (3, 5, 1088, 64, 96, 128),
+    (8, 16, 128, 64, 40, 64),
 ]
 
 
