@@ -39,34 +39,42 @@ __host__ __device__ inline int slot_to_elem16(int p) {
 //   Wt  (d x m)    Wt[t][slot]  = omega[feat(slot)][t]    A operand of dQ^T = omega^T dU^T  (per omega head)
 //   zp, cp (mf)    z, c in accumulator order of a 32-feature tile
 // ---------------------------------------------------------------------------
-__global__ void bwd_pack_kernel(uint16_t* Sp, float* zp, float* cp, const float* S, const float* z,
-                                const float* c, int mf, int d, long total) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const long bh = idx / ((long)mf * d);
-    const int rem = (int)(idx % ((long)mf * d));
-    if (rem < mf) {
-        const int slot = rem;
-        const int g = slot & 15, h = (slot >> 4) & 1;
-        const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
-        zp[bh * mf + slot] = z[bh * mf + fz];
-        cp[bh * mf + slot] = c[bh * mf + fz];
-    }
-    {   // Sp: rem = j * d + slot
+struct BwdPackArgs {
+    uint16_t* Sp; float* zp; float* cp; const float* S; const float* z; const float* c;
+    uint16_t* Wt; const uint16_t* omega;
+    int mf, d, m;
+    long total, wtotal;      // BH * mf * d elements of S; (H|1) * m * d elements of omega
+    unsigned s_blocks;       // blocks that pack S; the rest pack omega
+};
+
+__global__ void bwd_pack_kernel(BwdPackArgs a) {
+    if (blockIdx.x < a.s_blocks) {
+        const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+        if (idx >= a.total) return;
+        const int mf = a.mf, d = a.d;
+        const long bh = idx / ((long)mf * d);
+        const int rem = (int)(idx % ((long)mf * d));
+        if (rem < mf) {
+            const int slot = rem;
+            const int g = slot & 15, h = (slot >> 4) & 1;
+            const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
+            a.zp[bh * mf + slot] = a.z[bh * mf + fz];
+            a.cp[bh * mf + slot] = a.c[bh * mf + fz];
+        }
+        // Sp: rem = j * d + slot
         const int j = rem / d, slot = rem % d;
         const int t = (slot & ~15) + slot_to_elem16(slot & 15);
-        Sp[idx] = f32_to_bf16(S[(bh * mf + j) * d + t]);
+        a.Sp[idx] = f32_to_bf16(a.S[(bh * mf + j) * d + t]);
+    } else {
+        const long idx = (long)(blockIdx.x - a.s_blocks) * blockDim.x + threadIdx.x;
+        if (idx >= a.wtotal) return;
+        const int m = a.m, d = a.d;
+        const long h = idx / ((long)m * d);
+        const int rem = (int)(idx % ((long)m * d));
+        const int t = rem / m, slot = rem % m;
+        const int f = (slot & ~15) + slot_to_elem16(slot & 15);
+        a.Wt[idx] = a.omega[(h * m + f) * d + t];
     }
-}
-
-__global__ void bwd_pack_omega_kernel(uint16_t* Wt, const uint16_t* omega, int m, int d, long total) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const long h = idx / ((long)m * d);
-    const int rem = (int)(idx % ((long)m * d));
-    const int t = rem / m, slot = rem % m;
-    const int f = (slot & ~15) + slot_to_elem16(slot & 15);
-    Wt[idx] = omega[(h * m + f) * d + t];
 }
 
 // ---------------------------------------------------------------------------
@@ -729,17 +737,23 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     }
 }
 
-// dst (bf16) = sum over splits of src (fp32)
-__global__ void sum_splits_bf16_kernel(uint16_t* dst, const float* src, long count, long stride, int splits) {
-    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 2;
+// dst (bf16) = sum over splits of src (fp32), four elements per thread (count % 4 == 0); blockIdx.y
+// picks the (dst0, src) or (dst1, src + splits * stride) pair: dE and dF in one launch
+__global__ void sum_splits_bf16_kernel(uint16_t* dst0, uint16_t* dst1, const float* src, long count, long stride,
+                                       int splits) {
+    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i >= count) return;
-    float a0 = 0.f, a1 = 0.f;
+    uint16_t* dst = blockIdx.y ? dst1 : dst0;
+    const float* sp = src + (blockIdx.y ? (long)splits * stride : 0) + i;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < splits; ++s) {
-        a0 += src[(long)s * stride + i];
-        if (i + 1 < count) a1 += src[(long)s * stride + i + 1];
+        const float4 v = *(const float4*)(sp + (long)s * stride);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
-    if (i + 1 < count) *(uint32_t*)(dst + i) = pack_bf16(a0, a1);
-    else dst[i] = f32_to_bf16(a0);
+    uint2 o;
+    o.x = pack_bf16(acc.x, acc.y);
+    o.y = pack_bf16(acc.z, acc.w);
+    *(uint2*)(dst + i) = o;
 }
 
 // ---------------------------------------------------------------------------
@@ -841,13 +855,16 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     flurka_status st;
     {
         stage_begin(s);
-        const long total = (long)p.BH * p.mf * p.d;
-        hipLaunchKernelGGL(bwd_pack_kernel, grid1d(total, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Sp), (float*)(wsb + W.zp), (float*)(wsb + W.cp), a.ctx + L.S,
-                           a.ctx + L.z, a.ctx + L.c, p.mf, p.d, total);
-        FLURKA_CHECK_LAUNCH();
-        const long wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
-        hipLaunchKernelGGL(bwd_pack_omega_kernel, grid1d(wtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.Wt),
-                           (const uint16_t*)a.omega, p.m, p.d, wtotal);
+        BwdPackArgs pa{};
+        pa.Sp = (uint16_t*)(wsb + W.Sp); pa.zp = (float*)(wsb + W.zp); pa.cp = (float*)(wsb + W.cp);
+        pa.S = a.ctx + L.S; pa.z = a.ctx + L.z; pa.c = a.ctx + L.c;
+        pa.Wt = (uint16_t*)(wsb + W.Wt); pa.omega = (const uint16_t*)a.omega;
+        pa.mf = p.mf; pa.d = p.d; pa.m = p.m;
+        pa.total = (long)p.BH * p.mf * p.d;
+        pa.wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
+        pa.s_blocks = (unsigned)((pa.total + 255) / 256);
+        const unsigned w_blocks = (unsigned)((pa.wtotal + 255) / 256);
+        hipLaunchKernelGGL(bwd_pack_kernel, dim3(pa.s_blocks + w_blocks), dim3(256), 0, s, pa);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_PACK);
 
@@ -942,11 +959,8 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         if (st != FLURKA_OK) return st;
         stage_end(s, STAGE_K_GRAD_E);
         StageScope sc(s, STAGE_K_SUM_SPLITS);
-        hipLaunchKernelGGL(sum_splits_bf16_kernel, grid1d((kn + 1) / 2, 256), dim3(256), 0, s, (uint16_t*)a.dE,
-                           (const float*)part, kn, kn, e.splits);
-        FLURKA_CHECK_LAUNCH();
-        hipLaunchKernelGGL(sum_splits_bf16_kernel, grid1d((kn + 1) / 2, 256), dim3(256), 0, s, (uint16_t*)a.dF,
-                           (const float*)(part + (long)e.splits * kn), kn, kn, e.splits);
+        hipLaunchKernelGGL(sum_splits_bf16_kernel, dim3((unsigned)((kn / 4 + 255) / 256), 2), dim3(256), 0, s,
+                           (uint16_t*)a.dE, (uint16_t*)a.dF, (const float*)part, kn, kn, e.splits);
         FLURKA_CHECK_LAUNCH();
     }
     return FLURKA_OK;
