@@ -27,9 +27,12 @@ namespace flurka {
 constexpr int GBM = 256, GBN = 256, GBK = 64;
 constexpr int GA_PITCH = 144;                       // bytes per LDS row of a row-major tile (128 + 16)
 constexpr int GA_STAGE = GBM * GA_PITCH;            // 36,864
-constexpr int GB_STAGE_T = (GBK / 8) * GBN * 16;    // transposed tile: [8-position group][column][8]
+constexpr int GB_PITCH_T = GBN * 2 + 64;            // row of a [position][column] tile: 4 consecutive rows
+                                                    // fall into the 4 quarters of the LDS banks
+constexpr int GB_STAGE_T = GBK * GB_PITCH_T;        // 36,864
 constexpr int GB_STAGE_D = GBN * GA_PITCH;          // direct tile: like A
-constexpr int G_STAGE = GA_STAGE + GB_STAGE_D;      // 73,728 (the larger of the two layouts)
+constexpr int G_STAGE = GA_STAGE + GB_STAGE_D;      // 73,728 (both layouts of B take the same room)
+static_assert(GB_STAGE_T <= GB_STAGE_D, "B stage");
 constexpr int G_LDS = 2 * G_STAGE;                  // 147,456
 
 struct GemmParams {
@@ -55,6 +58,13 @@ __device__ __forceinline__ uint4 buf_ld16(__amdgpu_buffer_rsrc_t r, int voff, in
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+typedef short gemm_short4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 gemm_read_tr16(const unsigned char* p) {
+    const gemm_short4 v =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((gemm_short4 __attribute__((address_space(3)))*)p);
+    return __builtin_bit_cast(uint2, v);
 }
 
 template <class Pol>
@@ -85,15 +95,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
     // LDS addresses of this thread's writes and of this lane's fragment reads (per buffer: + G_STAGE)
     unsigned char* const a_dst = lds + (tid >> 3) * GA_PITCH + 16 * (tid & 7);                    // + 32*q rows
     const unsigned char* const fa_src = lds + (wm * 128 + l32) * GA_PITCH + 16 * half;           // + 32*i rows, + 32*s
-    // transposed B: thread = (8 positions b_kg, 8 columns b_cg); chunk of column c at c ^ ((c >> 4) & 15)
+    // B given as [position][column] ("transposed" with respect to what the MFMA wants): the tile goes
+    // to LDS as loaded, thread = (8 positions b_kg, 8 columns b_cg), and the fragments come out through
+    // ds_read_b64_tr_b16: in each group of 16 lanes, lane s points at 4 columns of row s/4 of a
+    // 4 x 16 block and receives one column of its 4 rows; two such reads are the 8 reduction slots.
     const int b_cg = tid & 31, b_kg = tid >> 5;
-    const int bt_dst0 = GA_STAGE + (b_kg * GBN + ((8 * b_cg) & ~15) + ((8 * (b_cg & 1)) ^ ((b_cg >> 1) & 15))) * 16;
+    unsigned char* const bt_dst = lds + GA_STAGE + (8 * b_kg) * GB_PITCH_T + 16 * b_cg;          // + q rows
     unsigned char* const bd_dst = lds + GA_STAGE + (tid >> 3) * GA_PITCH + 16 * (tid & 7);       // direct B
     const unsigned char* fb_src[4];
     if (BT) {
-        const int c0 = wn * 128 + (l32 & 16) + ((l32 & 15) ^ ((8 * wn + (l32 >> 4)) & 15));
+        const int s16 = lane & 15;
+        const int row = 8 * half + (s16 >> 2), colb = 2 * (wn * 128 + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fb_src[j] = lds + GA_STAGE + (half * GBN + ((c0 ^ (2 * j)) + 32 * j)) * 16;
+        for (int j = 0; j < 4; ++j) fb_src[j] = lds + GA_STAGE + row * GB_PITCH_T + colb + 64 * j;
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) fb_src[j] = lds + GA_STAGE + (wn * 128 + 32 * j + l32) * GA_PITCH + 16 * half;
@@ -111,25 +125,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 #define G_MMA(set, i, j) acc[i][j] = mfma32(FA[set][i], FB[set][j], acc[i][j])
 #define G_LDA(set, buf, s, i) \
     FA[set][i] = *(const uint4*)(fa_src + (buf) * G_STAGE + (32 * (i)) * GA_PITCH + 32 * (s))
-#define G_LDB(set, buf, s, j) \
-    FB[set][j] = *(const uint4*)(fb_src[j] + (buf) * G_STAGE + (BT ? ((2 * (s)) * GBN) * 16 : 32 * (s)))
+#define G_LDB(set, buf, s, j)                                                                         \
+    if (BT) {                                                                                         \
+        const unsigned char* bp_ = fb_src[j] + (buf) * G_STAGE + (16 * (s)) * GB_PITCH_T;             \
+        const uint2 lo_ = gemm_read_tr16(bp_), hi_ = gemm_read_tr16(bp_ + 4 * GB_PITCH_T);            \
+        FB[set][j] = make_uint4(lo_.x, lo_.y, hi_.x, hi_.y);                                          \
+    } else {                                                                                          \
+        FB[set][j] = *(const uint4*)(fb_src[j] + (buf) * G_STAGE + 32 * (s));                         \
+    }
 
     // store B row q of the staging set into LDS buffer `buf`
     auto store_b = [&](const uint4 (&rb)[8], int buf, int q) {
-        if (BT) {
-            // transpose 8 positions x 8 columns held in rb[0..7]; column q becomes one 16-byte chunk
-            const unsigned sel = (q & 1) ? 0x07060302u : 0x05040100u;
-            const int w = q >> 1;
-            auto dw = [&](const uint4& v) -> uint32_t { return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w)); };
-            uint4 o;
-            o.x = __builtin_amdgcn_perm(dw(rb[1]), dw(rb[0]), sel);
-            o.y = __builtin_amdgcn_perm(dw(rb[3]), dw(rb[2]), sel);
-            o.z = __builtin_amdgcn_perm(dw(rb[5]), dw(rb[4]), sel);
-            o.w = __builtin_amdgcn_perm(dw(rb[7]), dw(rb[6]), sel);
-            *(uint4*)(lds + ((bt_dst0 ^ (16 * q)) + buf * G_STAGE)) = o;
-        } else {
-            *(uint4*)(bd_dst + buf * G_STAGE + (32 * q) * GA_PITCH) = rb[q];
-        }
+        if (BT) *(uint4*)(bt_dst + buf * G_STAGE + q * GB_PITCH_T) = rb[q];
+        else    *(uint4*)(bd_dst + buf * G_STAGE + (32 * q) * GA_PITCH) = rb[q];
     };
 
     auto run_step = [&](auto par_c, int step_load) {
