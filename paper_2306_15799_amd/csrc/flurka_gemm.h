@@ -15,9 +15,8 @@
 // other register set.  Global data runs two steps ahead in registers: sub-step 0 issues the loads of
 // step + 2, sub-step 2 writes step + 1 into the other LDS buffer, then the single barrier of the step,
 // and sub-step 3 already prefetches from that buffer.  sched_barrier(0) after each "2 MFMA + few
-// others" group pins this order.  The last two steps fetch and store tiles nobody uses (reads past a
-// descriptor return zero); that keeps the loop body free of branches, which the 256 accumulator
-// registers do not survive well.
+// others" group pins this order.  The last two steps fetch and store tiles nobody uses; that keeps
+// the loop body free of branches, which the 256 accumulator registers do not survive well.
 #pragma once
 
 #include "flurka_mfma.h"
@@ -34,6 +33,7 @@ constexpr int GB_STAGE_D = GBN * GA_PITCH;          // direct tile: like A
 constexpr int G_STAGE = GA_STAGE + GB_STAGE_D;      // 73,728 (both layouts of B take the same room)
 static_assert(GB_STAGE_T <= GB_STAGE_D, "B stage");
 constexpr int G_LDS = 2 * G_STAGE;                  // 147,456
+constexpr int G_OOB = 0x7fffff00;                   // per-thread byte offset past any descriptor range
 
 struct GemmParams {
     const uint16_t* A[2];
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
         for (int j = 0; j < 4; ++j) fb_src[j] = lds + GA_STAGE + (wn * 128 + 32 * j + l32) * GA_PITCH + 16 * half;
     }
 
-    uint4 RA[2][8], RB[2][8];
+    uint4 RA[8], RB[8];
     uint4 FA[2][4], FB[2][4];
     floatx16 acc[4][4];
 #pragma unroll
@@ -134,15 +134,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
         FB[set][j] = *(const uint4*)(fb_src[j] + (buf) * G_STAGE + 32 * (s));                         \
     }
 
-    // store B row q of the staging set into LDS buffer `buf`
-    auto store_b = [&](const uint4 (&rb)[8], int buf, int q) {
-        if (BT) *(uint4*)(bt_dst + buf * G_STAGE + q * GB_PITCH_T) = rb[q];
-        else    *(uint4*)(bd_dst + buf * G_STAGE + (32 * q) * GA_PITCH) = rb[q];
+    // staging register q of A / B into LDS buffer `buf`
+    auto store_a = [&](int buf, int q) { *(uint4*)(a_dst + buf * G_STAGE + (32 * q) * GA_PITCH) = RA[q]; };
+    auto store_b = [&](int buf, int q) {
+        if (BT) *(uint4*)(bt_dst + buf * G_STAGE + q * GB_PITCH_T) = RB[q];
+        else    *(uint4*)(bd_dst + buf * G_STAGE + (32 * q) * GA_PITCH) = RB[q];
     };
 
     auto run_step = [&](auto par_c, int step_load) {
         constexpr int PAR = decltype(par_c)::value;
         const int sA = Pol::a_soff(pc, step_load), sB = Pol::b_soff(pc, step_load);
+        const int vB = step_load < step1 ? voffB : G_OOB;       // past the range: B reads as zero
 #define G_CHUNK(PH, q, i0, j0, i1, j1, LD)                                                      \
         {                                                                                       \
             constexpr int cur = (PH) & 1, nxt = cur ^ 1, ns = ((PH) + 1) & 3;                   \
@@ -150,15 +152,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
             G_MMA(cur, i0, j0); G_MMA(cur, i1, j1);                                             \
             LD(nxt, pbuf, ns, (q) >> 1);                                                        \
             constexpr int pos = 8 * (PH) + (q);      /* 0..31 within the step */                \
-            /* requests two steps ahead, one every other chunk: B in chunks 0..14, A in 16..30 */ \
-            if (pos < 16 && (pos & 1) == 0) RB[PAR][pos / 2] = buf_ld16(rsB, voffB, sB + (pos / 2) * pc.b_qstride); \
-            if (pos >= 16 && (pos & 1) == 0)                                                    \
-                RA[PAR][(pos - 16) / 2] = buf_ld16(rsA, voffA, sA + ((pos - 16) / 2) * pc.a_qstride); \
-            /* the step after this one goes to LDS, one store per chunk in 8..23: A in the even */ \
-            /* chunks, B (which needs all 8 of its loads) in the odd ones */                     \
-            if (pos >= 8 && pos < 24 && (pos & 1) == 0)                                         \
-                *(uint4*)(a_dst + (PAR ^ 1) * G_STAGE + (32 * ((pos - 8) / 2)) * GA_PITCH) = RA[PAR ^ 1][(pos - 8) / 2]; \
-            if (pos >= 9 && pos < 24 && (pos & 1) == 1) store_b(RB[PAR ^ 1], PAR ^ 1, (pos - 9) / 2); \
+            /* even chunk 2j: staging register j (A and B alternate) requests its part of the   */ \
+            /* tile two steps ahead; 25 chunks later (odd chunk) it is stored to LDS: chunks     */ \
+            /* 25..31 store into this step's own buffer, which nobody reads after the barrier,   */ \
+            /* chunks 1..23 of the next step finish the other buffer before that step's barrier  */ \
+            if ((pos & 1) == 0) {                                                               \
+                constexpr int j = pos / 2;                                                      \
+                if (j & 1) RB[j / 2] = buf_ld16(rsB, vB, sB + (j / 2) * pc.b_qstride);          \
+                else       RA[j / 2] = buf_ld16(rsA, voffA, sA + (j / 2) * pc.a_qstride);       \
+            } else {                                                                            \
+                constexpr int j = ((pos + 7) & 31) / 2;                                         \
+                constexpr int wbuf = pos >= 25 ? PAR : (PAR ^ 1);                               \
+                if (j & 1) store_b(wbuf, j / 2);                                                \
+                else       store_a(wbuf, j / 2);                                                \
+            }                                                                                   \
             G_SB();                                                                             \
         }
 #define G_PHASE(PH)                               \
@@ -181,38 +188,38 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
     };
 
     if (step0 < step1) {
-        // prologue: step0 through registers into buffer 0, step0 + 1 into staging set 1
+        // prologue: step0 through the staging registers into buffer 0; step0 + 1 requested, its first
+        // four registers (the ones the steady state stores in chunks 25..31) stored into buffer 1
         {
             const int sA = Pol::a_soff(pc, step0), sB = Pol::b_soff(pc, step0);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                RA[0][q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
-                RB[0][q] = buf_ld16(rsB, voffB, sB + q * pc.b_qstride);
+                RA[q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
+                RB[q] = buf_ld16(rsB, voffB, sB + q * pc.b_qstride);
             }
         }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { store_a(0, q); store_b(0, q); }
         {
             const int sA = Pol::a_soff(pc, step0 + 1), sB = Pol::b_soff(pc, step0 + 1);
+            const int vB = step0 + 1 < step1 ? voffB : G_OOB;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                RA[1][q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
-                RB[1][q] = buf_ld16(rsB, voffB, sB + q * pc.b_qstride);
+                RA[q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
+                RB[q] = buf_ld16(rsB, vB, sB + q * pc.b_qstride);
             }
         }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            *(uint4*)(a_dst + (32 * q) * GA_PITCH) = RA[0][q];
-            store_b(RB[0], 0, q);
-        }
+        store_a(1, 0); store_b(1, 0); store_a(1, 1); store_b(1, 1);
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) { G_LDA(0, 0, 0, i); G_LDB(0, 0, 0, i); }
         G_SB();
-        int step = step0;
-        for (; step + 1 < step1; step += 2) {
+        // steps always run in pairs (the two LDS buffers are compile-time roles); an odd count is
+        // completed by a step whose B tile reads as zero and so adds nothing
+        for (int step = step0; step < step1; step += 2) {
             run_step(IC<0>{}, step + 2);
             run_step(IC<1>{}, step + 3);
         }
-        if (step < step1) run_step(IC<0>{}, step + 2);
     }
 #undef G_SB
 #undef G_MMA
