@@ -737,23 +737,36 @@ __global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
     }
 }
 
-// dst (bf16) = sum over splits of src (fp32), four elements per thread (count % 4 == 0); blockIdx.y
-// picks the (dst0, src) or (dst1, src + splits * stride) pair: dE and dF in one launch
-__global__ void sum_splits_bf16_kernel(uint16_t* dst0, uint16_t* dst1, const float* src, long count, long stride,
-                                       int splits) {
-    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= count) return;
-    uint16_t* dst = blockIdx.y ? dst1 : dst0;
-    const float* sp = src + (blockIdx.y ? (long)splits * stride : 0) + i;
-    float4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < splits; ++s) {
-        const float4 v = *(const float4*)(sp + (long)s * stride);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+// dE, dF (k x n, bf16) = sum over splits of the tile-ordered fp32 partials of the dE/dF GEMM (layout in
+// flurka_gemm.h).  One thread = four consecutive rows (the four floats of one 16-byte element) of two
+// adjacent columns (two adjacent elements): 32 contiguous bytes per split.  blockIdx.y: dE or dF.
+struct SumSplitsArgs {
+    uint16_t* dst[2];
+    const float* part;
+    int k, n, splits, tilesM, tilesN;
+};
+
+__global__ __launch_bounds__(256) void sum_splits_bf16_kernel(SumSplitsArgs a) {
+    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+    const int half_n = a.n / 2;
+    const int c = 2 * (int)(gid % half_n);
+    const int r0 = 4 * (int)(gid / half_n);
+    if (r0 >= a.k) return;
+    const int which = blockIdx.y;
+    const int tm = r0 / GBM, tn = c / GBN;
+    const int eo = partial_elem_offset(r0 % GBM, c % GBN);
+    float4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < a.splits; ++s) {
+        const float* tp = a.part + partial_tile_index(which, s, tn, tm, a.splits, a.tilesN, a.tilesM) * G_TILE_ELEMS + eo;
+        const float4 x = *(const float4*)tp, y = *(const float4*)(tp + 4);
+        s0.x += x.x; s0.y += x.y; s0.z += x.z; s0.w += x.w;
+        s1.x += y.x; s1.y += y.y; s1.z += y.z; s1.w += y.w;
     }
-    uint2 o;
-    o.x = pack_bf16(acc.x, acc.y);
-    o.y = pack_bf16(acc.z, acc.w);
-    *(uint2*)(dst + i) = o;
+    uint16_t* o = a.dst[which] + (long)r0 * a.n + c;
+    const float v0[4] = {s0.x, s0.y, s0.z, s0.w}, v1[4] = {s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (r0 + e < a.k) *(uint32_t*)(o + (long)e * a.n) = pack_bf16(v0[e], v1[e]);
 }
 
 // ---------------------------------------------------------------------------
@@ -827,7 +840,7 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     const GradEPlan e = grad_e_plan(p);
     W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);        // dK' then dV'
     W.imgT = o;   o += round_up(2 * BH * W.kp * p.d * 2, 256);
-    W.epart = o;  o += round_up(2 * (size_t)e.splits * p.k * p.n * 4, 256);   // dE then dF partials
+    W.epart = o;  o += round_up((size_t)2 * e.splits * e.tilesM * e.tilesN * G_TILE_ELEMS * 4, 256);   // tile-ordered dE, dF partials
     W.total = o;
     return W;
 }
@@ -946,12 +959,11 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         stage_begin(s);
         const GradEPlan e = grad_e_plan(p);
         float* part = (float*)(wsb + W.epart);
-        const long kn = (long)p.k * p.n;
         GemmParams gp{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
         gp.A[0] = img; gp.A[1] = img + img_elems;
         gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
-        gp.C[0] = part; gp.C[1] = part + (long)e.splits * kn;
-        gp.c_split_stride = kn;
+        gp.C[0] = part; gp.C[1] = nullptr;
+        gp.c_split_stride = 0;
         gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
         gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
         gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
@@ -959,8 +971,11 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         if (st != FLURKA_OK) return st;
         stage_end(s, STAGE_K_GRAD_E);
         StageScope sc(s, STAGE_K_SUM_SPLITS);
-        hipLaunchKernelGGL(sum_splits_bf16_kernel, dim3((unsigned)((kn / 4 + 255) / 256), 2), dim3(256), 0, s,
-                           (uint16_t*)a.dE, (uint16_t*)a.dF, (const float*)part, kn, kn, e.splits);
+        SumSplitsArgs sa{};
+        sa.dst[0] = (uint16_t*)a.dE; sa.dst[1] = (uint16_t*)a.dF; sa.part = part;
+        sa.k = p.k; sa.n = p.n; sa.splits = e.splits; sa.tilesM = e.tilesM; sa.tilesN = e.tilesN;
+        const long threads = (long)((p.k + 3) / 4) * (p.n / 2);
+        hipLaunchKernelGGL(sum_splits_bf16_kernel, dim3((unsigned)((threads + 255) / 256), 2), dim3(256), 0, s, sa);
         FLURKA_CHECK_LAUNCH();
     }
     return FLURKA_OK;

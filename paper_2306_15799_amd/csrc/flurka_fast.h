@@ -26,10 +26,10 @@ struct KeyStateBuffers {
     float* cp;             // (BH, mf)
 };
 
-// Sums the projection partials into ctx (K', V'), then fills S, z, c in ctx and the St/zp/cp images.
-// `partials` points at split 0 of the [K' | V'] segments (ctx itself when splits == 1).
+// Sums the projection's tile-ordered split partials (tilesM x tilesN tiles per split and tensor) into
+// ctx (K', V'), then fills S, z, c in ctx and the St/zp/cp images.
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
-                             long split_stride, int splits, const KeyStateBuffers& b, hipStream_t s);
+                             int tilesM, int tilesN, int splits, const KeyStateBuffers& b, hipStream_t s);
 
 // Grid of a kernel whose workgroups split `items` evenly among themselves: as many workgroups as the
 // device keeps resident at once for this block size and LDS use (one round, no tail), at most `items`.

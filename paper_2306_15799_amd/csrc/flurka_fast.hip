@@ -255,18 +255,16 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 
 struct FastWs {
     size_t partial, Kimg, Vimg, nrm, Spart, zpart, cpart, St, zp, cp, total;    // byte offsets
-    size_t split_stride;              // floats between the partial results of consecutive splits
 };
 
 static FastWs fast_ws_layout(const Problem& p) {
     FastWs W{};
-    const CtxLayout L = ctx_layout(p);
     const ProjPlan q = proj_plan(p);
     const KeyStatePlan ks = key_state_plan(p);
     const size_t BH = (size_t)p.BH;
     size_t o = 0;
-    W.split_stride = L.S;             // K' and V' segments of ctx, back to back
-    W.partial = o; o += round_up((q.splits > 1 ? (size_t)q.splits : 0) * W.split_stride * 4, 256);
+    // tile-ordered fp32 partials of K' and V', one set per split
+    W.partial = o; o += round_up((size_t)2 * q.splits * q.tilesM * q.tilesN * G_TILE_ELEMS * 4, 256);
     W.Kimg = o;    o += round_up(p.elu ? 0 : 3 * BH * ks.kpad * p.d * 2, 256);
     W.Vimg = o;    o += round_up(2 * BH * (ks.kpad / 2) * p.d * 4, 256);
     W.nrm = o;     o += round_up(BH * ks.kpad * 4, 256);
@@ -313,10 +311,9 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         GemmParams gp{};
         gp.A[0] = (const uint16_t*)a.E; gp.A[1] = (const uint16_t*)a.F;
         gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
-        float* base = q.splits > 1 ? (float*)(wsb + W.partial) : a.ctx;
-        gp.C[0] = base + L.Kp;
-        gp.C[1] = base + L.Vp;
-        gp.c_split_stride = (long)W.split_stride;
+        gp.C[0] = wsb + W.partial;
+        gp.C[1] = nullptr;
+        gp.c_split_stride = 0;
         gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = p.k;
         gp.tilesM = q.tilesM; gp.tilesN = q.tilesN; gp.splits = q.splits;
         gp.steps_per_split = q.steps_per_split; gp.total_steps = q.total_steps;
@@ -329,8 +326,8 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         kb.Kimg = (uint16_t*)(wsb + W.Kimg); kb.Vimg = (uint32_t*)(wsb + W.Vimg); kb.nrm = (float*)(wsb + W.nrm);
         kb.Spart = (float*)(wsb + W.Spart); kb.zpart = (float*)(wsb + W.zpart); kb.cpart = (float*)(wsb + W.cpart);
         kb.St = (uint16_t*)(wsb + W.St); kb.zp = (float*)(wsb + W.zp); kb.cp = (float*)(wsb + W.cp);
-        const float* partials = proj_splits > 1 ? (const float*)(wsb + W.partial) : a.ctx;
-        st = fast_key_state(p, a.omega, a.ctx, partials, (long)W.split_stride, proj_splits, kb, s);
+        const ProjPlan q = proj_plan(p);
+        st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN, proj_splits, kb, s);
         if (st != FLURKA_OK) return st;
     }
     {

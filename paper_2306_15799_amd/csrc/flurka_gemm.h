@@ -2,9 +2,9 @@
 // of FLuRKA attention.  What differs between them (where the operands live, how a reduction step
 // maps to addresses, where the result goes) is supplied by a policy type:
 //
-//   ProjPolicy<D>   K' = E K, V' = F V          A = E rows, B = X (positions x columns, transposed on
-//                                               the way into LDS), fp32 split partials
-//   GradXPolicy<D>  dK = E^T dK', dV = F^T dV'  A = (dK')^T image rows, B = E (same transposing path),
+//   ProjPolicy<D>   K' = E K, V' = F V          A = E rows, B = X (positions x columns, read out of LDS
+//                                               with transposing loads), fp32 split partials
+//   GradXPolicy<D>  dK = E^T dK', dV = F^T dV'  A = (dK')^T image rows, B = E (same path as X above),
 //                                               bf16 result stored transposed into (B,H,n,d)
 //   GradEPolicy<D>  dE = sum_bh dK' K^T         A = dK' image rows, B = K rows (both contiguous along
 //                                               the reduction), fp32 split partials
@@ -35,11 +35,29 @@ static_assert(GB_STAGE_T <= GB_STAGE_D, "B stage");
 constexpr int G_LDS = 2 * G_STAGE;                  // 147,456
 constexpr int G_OOB = 0x7fffff00;                   // per-thread byte offset past any descriptor range
 
+// fp32 partial results of a split reduction are kept tile by tile in the order the accumulators
+// hold them, so that every store is 16 bytes per lane and 1 KiB per wavefront, with no bounds to check
+// (whole tiles are allocated).  Tile t of (which, split, column tile, row tile) starts at
+// partial_tile_index(...) * G_TILE_ELEMS floats; inside it element (r, c) of the 256 x 256 tile sits at
+// partial_elem_offset(r, c): [wavefront 2*(r/128) + c/128][i = r/32 % 4][j = c/32 % 4][q = r/8 % 4]
+// [lane = 32*(r/4 % 2) + c%32][e = r%4].
+constexpr int G_TILE_ELEMS = 256 * 256;
+__host__ __device__ inline long partial_tile_index(int which, int split, int tn, int tm, int splits, int tilesN,
+                                                   int tilesM) {
+    return (((long)which * splits + split) * tilesN + tn) * tilesM + tm;
+}
+__host__ __device__ inline int partial_elem_offset(int r, int c) {
+    const int wave = 2 * (r >> 7) + (c >> 7), i = (r >> 5) & 3, j = (c >> 5) & 3, q = (r >> 3) & 3;
+    const int lane = 32 * ((r >> 2) & 1) + (c & 31), e = r & 3;
+    return ((((wave * 4 + i) * 4 + j) * 4 + q) * 64 + lane) * 4 + e;
+}
+
 struct GemmParams {
     const uint16_t* A[2];
     const uint16_t* B[2];
-    void* C[2];
-    long c_split_stride;     // elements between the outputs of consecutive splits
+    void* C[2];              // result tensors (policies that store final results); C[0] = partial buffer
+                             // for policies with PARTIAL_TILES
+    long c_split_stride;     // unused with PARTIAL_TILES
     int tilesM, tilesN, splits, steps_per_split, total_steps;
     int n, d, k, BH, kp;     // problem sizes the policies need (kp: padded k of an image)
 };
@@ -227,20 +245,36 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 #undef G_LDB
 
     // epilogue: this lane holds, for every 32 x 32 tile (i, j), column 32*j + l32 and rows
-    // 32*i + 8*q + 4*half + {0..3}, q = 0..3; groups q and q + 1 are handed over together so that a
-    // policy may join the two halves of a wavefront into 8 consecutive rows per lane
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int col = n0 + wn * 128 + 32 * j + l32;
+    // 32*i + 8*q + 4*half + {0..3}, q = 0..3
+    if constexpr (Pol::PARTIAL_TILES) {
+        float* tp = (float*)g.C[0] + partial_tile_index(which, split, tn, tm, g.splits, g.tilesN, g.tilesM) * G_TILE_ELEMS +
+                    (long)wave * (16 * 4 * 256) + lane * 4;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; q += 2) {
-                const int row = m0 + wm * 128 + 32 * i + 8 * q;
-                const float ev[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                const float od[4] = {acc[i][j][4 * q + 4], acc[i][j][4 * q + 5], acc[i][j][4 * q + 6], acc[i][j][4 * q + 7]};
-                Pol::store_groups(g, pc, which, split, row, half, col, ev, od);
-            }
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float4 v;
+                    v.x = acc[i][j][4 * q]; v.y = acc[i][j][4 * q + 1]; v.z = acc[i][j][4 * q + 2]; v.w = acc[i][j][4 * q + 3];
+                    *(float4*)(tp + ((i * 4 + j) * 4 + q) * 256) = v;
+                }
+    } else {
+        // groups q and q + 1 are handed over together so that a policy may join the two halves of a
+        // wavefront into 8 consecutive rows per lane
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = n0 + wn * 128 + 32 * j + l32;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; q += 2) {
+                    const int row = m0 + wm * 128 + 32 * i + 8 * q;
+                    const float ev[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    const float od[4] = {acc[i][j][4 * q + 4], acc[i][j][4 * q + 5], acc[i][j][4 * q + 6], acc[i][j][4 * q + 7]};
+                    Pol::store_groups(g, pc, which, split, row, half, col, ev, od);
+                }
+        }
     }
 }
 
@@ -264,6 +298,7 @@ struct PolicyCtxBase {
 template <int D>
 struct ProjPolicy {
     static constexpr bool B_TRANSPOSE = true;
+    static constexpr bool PARTIAL_TILES = true;
     struct Ctx : PolicyCtxBase { int bh0; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -282,20 +317,6 @@ struct ProjPolicy {
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
     static __device__ __forceinline__ int b_soff(const Ctx&, int step) { return step * (GBK * D * 2); }
-    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx& c, int which, int split,
-                                                        int row, int half, int col, const float (&ev)[4],
-                                                        const float (&od)[4]) {
-        const int cl = col % GBN;
-        const int bh = c.bh0 + cl / D;
-        if (bh >= g.BH) return;
-        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + ((long)bh * g.k) * D + (cl % D);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int r0 = row + 4 * half + e, r1 = r0 + 8;
-            if (r0 < g.k) o[(long)r0 * D] = ev[e];
-            if (r1 < g.k) o[(long)r1 * D] = od[e];
-        }
-    }
 };
 
 // dX = E^T dX': rows = (head, t) of the (BH*D x kp) image of (dX')^T, columns = sequence positions,
@@ -303,6 +324,7 @@ struct ProjPolicy {
 template <int D>
 struct GradXPolicy {
     static constexpr bool B_TRANSPOSE = true;
+    static constexpr bool PARTIAL_TILES = false;
     struct Ctx : PolicyCtxBase {};
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -336,6 +358,7 @@ struct GradXPolicy {
 template <int D>
 struct GradEPolicy {
     static constexpr bool B_TRANSPOSE = false;
+    static constexpr bool PARTIAL_TILES = true;
     struct Ctx : PolicyCtxBase { int a_batch, b_batch; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -356,18 +379,6 @@ struct GradEPolicy {
     static __device__ __forceinline__ int b_soff(const Ctx& c, int step) {
         constexpr int spb = D / GBK;
         return (step / spb) * c.b_batch + (step % spb) * (GBK * 2);
-    }
-    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx&, int which, int split,
-                                                        int row, int half, int col, const float (&ev)[4],
-                                                        const float (&od)[4]) {
-        if (col >= g.n) return;
-        float* o = (float*)g.C[which] + (long)split * g.c_split_stride + col;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int r0 = row + 4 * half + e, r1 = r0 + 8;
-            if (r0 < g.k) o[(long)r0 * g.n] = ev[e];
-            if (r1 < g.k) o[(long)r1 * g.n] = od[e];
-        }
     }
 };
 

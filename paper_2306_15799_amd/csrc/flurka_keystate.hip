@@ -16,6 +16,7 @@
 //   merge_pack    joins the key ranges (log-sum-exp style), writes S, z, c (fp32, ctx) and the bf16
 //                 images the query-stream kernel loads into LDS
 #include "flurka_fast.h"
+#include "flurka_gemm.h"
 
 namespace flurka {
 
@@ -39,83 +40,78 @@ __device__ __forceinline__ void split2(float x, uint16_t& hi, uint16_t& lo) {
 }
 
 // ---------------------------------------------------------------------------
-// proj_finish: one thread per (head, pair of keys (2p, 2p+1), four consecutive coordinates t); the
-// d/4 threads of a pair are consecutive lanes (d/4 divides 64), so |k'|^2 is a short shuffle reduction.
+// proj_finish: one wavefront per (head, four consecutive keys 4g .. 4g+3); lane = coordinate t (and
+// t + 64 for d = 128).  The four keys are the four floats of one 16-byte element of the projection's
+// tile-ordered partial results, and consecutive t are consecutive elements: coalesced float4 loads.
 // ---------------------------------------------------------------------------
 struct FinishArgs {
-    const float* part;      // split 0 of [K' segment | V' segment]; split s at + s * split_stride
+    const float* part;      // tile-ordered split partials of the projection (see flurka_gemm.h)
     float* ctx;             // K' at ctx + Kp_off, V' at ctx + Vp_off
-    long split_stride, Kp_off, Vp_off;
+    long Kp_off, Vp_off;
     uint16_t* Kimg;         // 3 x (BH, kpad, d) bf16: hi, mid, lo      (nullptr for elu1)
     uint32_t* Vimg;         // 2 x (BH, kpad/2, d) dwords: hi, lo; low half = even key
     float* nrm;             // (BH, kpad): |k'|^2/2, +inf for the padding keys (nullptr for elu1)
-    int splits, k, kpad, d, BH;
+    int splits, tilesM, tilesN, k, kpad, d, BH;
 };
 
 __global__ __launch_bounds__(256) void proj_finish_kernel(FinishArgs a) {
-    const int tpp = a.d / 4;                                   // threads per pair: 16 or 32
-    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-    const long pair = gid / tpp;
-    const int t = 4 * (int)(gid % tpp);
-    const int pairs_per_head = a.kpad / 2;
-    if (pair >= (long)a.BH * pairs_per_head) return;           // whole pairs only: no partial shuffle groups
-    const int bh = (int)(pair / pairs_per_head);
-    const int p = (int)(pair % pairs_per_head);
+    const int lane = threadIdx.x & 63;
+    const long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int groups_per_head = a.kpad / 4;
+    if (wid >= (long)a.BH * groups_per_head) return;
+    const int bh = (int)(wid / groups_per_head);
+    const int r0 = 4 * (int)(wid % groups_per_head);           // keys r0 .. r0 + 3
+    const int hpt = GBN / a.d;                                  // heads per column tile
+    const int tn = bh / hpt, tm = r0 / GBM;
     const long img_plane = (long)a.BH * a.kpad * a.d;          // elements per K image plane
-    const long vimg_plane = (long)a.BH * pairs_per_head * a.d;
-    float4 kv[2], vv[2];
-    float sq[2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int r = 2 * p + e;
+    const long vimg_plane = (long)a.BH * (a.kpad / 2) * a.d;
+    float sq[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int t = lane; t < a.d; t += 64) {
+        const int eo = partial_elem_offset(r0 % GBM, (bh % hpt) * a.d + t);
         float4 ks = {0.f, 0.f, 0.f, 0.f}, vs = {0.f, 0.f, 0.f, 0.f};
-        if (r < a.k) {
-            const long off = ((long)bh * a.k + r) * a.d + t;
-            for (int s = 0; s < a.splits; ++s) {
-                const float4 x = *(const float4*)(a.part + (long)s * a.split_stride + a.Kp_off + off);
-                const float4 y = *(const float4*)(a.part + (long)s * a.split_stride + a.Vp_off + off);
-                ks.x += x.x; ks.y += x.y; ks.z += x.z; ks.w += x.w;
-                vs.x += y.x; vs.y += y.y; vs.z += y.z; vs.w += y.w;
+        for (int s = 0; s < a.splits; ++s) {
+            const float4 x = *(const float4*)(a.part + partial_tile_index(0, s, tn, tm, a.splits, a.tilesN, a.tilesM) * G_TILE_ELEMS + eo);
+            const float4 y = *(const float4*)(a.part + partial_tile_index(1, s, tn, tm, a.splits, a.tilesN, a.tilesM) * G_TILE_ELEMS + eo);
+            ks.x += x.x; ks.y += x.y; ks.z += x.z; ks.w += x.w;
+            vs.x += y.x; vs.y += y.y; vs.z += y.z; vs.w += y.w;
+        }
+        float kv[4] = {ks.x, ks.y, ks.z, ks.w}, vv[4] = {vs.x, vs.y, vs.z, vs.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r = r0 + e;
+            if (r < a.k) {
+                const long off = ((long)bh * a.k + r) * a.d + t;
+                a.ctx[a.Kp_off + off] = kv[e];
+                a.ctx[a.Vp_off + off] = vv[e];
+            } else {
+                kv[e] = 0.f; vv[e] = 0.f;                      // rows of a tile past k hold nothing useful
             }
-            *(float4*)(a.ctx + a.Kp_off + off) = ks;
-            *(float4*)(a.ctx + a.Vp_off + off) = vs;
+            sq[e] = fmaf(kv[e], kv[e], sq[e]);
+            if (a.Kimg) {
+                uint16_t hi, mid, lo;
+                split3(kv[e], hi, mid, lo);
+                const long io = ((long)bh * a.kpad + r) * a.d + t;
+                a.Kimg[io] = hi;
+                a.Kimg[img_plane + io] = mid;
+                a.Kimg[2 * img_plane + io] = lo;
+            }
         }
-        kv[e] = ks; vv[e] = vs;
-        sq[e] = fmaf(ks.x, ks.x, fmaf(ks.y, ks.y, fmaf(ks.z, ks.z, ks.w * ks.w)));
-        if (a.Kimg) {
-            const float x[4] = {ks.x, ks.y, ks.z, ks.w};
-            uint16_t hi[4], mid[4], lo[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) split3(x[i], hi[i], mid[i], lo[i]);
-            const long io = ((long)bh * a.kpad + r) * a.d + t;
-            *(uint2*)(a.Kimg + io) = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-            *(uint2*)(a.Kimg + img_plane + io) = make_uint2((uint32_t)mid[0] | ((uint32_t)mid[1] << 16), (uint32_t)mid[2] | ((uint32_t)mid[3] << 16));
-            *(uint2*)(a.Kimg + 2 * img_plane + io) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
-        }
-    }
-    {
-        const float v0[4] = {vv[0].x, vv[0].y, vv[0].z, vv[0].w};
-        const float v1[4] = {vv[1].x, vv[1].y, vv[1].z, vv[1].w};
-        uint32_t h[4], l[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int pr = 0; pr < 2; ++pr) {
             uint16_t h0, l0, h1, l1;
-            split2(v0[i], h0, l0);
-            split2(v1[i], h1, l1);
-            h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            split2(vv[2 * pr], h0, l0);
+            split2(vv[2 * pr + 1], h1, l1);
+            const long vo = ((long)bh * (a.kpad / 2) + r0 / 2 + pr) * a.d + t;
+            a.Vimg[vo] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            a.Vimg[vimg_plane + vo] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
-        const long vo = ((long)bh * pairs_per_head + p) * a.d + t;
-        *(uint4*)(a.Vimg + vo) = make_uint4(h[0], h[1], h[2], h[3]);
-        *(uint4*)(a.Vimg + vimg_plane + vo) = make_uint4(l[0], l[1], l[2], l[3]);
     }
     if (a.nrm) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            float tot = sq[e];
-            for (int o = tpp / 2; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
-            const int r = 2 * p + e;
-            if (t == 0) a.nrm[(long)bh * a.kpad + r] = r < a.k ? 0.5f * tot : INFINITY;
+        for (int e = 0; e < 4; ++e) {
+            const float tot = wave_sum(sq[e]);
+            const int r = r0 + e;
+            if (lane == 0) a.nrm[(long)bh * a.kpad + r] = r < a.k ? 0.5f * tot : INFINITY;
         }
     }
 }
@@ -389,18 +385,18 @@ static flurka_status launch_key_state(const Problem& p, const KeyStateArgs& ka, 
 }
 
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
-                             long split_stride, int splits, const KeyStateBuffers& b, hipStream_t s) {
+                             int tilesM, int tilesN, int splits, const KeyStateBuffers& b, hipStream_t s) {
     const CtxLayout L = ctx_layout(p);
     const KeyStatePlan q = key_state_plan(p);
     {
         StageScope sc(s, STAGE_K_PROJ_FINISH);
         FinishArgs fa{};
-        fa.part = partials; fa.ctx = ctx; fa.split_stride = split_stride;
+        fa.part = partials; fa.ctx = ctx; fa.tilesM = tilesM; fa.tilesN = tilesN;
         fa.Kp_off = (long)L.Kp; fa.Vp_off = (long)L.Vp;
         fa.Kimg = p.elu ? nullptr : b.Kimg; fa.Vimg = b.Vimg; fa.nrm = p.elu ? nullptr : b.nrm;
         fa.splits = splits; fa.k = p.k; fa.kpad = q.kpad; fa.d = p.d; fa.BH = p.BH;
-        const long threads = (long)p.BH * (q.kpad / 2) * (p.d / 4);
-        hipLaunchKernelGGL(proj_finish_kernel, grid1d(threads, 256), dim3(256), 0, s, fa);
+        const long waves = (long)p.BH * (q.kpad / 4);
+        hipLaunchKernelGGL(proj_finish_kernel, grid1d(waves, 4), dim3(256), 0, s, fa);
         FLURKA_CHECK_LAUNCH();
     }
     {
