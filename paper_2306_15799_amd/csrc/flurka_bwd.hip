@@ -289,7 +289,7 @@ struct BwdYArgs {
     int BH, H, n, mf, FT, R, tiles_per_range;
 };
 
-// A workgroup is four wavefronts = four feature tiles of one (head, query range).  They need the same
+// A workgroup is NW wavefronts = NW feature tiles of one (head, query range).  They need the same
 // Q rows (A operand of u = Q omega^T) and the same dOut rows (B operand of dS = W^T dOut, contraction
 // over queries), so blocks of Y_ST 32-query tiles are loaded once per workgroup with 16-byte loads and
 // kept in LDS row-major.  The B operand needs, per lane, one column t of dOut for 8 query rows: that is
@@ -314,14 +314,15 @@ __device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p) {
     return __builtin_bit_cast(uint2, v);
 }
 
-template <int D>
-__global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
     using L = BwdYLds<D>;
     constexpr int QP = L::q_pitch, GP = L::g_pitch, ROWS = L::rows;
     constexpr int CPR = D / 8;                 // 16-byte chunks per row
-    constexpr int LPT = ROWS * CPR / 256;      // 16-byte loads per thread per tensor per block
-    static_assert(2 * ROWS <= 256 && (ROWS * CPR) % 256 == 0, "one lambda or g value per thread");
+    constexpr int NT = NW * 64;
+    constexpr int LPT = ROWS * CPR / NT;       // 16-byte loads per thread per tensor per block
+    static_assert(2 * ROWS <= NT && (ROWS * CPR) % NT == 0, "one lambda or g value per thread");
     extern __shared__ __attribute__((aligned(16))) unsigned char sm[];
     unsigned char* qs = sm;
     unsigned char* gs = sm + ROWS * QP;
@@ -329,12 +330,12 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     float* ld = ll + ROWS;                     // g_i
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int FG = (a.FT + 3) / 4;
+    const int FG = (a.FT + NW - 1) / NW;
     int id = blockIdx.x;
     const int fg = id % FG; id /= FG;
     const int r = id % a.R;
     const int bh = id / a.R;
-    const int ft = 4 * fg + wave;
+    const int ft = NW * fg + wave;
     const bool active = ft < a.FT;
     const int ftc = active ? ft : a.FT - 1;
     const int QTn = a.n / 32;
@@ -362,7 +363,7 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     auto load_block = [&](int qt) {
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
-            const int chunk = tid + 256 * u;
+            const int chunk = tid + NT * u;
             int row = 32 * qt + chunk / CPR;
             if (row > row_last) row = row_last;
             const long off = head_off + (long)row * D + 8 * (chunk % CPR);
@@ -378,7 +379,7 @@ __global__ __launch_bounds__(256) void bwd_query_y_kernel(BwdYArgs a) {
     auto store_block = [&]() {
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
-            const int chunk = tid + 256 * u;
+            const int chunk = tid + NT * u;
             const int row = chunk / CPR, c = chunk % CPR;
             *(uint4*)(qs + row * QP + 16 * c) = rq[u];
             *(uint4*)(gs + row * GP + 16 * c) = rg[u];
@@ -802,17 +803,21 @@ static GradEPlan grad_e_plan(const Problem& p) {
     return q;
 }
 
-struct BwdYPlan { int FT, R, tiles_per_range; };
+struct BwdYPlan { int FT, NW, R, tiles_per_range; };
 
 static BwdYPlan bwd_y_plan(const Problem& p) {
     BwdYPlan q;
     q.FT = p.mf / 32;
+    q.NW = q.FT > 4 ? 8 : 4;                      // wavefronts (= feature tiles) per workgroup
     const int QT = p.n / 32;
-    // enough wavefronts to fill the chip several times over, ranges of at least 8 query tiles
-    int R = (4096 + p.BH * q.FT - 1) / (p.BH * q.FT);
-    if (R > QT / 8) R = QT / 8;
+    const int FG = (q.FT + q.NW - 1) / q.NW;
+    // one round of workgroups: the chip holds one 8-wavefront or two 4-wavefront workgroups per
+    // compute unit; ranges are whole staged blocks of query tiles
+    const int slots = 256 * (q.NW == 8 ? 1 : 2);
+    int R = slots / (p.BH * FG);
+    if (R > QT / Y_ST) R = QT / Y_ST;
     if (R < 1) R = 1;
-    q.tiles_per_range = ((QT + R - 1) / R + Y_ST - 1) / Y_ST * Y_ST;     // whole staged blocks
+    q.tiles_per_range = ((QT + R - 1) / R + Y_ST - 1) / Y_ST * Y_ST;
     q.R = (QT + q.tiles_per_range - 1) / q.tiles_per_range;
     return q;
 }
@@ -903,14 +908,20 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ya.omega_head_stride = omega_stride;
         ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
         ya.tiles_per_range = y.tiles_per_range;
-        const unsigned ygrid = (unsigned)((long)p.BH * y.R * ((y.FT + 3) / 4));
+        const unsigned ygrid = (unsigned)((long)p.BH * y.R * ((y.FT + y.NW - 1) / y.NW));
         stage_begin(s);
         const int ylds = p.d == 64 ? BwdYLds<64>::total : BwdYLds<128>::total;
-        const void* yk = p.d == 64 ? (const void*)bwd_query_y_kernel<64> : (const void*)bwd_query_y_kernel<128>;
+        const void* yk = p.d == 64 ? (y.NW == 8 ? (const void*)bwd_query_y_kernel<64, 8> : (const void*)bwd_query_y_kernel<64, 4>)
+                                   : (y.NW == 8 ? (const void*)bwd_query_y_kernel<128, 8> : (const void*)bwd_query_y_kernel<128, 4>);
         if (hipFuncSetAttribute(yk, hipFuncAttributeMaxDynamicSharedMemorySize, ylds) != hipSuccess)
             return FLURKA_ERR_LAUNCH;
-        if (p.d == 64) hipLaunchKernelGGL(bwd_query_y_kernel<64>, dim3(ygrid), dim3(256), ylds, s, ya);
-        else           hipLaunchKernelGGL(bwd_query_y_kernel<128>, dim3(ygrid), dim3(256), ylds, s, ya);
+        if (p.d == 64) {
+            if (y.NW == 8) hipLaunchKernelGGL((bwd_query_y_kernel<64, 8>), dim3(ygrid), dim3(512), ylds, s, ya);
+            else           hipLaunchKernelGGL((bwd_query_y_kernel<64, 4>), dim3(ygrid), dim3(256), ylds, s, ya);
+        } else {
+            if (y.NW == 8) hipLaunchKernelGGL((bwd_query_y_kernel<128, 8>), dim3(ygrid), dim3(512), ylds, s, ya);
+            else           hipLaunchKernelGGL((bwd_query_y_kernel<128, 4>), dim3(ygrid), dim3(256), ylds, s, ya);
+        }
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_Y);
     }
