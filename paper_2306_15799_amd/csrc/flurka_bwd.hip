@@ -524,7 +524,7 @@ struct BwdKeyLds {
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void bwd_key_kernel(BwdKeyArgs a) {
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
