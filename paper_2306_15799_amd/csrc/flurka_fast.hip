@@ -2,13 +2,15 @@
 //
 //   stage "project"      K' = E K, V' = F V     split-n GEMM on v_mfma_f32_32x32x16_bf16,
 //                                               fp32 partial sums, deterministic second-stage sum
-//   stage "key_state"    PhiK, S, z             fp32 kernels shared with the generic path (K' must stay
-//                                               fp32 into the exponent: exp() turns absolute error in
-//                                               omega.k' - |k'|^2/2 into relative error of the weights)
+//   stage "key_state"    PhiK, S, z             bf16 MFMA with split-precision operands
+//                                               (flurka_keystate.hip): K' enters the exponent as three
+//                                               bf16 terms, because exp() turns absolute error in
+//                                               omega.k' - |k'|^2/2 into relative error of the weights
 //   stage "query_stream" out = (P S) / (P z)    per 32 query rows of a wavefront:
 //                                               U^T = omega Q^T (MFMA) -> running row max -> exp ->
 //                                               bf16 P^T kept in registers as the B operand of
-//                                               N^T = S^T P^T (MFMA); the denominator on the VALU
+//                                               N^T = S^T P^T (MFMA); the denominator on the VALU;
+//                                               out and the log-denominator per row are stored
 // Formulas: Eq. 2 with the App. D row normaliser; feature maps of Sec. 2, "Kernel Methods".
 #include "flurka_fast.h"
 #include "flurka_gemm.h"

@@ -11,12 +11,15 @@
 //
 // Structure (one wavefront per SIMD, 4 per workgroup, wave tile 128 x 128 = 4 x 4 MFMA tiles, so all
 // latency hiding happens inside one instruction stream): a 64-deep step is four 16-deep sub-steps of
-// 16 MFMAs.  While sub-step s multiplies, the fragments of sub-step s+1 are read from LDS into the
-// other register set.  Global data runs two steps ahead in registers: sub-step 0 issues the loads of
-// step + 2, sub-step 2 writes step + 1 into the other LDS buffer, then the single barrier of the step,
-// and sub-step 3 already prefetches from that buffer.  sched_barrier(0) after each "2 MFMA + few
-// others" group pins this order.  The last two steps fetch and store tiles nobody uses; that keeps
-// the loop body free of branches, which the 256 accumulator registers do not survive well.
+// 16 MFMAs, i.e. 32 chunks of "2 MFMAs + one LDS fragment read".  While sub-step s multiplies, the
+// fragments of sub-step s+1 are read from LDS into the other fragment register set.  Global data runs
+// two steps ahead through ONE set of 16 staging registers reused in place: register j requests its
+// part of the tile in even chunk 2j and stores it to LDS 25 chunks later (an odd chunk), after which
+// it is free for its next request; so requests and LDS stores are spread evenly over the step instead
+// of arriving in bursts that fill the address FIFOs.  One barrier per step, before sub-step 3, which
+// already prefetches fragments from the other buffer.  sched_barrier(0) after each chunk pins this
+// order.  The last two steps fetch and store tiles nobody uses; that keeps the loop body free of
+// branches, which the 256 accumulator registers do not survive well.
 #pragma once
 
 #include "flurka_mfma.h"
