@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import flurka_oracle as fo
+from paper_2306_15799_amd import binding as fb
 from paper_2306_15799_amd import inputs
 
 import gpu_util as gu
@@ -42,3 +43,22 @@ def test_c5_forward_backward():
     w = inputs.WORKLOADS["C5"]
     errs = gu.check_forward_backward(w, seed=0, algo="auto")
     print("C5", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_every_output_row_is_a_weighted_mean_of_projected_values(name):
+    """Property that holds at any size, checked on ALL rows of the sampled-parity workloads: the weights
+    phi(q).phi(k'_r) are positive, so each out[b,h,i,:] lies inside the per-coordinate range of the rows
+    of V'[b,h] (up to bf16 rounding of out), and the stored log-denominators are finite."""
+    w = inputs.WORKLOADS[name]
+    t = inputs.make_inputs(w, seed=0)
+    g, out, ctx = gu.run_forward(w, t, "auto")
+    m_eff = w.d if w.phi == "elu1" else w.m
+    v = fb.ctx_views(ctx, w.B, w.H, w.n, w.d, w.k, m_eff, fb.BF16, w.phi)
+    lo = v["Vp"].amin(dim=2, keepdim=True)
+    hi = v["Vp"].amax(dim=2, keepdim=True)
+    o = out.float()
+    slack = 2.0 ** -7 * torch.maximum(lo.abs(), hi.abs()) + 1e-6
+    assert torch.isfinite(o).all()
+    assert bool(((o >= lo - slack) & (o <= hi + slack)).all())
+    assert torch.isfinite(v["lse"]).all()

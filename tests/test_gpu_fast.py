@@ -127,3 +127,35 @@ def test_backward_is_deterministic():
     b = gu.run_backward(w, g, out, ctx, "fast")
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+# ---- scratch independence ------------------------------------------------------------------
+@pytest.mark.parametrize("algo", ["fast", "generic"])
+def test_results_do_not_depend_on_what_the_scratch_buffers_held(algo):
+    """ctx, workspace and the result tensors are filled with NaN bit patterns (0xFF bytes) before the
+    calls: every byte a kernel reads must have been written by an earlier kernel of the same call.
+    Shape with ragged k (tile rows past k), ragged heads per projection tile and an odd step count."""
+    w = Workload("poison", 1, 3, 192, 64, 100, 96, "bf16", PHI_PERFORMER, True)
+    t = inputs.make_inputs(w, 21)
+    g = gu.to_device(t, w.dtype)
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    dev = g["Q"].device
+
+    def run(fill):
+        ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, fb.BF16, w.phi), dev).fill_(fill)
+        wf = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_FWD, algo), dev).fill_(fill)
+        wb = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_BWD, algo), dev).fill_(fill)
+        out = torch.empty_like(g["Q"]).view(torch.uint8).fill_(fill).view(torch.bfloat16).view(g["Q"].shape)
+        fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, algo=algo,
+                           out=out, ctx=ctx, workspace=wf)
+        grads = tuple(torch.empty_like(x).view(torch.uint8).fill_(fill).view(torch.bfloat16).view(x.shape)
+                      for x in (g["Q"], g["K"], g["V"], g["E"], g["F"]))
+        fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, g["dOut"], ctx,
+                           phi=w.phi, algo=algo, workspace=wb, grads=grads)
+        torch.cuda.synchronize()
+        return (out,) + grads
+
+    clean, dirty = run(0), run(0xFF)
+    for name, a, b in zip(["out", "dQ", "dK", "dV", "dE", "dF"], clean, dirty):
+        assert torch.isfinite(b.float()).all(), name
+        assert torch.equal(a, b), name
