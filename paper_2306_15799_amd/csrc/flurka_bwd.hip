@@ -101,11 +101,14 @@ template <int D>
 struct BwdXLds {
     static constexpr int w_pitch = (D + 8) * 2;                          // rows of length d
     static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }   // rows of length mf
-    static __host__ __device__ int total(int mf) { return 2 * mf * w_pitch + D * s_pitch(mf) + mf * 8; }
+    static __host__ __device__ int images(int mf) { return 2 * mf * w_pitch + D * s_pitch(mf) + mf * 8; }
+    static constexpr int scratch = 32 * D * 2;                           // per wavefront: one 32-row tile
+    static __host__ __device__ int total(int mf);
 };
 
 constexpr int X_NW = 12;                 // wavefronts per workgroup (three per SIMD)
-constexpr bool X_PREFETCH = false;       // request the next tile's rows a whole tile ahead
+template <int D>
+__host__ __device__ int BwdXLds<D>::total(int mf) { return images(mf) + X_NW * scratch; }
 
 template <int D>
 __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
@@ -162,25 +165,46 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
 
     // One tile = this lane's query row: Q as the B operand of u^T (8 consecutive d per step), dOut as
     // the B operand of S G^T (slots (h, j) of step s hold t = 16*s + 8*(j/4) + 4*h + j%4), the same
-    // elements of out (for g_i) and lambda_i.  The next tile is requested before this one is worked on.
+    // elements of out (for g_i) and lambda_i.
+    // Tiles move between memory and a wavefront-private 32 x D area of LDS as whole 16-byte chunks in
+    // memory order (32 rows are one contiguous block: every wavefront instruction covers 1 KiB of
+    // consecutive bytes), and between LDS and registers in the per-lane operand layouts.  Chunk c of
+    // row r sits at chunk position c ^ ((r >> 1) & 7): conflict-free both ways.  (n is a multiple of 32
+    // on this path, so tiles are always whole.)
+    constexpr int CPR = D / 8, ROWB = D * 2, LPT = 32 * CPR / 64;
+    unsigned char* const scr = lds + L::images(mf) + wave * L::scratch;
+    auto scr_at = [&](int row, int c) -> unsigned char* { return scr + row * ROWB + 16 * (c ^ ((row >> 1) & 7)); };
     struct Tile { uint4 q[KS], g[KS], o[KS]; float lam; };
     auto load_tile = [&](int row0, Tile& t) {
-        int r = row0 + l32;
-        if (r >= a.n) r = a.n - 1;
-        const uint16_t* qg = a.Q + head_off + (long)r * D + 8 * half;
-        const uint16_t* gg = a.G + head_off + (long)r * D + 4 * half;
-        const uint16_t* og = a.O + head_off + (long)r * D + 4 * half;
+        const long off = head_off + (long)row0 * D + 8 * lane;
+        uint4 xq[LPT], xg[LPT], xo[LPT];
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+            xq[u] = ld16(a.Q + off + 512 * u);
+            xg[u] = ld16(a.G + off + 512 * u);
+            xo[u] = ld16(a.O + off + 512 * u);
+        }
+        t.lam = a.lse[(long)bh * a.n + row0 + l32];
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = xq[u];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) t.q[s] = *(const uint4*)scr_at(l32, 2 * s + half);
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = xg[u];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            t.q[s] = ld16(qg + 16 * s);
-            const uint2 g0 = *(const uint2*)(gg + 16 * s);
-            const uint2 g1 = *(const uint2*)(gg + 16 * s + 8);
+            const uint2 g0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
+            const uint2 g1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
             t.g[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
-            const uint2 o0 = *(const uint2*)(og + 16 * s);
-            const uint2 o1 = *(const uint2*)(og + 16 * s + 8);
+        }
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = xo[u];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const uint2 o0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
+            const uint2 o1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
             t.o[s] = make_uint4(o0.x, o0.y, o1.x, o1.y);
         }
-        t.lam = a.lse[(long)bh * a.n + r];
     };
     auto dot2 = [](uint32_t x, uint32_t y, float acc) {
         acc = fmaf(bf16_to_f32((uint16_t)(x & 0xffffu)), bf16_to_f32((uint16_t)(y & 0xffffu)), acc);
@@ -188,13 +212,10 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
     };
 
     const int row_first = row_begin + 32 * wave;
-    Tile cur, nxt;
-    if (X_PREFETCH && row_first < row_end) load_tile(row_first, cur);
+    Tile cur;
     for (int row0 = row_first; row0 < row_end; row0 += 32 * X_NW) {
         const int qrow = row0 + l32;
-        const bool valid = qrow < a.n;
-        if (!X_PREFETCH) load_tile(row0, cur);
-        else if (row0 + 32 * X_NW < row_end) load_tile(row0 + 32 * X_NW, nxt);
+        load_tile(row0, cur);
 
         // g_i = G_i . out_i: the two halves of the wavefront hold complementary elements of the row
         float gdot = 0.f;
@@ -206,7 +227,7 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
             gdot = dot2(cur.g[s].w, cur.o[s].w, gdot);
         }
         const float gi = half_sum(gdot);
-        if (valid && half == 0) a.delta[(long)bh * a.n + qrow] = gi;
+        if (half == 0) a.delta[(long)bh * a.n + qrow] = gi;
 
         // dU^T tile by tile, dQ^T = omega^T dU^T
         floatx16 accQ[TT];
@@ -254,21 +275,24 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
                 accQ[t] = mfma32(*(const uint4*)(wp + 32), db1, accQ[t]);
             }
         }
-        if (valid) {
-            uint16_t* og = a.dQ + head_off + (long)qrow * D;
+        // dQ rows through the transposition area: 16-byte pieces in, whole chunks in memory order out
 #pragma unroll
-            for (int t = 0; t < TT; ++t)
+        for (int t = 0; t < TT; ++t)
 #pragma unroll
-                for (int q = 0; q < 4; q += 2) {
-                    uint2 ev, od;
-                    ev.x = pack_bf16(accQ[t][4 * q], accQ[t][4 * q + 1]);
-                    ev.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
-                    od.x = pack_bf16(accQ[t][4 * q + 4], accQ[t][4 * q + 5]);
-                    od.y = pack_bf16(accQ[t][4 * q + 6], accQ[t][4 * q + 7]);
-                    *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
-                }
+            for (int q = 0; q < 4; q += 2) {
+                uint2 ev, od;
+                ev.x = pack_bf16(accQ[t][4 * q], accQ[t][4 * q + 1]);
+                ev.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
+                od.x = pack_bf16(accQ[t][4 * q + 4], accQ[t][4 * q + 5]);
+                od.y = pack_bf16(accQ[t][4 * q + 6], accQ[t][4 * q + 7]);
+                *(uint4*)scr_at(l32, 4 * t + q + half) = join_halves(ev, od);
+            }
+        {
+            uint16_t* ob = a.dQ + head_off + (long)row0 * D + 8 * lane;
+#pragma unroll
+            for (int u = 0; u < LPT; ++u)
+                *(uint4*)(ob + 512 * u) = *(const uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR);
         }
-        if (X_PREFETCH) cur = nxt;
     }
     }   // head segments
 }
