@@ -106,7 +106,8 @@ struct BwdXLds {
     static __host__ __device__ int total(int mf);
 };
 
-constexpr int X_NW = 12;                 // wavefronts per workgroup (three per SIMD)
+constexpr int X_NW = 12;                 // wavefronts per workgroup (three per SIMD: measured better than
+                                         // two per SIMD with the next tile requested a whole tile ahead)
 template <int D>
 __host__ __device__ int BwdXLds<D>::total(int mf) { return images(mf) + X_NW * scratch; }
 
@@ -175,22 +176,25 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
     unsigned char* const scr = lds + L::images(mf) + wave * L::scratch;
     auto scr_at = [&](int row, int c) -> unsigned char* { return scr + row * ROWB + 16 * (c ^ ((row >> 1) & 7)); };
     struct Tile { uint4 q[KS], g[KS], o[KS]; float lam; };
-    auto load_tile = [&](int row0, Tile& t) {
+    struct Raw { uint4 q[LPT], g[LPT], o[LPT]; float lam; };     // a tile as requested from memory
+    auto request_tile = [&](int row0, Raw& x) {
         const long off = head_off + (long)row0 * D + 8 * lane;
-        uint4 xq[LPT], xg[LPT], xo[LPT];
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
-            xq[u] = ld16(a.Q + off + 512 * u);
-            xg[u] = ld16(a.G + off + 512 * u);
-            xo[u] = ld16(a.O + off + 512 * u);
+            x.q[u] = ld16(a.Q + off + 512 * u);
+            x.g[u] = ld16(a.G + off + 512 * u);
+            x.o[u] = ld16(a.O + off + 512 * u);
         }
-        t.lam = a.lse[(long)bh * a.n + row0 + l32];
+        x.lam = a.lse[(long)bh * a.n + row0 + l32];
+    };
+    auto unpack_tile = [&](const Raw& x, Tile& t) {
+        t.lam = x.lam;
 #pragma unroll
-        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = xq[u];
+        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = x.q[u];
 #pragma unroll
         for (int s = 0; s < KS; ++s) t.q[s] = *(const uint4*)scr_at(l32, 2 * s + half);
 #pragma unroll
-        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = xg[u];
+        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = x.g[u];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const uint2 g0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
@@ -198,7 +202,7 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
             t.g[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
         }
 #pragma unroll
-        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = xo[u];
+        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = x.o[u];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const uint2 o0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
@@ -213,9 +217,11 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
 
     const int row_first = row_begin + 32 * wave;
     Tile cur;
+    Raw raw;
     for (int row0 = row_first; row0 < row_end; row0 += 32 * X_NW) {
         const int qrow = row0 + l32;
-        load_tile(row0, cur);
+        request_tile(row0, raw);
+        unpack_tile(raw, cur);
 
         // g_i = G_i . out_i: the two halves of the wavefront hold complementary elements of the row
         float gdot = 0.f;
