@@ -79,8 +79,13 @@ struct QueryLds {
 // One workgroup = NW wavefronts sharing the LDS image of omega, S^T and z of one head; each wavefront
 // streams QT tiles of 32 query rows at a time.  With QT = 2 every operand fragment read from LDS
 // feeds two MFMAs, which halves the LDS traffic per flop (the limiter at one tile per wavefront).
-template <int D, bool ELU, int NW, int QT>
+// STAGED: the Q and out tiles of a wavefront cross a private 32 x D area of LDS (placed after the
+// image), so that every global access of a wavefront is 1 KiB of consecutive bytes instead of 32-byte
+// pieces of 32 rows; used when the area fits beside the image (QT = 1; n is a multiple of 32 here).
+// Chunk c of row r sits at chunk position c ^ ((r >> 1) & 7): conflict-free for both access patterns.
+template <int D, bool ELU, int NW, int QT, bool STAGED>
 __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
+    static_assert(!STAGED || QT == 1, "staged tiles are one 32-row tile per wavefront");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     using L = QueryLds<D>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -138,14 +143,23 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     int qrow[QT];
     bool valid[QT];
     uint4 qf[QT][KS];
+    constexpr int CPR = D / 8, ROWB = D * 2, LPT = 32 * CPR / 64;
+    unsigned char* const scr = lds + L::total(mf, ELU) + wave * (32 * ROWB);
+    auto scr_at = [&](int row, int c) -> unsigned char* { return scr + row * ROWB + 16 * (c ^ ((row >> 1) & 7)); };
+    uint4 raw[LPT];                       // STAGED: the next tile as requested from memory
     auto load_queries = [&](int row0, uint4 (&dst)[QT][KS]) {
+        if constexpr (STAGED) {
 #pragma unroll
-        for (int i = 0; i < QT; ++i) {
-            int r = row0 + 32 * i + l32;
-            if (r >= a.n) r = a.n - 1;
-            const uint16_t* qg = a.Q + head_off + (long)r * D + 8 * half;
+            for (int u = 0; u < LPT; ++u) raw[u] = ld16(a.Q + head_off + (long)row0 * D + 8 * lane + 512 * u);
+        } else {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) dst[i][s] = ld16(qg + 16 * s);
+            for (int i = 0; i < QT; ++i) {
+                int r = row0 + 32 * i + l32;
+                if (r >= a.n) r = a.n - 1;
+                const uint16_t* qg = a.Q + head_off + (long)r * D + 8 * half;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) dst[i][s] = ld16(qg + 16 * s);
+            }
         }
     };
     const int row_first = row_begin + 32 * QT * wave;
@@ -158,6 +172,12 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
 #pragma unroll
         for (int i = 0; i < QT; ++i) {
             qrow[i] = row0 + 32 * i + l32;
+            if constexpr (STAGED) {
+#pragma unroll
+                for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = raw[u];
+#pragma unroll
+                for (int s = 0; s < KS; ++s) qf[i][s] = *(const uint4*)scr_at(l32, 2 * s + half);
+            }
             valid[i] = qrow[i] < a.n;
             if (!valid[i]) qrow[i] = a.n - 1;
 #pragma unroll
@@ -219,8 +239,15 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
                         ev.y = pack_bf16(accN[i][t][4 * q + 2] * inv, accN[i][t][4 * q + 3] * inv);
                         od.x = pack_bf16(accN[i][t][4 * q + 4] * inv, accN[i][t][4 * q + 5] * inv);
                         od.y = pack_bf16(accN[i][t][4 * q + 6] * inv, accN[i][t][4 * q + 7] * inv);
-                        *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
+                        if constexpr (STAGED) *(uint4*)scr_at(l32, 4 * t + q + half) = join_halves(ev, od);
+                        else                  *(uint4*)(og + 32 * t + 8 * (q + half)) = join_halves(ev, od);
                     }
+            }
+            if constexpr (STAGED) {
+                uint16_t* ob = a.out + head_off + (long)row0 * D + 8 * lane;
+#pragma unroll
+                for (int u = 0; u < LPT; ++u)
+                    *(uint4*)(ob + 512 * u) = *(const uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR);
             }
         }
     }
@@ -288,10 +315,10 @@ constexpr int QS_QT = 1;                  // 32-row tiles per wavefront
 // wavefronts per workgroup: as many per SIMD as the register budget of the kernel allows
 template <int D> struct QsWaves { static constexpr int value = D == 64 ? 12 : 8; };
 
-template <int D, bool ELU>
-static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int ldsb, hipStream_t s) {
+template <int D, bool ELU, bool STAGED>
+static flurka_status launch_query_impl(const QueryArgs& qa, int ldsb, hipStream_t s) {
     constexpr int QS_NW = QsWaves<D>::value;
-    auto kern = query_stream_kernel<D, ELU, QS_NW, QS_QT>;
+    auto kern = query_stream_kernel<D, ELU, QS_NW, QS_QT, STAGED>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
     const int grid = resident_grid((const void*)kern, QS_NW * 64, ldsb, qa.total_tiles);
@@ -299,6 +326,19 @@ static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int lds
     hipLaunchKernelGGL(kern, dim3(grid), dim3(QS_NW * 64), ldsb, s, qa);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
+}
+
+// The LDS image alone must fit (fast_supported).  The staged tiles are used for the elu1 map when they
+// fit beside it: that kernel is bound by its Q and out traffic (measured: 71 -> 49 us at n = 16384,
+// B*H = 64); with the random-feature map the kernel is not, and the extra registers cost as much as the
+// better access pattern gains.
+template <int D, bool ELU>
+static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int ldsb, hipStream_t s) {
+    if constexpr (ELU && QS_QT == 1) {
+        const int staged = ldsb + QsWaves<D>::value * 32 * D * 2;
+        if (staged <= 160 * 1024) return launch_query_impl<D, ELU, true>(qa, staged, s);
+    }
+    return launch_query_impl<D, ELU, false>(qa, ldsb, s);
 }
 
 flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
