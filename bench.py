@@ -149,6 +149,8 @@ def main():
     ap.add_argument("--workload", default="C5", help="C1..C5 (C5 = forward+backward, the headline metric)")
     ap.add_argument("--algo", default="auto", choices=["auto", "generic", "fast"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the device copy and library GEMM that give the box's achievable HBM and MFMA rates")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample")
     args = ap.parse_args()
 
@@ -273,6 +275,33 @@ def main():
         "kernels": kernels_out,
         "roofline": roof,
     }
+
+    if not args.no_measured_peaks:
+        # What this machine sustains, beside the published peaks: a plain device copy (read + write) and the
+        # vendor library's bf16 GEMM, both through torch.  Context for the fractions above, not a target.
+        def timed(fn, reps):
+            fn(); torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / reps
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB
+        dst = torch.empty_like(src)
+        t_copy = timed(lambda: dst.copy_(src), 10)
+        del dst
+        a_ = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+        b_ = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+        t_mm = timed(lambda: torch.matmul(a_, b_), 10)
+        copy_gbs = 2.0 * src.numel() * 4 / t_copy / 1e9
+        mm_tflops = 2.0 * 8192 ** 3 / t_mm / 1e12
+        del src, a_, b_
+        result["measured_peaks"] = {"hbm_copy_gbs": round(copy_gbs, 1), "bf16_gemm_tflops": round(mm_tflops, 1),
+                                    "how": "torch copy_ of 1 GiB fp32 (bytes read + written); torch.matmul 8192^3 bf16"}
+        meas = copy_gbs if roof["bound"] == "hbm" else (mm_tflops if roof["bound"] == "mfma" else None)
+        if meas:
+            roof["frac_of_measured_peak"] = round(roof["achieved"] / meas, 4)
 
     if not args.no_cpu_baseline:
         from oracle import flurka_oracle as fo
