@@ -1004,7 +1004,6 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         gp.A[0] = img; gp.A[1] = img + img_elems;
         gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
         gp.C[0] = part; gp.C[1] = nullptr;
-        gp.c_split_stride = 0;
         gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
         gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
         gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;

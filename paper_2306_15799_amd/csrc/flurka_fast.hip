@@ -77,8 +77,9 @@ struct QueryLds {
 };
 
 // One workgroup = NW wavefronts sharing the LDS image of omega, S^T and z of one head; each wavefront
-// streams QT tiles of 32 query rows at a time.  With QT = 2 every operand fragment read from LDS
-// feeds two MFMAs, which halves the LDS traffic per flop (the limiter at one tile per wavefront).
+// streams QT tiles of 32 query rows at a time.  (QT = 2 would feed two MFMAs per operand fragment read
+// from LDS, but needs more than the 256 architectural VGPRs of a wavefront; the register allocator then
+// shuttles values through AGPRs and the kernel is slower than QT = 1.)
 // STAGED: the Q and out tiles of a wavefront cross a private 32 x D area of LDS (placed after the
 // image), so that every global access of a wavefront is 1 KiB of consecutive bytes instead of 32-byte
 // pieces of 32 rows; used when the area fits beside the image (QT = 1; n is a multiple of 32 here).
@@ -355,7 +356,6 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
         gp.C[0] = wsb + W.partial;
         gp.C[1] = nullptr;
-        gp.c_split_stride = 0;
         gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = p.k;
         gp.tilesM = q.tilesM; gp.tilesN = q.tilesN; gp.splits = q.splits;
         gp.steps_per_split = q.steps_per_split; gp.total_steps = q.total_steps;

@@ -60,7 +60,6 @@ struct GemmParams {
     const uint16_t* B[2];
     void* C[2];              // result tensors (policies that store final results); C[0] = partial buffer
                              // for policies with PARTIAL_TILES
-    long c_split_stride;     // unused with PARTIAL_TILES
     int tilesM, tilesN, splits, steps_per_split, total_steps;
     int n, d, k, BH, kp;     // problem sizes the policies need (kp: padded k of an image)
 };
