@@ -72,7 +72,7 @@ struct QueryLds {
     static __host__ __device__ int w_bytes(int mf) { return mf * w_pitch; }
     static __host__ __device__ int s_bytes(int mf) { return D * s_pitch(mf); }
     static __host__ __device__ int total(int mf, int elu) {
-        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + mf * 8;
+        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + mf * 8 + 16;       // + the tile counter
     }
 };
 
@@ -97,6 +97,7 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     unsigned char* ls = lds + (ELU ? 0 : L::w_bytes(mf));
     float* lz = (float*)(ls + L::s_bytes(mf));
     float* lc = lz + mf;
+    int* const next_tile = (int*)(lc + mf);
     constexpr int KS = D / 16;      // reduction steps over d
     constexpr int TT = D / 32;      // 32-row tiles of N^T
 
@@ -131,6 +132,11 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
         const float* cg = a.cp + (long)bh * mf;
         for (int c = tid; c < mf; c += NW * 64) { lz[c] = zg[c]; lc[c] = cg[c]; }
     }
+    // Tiles of the segment are handed out on demand: wavefront w starts with tile w and takes the next
+    // free one from this counter whenever it finishes.  (The wavefronts of a SIMD do not progress at the
+    // same rate -- the older one is served first -- so a fixed split leaves the SIMD half empty at the
+    // end; which wavefront computes a tile does not change its result.)
+    if (tid == 0) *next_tile = NW;
     __syncthreads();
 
     const long head_off = (long)bh * a.n * D;
@@ -166,10 +172,12 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     const int row_first = row_begin + 32 * QT * wave;
     if (row_first < row_end) load_queries(row_first, qf);
 
-    for (int row0 = row_first; row0 < row_end; row0 += 32 * QT * NW) {
+    for (int row0 = row_first; row0 < row_end;) {
         floatx16 accN[QT][TT];
         float den[QT];
-        const int row_next = row0 + 32 * QT * NW;
+        int grabbed = 0;
+        if (lane == 0) grabbed = atomicAdd(next_tile, 1);
+        const int row_next = row_begin + 32 * QT * __builtin_amdgcn_readfirstlane(grabbed);
 #pragma unroll
         for (int i = 0; i < QT; ++i) {
             qrow[i] = row0 + 32 * i + l32;
@@ -251,6 +259,7 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
                     *(uint4*)(ob + 512 * u) = *(const uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR);
             }
         }
+        row0 = row_next;
     }
     }   // head segments
 }
