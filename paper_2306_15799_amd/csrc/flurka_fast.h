@@ -21,13 +21,13 @@ struct KeyStateBuffers {
     float* Spart;          // (BH, KR, mf, d)
     float* zpart;          // (BH, KR, mf)
     float* cpart;          // (BH, KR, mf)
-    uint16_t* St;          // (BH, d, mf) bf16, feature slots in operand order
+    uint16_t* St;          // (BH, d, mf) bf16, feature slots in operand order; performer: S_j / z_j
     float* zp;             // (BH, mf)
-    float* cp;             // (BH, mf)
+    uint16_t* cw;          // (BH, mf, 4) bf16: hi, mid, lo terms of c + ln z, then 0 (performer only)
 };
 
 // Sums the projection's tile-ordered split partials (tilesM x tilesN tiles per split and tensor) into
-// ctx (K', V'), then fills S, z, c in ctx and the St/zp/cp images.
+// ctx (K', V'), then fills S, z, c in ctx and the St/zp/cw images.
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
                              int tilesM, int tilesN, int splits, const KeyStateBuffers& b, hipStream_t s);
 

@@ -55,9 +55,9 @@ static ProjPlan proj_plan(const Problem& p) {
 struct QueryArgs {
     const uint16_t* Q;
     const uint16_t* omega;     // (H|1, m, d)
-    const uint16_t* St;        // (BH, d, mf) bf16
+    const uint16_t* St;        // (BH, d, mf) bf16 (performer: S_j / z_j)
     const float* zp;           // (BH, mf)
-    const float* cp;           // (BH, mf) exponent shifts, same order as zp
+    const uint16_t* cw;        // (BH, mf, 4) bf16 terms of c + ln z (performer)
     uint16_t* out;
     float* lse;                // (BH, n) log of the denominator, kept for the backward pass
     int n, H, mf, tiles_per_head;   // tiles of 32*QT rows
@@ -67,12 +67,14 @@ struct QueryArgs {
 
 template <int D>
 struct QueryLds {
-    static constexpr int w_pitch = (D + 8) * 2;                  // bytes per omega row
+    // omega row: d coordinates, then one more 16-slot reduction step (the three bf16 terms of the
+    // feature's exponent shift, zeros), then 16 bytes of padding
+    static constexpr int w_pitch = (D + 16 + 8) * 2;
     static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }
     static __host__ __device__ int w_bytes(int mf) { return mf * w_pitch; }
     static __host__ __device__ int s_bytes(int mf) { return D * s_pitch(mf); }
     static __host__ __device__ int total(int mf, int elu) {
-        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + mf * 8 + 16;       // + the tile counter
+        return (elu ? 0 : w_bytes(mf)) + s_bytes(mf) + (elu ? mf * 4 : 0) + 16;       // + z (elu1), tile counter
     }
 };
 
@@ -95,9 +97,8 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
     const int s_pitch = L::s_pitch(mf);
     unsigned char* lw = lds;
     unsigned char* ls = lds + (ELU ? 0 : L::w_bytes(mf));
-    float* lz = (float*)(ls + L::s_bytes(mf));
-    float* lc = lz + mf;
-    int* const next_tile = (int*)(lc + mf);
+    float* lz = (float*)(ls + L::s_bytes(mf));                 // elu1 only
+    int* const next_tile = (int*)(lz + (ELU ? mf : 0));
     constexpr int KS = D / 16;      // reduction steps over d
     constexpr int TT = D / 32;      // 32-row tiles of N^T
 
@@ -120,6 +121,12 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
         }
+        const uint16_t* cwg = a.cw + (long)bh * mf * 4;
+        for (int r = tid; r < mf; r += NW * 64) {
+            const uint2 t3 = *(const uint2*)(cwg + 4 * r);
+            *(uint4*)(lw + r * L::w_pitch + 2 * D) = make_uint4(t3.x, t3.y, 0u, 0u);
+            *(uint4*)(lw + r * L::w_pitch + 2 * D + 16) = make_uint4(0u, 0u, 0u, 0u);
+        }
     }
     {
         const uint16_t* sg = a.St + (long)bh * D * mf;
@@ -128,9 +135,10 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(ls + r * s_pitch + 16 * q) = ld16(sg + (long)r * mf + 8 * q);
         }
-        const float* zg = a.zp + (long)bh * mf;
-        const float* cg = a.cp + (long)bh * mf;
-        for (int c = tid; c < mf; c += NW * 64) { lz[c] = zg[c]; lc[c] = cg[c]; }
+        if (ELU) {
+            const float* zg = a.zp + (long)bh * mf;
+            for (int c = tid; c < mf; c += NW * 64) lz[c] = zg[c];
+        }
     }
     // Tiles of the segment are handed out on demand: wavefront w starts with tile w and takes the next
     // free one from this counter whenever it finishes.  (The wavefronts of a SIMD do not progress at the
@@ -229,7 +237,7 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
             }
             if (row_next < row_end) load_queries(row_next, qf);
         } else {
-            forward_feature_pass<D, QT>(lw, L::w_pitch, ls, s_pitch, lz, lc, mf / 32, l32, half, qf, accN, den, mu,
+            forward_feature_pass<D, QT>(lw, L::w_pitch, ls, s_pitch, mf / 32, l32, half, qf, accN, den, mu,
                                         [&] { if (row_next < row_end) load_queries(row_next, qf); });
         }
 #pragma unroll
@@ -293,7 +301,7 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 }
 
 struct FastWs {
-    size_t partial, Kimg, Vimg, nrm, Spart, zpart, cpart, St, zp, cp, total;    // byte offsets
+    size_t partial, Kimg, Vimg, nrm, Spart, zpart, cpart, St, zp, cw, total;    // byte offsets
 };
 
 static FastWs fast_ws_layout(const Problem& p) {
@@ -312,7 +320,7 @@ static FastWs fast_ws_layout(const Problem& p) {
     W.cpart = o;   o += round_up(BH * ks.KR * p.mf * 4, 256);
     W.St = o;      o += round_up(BH * p.d * p.mf * 2, 256);
     W.zp = o;      o += round_up(BH * p.mf * 4, 256);
-    W.cp = o;      o += round_up(BH * p.mf * 4, 256);
+    W.cw = o;      o += round_up(BH * p.mf * 8, 256);
     W.total = o;
     return W;
 }
@@ -376,7 +384,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         KeyStateBuffers kb{};
         kb.Kimg = (uint16_t*)(wsb + W.Kimg); kb.Vimg = (uint32_t*)(wsb + W.Vimg); kb.nrm = (float*)(wsb + W.nrm);
         kb.Spart = (float*)(wsb + W.Spart); kb.zpart = (float*)(wsb + W.zpart); kb.cpart = (float*)(wsb + W.cpart);
-        kb.St = (uint16_t*)(wsb + W.St); kb.zp = (float*)(wsb + W.zp); kb.cp = (float*)(wsb + W.cp);
+        kb.St = (uint16_t*)(wsb + W.St); kb.zp = (float*)(wsb + W.zp); kb.cw = (uint16_t*)(wsb + W.cw);
         const ProjPlan q = proj_plan(p);
         st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN, proj_splits, kb, s);
         if (st != FLURKA_OK) return st;
@@ -388,7 +396,7 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         qa.omega = (const uint16_t*)a.omega;
         qa.St = (const uint16_t*)(wsb + W.St);
         qa.zp = (const float*)(wsb + W.zp);
-        qa.cp = (const float*)(wsb + W.cp);
+        qa.cw = (const uint16_t*)(wsb + W.cw);
         qa.out = (uint16_t*)a.out;
         qa.lse = a.ctx + L.lse;
         qa.n = p.n; qa.H = p.H; qa.mf = p.mf;

@@ -291,7 +291,10 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
 // ---------------------------------------------------------------------------
 // merge_pack: one workgroup per (head, 32 features).
 //   c_j = max_r c_jr,  S_j = sum_r exp(c_jr - c_j) S_jr,  z_j likewise
-//   St (d x mf) bf16: St[t][slot] = S[feature(slot)][t];  zp, cp: z, c in accumulator order of a tile
+//   St (d x mf) bf16: St[t][slot] = S[feature(slot)][t];  zp: z in accumulator order of a tile
+// For the random-feature map the query stream works with p'_ij = p_ij z_j, so that its denominator is
+// the plain sum of p': St holds S_j / z_j, and cw the exponent shift c_j + ln z_j as three bf16 terms
+// (it enters the query kernel's first contraction as extra reduction slots against ones).
 // The slot -> feature order inside each group of 16 is the order in which the first MFMA of the
 // query-stream kernel hands P^T on as the B operand of the second:
 //   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4          (natural order for elu1)
@@ -299,13 +302,14 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
 struct MergeArgs {
     const float* Spart; const float* zpart; const float* cpart;
     float* S; float* z; float* c;        // ctx
-    uint16_t* St; float* zp; float* cp;  // images for the query stream
+    uint16_t* St; float* zp; uint16_t* cw;  // images for the query stream
     int KR, mf, d, permute;
 };
 
 // Grid: (head, 32 features) x chunks of 32 coordinates t, so that even a few heads fill the chip.
 __global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
     __shared__ float w[32][32];          // weights exp(c_jr - c_j) per range and feature
+    __shared__ float zinv[32];           // 1 / z_j (random-feature map), 1 (elu1)
     __shared__ float tile[32][33];       // merged S tile (features x 32 t), padded
     const int FT = a.mf / 32;
     const int bh = blockIdx.x / FT, ft = blockIdx.x % FT;
@@ -332,8 +336,16 @@ __global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
                 pos = 16 * h + 4 * q + e;
             }
             a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
-            a.cp[(long)bh * a.mf + 32 * ft + pos] = cm;
+            if (a.permute) {
+                uint16_t hi, mid, lo;
+                split3(cm + logf(zs), hi, mid, lo);
+                uint2 pk;
+                pk.x = (uint32_t)hi | ((uint32_t)mid << 16);
+                pk.y = (uint32_t)lo;
+                *(uint2*)(a.cw + ((long)bh * a.mf + f) * 4) = pk;
+            }
         }
+        zinv[tid] = a.permute ? 1.f / zs : 1.f;
     }
     __syncthreads();
     for (int i = tid; i < 32 * 32; i += 256) {
@@ -352,7 +364,7 @@ __global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
             const int e = sl & 7, h = (sl >> 3) & 1;
             fl = (sl & 16) + 8 * (e >> 2) + 4 * h + (e & 3);
         }
-        a.St[((long)bh * a.d + t0 + tl) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl][tl]);
+        a.St[((long)bh * a.d + t0 + tl) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl][tl] * zinv[fl]);
     }
 }
 
@@ -416,7 +428,7 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         MergeArgs ma{};
         ma.Spart = b.Spart; ma.zpart = b.zpart; ma.cpart = b.cpart;
         ma.S = ctx + L.S; ma.z = ctx + L.z; ma.c = ctx + L.c;
-        ma.St = b.St; ma.zp = b.zp; ma.cp = b.cp;
+        ma.St = b.St; ma.zp = b.zp; ma.cw = b.cw;
         ma.KR = q.KR; ma.mf = p.mf; ma.d = p.d; ma.permute = p.elu ? 0 : 1;
         hipLaunchKernelGGL(merge_pack_kernel, dim3(p.BH * q.FT, p.d / 32), dim3(256), 0, s, ma);
         FLURKA_CHECK_LAUNCH();

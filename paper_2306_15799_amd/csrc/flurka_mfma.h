@@ -82,50 +82,43 @@ constexpr float FLURKA_LOG2E = 1.4426950408889634f;
 constexpr float FLURKA_LAZY_MAX = 5.0f;
 
 // Forward pass over all feature tiles for the 32 query rows of one wavefront (lane = query):
-//   u^T = omega q^T (accumulator starts at the key side's shift c_j) -> running max mu -> P^T = exp ->
-//   N^T += S^T P^T (P^T goes from the accumulator registers straight into the B operand),
-//   den += P z on the VALU.
+//   u^T = [omega | c'] [q | 1]^T -> running max mu -> P'^T = exp -> N^T += S'^T P'^T (P'^T goes from the
+//   accumulator registers straight into the B operand), den += sum of the bf16 P'.
+// The key side hands over S'_j = S_j / z_j and c'_j = c_j + ln z_j, so that P'_ij = P_ij z_j: the
+// denominator is a plain sum, and the shift enters the first contraction as one more reduction step
+// (three bf16 terms of c' against ones): no per-feature vector is touched on the VALU, which is the
+// unit this loop is bound by.
 // An in-order wavefront overlaps its matrix and vector pipes only if the two kinds of instruction
 // alternate in program order, so the loop is software-pipelined by hand: iteration ft runs the exp
 // work of tile ft, and between those VALU groups issues the (dependent) MFMAs of u^T for tile ft + 1
 // and the MFMAs of N^T for tile ft; the maximum of tile ft + 1 is taken in the shadow of the last
 // N^T MFMAs.  sched_barrier(0) after each group pins the order.  The only branch is the (rare, see
 // FLURKA_LAZY_MAX) rescaling between iterations.
-// lw: omega [feature][D] (pitch w_pitch), ls: S^T [t][feature slot] (pitch s_pitch), lz, lc: z, c in
-// accumulator order; all in LDS.
+// lw: [omega | c' terms | 0] rows [feature][D + 16] (pitch w_pitch), ls: S'^T [t][feature slot] (pitch
+// s_pitch); both in LDS.
 // `last_hook()` runs at the start of the last iteration, which no longer needs qf: a caller that
 // streams over query tiles issues the loads of its next tile there (it may overwrite qf).
 template <int N> struct IterTag { static constexpr int value = N; };
 
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 flurka_bf16x2;
+// acc + lo(p) + hi(p) for a packed pair of bf16
+__device__ __forceinline__ float add_bf16_pair(uint32_t p, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(flurka_bf16x2, p),
+                                           __builtin_bit_cast(flurka_bf16x2, 0x3f803f80u), acc, false);
+}
+
 template <int D, int QT, class LastHook>
 __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, int w_pitch, const unsigned char* ls,
-                                                     int s_pitch, const float* lz, const float* lc, int FT,
-                                                     int l32, int half, uint4 (&qf)[QT][D / 16],
-                                                     floatx16 (&accN)[QT][D / 32], float (&den)[QT],
-                                                     float (&mu)[QT], LastHook&& last_hook) {
+                                                     int s_pitch, int FT, int l32, int half,
+                                                     uint4 (&qf)[QT][D / 16], floatx16 (&accN)[QT][D / 32],
+                                                     float (&den)[QT], float (&mu)[QT], LastHook&& last_hook) {
     constexpr int KS = D / 16, TT = D / 32;
     constexpr int EPC = 16 / KS;                 // accumulator elements handled per group
     const unsigned char* wrow = lw + l32 * w_pitch + 16 * half;        // + 32*ft rows, + 32*s
     const unsigned char* srow = ls + l32 * s_pitch + 16 * half;        // + 32*t rows, + 64*ft (+32)
+    // B operand of the extra reduction step: ones against the three terms of c' (slots 0..2)
+    const uint4 qone = half == 0 ? make_uint4(0x3f803f80u, 0x00003f80u, 0u, 0u) : make_uint4(0u, 0u, 0u, 0u);
 
-    const int slot = acc_order_slot(32 * half + l32);
-    // u <- u + c, element g taking the shift of its own feature
-    auto add_shift = [&](floatx16& u, float cr) {
-        u[0] += bcast16<0>(cr);   u[1] += bcast16<1>(cr);   u[2] += bcast16<2>(cr);   u[3] += bcast16<3>(cr);
-        u[4] += bcast16<4>(cr);   u[5] += bcast16<5>(cr);   u[6] += bcast16<6>(cr);   u[7] += bcast16<7>(cr);
-        u[8] += bcast16<8>(cr);   u[9] += bcast16<9>(cr);   u[10] += bcast16<10>(cr); u[11] += bcast16<11>(cr);
-        u[12] += bcast16<12>(cr); u[13] += bcast16<13>(cr); u[14] += bcast16<14>(cr); u[15] += bcast16<15>(cr);
-    };
-    auto z_of = [&](float zr, int g) -> float {
-        switch (g) {
-            case 0: return bcast16<0>(zr);   case 1: return bcast16<1>(zr);   case 2: return bcast16<2>(zr);
-            case 3: return bcast16<3>(zr);   case 4: return bcast16<4>(zr);   case 5: return bcast16<5>(zr);
-            case 6: return bcast16<6>(zr);   case 7: return bcast16<7>(zr);   case 8: return bcast16<8>(zr);
-            case 9: return bcast16<9>(zr);   case 10: return bcast16<10>(zr); case 11: return bcast16<11>(zr);
-            case 12: return bcast16<12>(zr); case 13: return bcast16<13>(zr); case 14: return bcast16<14>(zr);
-            default: return bcast16<15>(zr);
-        }
-    };
     auto tile_max = [&](const floatx16& u) -> float {
         float tmax = fmaxf(fmaxf(u[0], u[1]), u[2]);
 #pragma unroll
@@ -147,20 +140,16 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
     // prologue: tile 0
     floatx16 u[QT];
     {
-        const float c0 = lc[slot];
 #pragma unroll
         for (int i = 0; i < QT; ++i) u[i] = zero16();
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
+        for (int s = 0; s <= KS; ++s) {
             const uint4 wa = *(const uint4*)(wrow + 32 * s);
 #pragma unroll
-            for (int i = 0; i < QT; ++i) u[i] = mfma32(wa, qf[i][s], u[i]);
+            for (int i = 0; i < QT; ++i) u[i] = mfma32(wa, s < KS ? qf[i][s] : qone, u[i]);
         }
 #pragma unroll
-        for (int i = 0; i < QT; ++i) {
-            add_shift(u[i], c0);
-            maybe_rescale(i, tile_max(u[i]));
-        }
+        for (int i = 0; i < QT; ++i) maybe_rescale(i, tile_max(u[i]));
     }
 
     auto iteration = [&](int ft, auto last_tag) {
@@ -171,22 +160,20 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         if constexpr (LAST) last_hook();
 #pragma unroll
         for (int i = 0; i < QT; ++i) nshift[i] = -mu[i] * FLURKA_LOG2E;
-        float cn = 0.f;
-        if constexpr (!LAST) {
-            cn = lc[32 * nft + slot];
-#pragma unroll
-            for (int i = 0; i < QT; ++i) un[i] = zero16();
-        }
-        const float zr = lz[32 * ft + slot];
-        uint4 wa[KS], sa[2 * TT];
+        uint4 wa[KS + 1], sa[2 * TT];
         if constexpr (!LAST) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s) wa[s] = *(const uint4*)(wrow + (32 * nft) * w_pitch + 32 * s);
+            for (int s = 0; s <= KS; ++s) wa[s] = *(const uint4*)(wrow + (32 * nft) * w_pitch + 32 * s);
         }
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
             sa[2 * t] = *(const uint4*)(srow + (32 * t) * s_pitch + 64 * ft);
             sa[2 * t + 1] = *(const uint4*)(srow + (32 * t) * s_pitch + 64 * ft + 32);
+        }
+        if constexpr (!LAST) {
+            // the shift step opens the chain of the next tile's u^T
+#pragma unroll
+            for (int i = 0; i < QT; ++i) un[i] = mfma32(wa[KS], qone, zero16());
         }
         __builtin_amdgcn_sched_barrier(0);
         uint32_t pk[QT][8];
@@ -202,12 +189,12 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
             for (int i = 0; i < QT; ++i) {
                 float p[EPC];
 #pragma unroll
-                for (int e = 0; e < EPC; ++e) {
-                    p[e] = fast_exp2(fmaf(u[i][s * EPC + e], FLURKA_LOG2E, nshift[i]));
-                    den[i] = fmaf(z_of(zr, s * EPC + e), p[e], den[i]);
-                }
+                for (int e = 0; e < EPC; ++e) p[e] = fast_exp2(fmaf(u[i][s * EPC + e], FLURKA_LOG2E, nshift[i]));
 #pragma unroll
-                for (int e = 0; e < EPC; e += 2) pk[i][(s * EPC + e) / 2] = pack_bf16(p[e], p[e + 1]);
+                for (int e = 0; e < EPC; e += 2) {
+                    pk[i][(s * EPC + e) / 2] = pack_bf16(p[e], p[e + 1]);
+                    den[i] = add_bf16_pair(pk[i][(s * EPC + e) / 2], den[i]);
+                }
             }
             // second half of the groups: N^T MFMAs with the first half of P^T (elements 0..7)
             if (s >= KS / 2) {
@@ -228,10 +215,7 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
         float tmax[QT];
         if constexpr (!LAST) {
 #pragma unroll
-            for (int i = 0; i < QT; ++i) {
-                add_shift(un[i], cn);
-                tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
-            }
+            for (int i = 0; i < QT; ++i) tmax[i] = fmaxf(fmaxf(un[i][0], un[i][1]), un[i][2]);
         }
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
