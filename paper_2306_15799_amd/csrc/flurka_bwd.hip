@@ -109,7 +109,7 @@ struct BwdXLds {
 constexpr int X_NW = 12;                 // wavefronts per workgroup (three per SIMD: measured better than
                                          // two per SIMD with the next tile requested a whole tile ahead)
 template <int D>
-__host__ __device__ int BwdXLds<D>::total(int mf) { return images(mf) + X_NW * scratch; }
+__host__ __device__ int BwdXLds<D>::total(int mf) { return images(mf) + X_NW * scratch + 16; }    // + tile counter
 
 template <int D>
 __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
@@ -156,6 +156,10 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
         const float* cg = a.cp + (long)bh * mf;
         for (int c = tid; c < mf; c += X_NW * 64) { lz[c] = zg[c]; lc[c] = cg[c]; }
     }
+    // tiles of the segment are handed out on demand (see query_stream_kernel): wavefront w starts with
+    // tile w and takes the next free one from this counter whenever it finishes
+    int* const next_tile = (int*)(lds + L::images(mf) + X_NW * L::scratch);
+    if (tid == 0) *next_tile = X_NW;
     __syncthreads();
 
     const long head_off = (long)bh * a.n * D;
@@ -218,8 +222,11 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
     const int row_first = row_begin + 32 * wave;
     Tile cur;
     Raw raw;
-    for (int row0 = row_first; row0 < row_end; row0 += 32 * X_NW) {
+    for (int row0 = row_first; row0 < row_end;) {
         const int qrow = row0 + l32;
+        int grabbed = 0;
+        if (lane == 0) grabbed = atomicAdd(next_tile, 1);
+        const int row_next = row_begin + 32 * __builtin_amdgcn_readfirstlane(grabbed);
         request_tile(row0, raw);
         unpack_tile(raw, cur);
 
@@ -299,6 +306,7 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
             for (int u = 0; u < LPT; ++u)
                 *(uint4*)(ob + 512 * u) = *(const uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR);
         }
+        row0 = row_next;
     }
     }   // head segments
 }
