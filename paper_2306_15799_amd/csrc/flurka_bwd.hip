@@ -851,7 +851,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
     const int FG = (q.FT + q.NW - 1) / q.NW;
     // one round of workgroups: the chip holds one 8-wavefront or two 4-wavefront workgroups per
     // compute unit; ranges are whole staged blocks of query tiles
-    const int slots = 256 * (q.NW == 8 ? 1 : 2);
+    const int slots = 512;
     int R = slots / (p.BH * FG);
     if (R > QT / Y_ST) R = QT / Y_ST;
     if (R < 1) R = 1;
