@@ -65,7 +65,7 @@ def stage_model(w, stage: str):
 
 # timer name of an MFMA-path kernel -> (name in rocprofv3 traces, stage it belongs to)
 KERNEL_TRACE_NAME = {
-    "gemm_mfma_proj": "gemm_mfma_kernel<ProjPolicy<{d}> >",
+    "gemm_mfma_proj": "gemm_mfma_kernel<ProjPolicy<{d}>, false>",        # one item per workgroup
     "proj_finish": "proj_finish_kernel",
     "key_state": "key_state_kernel<{d}, false>",
     "merge_pack": "merge_pack_kernel",
@@ -75,8 +75,8 @@ KERNEL_TRACE_NAME = {
     "bwd_query_y": "bwd_query_y_kernel<{d}>",
     "bwd_merge": "bwd_merge_kernel",
     "bwd_key": "bwd_key_kernel<{d}>",
-    "gemm_mfma_gradx": "gemm_mfma_kernel<GradXPolicy<{d}> >",
-    "gemm_mfma_grade": "gemm_mfma_kernel<GradEPolicy<{d}> >",
+    "gemm_mfma_gradx": "gemm_mfma_kernel<GradXPolicy<{d}>, true>",      # several items per workgroup
+    "gemm_mfma_grade": "gemm_mfma_kernel<GradEPolicy<{d}>, false>",
     "sum_splits": "sum_splits_bf16_kernel",
 }
 

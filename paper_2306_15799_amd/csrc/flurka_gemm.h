@@ -87,7 +87,9 @@ __device__ __forceinline__ uint2 gemm_read_tr16(const unsigned char* p) {
     return __builtin_bit_cast(uint2, v);
 }
 
-template <class Pol>
+// STREAM: a workgroup may take several work items (launched with fewer workgroups than items); the
+// one-item form keeps the step bookkeeping out of the long reductions, where it costs a few percent.
+template <class Pol, bool STREAM>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr bool BT = Pol::B_TRANSPOSE;
@@ -96,21 +98,32 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
     const int wm = wave >> 1, wn = wave & 1;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // workgroup -> (split, row tile, column tile, which); consecutive ids walk the splits first, so
-    // with a split count that is a multiple of 8 every XCD (ids mod 8) keeps to its own reduction range
-    int id = blockIdx.x;
-    const int split = id % g.splits; id /= g.splits;
-    const int tm = id % g.tilesM;    id /= g.tilesM;
-    const int tn = id % g.tilesN;    id /= g.tilesN;
-    const int which = id;
-    const int m0 = tm * GBM, n0 = tn * GBN;
-    const int step0 = split * g.steps_per_split;
-    int step1 = step0 + g.steps_per_split;
-    if (step1 > g.total_steps) step1 = g.total_steps;
-
-    const typename Pol::Ctx pc = Pol::make(g, which, m0, n0, tid);
-    const __amdgpu_buffer_rsrc_t rsA = pc.rsA, rsB = pc.rsB;
-    const int voffA = pc.voffA, voffB = pc.voffB;
+    // Work items = (split, row tile, column tile, which); consecutive ids walk the splits first, so with
+    // a split count that is a multiple of 8 every XCD (ids mod 8) keeps to its own reduction range.
+    // A workgroup takes items blockIdx.x, blockIdx.x + gridDim.x, ... and runs their reduction steps as
+    // ONE stream: the requests issued during the last two steps of an item already fetch the first two
+    // steps of the next one, so only the first item of a workgroup pays for an empty pipeline.
+    struct Item { int split, tm, tn, which, step0, step1, send; bool valid; };
+    const int total_items = g.tilesM * g.tilesN * 2 * g.splits;
+    auto decode = [&](int id) -> Item {
+        Item it;
+        it.valid = id < total_items;
+        if (!it.valid) id = 0;
+        it.split = id % g.splits; id /= g.splits;
+        it.tm = id % g.tilesM;    id /= g.tilesM;
+        it.tn = id % g.tilesN;    id /= g.tilesN;
+        it.which = id;
+        it.step0 = it.split * g.steps_per_split;
+        it.step1 = it.step0 + g.steps_per_split;
+        if (it.step1 > g.total_steps) it.step1 = g.total_steps;
+        if (!it.valid) it.step1 = it.step0;                           // nothing of it is real
+        it.send = it.step0 + ((it.step1 - it.step0 + 1) & ~1);        // steps run in pairs
+        return it;
+    };
+    int item_id = blockIdx.x;
+    Item cur = decode(item_id), nxt = decode(STREAM ? item_id + (int)gridDim.x : total_items);
+    typename Pol::Ctx pc = Pol::make(g, cur.which, cur.tm * GBM, cur.tn * GBN, tid);
+    typename Pol::Ctx pn = Pol::make(g, nxt.which, nxt.tm * GBM, nxt.tn * GBN, tid);
 
     // LDS addresses of this thread's writes and of this lane's fragment reads (per buffer: + G_STAGE)
     unsigned char* const a_dst = lds + (tid >> 3) * GA_PITCH + 16 * (tid & 7);                    // + 32*q rows
@@ -163,8 +176,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 
     auto run_step = [&](auto par_c, int step_load) {
         constexpr int PAR = decltype(par_c)::value;
-        const int sA = Pol::a_soff(pc, step_load), sB = Pol::b_soff(pc, step_load);
-        const int vB = step_load < step1 ? voffB : G_OOB;       // past the range: B reads as zero
+        // where the step two ahead comes from: this item, its zero step (odd counts), or the next item
+        const bool in_cur = !STREAM || step_load < cur.send;
+        const int sl = in_cur ? step_load : nxt.step0 + (step_load - cur.send);
+        const bool real = in_cur ? step_load < cur.step1 : sl < nxt.step1;
+        const typename Pol::Ctx& sc = in_cur ? pc : pn;
+        const int sA = Pol::a_soff(sc, sl), sB = Pol::b_soff(sc, sl);
+        const __amdgpu_buffer_rsrc_t rsA = sc.rsA, rsB = sc.rsB;
+        const int voffA = sc.voffA, aq = sc.a_qstride, bq = sc.b_qstride;
+        const int vB = real ? sc.voffB : G_OOB;                 // past the range: B reads as zero
 #define G_CHUNK(PH, q, i0, j0, i1, j1, LD)                                                      \
         {                                                                                       \
             constexpr int cur = (PH) & 1, nxt = cur ^ 1, ns = ((PH) + 1) & 3;                   \
@@ -178,8 +198,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
             /* chunks 1..23 of the next step finish the other buffer before that step's barrier  */ \
             if ((pos & 1) == 0) {                                                               \
                 constexpr int j = pos / 2;                                                      \
-                if (j & 1) RB[j / 2] = buf_ld16(rsB, vB, sB + (j / 2) * pc.b_qstride);          \
-                else       RA[j / 2] = buf_ld16(rsA, voffA, sA + (j / 2) * pc.a_qstride);       \
+                if (j & 1) RB[j / 2] = buf_ld16(rsB, vB, sB + (j / 2) * bq);                    \
+                else       RA[j / 2] = buf_ld16(rsA, voffA, sA + (j / 2) * aq);                 \
             } else {                                                                            \
                 constexpr int j = ((pos + 7) & 31) / 2;                                         \
                 constexpr int wbuf = pos >= 25 ? PAR : (PAR ^ 1);                               \
@@ -207,26 +227,64 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 #undef G_CHUNK
     };
 
-    if (step0 < step1) {
-        // prologue: step0 through the staging registers into buffer 0; step0 + 1 requested, its first
-        // four registers (the ones the steady state stores in chunks 25..31) stored into buffer 1
+    auto epilogue = [&](const Item& it) {
+        // this lane holds, for every 32 x 32 tile (i, j), column 32*j + l32 and rows
+        // 32*i + 8*q + 4*half + {0..3}, q = 0..3
+        if constexpr (Pol::PARTIAL_TILES) {
+            float* tp = (float*)g.C[0] +
+                        partial_tile_index(it.which, it.split, it.tn, it.tm, g.splits, g.tilesN, g.tilesM) * G_TILE_ELEMS +
+                        (long)wave * (16 * 4 * 256) + lane * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float4 v;
+                        v.x = acc[i][j][4 * q]; v.y = acc[i][j][4 * q + 1]; v.z = acc[i][j][4 * q + 2]; v.w = acc[i][j][4 * q + 3];
+                        *(float4*)(tp + ((i * 4 + j) * 4 + q) * 256) = v;
+                    }
+        } else {
+            // groups q and q + 1 are handed over together so that a policy may join the two halves of a
+            // wavefront into 8 consecutive rows per lane
+            const int m0 = it.tm * GBM, n0 = it.tn * GBN;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = n0 + wn * 128 + 32 * j + l32;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; q += 2) {
+                        const int row = m0 + wm * 128 + 32 * i + 8 * q;
+                        const float ev[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        const float od[4] = {acc[i][j][4 * q + 4], acc[i][j][4 * q + 5], acc[i][j][4 * q + 6], acc[i][j][4 * q + 7]};
+                        Pol::store_groups(g, pc, it.which, it.split, row, half, col, ev, od);
+                    }
+            }
+        }
+    };
+
+    if (cur.valid && cur.step0 < cur.step1) {
+        // prologue (first item only): step0 through the staging registers into buffer 0; step0 + 1
+        // requested, its first four registers (the ones the steady state stores in chunks 25..31) stored
+        // into buffer 1
         {
-            const int sA = Pol::a_soff(pc, step0), sB = Pol::b_soff(pc, step0);
+            const int sA = Pol::a_soff(pc, cur.step0), sB = Pol::b_soff(pc, cur.step0);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                RA[q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
-                RB[q] = buf_ld16(rsB, voffB, sB + q * pc.b_qstride);
+                RA[q] = buf_ld16(pc.rsA, pc.voffA, sA + q * pc.a_qstride);
+                RB[q] = buf_ld16(pc.rsB, pc.voffB, sB + q * pc.b_qstride);
             }
         }
 #pragma unroll
         for (int q = 0; q < 8; ++q) { store_a(0, q); store_b(0, q); }
         {
-            const int sA = Pol::a_soff(pc, step0 + 1), sB = Pol::b_soff(pc, step0 + 1);
-            const int vB = step0 + 1 < step1 ? voffB : G_OOB;
+            const int sA = Pol::a_soff(pc, cur.step0 + 1), sB = Pol::b_soff(pc, cur.step0 + 1);
+            const int vB = cur.step0 + 1 < cur.step1 ? pc.voffB : G_OOB;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                RA[q] = buf_ld16(rsA, voffA, sA + q * pc.a_qstride);
-                RB[q] = buf_ld16(rsB, vB, sB + q * pc.b_qstride);
+                RA[q] = buf_ld16(pc.rsA, pc.voffA, sA + q * pc.a_qstride);
+                RB[q] = buf_ld16(pc.rsB, vB, sB + q * pc.b_qstride);
             }
         }
         store_a(1, 0); store_b(1, 0); store_a(1, 1); store_b(1, 1);
@@ -234,50 +292,30 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) { G_LDA(0, 0, 0, i); G_LDB(0, 0, 0, i); }
         G_SB();
-        // steps always run in pairs (the two LDS buffers are compile-time roles); an odd count is
-        // completed by a step whose B tile reads as zero and so adds nothing
-        for (int step = step0; step < step1; step += 2) {
-            run_step(IC<0>{}, step + 2);
-            run_step(IC<1>{}, step + 3);
+        for (;;) {
+            // steps always run in pairs (the two LDS buffers are compile-time roles); an odd count is
+            // completed by a step whose B tile reads as zero and so adds nothing
+            for (int step = cur.step0; step < cur.send; step += 2) {
+                run_step(IC<0>{}, step + 2);
+                run_step(IC<1>{}, step + 3);
+            }
+            epilogue(cur);
+            if (!STREAM || !nxt.valid) break;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = zero16();
+            item_id += gridDim.x;
+            cur = nxt;
+            pc = pn;
+            nxt = decode(item_id + gridDim.x);
+            pn = Pol::make(g, nxt.which, nxt.tm * GBM, nxt.tn * GBN, tid);
         }
     }
 #undef G_SB
 #undef G_MMA
 #undef G_LDA
 #undef G_LDB
-
-    // epilogue: this lane holds, for every 32 x 32 tile (i, j), column 32*j + l32 and rows
-    // 32*i + 8*q + 4*half + {0..3}, q = 0..3
-    if constexpr (Pol::PARTIAL_TILES) {
-        float* tp = (float*)g.C[0] + partial_tile_index(which, split, tn, tm, g.splits, g.tilesN, g.tilesM) * G_TILE_ELEMS +
-                    (long)wave * (16 * 4 * 256) + lane * 4;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float4 v;
-                    v.x = acc[i][j][4 * q]; v.y = acc[i][j][4 * q + 1]; v.z = acc[i][j][4 * q + 2]; v.w = acc[i][j][4 * q + 3];
-                    *(float4*)(tp + ((i * 4 + j) * 4 + q) * 256) = v;
-                }
-    } else {
-        // groups q and q + 1 are handed over together so that a policy may join the two halves of a
-        // wavefront into 8 consecutive rows per lane
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = n0 + wn * 128 + 32 * j + l32;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; q += 2) {
-                    const int row = m0 + wm * 128 + 32 * i + 8 * q;
-                    const float ev[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    const float od[4] = {acc[i][j][4 * q + 4], acc[i][j][4 * q + 5], acc[i][j][4 * q + 6], acc[i][j][4 * q + 7]};
-                    Pol::store_groups(g, pc, which, split, row, half, col, ev, od);
-                }
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -384,15 +422,25 @@ struct GradEPolicy {
     }
 };
 
-template <class Pol>
-static inline flurka_status launch_gemm_mfma(const GemmParams& g, hipStream_t s) {
-    auto kern = gemm_mfma_kernel<Pol>;
+template <class Pol, bool STREAM>
+static inline flurka_status launch_gemm_mfma_impl(const GemmParams& g, int grid, hipStream_t s) {
+    auto kern = gemm_mfma_kernel<Pol, STREAM>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
-    const int grid = g.tilesM * g.tilesN * 2 * g.splits;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G_LDS, s, g);
     if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH;
     return FLURKA_OK;
+}
+
+// One workgroup per item while the items fit one resident round; with more items than that (the short
+// reductions of dK, dV), one resident round of workgroups that stream several items each.
+template <class Pol>
+static inline flurka_status launch_gemm_mfma(const GemmParams& g, hipStream_t s) {
+    const long items = (long)g.tilesM * g.tilesN * 2 * g.splits;
+    const int resident = resident_grid((const void*)gemm_mfma_kernel<Pol, true>, 256, G_LDS, items);
+    if (resident < 1) return FLURKA_ERR_LAUNCH;
+    if (items <= resident) return launch_gemm_mfma_impl<Pol, false>(g, (int)items, s);
+    return launch_gemm_mfma_impl<Pol, true>(g, resident, s);
 }
 
 }  // namespace flurka
