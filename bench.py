@@ -146,7 +146,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="C5", help="C1..C5 (C5 = forward+backward, the headline metric)")
+    ap.add_argument("--workload", default="C5", help="C1..C5 (C5 = forward+backward, the headline metric); C4T = C4's shape with a backward pass")
     ap.add_argument("--algo", default="auto", choices=["auto", "generic", "fast"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-measured-peaks", action="store_true",
@@ -170,7 +170,7 @@ def main():
         sys.exit(3)
     fb.load_library()          # raises if the HIP library has not been built: there is no fallback
 
-    w = inputs.WORKLOADS[args.workload]
+    w = {**inputs.WORKLOADS, **inputs.DERIVED_WORKLOADS}[args.workload]
     t = inputs.make_inputs(w, seed=0)
     td = torch.float32 if w.dtype == "f32" else torch.bfloat16
     dev = torch.device("cuda:0")

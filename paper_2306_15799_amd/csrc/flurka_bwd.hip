@@ -43,6 +43,7 @@ struct BwdPackArgs {
     uint16_t* Sp; float* zp; float* cp; const float* S; const float* z; const float* c;
     uint16_t* Wt; const uint16_t* omega;
     int mf, d, m;
+    int natural;             // Sp keeps the order of t (head sizes whose dOut rows are loaded as they lie)
     long total, wtotal;      // BH * mf * d elements of S; (H|1) * m * d elements of omega
     unsigned s_blocks;       // blocks that pack S; the rest pack omega
 };
@@ -63,7 +64,7 @@ __global__ void bwd_pack_kernel(BwdPackArgs a) {
         }
         // Sp: rem = j * d + slot
         const int j = rem / d, slot = rem % d;
-        const int t = (slot & ~15) + slot_to_elem16(slot & 15);
+        const int t = a.natural ? slot : (slot & ~15) + slot_to_elem16(slot & 15);
         a.Sp[idx] = f32_to_bf16(a.S[(bh * mf + j) * d + t]);
     } else {
         const long idx = (long)(blockIdx.x - a.s_blocks) * blockDim.x + threadIdx.x;
@@ -75,6 +76,12 @@ __global__ void bwd_pack_kernel(BwdPackArgs a) {
         const int f = (slot & ~15) + slot_to_elem16(slot & 15);
         a.Wt[idx] = a.omega[(h * m + f) * d + t];
     }
+}
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p) {
+    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+    return __builtin_bit_cast(uint2, v);
 }
 
 // ---------------------------------------------------------------------------
@@ -97,36 +104,49 @@ struct BwdXArgs {
     long omega_head_stride;    // 0 if shared
 };
 
+// Two variants.  Head size 64: omega, Sp and the transposed omega fit LDS together with a 32 x D area
+// per wavefront through which tiles cross between memory order and operand order.  Larger head sizes
+// ("direct"): LDS holds omega and Sp only; omega^T is read out of the omega image with transposing
+// loads (see bwd_query_y for their layout), and rows of Q, dOut, out, dQ move between memory and
+// registers directly, 16 bytes per lane and step.  The direct omega image has unpadded 256-byte rows
+// whose 16-byte chunk c of row r sits at chunk position c ^ (4*(r%4) + (r/4)%4): 16 consecutive rows
+// put the same chunk into 16 different bank groups (plain reads down a column of rows), and 4
+// consecutive rows put a 64-byte column group into 4 different quarters of the banks (transposing reads).
 template <int D>
 struct BwdXLds {
-    static constexpr int w_pitch = (D + 8) * 2;                          // rows of length d
+    static constexpr bool direct = D > 64;
+    static constexpr int nw = direct ? 8 : 12;       // wavefronts per workgroup (64: three per SIMD measured
+                                                     // better than two with the next tile requested a tile ahead)
+    static constexpr int w_pitch = direct ? D * 2 : (D + 8) * 2;         // omega rows
+    static constexpr int sp_pitch = (D + 8) * 2;                         // Sp rows
     static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }   // rows of length mf
-    static __host__ __device__ int images(int mf) { return 2 * mf * w_pitch + D * s_pitch(mf) + mf * 8; }
-    static constexpr int scratch = 32 * D * 2;                           // per wavefront: one 32-row tile
-    static __host__ __device__ int total(int mf);
+    static __host__ __device__ int images(int mf) {
+        return mf * w_pitch + mf * sp_pitch + (direct ? 0 : D * s_pitch(mf)) + mf * 8;
+    }
+    static constexpr int scratch = direct ? 0 : 32 * D * 2;              // per wavefront: one 32-row tile
+    static __host__ __device__ int total(int mf) { return images(mf) + nw * scratch + 16; }    // + tile counter
 };
-
-constexpr int X_NW = 12;                 // wavefronts per workgroup (three per SIMD: measured better than
-                                         // two per SIMD with the next tile requested a whole tile ahead)
-template <int D>
-__host__ __device__ int BwdXLds<D>::total(int mf) { return images(mf) + X_NW * scratch + 16; }    // + tile counter
+static_assert(!BwdXLds<128>::direct || BwdXLds<128>::w_pitch == 256, "swizzle assumes 16 chunks per omega row");
 
 template <int D>
-__global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
+__global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     using L = BwdXLds<D>;
+    constexpr bool DIRECT = L::direct;
+    constexpr int X_NW = L::nw;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int mf = a.mf;
     const int s_pitch = L::s_pitch(mf);
     unsigned char* lw = lds;                              // omega   [feature][d]
     unsigned char* lsp = lw + mf * L::w_pitch;            // Sp      [feature][t slot]
-    unsigned char* lwt = lsp + mf * L::w_pitch;           // Wt      [t][feature slot]
-    float* lz = (float*)(lwt + D * s_pitch);
+    unsigned char* lwt = lsp + mf * L::sp_pitch;          // Wt      [t][feature slot]   (not direct)
+    float* lz = (float*)(lwt + (DIRECT ? 0 : D * s_pitch));
     float* lc = lz + mf;
     constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
     constexpr int TT = D / 32;      // 32-row tiles of dQ^T
     const int FT = mf / 32;
+    auto swz = [](int row) { return ((row & 3) << 2) | ((row >> 2) & 3); };
 
     // Resident grid: each workgroup takes an equal, contiguous share of all (head, 32-row tile) pairs
     // and walks it head by head, refilling the LDS image when the head changes.
@@ -143,14 +163,17 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
         constexpr int cpr = D / 8;
         for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
-            *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
-            *(uint4*)(lsp + r * L::w_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
+            const int qw = DIRECT ? (q ^ swz(r)) : q;
+            *(uint4*)(lw + r * L::w_pitch + 16 * qw) = ld16(og + (long)r * D + 8 * q);
+            *(uint4*)(lsp + r * L::sp_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
         }
-        const uint16_t* wtg = a.Wt + (long)(bh % a.H) * a.omega_head_stride;
-        const int cps = mf / 8;
-        for (int c = tid; c < D * cps; c += X_NW * 64) {
-            const int r = c / cps, q = c % cps;
-            *(uint4*)(lwt + r * s_pitch + 16 * q) = ld16(wtg + (long)r * mf + 8 * q);
+        if constexpr (!DIRECT) {
+            const uint16_t* wtg = a.Wt + (long)(bh % a.H) * a.omega_head_stride;
+            const int cps = mf / 8;
+            for (int c = tid; c < D * cps; c += X_NW * 64) {
+                const int r = c / cps, q = c % cps;
+                *(uint4*)(lwt + r * s_pitch + 16 * q) = ld16(wtg + (long)r * mf + 8 * q);
+            }
         }
         const float* zg = a.zp + (long)bh * mf;
         const float* cg = a.cp + (long)bh * mf;
@@ -169,13 +192,13 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
     seg = seg_end;
 
     // One tile = this lane's query row: Q as the B operand of u^T (8 consecutive d per step), dOut as
-    // the B operand of S G^T (slots (h, j) of step s hold t = 16*s + 8*(j/4) + 4*h + j%4), the same
-    // elements of out (for g_i) and lambda_i.
-    // Tiles move between memory and a wavefront-private 32 x D area of LDS as whole 16-byte chunks in
-    // memory order (32 rows are one contiguous block: every wavefront instruction covers 1 KiB of
-    // consecutive bytes), and between LDS and registers in the per-lane operand layouts.  Chunk c of
-    // row r sits at chunk position c ^ ((r >> 1) & 7): conflict-free both ways.  (n is a multiple of 32
-    // on this path, so tiles are always whole.)
+    // the B operand of S G^T, the same elements of out (for g_i) and lambda_i.
+    // Head size 64: slots (h, j) of step s of dOut hold t = 16*s + 8*(j/4) + 4*h + j%4 (Sp is packed to
+    // match).  Tiles move between memory and a wavefront-private 32 x D area of LDS as whole 16-byte
+    // chunks in memory order (32 rows are one contiguous block: every wavefront instruction covers
+    // 1 KiB of consecutive bytes), and between LDS and registers in the per-lane operand layouts.
+    // Chunk c of row r sits at chunk position c ^ ((r >> 1) & 7): conflict-free both ways.
+    // Direct: dOut and out are taken like Q.  (n is a multiple of 32 on this path: tiles are whole.)
     constexpr int CPR = D / 8, ROWB = D * 2, LPT = 32 * CPR / 64;
     unsigned char* const scr = lds + L::images(mf) + wave * L::scratch;
     auto scr_at = [&](int row, int c) -> unsigned char* { return scr + row * ROWB + 16 * (c ^ ((row >> 1) & 7)); };
@@ -214,21 +237,44 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
             t.o[s] = make_uint4(o0.x, o0.y, o1.x, o1.y);
         }
     };
+    auto load_tile_direct = [&](int row0, Tile& t) {
+        const long off = head_off + (long)(row0 + l32) * D + 8 * half;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            t.q[s] = ld16(a.Q + off + 16 * s);
+            t.g[s] = ld16(a.G + off + 16 * s);
+            t.o[s] = ld16(a.O + off + 16 * s);
+        }
+        t.lam = a.lse[(long)bh * a.n + row0 + l32];
+    };
     auto dot2 = [](uint32_t x, uint32_t y, float acc) {
         acc = fmaf(bf16_to_f32((uint16_t)(x & 0xffffu)), bf16_to_f32((uint16_t)(y & 0xffffu)), acc);
         return fmaf(bf16_to_f32((uint16_t)(x >> 16)), bf16_to_f32((uint16_t)(y >> 16)), acc);
     };
+    // direct: this lane's byte offsets into the omega image
+    //   plain reads (A operand of u^T): row 32*ft + l32, chunk 2*s + half
+    //   transposing reads (A operand of dQ^T, column t = 32*tt + l32 of 8 features): this lane supplies
+    //   row 4*half + s16/4 (+ 8 for the second read) of a 16-feature group, 8 bytes at column
+    //   16*(lane/16 % 2) + 4*(s16 % 4) of the 32-column group tt
+    const int s16 = lane & 15, r4 = s16 >> 2;
+    const int u_lane = l32 * L::w_pitch, u_xor = 16 * (swz(l32) ^ half);
+    const int tr_row = (4 * half + r4) * L::w_pitch + 8 * (s16 & 1);
+    const int tr_low0 = 16 * ((2 * ((lane >> 4) & 1) + ((s16 >> 1) & 1)) ^ half);     // first read; second: ^ 32
 
     const int row_first = row_begin + 32 * wave;
     Tile cur;
-    Raw raw;
     for (int row0 = row_first; row0 < row_end;) {
         const int qrow = row0 + l32;
         int grabbed = 0;
         if (lane == 0) grabbed = atomicAdd(next_tile, 1);
         const int row_next = row_begin + 32 * __builtin_amdgcn_readfirstlane(grabbed);
-        request_tile(row0, raw);
-        unpack_tile(raw, cur);
+        if constexpr (DIRECT) {
+            load_tile_direct(row0, cur);
+        } else {
+            Raw raw;
+            request_tile(row0, raw);
+            unpack_tile(raw, cur);
+        }
 
         // g_i = G_i . out_i: the two halves of the wavefront hold complementary elements of the row
         float gdot = 0.f;
@@ -260,8 +306,10 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
             floatx16 tp = zero16();                          // T'^T tile: G_i . S_j
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                u = mfma32(*(const uint4*)(lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), cur.q[s], u);
-                tp = mfma32(*(const uint4*)(lsp + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half), cur.g[s], tp);
+                const unsigned char* wsrc = DIRECT ? lw + 32 * ft * L::w_pitch + u_lane + ((32 * s) ^ u_xor)
+                                                   : lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half;
+                u = mfma32(*(const uint4*)wsrc, cur.q[s], u);
+                tp = mfma32(*(const uint4*)(lsp + (32 * ft + l32) * L::sp_pitch + 32 * s + 16 * half), cur.g[s], tp);
             }
             const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
             uint32_t pk[8];
@@ -279,16 +327,30 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
                 pk[2 * q] = pack_bf16(d0, d1);
                 pk[2 * q + 1] = pack_bf16(d2, d3);
             }
-            const uint4 db0 = {pk[0], pk[1], pk[2], pk[3]};
-            const uint4 db1 = {pk[4], pk[5], pk[6], pk[7]};
+            const uint4 db[2] = {{pk[0], pk[1], pk[2], pk[3]}, {pk[4], pk[5], pk[6], pk[7]}};
+            if constexpr (DIRECT) {
 #pragma unroll
-            for (int t = 0; t < TT; ++t) {
-                const unsigned char* wp = lwt + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
-                accQ[t] = mfma32(*(const uint4*)wp, db0, accQ[t]);
-                accQ[t] = mfma32(*(const uint4*)(wp + 32), db1, accQ[t]);
+                for (int sp = 0; sp < 2; ++sp) {
+                    const unsigned char* fb = lw + (32 * ft + 16 * sp) * L::w_pitch + tr_row;
+#pragma unroll
+                    for (int t = 0; t < TT; ++t) {
+                        const int col = ((t ^ r4) << 6) + tr_low0;
+                        const uint2 w0 = lds_read_tr16(fb + col);
+                        const uint2 w1 = lds_read_tr16(fb + 8 * L::w_pitch + (col ^ 32));
+                        accQ[t] = mfma32(make_uint4(w0.x, w0.y, w1.x, w1.y), db[sp], accQ[t]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < TT; ++t) {
+                    const unsigned char* wp = lwt + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
+                    accQ[t] = mfma32(*(const uint4*)wp, db[0], accQ[t]);
+                    accQ[t] = mfma32(*(const uint4*)(wp + 32), db[1], accQ[t]);
+                }
             }
         }
-        // dQ rows through the transposition area: 16-byte pieces in, whole chunks in memory order out
+        // dQ rows: 16-byte pieces; head size 64 passes them through the transposition area so that whole
+        // chunks leave in memory order
 #pragma unroll
         for (int t = 0; t < TT; ++t)
 #pragma unroll
@@ -298,9 +360,11 @@ __global__ __launch_bounds__(X_NW * 64) void bwd_query_x_kernel(BwdXArgs a) {
                 ev.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
                 od.x = pack_bf16(accQ[t][4 * q + 4], accQ[t][4 * q + 5]);
                 od.y = pack_bf16(accQ[t][4 * q + 6], accQ[t][4 * q + 7]);
-                *(uint4*)scr_at(l32, 4 * t + q + half) = join_halves(ev, od);
+                const uint4 piece = join_halves(ev, od);
+                if constexpr (DIRECT) *(uint4*)(a.dQ + head_off + (long)qrow * D + 8 * (4 * t + q + half)) = piece;
+                else                  *(uint4*)scr_at(l32, 4 * t + q + half) = piece;
             }
-        {
+        if constexpr (!DIRECT) {
             uint16_t* ob = a.dQ + head_off + (long)row0 * D + 8 * lane;
 #pragma unroll
             for (int u = 0; u < LPT; ++u)
@@ -346,11 +410,6 @@ struct BwdYLds {
     static constexpr int total = rows * (q_pitch + g_pitch) + 2 * rows * 4;
 };
 
-typedef short short4v __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p) {
-    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
-    return __builtin_bit_cast(uint2, v);
-}
 
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
@@ -895,9 +954,10 @@ static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
     auto kern = bwd_query_x_kernel<D>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
-    const int grid = resident_grid((const void*)kern, X_NW * 64, ldsb, xa.total_tiles);
+    constexpr int threads = BwdXLds<D>::nw * 64;
+    const int grid = resident_grid((const void*)kern, threads, ldsb, xa.total_tiles);
     if (grid < 1) return FLURKA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(X_NW * 64), ldsb, s, xa);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), ldsb, s, xa);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
 }
@@ -916,8 +976,10 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         pa.S = a.ctx + L.S; pa.z = a.ctx + L.z; pa.c = a.ctx + L.c;
         pa.Wt = (uint16_t*)(wsb + W.Wt); pa.omega = (const uint16_t*)a.omega;
         pa.mf = p.mf; pa.d = p.d; pa.m = p.m;
+        const bool direct = p.d == 64 ? BwdXLds<64>::direct : BwdXLds<128>::direct;
+        pa.natural = direct;
         pa.total = (long)p.BH * p.mf * p.d;
-        pa.wtotal = (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;
+        pa.wtotal = direct ? 0 : (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;   // direct: no transposed omega
         pa.s_blocks = (unsigned)((pa.total + 255) / 256);
         const unsigned w_blocks = (unsigned)((pa.wtotal + 255) / 256);
         hipLaunchKernelGGL(bwd_pack_kernel, dim3(pa.s_blocks + w_blocks), dim3(256), 0, s, pa);

@@ -57,6 +57,12 @@ WORKLOADS = {
     "C5": Workload("C5", 4, 12, 8192, 64, 256, 256, "bf16", PHI_PERFORMER, True),
 }
 
+# Not benchmark configurations: shapes derived from them for timing code paths the five do not reach.
+# C4T is the long-sequence shape as a training step (head size 128 through the backward kernels).
+DERIVED_WORKLOADS = {
+    "C4T": Workload("C4T", 1, 16, 65536, 128, 512, 256, "bf16", PHI_PERFORMER, True),
+}
+
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bfloat16 (ties to even).

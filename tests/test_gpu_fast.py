@@ -95,6 +95,11 @@ BWD_SHAPES = [
     (2, 2, 2048, 64, 64, 32),
     (3, 5, 1088, 64, 96, 128),
     (8, 16, 128, 64, 40, 64),
+    # head size 128: the variant of the dQ kernel that keeps omega only once in LDS
+    (1, 3, 640, 128, 300, 160),
+    (2, 2, 1024, 128, 256, 256),
+    (3, 2, 2048, 128, 512, 32),
+    (4, 8, 192, 128, 40, 288),
 ]
 
 
