@@ -942,7 +942,8 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     const GradEPlan e = grad_e_plan(p);
     W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);        // dK' then dV'
     W.imgT = o;   o += round_up(2 * BH * W.kp * p.d * 2, 256);
-    W.epart = o;  o += round_up((size_t)2 * e.splits * e.tilesM * e.tilesN * G_TILE_ELEMS * 4, 256);   // tile-ordered dE, dF partials
+    // tile-ordered dE, dF partials (none when the reduction is not split)
+    W.epart = o;  o += e.splits == 1 ? 0 : round_up((size_t)2 * e.splits * e.tilesM * e.tilesN * G_TILE_ELEMS * 4, 256);
     W.total = o;
     return W;
 }
@@ -1073,10 +1074,18 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         GemmParams gp{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
         gp.A[0] = img; gp.A[1] = img + img_elems;
         gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
-        gp.C[0] = part; gp.C[1] = nullptr;
         gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
         gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
         gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
+        if (e.splits == 1) {
+            // enough tiles to fill the chip without splitting the reduction: results leave as bf16
+            gp.C[0] = a.dE; gp.C[1] = a.dF;
+            st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64, true>>(gp, s) : launch_gemm_mfma<GradEPolicy<128, true>>(gp, s);
+            if (st != FLURKA_OK) return st;
+            stage_end(s, STAGE_K_GRAD_E);
+            return FLURKA_OK;
+        }
+        gp.C[0] = part; gp.C[1] = nullptr;
         st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64>>(gp, s) : launch_gemm_mfma<GradEPolicy<128>>(gp, s);
         if (st != FLURKA_OK) return st;
         stage_end(s, STAGE_K_GRAD_E);

@@ -87,6 +87,13 @@ __device__ __forceinline__ uint2 gemm_read_tr16(const unsigned char* p) {
     return __builtin_bit_cast(uint2, v);
 }
 
+// ids handed to workgroups (SHARE_B pads the (split, column tile, which) index to a multiple of 8)
+template <class Pol>
+__host__ __device__ inline int gemm_item_count(const GemmParams& g) {
+    const int outer = g.splits * g.tilesN * 2;
+    return Pol::SHARE_B ? 8 * g.tilesM * ((outer + 7) / 8) : g.tilesM * outer;
+}
+
 // STREAM: a workgroup may take several work items (launched with fewer workgroups than items); the
 // one-item form keeps the step bookkeeping out of the long reductions, where it costs a few percent.
 template <class Pol, bool STREAM>
@@ -98,21 +105,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
     const int wm = wave >> 1, wn = wave & 1;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // Work items = (split, row tile, column tile, which); consecutive ids walk the splits first, so with
-    // a split count that is a multiple of 8 every XCD (ids mod 8) keeps to its own reduction range.
-    // A workgroup takes items blockIdx.x, blockIdx.x + gridDim.x, ... and runs their reduction steps as
+    // Work items = (split, row tile, column tile, which).  A workgroup takes items blockIdx.x,
+    // blockIdx.x + gridDim.x, ... (gridDim.x is a multiple of 8 whenever there is more than one item per
+    // workgroup, so a workgroup's items all run on one XCD = id mod 8) and runs their reduction steps as
     // ONE stream: the requests issued during the last two steps of an item already fetch the first two
     // steps of the next one, so only the first item of a workgroup pays for an empty pipeline.
+    // Order of ids:
+    //   split-major (projection): consecutive ids walk the splits first, so with a split count that is a
+    //     multiple of 8 every XCD keeps to its own reduction range of both operands;
+    //   SHARE_B (gradient GEMMs, whose B operand is the large one): id mod 8 is the low part of the
+    //     (split, column tile, which) index and the row tiles follow, so all row tiles that read one B
+    //     tile run on the same XCD at about the same time and that tile leaves HBM once.
     struct Item { int split, tm, tn, which, step0, step1, send; bool valid; };
-    const int total_items = g.tilesM * g.tilesN * 2 * g.splits;
+    const int total_items = gemm_item_count<Pol>(g);
     auto decode = [&](int id) -> Item {
         Item it;
         it.valid = id < total_items;
         if (!it.valid) id = 0;
-        it.split = id % g.splits; id /= g.splits;
-        it.tm = id % g.tilesM;    id /= g.tilesM;
-        it.tn = id % g.tilesN;    id /= g.tilesN;
-        it.which = id;
+        if constexpr (Pol::SHARE_B) {
+            const int xcd = id & 7; id >>= 3;
+            it.tm = id % g.tilesM;    id /= g.tilesM;
+            int u = 8 * id + xcd;                                     // (split, column tile, which)
+            it.split = u % g.splits;  u /= g.splits;
+            it.tn = u % g.tilesN;     u /= g.tilesN;
+            it.which = u;
+            if (u > 1) { it.valid = false; it.which = 0; }            // only past the last real item
+        } else {
+            it.split = id % g.splits; id /= g.splits;
+            it.tm = id % g.tilesM;    id /= g.tilesM;
+            it.tn = id % g.tilesN;    id /= g.tilesN;
+            it.which = id;
+        }
         it.step0 = it.split * g.steps_per_split;
         it.step1 = it.step0 + g.steps_per_split;
         if (it.step1 > g.total_steps) it.step1 = g.total_steps;
@@ -339,6 +362,7 @@ template <int D>
 struct ProjPolicy {
     static constexpr bool B_TRANSPOSE = true;
     static constexpr bool PARTIAL_TILES = true;
+    static constexpr bool SHARE_B = false;
     struct Ctx : PolicyCtxBase { int bh0; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -365,6 +389,7 @@ template <int D>
 struct GradXPolicy {
     static constexpr bool B_TRANSPOSE = true;
     static constexpr bool PARTIAL_TILES = false;
+    static constexpr bool SHARE_B = true;
     struct Ctx : PolicyCtxBase {};
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -394,11 +419,13 @@ struct GradXPolicy {
 };
 
 // dE = sum_bh dX' X^T: rows = projected slots of the (BH, kp, D) image of dX', columns = sequence
-// positions, reduction = (head, t) pairs, 64 of them per step.
-template <int D>
+// positions, reduction = (head, t) pairs, 64 of them per step.  FINAL: the reduction is not split, the
+// bf16 result goes straight to dE / dF (k x n); otherwise fp32 split partials.
+template <int D, bool FINAL = false>
 struct GradEPolicy {
     static constexpr bool B_TRANSPOSE = false;
-    static constexpr bool PARTIAL_TILES = true;
+    static constexpr bool PARTIAL_TILES = !FINAL;
+    static constexpr bool SHARE_B = true;
     struct Ctx : PolicyCtxBase { int a_batch, b_batch; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -420,6 +447,19 @@ struct GradEPolicy {
         constexpr int spb = D / GBK;
         return (step / spb) * c.b_batch + (step % spb) * (GBK * 2);
     }
+    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx&, int which, int, int row,
+                                                        int half, int col, const float (&ev)[4],
+                                                        const float (&od)[4]) {
+        // one 32-column segment of a row per half-wavefront and store
+        if (col >= g.n) return;
+        uint16_t* o = (uint16_t*)g.C[which] + col;
+        const int r0 = row + 4 * half;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (r0 + e < g.k) o[(long)(r0 + e) * g.n] = f32_to_bf16(ev[e]);
+            if (r0 + 8 + e < g.k) o[(long)(r0 + 8 + e) * g.n] = f32_to_bf16(od[e]);
+        }
+    }
 };
 
 template <class Pol, bool STREAM>
@@ -436,10 +476,13 @@ static inline flurka_status launch_gemm_mfma_impl(const GemmParams& g, int grid,
 // reductions of dK, dV), one resident round of workgroups that stream several items each.
 template <class Pol>
 static inline flurka_status launch_gemm_mfma(const GemmParams& g, hipStream_t s) {
-    const long items = (long)g.tilesM * g.tilesN * 2 * g.splits;
-    const int resident = resident_grid((const void*)gemm_mfma_kernel<Pol, true>, 256, G_LDS, items);
+    const long items = gemm_item_count<Pol>(g);
+    int resident = resident_grid((const void*)gemm_mfma_kernel<Pol, true>, 256, G_LDS, items);
     if (resident < 1) return FLURKA_ERR_LAUNCH;
-    if (items <= resident) return launch_gemm_mfma_impl<Pol, false>(g, (int)items, s);
+    // streaming needs a grid that is a multiple of 8: a workgroup's items then share id mod 8, and in
+    // the SHARE_B order the ids past the last real item come last for every workgroup
+    if (items > resident) resident = resident / 8 * 8;
+    if (items <= resident || resident < 8) return launch_gemm_mfma_impl<Pol, false>(g, (int)items, s);
     return launch_gemm_mfma_impl<Pol, true>(g, resident, s);
 }
 

@@ -100,6 +100,10 @@ BWD_SHAPES = [
     (2, 2, 1024, 128, 256, 256),
     (3, 2, 2048, 128, 512, 32),
     (4, 8, 192, 128, 40, 288),
+    # many tiles: the dE/dF contraction fills the chip without splitting its reduction and stores its
+    # result directly (ragged k and a ragged last column tile; both head sizes)
+    (1, 1, 8256, 64, 1000, 32),
+    (1, 2, 4160, 128, 1000, 32),
 ]
 
 
