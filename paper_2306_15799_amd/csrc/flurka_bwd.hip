@@ -7,11 +7,26 @@
 //     dS_j  = sum_i W_ij G_i                    dz_j = - sum_i W_ij g_i
 // (the -rowsum(dU) q term of the feature map's derivative vanishes: sum_j dU_ij = 0 identically).
 //
+// Where attention is concentrated on few (key, feature) pairs these sums cancel almost completely:
+// G_i . S_j - g_i z_j = z_j G_i . (S_j / z_j - out_i) with out_i close to S_j / z_j for the features that
+// carry the weight, and likewise dPhiK_rj = sum_i W_ij (G_i . V'_r - g_i) on the key side.  A g_i taken
+// from the rounded output (relative error 2^-9), or S rounded to one bf16 term, then leaves errors far
+// larger than the result.  So:
+//   * S_j / z_j enters as a two-term bf16 split (hi + lo), and b_ij = W_ij z_j is what is exponentiated
+//     (c_j + ln z_j is the shift), so that r_ij = b_ij (G_i . S_j / z_j - ghat_i) is small where it cancels;
+//   * ghat_i = G_i . out_i (rounded output) is only a first estimate: with sR_i = sum_j r_ij and
+//     sB_i = sum_j b_ij (= 1 up to the rounding of the forward's lambda_i), g_i = ghat_i + sR_i / sB_i is
+//     consistent with the weights this kernel uses, and
+//         dQ_i = (sum_j r_ij omega_j - (sR_i / sB_i) sum_j b_ij omega_j) / sB_i
+//     needs a second accumulator (sum_j b_ij omega_j) but no second pass;
+//   * the dS kernel uses the renormalised lambda_i + ln sB_i and forms dz_j from the same bf16-rounded
+//     weights that enter dS_j.
+//
 // Two kernels, both built on v_mfma_f32_32x32x16_bf16 with operands chained through registers:
-//   bwd_query_x  one wavefront per 32 query rows, lane = query: lambda_i comes from the forward (ctx),
-//                g_i from the rows of dOut and out; forms dU^T tile by tile and accumulates dQ^T
+//   bwd_query_x  one wavefront per 32 query rows, lane = query: lambda_i comes from the forward (ctx);
+//                forms r^T and b^T tile by tile and accumulates the two parts of dQ^T
 //   bwd_query_y  one wavefront per (head, 32 features, query range), lane = feature: recomputes W with
-//                the same lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
+//                the renormalised lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
 #include "flurka_fast.h"
 #include "flurka_gemm.h"
 
@@ -34,48 +49,38 @@ __host__ __device__ inline int slot_to_elem16(int p) {
 }
 
 // ---------------------------------------------------------------------------
-// Operand images for bwd_query_x, per head (S, z, c from ctx; omega from the caller):
-//   Sp  (mf x d)   Sp[j][slot]  = S[j][t(slot)]           A operand of T'^T = S G^T
-//   Wt  (d x m)    Wt[t][slot]  = omega[feat(slot)][t]    A operand of dQ^T = omega^T dU^T  (per omega head)
-//   zp, cp (mf)    z, c in accumulator order of a 32-feature tile
+// Operand images for bwd_query_x, per head (S, z, c from ctx):
+//   Sp  2 x (BH, mf, d)  hi and lo bf16 terms of S[j][t(slot)] / z[j]     A operand of T'^T = (S/z) G^T
+//   cp  (BH, mf)         c + ln z in accumulator order of a 32-feature tile
+// t(slot): head size 64 stages dOut through LDS in accumulator order (slot 8h + e of a group of 16 holds
+// t = 8*(e/4) + 4*h + e%4); larger head sizes load dOut rows as they lie (`natural`).
 // ---------------------------------------------------------------------------
 struct BwdPackArgs {
-    uint16_t* Sp; float* zp; float* cp; const float* S; const float* z; const float* c;
-    uint16_t* Wt; const uint16_t* omega;
-    int mf, d, m;
-    int natural;             // Sp keeps the order of t (head sizes whose dOut rows are loaded as they lie)
-    long total, wtotal;      // BH * mf * d elements of S; (H|1) * m * d elements of omega
-    unsigned s_blocks;       // blocks that pack S; the rest pack omega
+    uint16_t* Sp; float* cp; const float* S; const float* z; const float* c;
+    int mf, d;
+    int natural;
+    long total;              // BH * mf * d elements of S
 };
 
 __global__ void bwd_pack_kernel(BwdPackArgs a) {
-    if (blockIdx.x < a.s_blocks) {
-        const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-        if (idx >= a.total) return;
-        const int mf = a.mf, d = a.d;
-        const long bh = idx / ((long)mf * d);
-        const int rem = (int)(idx % ((long)mf * d));
-        if (rem < mf) {
-            const int slot = rem;
-            const int g = slot & 15, h = (slot >> 4) & 1;
-            const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
-            a.zp[bh * mf + slot] = a.z[bh * mf + fz];
-            a.cp[bh * mf + slot] = a.c[bh * mf + fz];
-        }
-        // Sp: rem = j * d + slot
-        const int j = rem / d, slot = rem % d;
-        const int t = a.natural ? slot : (slot & ~15) + slot_to_elem16(slot & 15);
-        a.Sp[idx] = f32_to_bf16(a.S[(bh * mf + j) * d + t]);
-    } else {
-        const long idx = (long)(blockIdx.x - a.s_blocks) * blockDim.x + threadIdx.x;
-        if (idx >= a.wtotal) return;
-        const int m = a.m, d = a.d;
-        const long h = idx / ((long)m * d);
-        const int rem = (int)(idx % ((long)m * d));
-        const int t = rem / m, slot = rem % m;
-        const int f = (slot & ~15) + slot_to_elem16(slot & 15);
-        a.Wt[idx] = a.omega[(h * m + f) * d + t];
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= a.total) return;
+    const int mf = a.mf, d = a.d;
+    const long bh = idx / ((long)mf * d);
+    const int rem = (int)(idx % ((long)mf * d));
+    if (rem < mf) {
+        const int slot = rem;
+        const int g = slot & 15, h = (slot >> 4) & 1;
+        const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
+        a.cp[bh * mf + slot] = a.c[bh * mf + fz] + logf(a.z[bh * mf + fz]);
     }
+    // Sp: rem = j * d + slot
+    const int j = rem / d, slot = rem % d;
+    const int t = a.natural ? slot : (slot & ~15) + slot_to_elem16(slot & 15);
+    const float v = a.S[(bh * mf + j) * d + t] / a.z[bh * mf + j];
+    const uint16_t hi = f32_to_bf16(v);
+    a.Sp[idx] = hi;
+    a.Sp[a.total + idx] = f32_to_bf16(v - bf16_to_f32(hi));
 }
 
 typedef short short4v __attribute__((ext_vector_type(4)));
@@ -92,41 +97,44 @@ struct BwdXArgs {
     const uint16_t* G;         // dOut
     const uint16_t* O;         // out
     const uint16_t* omega;     // (H|1, m, d)
-    const uint16_t* Sp;        // (BH, mf, d)
-    const uint16_t* Wt;        // (H|1, d, m)
-    const float* zp;
-    const float* cp;
+    const uint16_t* Sp;        // 2 x (BH, mf, d): hi, lo terms of S / z
+    long sp_plane;             // BH * mf * d
+    const float* cp;           // (BH, mf)  c + ln z, accumulator order
     const float* lse;          // (BH, n)  lambda_i, written by the forward
     uint16_t* dQ;
     float* delta;              // (BH, n)  g_i
+    float* lam2;               // (BH, n)  lambda_i + ln sB_i: the normaliser the dS kernel uses
     int n, H, mf, tiles_per_head;   // tiles of 32 rows
     long total_tiles;               // BH * tiles_per_head
     long omega_head_stride;    // 0 if shared
 };
 
-// Two variants.  Head size 64: omega, Sp and the transposed omega fit LDS together with a 32 x D area
-// per wavefront through which tiles cross between memory order and operand order.  Larger head sizes
-// ("direct"): LDS holds omega and Sp only; omega^T is read out of the omega image with transposing
-// loads (see bwd_query_y for their layout), and rows of Q, dOut, out, dQ move between memory and
-// registers directly, 16 bytes per lane and step.  The direct omega image has unpadded 256-byte rows
-// whose 16-byte chunk c of row r sits at chunk position c ^ (4*(r%4) + (r/4)%4): 16 consecutive rows
-// put the same chunk into 16 different bank groups (plain reads down a column of rows), and 4
-// consecutive rows put a 64-byte column group into 4 different quarters of the banks (transposing reads).
+// LDS of a workgroup: omega (once: omega^T is read out of the same image with transposing loads, see
+// bwd_query_y for their layout), the two terms of Sp, c', and -- head size 64 -- a 32 x D area per
+// wavefront through which tiles cross between memory order and operand order.  Larger head sizes
+// ("direct") move rows of Q, dOut, out, dQ between memory and registers directly, 16 bytes per lane
+// and step.
+// The omega image has unpadded rows; 16-byte chunk c of row r sits at chunk position c ^ swz(r):
+//   256-byte rows (d = 128): swz(r) = 4*(r%4) + (r/4)%4
+//   128-byte rows (d = 64):  swz(r) = 4*((r/2)%2) + (r/4)%4
+// Either way 16 consecutive rows put the same chunk into 16 different bank groups (plain reads down a
+// column of rows), and 4 consecutive rows put a 64-byte column group into 4 different quarters of the
+// banks (transposing reads).
 template <int D>
 struct BwdXLds {
+    static_assert(D == 64 || D == 128, "row swizzles are written for 128- and 256-byte rows");
     static constexpr bool direct = D > 64;
-    static constexpr int nw = direct ? 8 : 12;       // wavefronts per workgroup (64: three per SIMD measured
-                                                     // better than two with the next tile requested a tile ahead)
-    static constexpr int w_pitch = direct ? D * 2 : (D + 8) * 2;         // omega rows
+    static constexpr int nw = 8;                     // wavefronts per workgroup: two per SIMD (the two
+                                                     // accumulator sets leave no room for a third)
+    static constexpr int w_pitch = D * 2;                                // omega rows
     static constexpr int sp_pitch = (D + 8) * 2;                         // Sp rows
-    static __host__ __device__ int s_pitch(int mf) { return (mf + 8) * 2; }   // rows of length mf
-    static __host__ __device__ int images(int mf) {
-        return mf * w_pitch + mf * sp_pitch + (direct ? 0 : D * s_pitch(mf)) + mf * 8;
-    }
+    static __host__ __device__ int images(int mf) { return mf * w_pitch + 2 * mf * sp_pitch + mf * 4; }
     static constexpr int scratch = direct ? 0 : 32 * D * 2;              // per wavefront: one 32-row tile
     static __host__ __device__ int total(int mf) { return images(mf) + nw * scratch + 16; }    // + tile counter
+    static __host__ __device__ int swz(int r) {
+        return D == 128 ? ((r & 3) << 2) | ((r >> 2) & 3) : (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
+    }
 };
-static_assert(!BwdXLds<128>::direct || BwdXLds<128>::w_pitch == 256, "swizzle assumes 16 chunks per omega row");
 
 template <int D>
 __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXArgs a) {
@@ -137,16 +145,13 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int mf = a.mf;
-    const int s_pitch = L::s_pitch(mf);
-    unsigned char* lw = lds;                              // omega   [feature][d]
-    unsigned char* lsp = lw + mf * L::w_pitch;            // Sp      [feature][t slot]
-    unsigned char* lwt = lsp + mf * L::sp_pitch;          // Wt      [t][feature slot]   (not direct)
-    float* lz = (float*)(lwt + (DIRECT ? 0 : D * s_pitch));
-    float* lc = lz + mf;
+    unsigned char* lw = lds;                              // omega    [feature][d], swizzled chunks
+    unsigned char* lsh = lw + mf * L::w_pitch;            // Sp hi    [feature][t slot]
+    unsigned char* lsl = lsh + mf * L::sp_pitch;          // Sp lo
+    float* lc = (float*)(lsl + mf * L::sp_pitch);         // c'
     constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
     constexpr int TT = D / 32;      // 32-row tiles of dQ^T
     const int FT = mf / 32;
-    auto swz = [](int row) { return ((row & 3) << 2) | ((row >> 2) & 3); };
 
     // Resident grid: each workgroup takes an equal, contiguous share of all (head, 32-row tile) pairs
     // and walks it head by head, refilling the LDS image when the head changes.
@@ -163,21 +168,12 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
         constexpr int cpr = D / 8;
         for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
-            const int qw = DIRECT ? (q ^ swz(r)) : q;
-            *(uint4*)(lw + r * L::w_pitch + 16 * qw) = ld16(og + (long)r * D + 8 * q);
-            *(uint4*)(lsp + r * L::sp_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
+            *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = ld16(og + (long)r * D + 8 * q);
+            *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
+            *(uint4*)(lsl + r * L::sp_pitch + 16 * q) = ld16(spg + a.sp_plane + (long)r * D + 8 * q);
         }
-        if constexpr (!DIRECT) {
-            const uint16_t* wtg = a.Wt + (long)(bh % a.H) * a.omega_head_stride;
-            const int cps = mf / 8;
-            for (int c = tid; c < D * cps; c += X_NW * 64) {
-                const int r = c / cps, q = c % cps;
-                *(uint4*)(lwt + r * s_pitch + 16 * q) = ld16(wtg + (long)r * mf + 8 * q);
-            }
-        }
-        const float* zg = a.zp + (long)bh * mf;
         const float* cg = a.cp + (long)bh * mf;
-        for (int c = tid; c < mf; c += X_NW * 64) { lz[c] = zg[c]; lc[c] = cg[c]; }
+        for (int c = tid; c < mf; c += X_NW * 64) lc[c] = cg[c];
     }
     // tiles of the segment are handed out on demand (see query_stream_kernel): wavefront w starts with
     // tile w and takes the next free one from this counter whenever it finishes
@@ -192,7 +188,7 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     seg = seg_end;
 
     // One tile = this lane's query row: Q as the B operand of u^T (8 consecutive d per step), dOut as
-    // the B operand of S G^T, the same elements of out (for g_i) and lambda_i.
+    // the B operand of (S/z) G^T, the same elements of out (for ghat_i) and lambda_i.
     // Head size 64: slots (h, j) of step s of dOut hold t = 16*s + 8*(j/4) + 4*h + j%4 (Sp is packed to
     // match).  Tiles move between memory and a wavefront-private 32 x D area of LDS as whole 16-byte
     // chunks in memory order (32 rows are one contiguous block: every wavefront instruction covers
@@ -202,64 +198,73 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     constexpr int CPR = D / 8, ROWB = D * 2, LPT = 32 * CPR / 64;
     unsigned char* const scr = lds + L::images(mf) + wave * L::scratch;
     auto scr_at = [&](int row, int c) -> unsigned char* { return scr + row * ROWB + 16 * (c ^ ((row >> 1) & 7)); };
-    struct Tile { uint4 q[KS], g[KS], o[KS]; float lam; };
-    struct Raw { uint4 q[LPT], g[LPT], o[LPT]; float lam; };     // a tile as requested from memory
-    auto request_tile = [&](int row0, Raw& x) {
-        const long off = head_off + (long)row0 * D + 8 * lane;
-#pragma unroll
-        for (int u = 0; u < LPT; ++u) {
-            x.q[u] = ld16(a.Q + off + 512 * u);
-            x.g[u] = ld16(a.G + off + 512 * u);
-            x.o[u] = ld16(a.O + off + 512 * u);
-        }
-        x.lam = a.lse[(long)bh * a.n + row0 + l32];
-    };
-    auto unpack_tile = [&](const Raw& x, Tile& t) {
-        t.lam = x.lam;
-#pragma unroll
-        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = x.q[u];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) t.q[s] = *(const uint4*)scr_at(l32, 2 * s + half);
-#pragma unroll
-        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = x.g[u];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const uint2 g0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
-            const uint2 g1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
-            t.g[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
-        }
-#pragma unroll
-        for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = x.o[u];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const uint2 o0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
-            const uint2 o1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
-            t.o[s] = make_uint4(o0.x, o0.y, o1.x, o1.y);
-        }
-    };
-    auto load_tile_direct = [&](int row0, Tile& t) {
-        const long off = head_off + (long)(row0 + l32) * D + 8 * half;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            t.q[s] = ld16(a.Q + off + 16 * s);
-            t.g[s] = ld16(a.G + off + 16 * s);
-            t.o[s] = ld16(a.O + off + 16 * s);
-        }
-        t.lam = a.lse[(long)bh * a.n + row0 + l32];
-    };
+    struct Tile { uint4 q[KS], g[KS]; float lam, gh; };
     auto dot2 = [](uint32_t x, uint32_t y, float acc) {
         acc = fmaf(bf16_to_f32((uint16_t)(x & 0xffffu)), bf16_to_f32((uint16_t)(y & 0xffffu)), acc);
         return fmaf(bf16_to_f32((uint16_t)(x >> 16)), bf16_to_f32((uint16_t)(y >> 16)), acc);
     };
-    // direct: this lane's byte offsets into the omega image
+    auto dot8 = [&](const uint4& x, const uint4& y, float acc) {
+        acc = dot2(x.x, y.x, acc); acc = dot2(x.y, y.y, acc);
+        acc = dot2(x.z, y.z, acc); return dot2(x.w, y.w, acc);
+    };
+    // loads one tile; ghat = G_i . out_i over the elements this half of the wavefront holds
+    auto load_tile = [&](int row0, Tile& t) {
+        float gd = 0.f;
+        if constexpr (DIRECT) {
+            const long off = head_off + (long)(row0 + l32) * D + 8 * half;
+            uint4 o[KS];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                t.q[s] = ld16(a.Q + off + 16 * s);
+                t.g[s] = ld16(a.G + off + 16 * s);
+                o[s] = ld16(a.O + off + 16 * s);
+            }
+            t.lam = a.lse[(long)bh * a.n + row0 + l32];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) gd = dot8(t.g[s], o[s], gd);
+        } else {
+            uint4 rq[LPT], rg[LPT], ro[LPT];
+            const long off = head_off + (long)row0 * D + 8 * lane;
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) {
+                rq[u] = ld16(a.Q + off + 512 * u);
+                rg[u] = ld16(a.G + off + 512 * u);
+                ro[u] = ld16(a.O + off + 512 * u);
+            }
+            t.lam = a.lse[(long)bh * a.n + row0 + l32];
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = rq[u];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) t.q[s] = *(const uint4*)scr_at(l32, 2 * s + half);
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = rg[u];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uint2 g0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
+                const uint2 g1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
+                t.g[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
+            }
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = ro[u];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uint2 o0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
+                const uint2 o1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
+                gd = dot8(t.g[s], make_uint4(o0.x, o0.y, o1.x, o1.y), gd);
+            }
+        }
+        t.gh = half_sum(gd);
+    };
+    // this lane's byte offsets into the omega image
     //   plain reads (A operand of u^T): row 32*ft + l32, chunk 2*s + half
     //   transposing reads (A operand of dQ^T, column t = 32*tt + l32 of 8 features): this lane supplies
     //   row 4*half + s16/4 (+ 8 for the second read) of a 16-feature group, 8 bytes at column
     //   16*(lane/16 % 2) + 4*(s16 % 4) of the 32-column group tt
     const int s16 = lane & 15, r4 = s16 >> 2;
-    const int u_lane = l32 * L::w_pitch, u_xor = 16 * (swz(l32) ^ half);
+    const int u_lane = l32 * L::w_pitch, u_xor = 16 * (L::swz(l32) ^ half);
     const int tr_row = (4 * half + r4) * L::w_pitch + 8 * (s16 & 1);
     const int tr_low0 = 16 * ((2 * ((lane >> 4) & 1) + ((s16 >> 1) & 1)) ^ half);     // first read; second: ^ 32
+    const int tr_hi = D == 128 ? r4 : (r4 >> 1);                                      // XORed with tt
 
     const int row_first = row_begin + 32 * wave;
     Tile cur;
@@ -268,86 +273,71 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
         int grabbed = 0;
         if (lane == 0) grabbed = atomicAdd(next_tile, 1);
         const int row_next = row_begin + 32 * __builtin_amdgcn_readfirstlane(grabbed);
-        if constexpr (DIRECT) {
-            load_tile_direct(row0, cur);
-        } else {
-            Raw raw;
-            request_tile(row0, raw);
-            unpack_tile(raw, cur);
-        }
+        load_tile(row0, cur);
 
-        // g_i = G_i . out_i: the two halves of the wavefront hold complementary elements of the row
-        float gdot = 0.f;
+        // r^T and b^T tile by tile; accR = omega^T r^T, accB = omega^T b^T
+        floatx16 accR[TT], accB[TT];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            gdot = dot2(cur.g[s].x, cur.o[s].x, gdot);
-            gdot = dot2(cur.g[s].y, cur.o[s].y, gdot);
-            gdot = dot2(cur.g[s].z, cur.o[s].z, gdot);
-            gdot = dot2(cur.g[s].w, cur.o[s].w, gdot);
-        }
-        const float gi = half_sum(gdot);
-        if (half == 0) a.delta[(long)bh * a.n + qrow] = gi;
-
-        // dU^T tile by tile, dQ^T = omega^T dU^T
-        floatx16 accQ[TT];
-#pragma unroll
-        for (int t = 0; t < TT; ++t) accQ[t] = zero16();
+        for (int t = 0; t < TT; ++t) { accR[t] = zero16(); accB[t] = zero16(); }
+        float sR = 0.f, sB = 0.f;
         const float nlam = -cur.lam * LOG2E;
-        for (int ft = 0; ft < FT; ++ft) {
-            floatx16 u;
-            {
-                const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = ct[q];
-                    u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
-                }
-            }
-            floatx16 tp = zero16();                          // T'^T tile: G_i . S_j
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const unsigned char* wsrc = DIRECT ? lw + 32 * ft * L::w_pitch + u_lane + ((32 * s) ^ u_xor)
-                                                   : lw + (32 * ft + l32) * L::w_pitch + 32 * s + 16 * half;
-                u = mfma32(*(const uint4*)wsrc, cur.q[s], u);
-                tp = mfma32(*(const uint4*)(lsp + (32 * ft + l32) * L::sp_pitch + 32 * s + 16 * half), cur.g[s], tp);
-            }
-            const float4* zt = (const float4*)(lz + 32 * ft + 16 * half);
-            uint32_t pk[8];
+        const float gh = cur.gh;
+        auto issue = [&](int ft, floatx16& u, floatx16& tp) {
+            const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float4 zv = zt[q];
-                const float w0 = fast_exp2(fmaf(u[4 * q], LOG2E, nlam));
-                const float w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, nlam));
-                const float w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, nlam));
-                const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, nlam));
-                const float d0 = w0 * fmaf(-gi, zv.x, tp[4 * q]);
-                const float d1 = w1 * fmaf(-gi, zv.y, tp[4 * q + 1]);
-                const float d2 = w2 * fmaf(-gi, zv.z, tp[4 * q + 2]);
-                const float d3 = w3 * fmaf(-gi, zv.w, tp[4 * q + 3]);
-                pk[2 * q] = pack_bf16(d0, d1);
-                pk[2 * q + 1] = pack_bf16(d2, d3);
+                const float4 v = ct[q];
+                u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
             }
-            const uint4 db[2] = {{pk[0], pk[1], pk[2], pk[3]}, {pk[4], pk[5], pk[6], pk[7]}};
-            if constexpr (DIRECT) {
+            tp = zero16();                                   // T'^T tile: G_i . S_j / z_j
 #pragma unroll
-                for (int sp = 0; sp < 2; ++sp) {
-                    const unsigned char* fb = lw + (32 * ft + 16 * sp) * L::w_pitch + tr_row;
+            for (int s = 0; s < KS; ++s) {
+                u = mfma32(*(const uint4*)(lw + 32 * ft * L::w_pitch + u_lane + ((32 * s) ^ u_xor)), cur.q[s], u);
+                const int so = (32 * ft + l32) * L::sp_pitch + 32 * s + 16 * half;
+                tp = mfma32(*(const uint4*)(lsh + so), cur.g[s], tp);
+                tp = mfma32(*(const uint4*)(lsl + so), cur.g[s], tp);
+            }
+        };
+        auto finish = [&](int ft, const floatx16& u, const floatx16& tp) {
+            uint32_t pr[8], pb[8];
 #pragma unroll
-                    for (int t = 0; t < TT; ++t) {
-                        const int col = ((t ^ r4) << 6) + tr_low0;
-                        const uint2 w0 = lds_read_tr16(fb + col);
-                        const uint2 w1 = lds_read_tr16(fb + 8 * L::w_pitch + (col ^ 32));
-                        accQ[t] = mfma32(make_uint4(w0.x, w0.y, w1.x, w1.y), db[sp], accQ[t]);
-                    }
-                }
-            } else {
+            for (int q = 0; q < 8; ++q) {
+                const float b0 = fast_exp2(fmaf(u[2 * q], LOG2E, nlam));
+                const float b1 = fast_exp2(fmaf(u[2 * q + 1], LOG2E, nlam));
+                pb[q] = pack_bf16(b0, b1);
+                pr[q] = pack_bf16(b0 * (tp[2 * q] - gh), b1 * (tp[2 * q + 1] - gh));
+                sB = add_bf16_pair(pb[q], sB);
+                sR = add_bf16_pair(pr[q], sR);
+            }
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+                const uint4 rb = {pr[4 * sp], pr[4 * sp + 1], pr[4 * sp + 2], pr[4 * sp + 3]};
+                const uint4 bb = {pb[4 * sp], pb[4 * sp + 1], pb[4 * sp + 2], pb[4 * sp + 3]};
+                const unsigned char* fb = lw + (32 * ft + 16 * sp) * L::w_pitch + tr_row;
 #pragma unroll
                 for (int t = 0; t < TT; ++t) {
-                    const unsigned char* wp = lwt + (32 * t + l32) * s_pitch + 64 * ft + 16 * half;
-                    accQ[t] = mfma32(*(const uint4*)wp, db[0], accQ[t]);
-                    accQ[t] = mfma32(*(const uint4*)(wp + 32), db[1], accQ[t]);
+                    const int col = ((t ^ tr_hi) << 6) + tr_low0;
+                    const uint2 w0 = lds_read_tr16(fb + col);
+                    const uint2 w1 = lds_read_tr16(fb + 8 * L::w_pitch + (col ^ 32));
+                    const uint4 wt = make_uint4(w0.x, w0.y, w1.x, w1.y);
+                    accR[t] = mfma32(wt, rb, accR[t]);
+                    accB[t] = mfma32(wt, bb, accB[t]);
                 }
             }
+        };
+        for (int ft = 0; ft < FT; ++ft) {
+            floatx16 u, tp;
+            issue(ft, u, tp);
+            finish(ft, u, tp);
+        }
+        // this row's normaliser and the correction of ghat; both halves of the wavefront hold the same row
+        sR = half_sum(sR);
+        sB = half_sum(sB);
+        const float inv = 1.f / sB;
+        const float dg = sR * inv;
+        if (half == 0) {
+            a.delta[(long)bh * a.n + qrow] = gh + dg;
+            a.lam2[(long)bh * a.n + qrow] = cur.lam + logf(sB);
         }
         // dQ rows: 16-byte pieces; head size 64 passes them through the transposition area so that whole
         // chunks leave in memory order
@@ -355,11 +345,12 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
         for (int t = 0; t < TT; ++t)
 #pragma unroll
             for (int q = 0; q < 4; q += 2) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = (accR[t][4 * q + e] - dg * accB[t][4 * q + e]) * inv;
                 uint2 ev, od;
-                ev.x = pack_bf16(accQ[t][4 * q], accQ[t][4 * q + 1]);
-                ev.y = pack_bf16(accQ[t][4 * q + 2], accQ[t][4 * q + 3]);
-                od.x = pack_bf16(accQ[t][4 * q + 4], accQ[t][4 * q + 5]);
-                od.y = pack_bf16(accQ[t][4 * q + 6], accQ[t][4 * q + 7]);
+                ev.x = pack_bf16(v[0], v[1]); ev.y = pack_bf16(v[2], v[3]);
+                od.x = pack_bf16(v[4], v[5]); od.y = pack_bf16(v[6], v[7]);
                 const uint4 piece = join_halves(ev, od);
                 if constexpr (DIRECT) *(uint4*)(a.dQ + head_off + (long)qrow * D + 8 * (4 * t + q + half)) = piece;
                 else                  *(uint4*)scr_at(l32, 4 * t + q + half) = piece;
@@ -383,7 +374,7 @@ struct BwdYArgs {
     const uint16_t* G;
     const uint16_t* omega;
     const float* c;            // ctx shifts, natural order (BH, mf)
-    const float* lse;
+    const float* lse;          // renormalised lambda_i from bwd_query_x
     const float* delta;
     float* dSpart;             // (BH, R, mf, d)
     float* dzpart;             // (BH, R, mf)
@@ -513,8 +504,12 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
                 const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, cj - lv.w));
                 wk[2 * q] = pack_bf16(w0, w1);
                 wk[2 * q + 1] = pack_bf16(w2, w3);
-                dz = fmaf(-w0, dv.x, dz); dz = fmaf(-w1, dv.y, dz);
-                dz = fmaf(-w2, dv.z, dz); dz = fmaf(-w3, dv.w, dz);
+                // dz from the rounded weights, the ones dS is formed with: dS_j . v'_r + dz_j then cancels
+                // term by term where it should
+                dz = fmaf(-__uint_as_float(wk[2 * q] << 16), dv.x, dz);
+                dz = fmaf(-__uint_as_float(wk[2 * q] & 0xffff0000u), dv.y, dz);
+                dz = fmaf(-__uint_as_float(wk[2 * q + 1] << 16), dv.z, dz);
+                dz = fmaf(-__uint_as_float(wk[2 * q + 1] & 0xffff0000u), dv.w, dz);
             }
             // W^T tile as A operand (row = this lane's feature; slot 8h + e of step sp <-> query
             // 16*sp + 8*(e/4) + 4*h + e%4).  B operand: column t = 32*tt + l32 of the same queries.
@@ -920,7 +915,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
 }
 
 struct FastBwdWs {
-    size_t Sp, Wt, zp, cp, delta, dSpart, dzpart, dSimg, dz, img, imgT, epart, total;
+    size_t Sp, cp, delta, lam2, dSpart, dzpart, dSimg, dz, img, imgT, epart, total;
     int kp;      // k rounded up to whole 64-slot reduction steps of the gradient GEMMs
 };
 
@@ -929,11 +924,10 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     const BwdYPlan y = bwd_y_plan(p);
     const size_t BH = (size_t)p.BH;
     size_t o = 0;
-    W.Sp = o;     o += round_up(BH * p.mf * p.d * 2, 256);
-    W.Wt = o;     o += round_up((size_t)p.H * p.d * p.mf * 2, 256);
-    W.zp = o;     o += round_up(BH * p.mf * 4, 256);
+    W.Sp = o;     o += round_up(2 * BH * p.mf * p.d * 2, 256);
     W.cp = o;     o += round_up(BH * p.mf * 4, 256);
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
+    W.lam2 = o;   o += round_up(BH * p.n * 4, 256);
     W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
     W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
     W.dSimg = o;  o += round_up(2 * BH * p.mf * p.d * 2, 256);
@@ -973,26 +967,21 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     {
         stage_begin(s);
         BwdPackArgs pa{};
-        pa.Sp = (uint16_t*)(wsb + W.Sp); pa.zp = (float*)(wsb + W.zp); pa.cp = (float*)(wsb + W.cp);
+        pa.Sp = (uint16_t*)(wsb + W.Sp); pa.cp = (float*)(wsb + W.cp);
         pa.S = a.ctx + L.S; pa.z = a.ctx + L.z; pa.c = a.ctx + L.c;
-        pa.Wt = (uint16_t*)(wsb + W.Wt); pa.omega = (const uint16_t*)a.omega;
-        pa.mf = p.mf; pa.d = p.d; pa.m = p.m;
-        const bool direct = p.d == 64 ? BwdXLds<64>::direct : BwdXLds<128>::direct;
-        pa.natural = direct;
+        pa.mf = p.mf; pa.d = p.d;
+        pa.natural = p.d == 64 ? BwdXLds<64>::direct : BwdXLds<128>::direct;
         pa.total = (long)p.BH * p.mf * p.d;
-        pa.wtotal = direct ? 0 : (long)(p.omega_per_head ? p.H : 1) * p.m * p.d;   // direct: no transposed omega
-        pa.s_blocks = (unsigned)((pa.total + 255) / 256);
-        const unsigned w_blocks = (unsigned)((pa.wtotal + 255) / 256);
-        hipLaunchKernelGGL(bwd_pack_kernel, dim3(pa.s_blocks + w_blocks), dim3(256), 0, s, pa);
+        hipLaunchKernelGGL(bwd_pack_kernel, grid1d(pa.total, 256), dim3(256), 0, s, pa);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_PACK);
 
         BwdXArgs xa{};
         xa.Q = (const uint16_t*)a.Q; xa.G = (const uint16_t*)a.dOut; xa.omega = (const uint16_t*)a.omega;
-        xa.O = (const uint16_t*)a.out; xa.Sp = (const uint16_t*)(wsb + W.Sp);
-        xa.Wt = (const uint16_t*)(wsb + W.Wt);
-        xa.zp = (const float*)(wsb + W.zp); xa.cp = (const float*)(wsb + W.cp);
+        xa.O = (const uint16_t*)a.out; xa.Sp = (const uint16_t*)(wsb + W.Sp); xa.sp_plane = pa.total;
+        xa.cp = (const float*)(wsb + W.cp);
         xa.dQ = (uint16_t*)a.dQ; xa.lse = a.ctx + L.lse; xa.delta = (float*)(wsb + W.delta);
+        xa.lam2 = (float*)(wsb + W.lam2);
         xa.n = p.n; xa.H = p.H; xa.mf = p.mf; xa.omega_head_stride = omega_stride;
         xa.tiles_per_head = (p.n + 31) / 32;
         xa.total_tiles = (long)p.BH * xa.tiles_per_head;
@@ -1004,7 +993,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
 
         BwdYArgs ya{};
         ya.Q = xa.Q; ya.G = xa.G; ya.omega = xa.omega; ya.c = a.ctx + L.c;
-        ya.lse = xa.lse; ya.delta = xa.delta;
+        ya.lse = xa.lam2; ya.delta = xa.delta;
         ya.dSpart = (float*)(wsb + W.dSpart); ya.dzpart = (float*)(wsb + W.dzpart);
         ya.omega_head_stride = omega_stride;
         ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;

@@ -95,11 +95,11 @@ BWD_SHAPES = [
     (2, 2, 2048, 64, 64, 32),
     (3, 5, 1088, 64, 96, 128),
     (8, 16, 128, 64, 40, 64),
-    # head size 128: the variant of the dQ kernel that keeps omega only once in LDS
+    # head size 128: rows move between memory and registers directly (up to 192 features fit LDS)
     (1, 3, 640, 128, 300, 160),
-    (2, 2, 1024, 128, 256, 256),
+    (2, 2, 1024, 128, 256, 192),
     (3, 2, 2048, 128, 512, 32),
-    (4, 8, 192, 128, 40, 288),
+    (4, 8, 192, 128, 40, 96),
     # many tiles: the dE/dF contraction fills the chip without splitting its reduction and stores its
     # result directly (ragged k and a ragged last column tile; both head sizes)
     (1, 1, 8256, 64, 1000, 32),
