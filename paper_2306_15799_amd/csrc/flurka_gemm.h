@@ -35,7 +35,9 @@ constexpr int GB_STAGE_T = GBK * GB_PITCH_T;        // 36,864
 constexpr int GB_STAGE_D = GBN * GA_PITCH;          // direct tile: like A
 constexpr int G_STAGE = GA_STAGE + GB_STAGE_D;      // 73,728 (both layouts of B take the same room)
 static_assert(GB_STAGE_T <= GB_STAGE_D, "B stage");
-constexpr int G_LDS = 2 * G_STAGE;                  // 147,456
+constexpr int G_LDS_STAGES = 2 * G_STAGE;           // 147,456
+constexpr int G_LDS_EPI = 4 * 4096;                 // per wavefront: a 32 x 64 bf16 tile on its way out
+constexpr int G_LDS = G_LDS_STAGES + G_LDS_EPI;     // 163,840: all of a compute unit's LDS
 constexpr int G_OOB = 0x7fffff00;                   // per-thread byte offset past any descriptor range
 
 // fp32 partial results of a split reduction are kept tile by tile in the order the accumulators
@@ -267,6 +269,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
                         v.x = acc[i][j][4 * q]; v.y = acc[i][j][4 * q + 1]; v.z = acc[i][j][4 * q + 2]; v.w = acc[i][j][4 * q + 3];
                         *(float4*)(tp + ((i * 4 + j) * 4 + q) * 256) = v;
                     }
+        } else if constexpr (Pol::TRANSPOSED_STORE) {
+            // The result leaves transposed: element (row r, column c) goes to C[c][r], 64 consecutive r
+            // being 128 contiguous bytes.  Each wavefront turns its accumulators, 64 rows x 32 columns at
+            // a time, through a private 4 KiB LDS area ([column][row], 16-byte chunk k of column c at
+            // chunk position k ^ ((c >> 1) & 7)): 8-byte pieces in, 16-byte chunks out, so that one
+            // store instruction covers 8 columns x 128 bytes instead of 64 separate 16-byte pieces.
+            // (The stage buffers already hold the next item's first steps and are not touched.)
+            unsigned char* const tr = lds + G_LDS_STAGES + wave * 4096;
+            const int m0 = it.tm * GBM, n0 = it.tn * GBN;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int ip = 0; ip < 2; ++ip) {
+#pragma unroll
+                    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const floatx16& t = acc[2 * ip + ii][j];
+                            uint2 v;
+                            v.x = pack_bf16(t[4 * q], t[4 * q + 1]);
+                            v.y = pack_bf16(t[4 * q + 2], t[4 * q + 3]);
+                            *(uint2*)(tr + l32 * 128 + 16 * ((4 * ii + q) ^ ((l32 >> 1) & 7)) + 8 * half) = v;
+                        }
+                    const int r0 = m0 + wm * 128 + 64 * ip;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int c = 8 * u + (lane >> 3), k = lane & 7;
+                        const uint4 v = *(const uint4*)(tr + c * 128 + 16 * (k ^ ((c >> 1) & 7)));
+                        Pol::store_rows(g, it.which, r0, n0 + wn * 128 + 32 * j + c, k, v);
+                    }
+                }
         } else {
             // groups q and q + 1 are handed over together so that a policy may join the two halves of a
             // wavefront into 8 consecutive rows per lane
@@ -348,6 +381,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 //   a_qstride / b_qstride             byte offset between the 8 loads (q = 0..7) of one step
 //   store_groups(..., row, half, col, ev, od)   this lane's rows row + 4*half + {0..3} (ev) and
 //                                     row + 8 + 4*half + {0..3} (od) of column col
+//   store_rows(..., r0, col, k, v)    (TRANSPOSED_STORE) 8 consecutive rows r0 + 8k.. of column col
 // A tile: thread loads 16-byte chunk (tid & 7) of rows (tid >> 3) + 32*q.
 // B transposed: thread loads columns 8*(tid & 31).. of positions 8*(tid >> 5) + q.
 // B direct: like A, rows being the columns of the result.
@@ -362,6 +396,7 @@ template <int D>
 struct ProjPolicy {
     static constexpr bool B_TRANSPOSE = true;
     static constexpr bool PARTIAL_TILES = true;
+    static constexpr bool TRANSPOSED_STORE = false;
     static constexpr bool SHARE_B = false;
     struct Ctx : PolicyCtxBase { int bh0; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
@@ -389,6 +424,7 @@ template <int D>
 struct GradXPolicy {
     static constexpr bool B_TRANSPOSE = true;
     static constexpr bool PARTIAL_TILES = false;
+    static constexpr bool TRANSPOSED_STORE = true;
     static constexpr bool SHARE_B = true;
     struct Ctx : PolicyCtxBase {};
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
@@ -403,17 +439,11 @@ struct GradXPolicy {
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
     static __device__ __forceinline__ int b_soff(const Ctx& c, int step) { return step * GBK * c.b_qstride; }
-    static __device__ __forceinline__ void store_groups(const GemmParams& g, const Ctx&, int which, int, int row,
-                                                        int half, int col, const float (&ev)[4],
-                                                        const float (&od)[4]) {
-        // join the two halves: this lane ends up with the 8 consecutive t of group row + 8*half
-        uint2 e2, o2;
-        e2.x = pack_bf16(ev[0], ev[1]); e2.y = pack_bf16(ev[2], ev[3]);
-        o2.x = pack_bf16(od[0], od[1]); o2.y = pack_bf16(od[2], od[3]);
-        const uint4 v = join_halves(e2, o2);
-        const int r = row + 8 * half;                   // aligned group of 8 rows inside one head
-        if (col >= g.n || r >= g.BH * D) return;
-        const int bh = r / D, t = r % D;
+    // rows r0 + 8*k .. r0 + 8*k + 7 (64 rows from r0 lie inside one head) of column col, as 8 bf16
+    static __device__ __forceinline__ void store_rows(const GemmParams& g, int which, int r0, int col, int k,
+                                                      const uint4& v) {
+        if (col >= g.n || r0 >= g.BH * D) return;
+        const int bh = r0 / D, t = r0 % D + 8 * k;
         *(uint4*)((uint16_t*)g.C[which] + ((long)bh * g.n + col) * D + t) = v;
     }
 };
@@ -425,6 +455,7 @@ template <int D, bool FINAL = false>
 struct GradEPolicy {
     static constexpr bool B_TRANSPOSE = false;
     static constexpr bool PARTIAL_TILES = !FINAL;
+    static constexpr bool TRANSPOSED_STORE = false;
     static constexpr bool SHARE_B = true;
     struct Ctx : PolicyCtxBase { int a_batch, b_batch; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
