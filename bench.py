@@ -70,7 +70,6 @@ KERNEL_TRACE_NAME = {
     "key_state": "key_state_kernel<{d}, false>",
     "merge_pack": "merge_pack_kernel",
     "query_stream": "query_stream_kernel<{d}, {elu}, {qs_waves}, 1, {elu}>",     # staged tiles: elu1 only
-    "bwd_pack": "bwd_pack_kernel",
     "bwd_query_x": "bwd_query_x_kernel<{d}>",
     "bwd_query_y": "bwd_query_y_kernel<{d}>",
     "bwd_merge": "bwd_merge_kernel",

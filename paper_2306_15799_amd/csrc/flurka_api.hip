@@ -232,7 +232,6 @@ const char* flurka_profile_stage_name(int id) {
         case STAGE_K_KEY_STATE: return "key_state:key_state";
         case STAGE_K_MERGE_PACK: return "key_state:merge_pack";
         case STAGE_K_QUERY_STREAM: return "query_stream:query_stream";
-        case STAGE_K_BWD_PACK: return "bwd_query:bwd_pack";
         case STAGE_K_BWD_X: return "bwd_query:bwd_query_x";
         case STAGE_K_BWD_Y: return "bwd_query:bwd_query_y";
         case STAGE_K_BWD_MERGE: return "bwd_key:bwd_merge";

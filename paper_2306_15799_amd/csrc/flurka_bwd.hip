@@ -41,48 +41,6 @@ static inline dim3 grid1d(long total, int block) { return dim3((unsigned)((total
 
 constexpr float LOG2E = FLURKA_LOG2E;
 
-// position p (0..15) inside a group of 16 operand slots <-> element offset 8*(e/4) + 4*h + e%4 with
-// p = 8*h + e: the order in which a 32x32 accumulator hands 16 consecutive rows to the next MFMA
-__host__ __device__ inline int slot_to_elem16(int p) {
-    const int e = p & 7, h = (p >> 3) & 1;
-    return 8 * (e >> 2) + 4 * h + (e & 3);
-}
-
-// ---------------------------------------------------------------------------
-// Operand images for bwd_query_x, per head (S, z, c from ctx):
-//   Sp  2 x (BH, mf, d)  hi and lo bf16 terms of S[j][t(slot)] / z[j]     A operand of T'^T = (S/z) G^T
-//   cp  (BH, mf)         c + ln z in accumulator order of a 32-feature tile
-// t(slot): head size 64 stages dOut through LDS in accumulator order (slot 8h + e of a group of 16 holds
-// t = 8*(e/4) + 4*h + e%4); larger head sizes load dOut rows as they lie (`natural`).
-// ---------------------------------------------------------------------------
-struct BwdPackArgs {
-    uint16_t* Sp; float* cp; const float* S; const float* z; const float* c;
-    int mf, d;
-    int natural;
-    long total;              // BH * mf * d elements of S
-};
-
-__global__ void bwd_pack_kernel(BwdPackArgs a) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= a.total) return;
-    const int mf = a.mf, d = a.d;
-    const long bh = idx / ((long)mf * d);
-    const int rem = (int)(idx % ((long)mf * d));
-    if (rem < mf) {
-        const int slot = rem;
-        const int g = slot & 15, h = (slot >> 4) & 1;
-        const int fz = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
-        a.cp[bh * mf + slot] = a.c[bh * mf + fz] + logf(a.z[bh * mf + fz]);
-    }
-    // Sp: rem = j * d + slot
-    const int j = rem / d, slot = rem % d;
-    const int t = a.natural ? slot : (slot & ~15) + slot_to_elem16(slot & 15);
-    const float v = a.S[(bh * mf + j) * d + t] / a.z[bh * mf + j];
-    const uint16_t hi = f32_to_bf16(v);
-    a.Sp[idx] = hi;
-    a.Sp[a.total + idx] = f32_to_bf16(v - bf16_to_f32(hi));
-}
-
 typedef short short4v __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint2 lds_read_tr16(const unsigned char* p) {
     const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
@@ -97,9 +55,9 @@ struct BwdXArgs {
     const uint16_t* G;         // dOut
     const uint16_t* O;         // out
     const uint16_t* omega;     // (H|1, m, d)
-    const uint16_t* Sp;        // 2 x (BH, mf, d): hi, lo terms of S / z
-    long sp_plane;             // BH * mf * d
-    const float* cp;           // (BH, mf)  c + ln z, accumulator order
+    const float* S;            // ctx: (BH, mf, d), (BH, mf), (BH, mf)
+    const float* z;
+    const float* c;
     const float* lse;          // (BH, n)  lambda_i, written by the forward
     uint16_t* dQ;
     float* delta;              // (BH, n)  g_i
@@ -163,17 +121,37 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     if (seg_end > tile_end) seg_end = tile_end;
     if (seg != tile_begin) __syncthreads();          // every wavefront is done with the previous image
     {
+        // omega as it lies; S_j / z_j as two bf16 terms (hi + lo), 8 slots per chunk: the slots of dOut's
+        // operand order (head size 64: slot 8h + e of a group of 16 holds t = 8*(e/4) + 4*h + e%4; direct:
+        // t = slot); c + ln z in the accumulator order of a 32-feature tile
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
-        const uint16_t* spg = a.Sp + (long)bh * mf * D;
+        const float* Sg = a.S + (long)bh * mf * D;
+        const float* zg = a.z + (long)bh * mf;
         constexpr int cpr = D / 8;
         for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = ld16(og + (long)r * D + 8 * q);
-            *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = ld16(spg + (long)r * D + 8 * q);
-            *(uint4*)(lsl + r * L::sp_pitch + 16 * q) = ld16(spg + a.sp_plane + (long)r * D + 8 * q);
+            const int t0 = DIRECT ? 8 * q : 16 * (q >> 1) + 4 * (q & 1);
+            const float4 s0 = *(const float4*)(Sg + (long)r * D + t0);
+            const float4 s1 = *(const float4*)(Sg + (long)r * D + t0 + (DIRECT ? 4 : 8));
+            const float zr = zg[r];
+            const float v[8] = {s0.x / zr, s0.y / zr, s0.z / zr, s0.w / zr, s1.x / zr, s1.y / zr, s1.z / zr, s1.w / zr};
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint16_t h0 = f32_to_bf16(v[2 * e]), h1 = f32_to_bf16(v[2 * e + 1]);
+                hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                lo[e] = pack_bf16(v[2 * e] - bf16_to_f32(h0), v[2 * e + 1] - bf16_to_f32(h1));
+            }
+            *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *(uint4*)(lsl + r * L::sp_pitch + 16 * q) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         }
-        const float* cg = a.cp + (long)bh * mf;
-        for (int c = tid; c < mf; c += X_NW * 64) lc[c] = cg[c];
+        const float* cg = a.c + (long)bh * mf;
+        for (int slot = tid; slot < mf; slot += X_NW * 64) {
+            const int g = slot & 15, h = (slot >> 4) & 1;
+            const int f = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
+            lc[slot] = cg[f] + logf(zg[f]);
+        }
     }
     // tiles of the segment are handed out on demand (see query_stream_kernel): wavefront w starts with
     // tile w and takes the next free one from this counter whenever it finishes
@@ -915,7 +893,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
 }
 
 struct FastBwdWs {
-    size_t Sp, cp, delta, lam2, dSpart, dzpart, dSimg, dz, img, imgT, epart, total;
+    size_t delta, lam2, dSpart, dzpart, dSimg, dz, img, imgT, epart, total;
     int kp;      // k rounded up to whole 64-slot reduction steps of the gradient GEMMs
 };
 
@@ -924,8 +902,6 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     const BwdYPlan y = bwd_y_plan(p);
     const size_t BH = (size_t)p.BH;
     size_t o = 0;
-    W.Sp = o;     o += round_up(2 * BH * p.mf * p.d * 2, 256);
-    W.cp = o;     o += round_up(BH * p.mf * 4, 256);
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.lam2 = o;   o += round_up(BH * p.n * 4, 256);
     W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
@@ -965,21 +941,10 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     const long omega_stride = p.omega_per_head ? (long)p.m * p.d : 0;
     flurka_status st;
     {
-        stage_begin(s);
-        BwdPackArgs pa{};
-        pa.Sp = (uint16_t*)(wsb + W.Sp); pa.cp = (float*)(wsb + W.cp);
-        pa.S = a.ctx + L.S; pa.z = a.ctx + L.z; pa.c = a.ctx + L.c;
-        pa.mf = p.mf; pa.d = p.d;
-        pa.natural = p.d == 64 ? BwdXLds<64>::direct : BwdXLds<128>::direct;
-        pa.total = (long)p.BH * p.mf * p.d;
-        hipLaunchKernelGGL(bwd_pack_kernel, grid1d(pa.total, 256), dim3(256), 0, s, pa);
-        FLURKA_CHECK_LAUNCH();
-        stage_end(s, STAGE_K_BWD_PACK);
-
         BwdXArgs xa{};
         xa.Q = (const uint16_t*)a.Q; xa.G = (const uint16_t*)a.dOut; xa.omega = (const uint16_t*)a.omega;
-        xa.O = (const uint16_t*)a.out; xa.Sp = (const uint16_t*)(wsb + W.Sp); xa.sp_plane = pa.total;
-        xa.cp = (const float*)(wsb + W.cp);
+        xa.O = (const uint16_t*)a.out;
+        xa.S = a.ctx + L.S; xa.z = a.ctx + L.z; xa.c = a.ctx + L.c;
         xa.dQ = (uint16_t*)a.dQ; xa.lse = a.ctx + L.lse; xa.delta = (float*)(wsb + W.delta);
         xa.lam2 = (float*)(wsb + W.lam2);
         xa.n = p.n; xa.H = p.H; xa.mf = p.mf; xa.omega_head_stride = omega_stride;

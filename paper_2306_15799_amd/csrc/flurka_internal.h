@@ -114,7 +114,6 @@ enum Stage {
     STAGE_K_KEY_STATE = 9,
     STAGE_K_MERGE_PACK = 10,
     STAGE_K_QUERY_STREAM = 11,
-    STAGE_K_BWD_PACK = 12,
     STAGE_K_BWD_X = 13,
     STAGE_K_BWD_Y = 14,
     STAGE_K_BWD_MERGE = 15,
