@@ -78,15 +78,23 @@ struct BwdXArgs {
 // Either way 16 consecutive rows put the same chunk into 16 different bank groups (plain reads down a
 // column of rows), and 4 consecutive rows put a 64-byte column group into 4 different quarters of the
 // banks (transposing reads).
-template <int D>
+// RING (d = 128 with more features than all three images have room for): the lo terms of S/z are not
+// resident; the wavefronts of a workgroup walk the feature tiles in step, and the 32 lo rows of the next
+// tile are built from ctx into one of two LDS slots while the current tile is worked on (one barrier
+// per feature tile).
+template <int D, bool RING = false>
 struct BwdXLds {
     static_assert(D == 64 || D == 128, "row swizzles are written for 128- and 256-byte rows");
+    static_assert(!RING || D == 128, "the ring variant fills one slot with 512 threads x 16 bytes");
     static constexpr bool direct = D > 64;
     static constexpr int nw = 8;                     // wavefronts per workgroup: two per SIMD (the two
                                                      // accumulator sets leave no room for a third)
     static constexpr int w_pitch = D * 2;                                // omega rows
     static constexpr int sp_pitch = (D + 8) * 2;                         // Sp rows
-    static __host__ __device__ int images(int mf) { return mf * w_pitch + 2 * mf * sp_pitch + mf * 4; }
+    static __host__ __device__ int lo_rows(int mf) { return RING ? 64 : mf; }
+    static __host__ __device__ int images(int mf) {
+        return mf * w_pitch + mf * sp_pitch + lo_rows(mf) * sp_pitch + mf * 4;
+    }
     static constexpr int scratch = direct ? 0 : 32 * D * 2;              // per wavefront: one 32-row tile
     static __host__ __device__ int total(int mf) { return images(mf) + nw * scratch + 16; }    // + tile counter
     static __host__ __device__ int swz(int r) {
@@ -94,10 +102,12 @@ struct BwdXLds {
     }
 };
 
-template <int D>
-__global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXArgs a) {
+constexpr int X_THREADS = 512;
+template <int D, bool RING>
+__global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    using L = BwdXLds<D>;
+    using L = BwdXLds<D, RING>;
+    static_assert(L::nw * 64 == X_THREADS, "launch bounds");
     constexpr bool DIRECT = L::direct;
     constexpr int X_NW = L::nw;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -105,8 +115,8 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     const int mf = a.mf;
     unsigned char* lw = lds;                              // omega    [feature][d], swizzled chunks
     unsigned char* lsh = lw + mf * L::w_pitch;            // Sp hi    [feature][t slot]
-    unsigned char* lsl = lsh + mf * L::sp_pitch;          // Sp lo
-    float* lc = (float*)(lsl + mf * L::sp_pitch);         // c'
+    unsigned char* lsl = lsh + mf * L::sp_pitch;          // Sp lo    (RING: two slots of 32 rows)
+    float* lc = (float*)(lsl + L::lo_rows(mf) * L::sp_pitch);    // c'
     constexpr int KS = D / 16;      // reduction steps over d (also over the t slots of G)
     constexpr int TT = D / 32;      // 32-row tiles of dQ^T
     const int FT = mf / 32;
@@ -120,31 +130,42 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     long seg_end = (long)(bh + 1) * a.tiles_per_head;
     if (seg_end > tile_end) seg_end = tile_end;
     if (seg != tile_begin) __syncthreads();          // every wavefront is done with the previous image
+    // omega as it lies; S_j / z_j as two bf16 terms (hi + lo), 8 slots per chunk: the slots of dOut's
+    // operand order (head size 64: slot 8h + e of a group of 16 holds t = 8*(e/4) + 4*h + e%4; direct:
+    // t = slot); c + ln z in the accumulator order of a 32-feature tile
+    const float* Sg = a.S + (long)bh * mf * D;
+    const float* zg = a.z + (long)bh * mf;
+    constexpr int cpr = D / 8;
+    auto sp_terms = [&](int r, int q, uint4& hi4, uint4& lo4) {      // chunk q of feature row r
+        const int t0 = DIRECT ? 8 * q : 16 * (q >> 1) + 4 * (q & 1);
+        const float4 s0 = *(const float4*)(Sg + (long)r * D + t0);
+        const float4 s1 = *(const float4*)(Sg + (long)r * D + t0 + (DIRECT ? 4 : 8));
+        const float rz = 1.f / zg[r];
+        const float v[8] = {s0.x * rz, s0.y * rz, s0.z * rz, s0.w * rz, s1.x * rz, s1.y * rz, s1.z * rz, s1.w * rz};
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint16_t h0 = f32_to_bf16(v[2 * e]), h1 = f32_to_bf16(v[2 * e + 1]);
+            hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            lo[e] = pack_bf16(v[2 * e] - bf16_to_f32(h0), v[2 * e + 1] - bf16_to_f32(h1));
+        }
+        hi4 = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        lo4 = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    };
     {
-        // omega as it lies; S_j / z_j as two bf16 terms (hi + lo), 8 slots per chunk: the slots of dOut's
-        // operand order (head size 64: slot 8h + e of a group of 16 holds t = 8*(e/4) + 4*h + e%4; direct:
-        // t = slot); c + ln z in the accumulator order of a 32-feature tile
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
-        const float* Sg = a.S + (long)bh * mf * D;
-        const float* zg = a.z + (long)bh * mf;
-        constexpr int cpr = D / 8;
         for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
             *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = ld16(og + (long)r * D + 8 * q);
-            const int t0 = DIRECT ? 8 * q : 16 * (q >> 1) + 4 * (q & 1);
-            const float4 s0 = *(const float4*)(Sg + (long)r * D + t0);
-            const float4 s1 = *(const float4*)(Sg + (long)r * D + t0 + (DIRECT ? 4 : 8));
-            const float zr = zg[r];
-            const float v[8] = {s0.x / zr, s0.y / zr, s0.z / zr, s0.w / zr, s1.x / zr, s1.y / zr, s1.z / zr, s1.w / zr};
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint16_t h0 = f32_to_bf16(v[2 * e]), h1 = f32_to_bf16(v[2 * e + 1]);
-                hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                lo[e] = pack_bf16(v[2 * e] - bf16_to_f32(h0), v[2 * e + 1] - bf16_to_f32(h1));
-            }
-            *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-            *(uint4*)(lsl + r * L::sp_pitch + 16 * q) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            uint4 hi, lo;
+            sp_terms(r, q, hi, lo);
+            *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = hi;
+            if constexpr (!RING) *(uint4*)(lsl + r * L::sp_pitch + 16 * q) = lo;
+        }
+        if constexpr (RING) {          // slot 0 <- feature tile 0
+            uint4 hi, lo;
+            sp_terms(tid / cpr, tid % cpr, hi, lo);
+            *(uint4*)(lsl + (tid / cpr) * L::sp_pitch + 16 * (tid % cpr)) = lo;
         }
         const float* cg = a.c + (long)bh * mf;
         for (int slot = tid; slot < mf; slot += X_NW * 64) {
@@ -244,78 +265,69 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
     const int tr_low0 = 16 * ((2 * ((lane >> 4) & 1) + ((s16 >> 1) & 1)) ^ half);     // first read; second: ^ 32
     const int tr_hi = D == 128 ? r4 : (r4 >> 1);                                      // XORed with tt
 
-    const int row_first = row_begin + 32 * wave;
+    // per-tile state: r^T and b^T tile by tile; accR = omega^T r^T, accB = omega^T b^T
     Tile cur;
-    for (int row0 = row_first; row0 < row_end;) {
-        const int qrow = row0 + l32;
-        int grabbed = 0;
-        if (lane == 0) grabbed = atomicAdd(next_tile, 1);
-        const int row_next = row_begin + 32 * __builtin_amdgcn_readfirstlane(grabbed);
+    floatx16 accR[TT], accB[TT];
+    float sR = 0.f, sB = 0.f, nlam = 0.f, gh = 0.f;
+    auto begin_tile = [&](int row0) {
         load_tile(row0, cur);
-
-        // r^T and b^T tile by tile; accR = omega^T r^T, accB = omega^T b^T
-        floatx16 accR[TT], accB[TT];
 #pragma unroll
         for (int t = 0; t < TT; ++t) { accR[t] = zero16(); accB[t] = zero16(); }
-        float sR = 0.f, sB = 0.f;
-        const float nlam = -cur.lam * LOG2E;
-        const float gh = cur.gh;
-        auto issue = [&](int ft, floatx16& u, floatx16& tp) {
-            const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
+        sR = 0.f; sB = 0.f;
+        nlam = -cur.lam * LOG2E;
+        gh = cur.gh;
+    };
+    // one feature tile; lo_rows: the 32 rows of the lo term of S/z that belong to it
+    auto feature_tile = [&](int ft, const unsigned char* lo_rows) {
+        floatx16 u, tp = zero16();                           // tp: T'^T tile, G_i . S_j / z_j
+        const float4* ct = (const float4*)(lc + 32 * ft + 16 * half);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = ct[q];
-                u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
-            }
-            tp = zero16();                                   // T'^T tile: G_i . S_j / z_j
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                u = mfma32(*(const uint4*)(lw + 32 * ft * L::w_pitch + u_lane + ((32 * s) ^ u_xor)), cur.q[s], u);
-                const int so = (32 * ft + l32) * L::sp_pitch + 32 * s + 16 * half;
-                tp = mfma32(*(const uint4*)(lsh + so), cur.g[s], tp);
-                tp = mfma32(*(const uint4*)(lsl + so), cur.g[s], tp);
-            }
-        };
-        auto finish = [&](int ft, const floatx16& u, const floatx16& tp) {
-            uint32_t pr[8], pb[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const float b0 = fast_exp2(fmaf(u[2 * q], LOG2E, nlam));
-                const float b1 = fast_exp2(fmaf(u[2 * q + 1], LOG2E, nlam));
-                pb[q] = pack_bf16(b0, b1);
-                pr[q] = pack_bf16(b0 * (tp[2 * q] - gh), b1 * (tp[2 * q + 1] - gh));
-                sB = add_bf16_pair(pb[q], sB);
-                sR = add_bf16_pair(pr[q], sR);
-            }
-#pragma unroll
-            for (int sp = 0; sp < 2; ++sp) {
-                const uint4 rb = {pr[4 * sp], pr[4 * sp + 1], pr[4 * sp + 2], pr[4 * sp + 3]};
-                const uint4 bb = {pb[4 * sp], pb[4 * sp + 1], pb[4 * sp + 2], pb[4 * sp + 3]};
-                const unsigned char* fb = lw + (32 * ft + 16 * sp) * L::w_pitch + tr_row;
-#pragma unroll
-                for (int t = 0; t < TT; ++t) {
-                    const int col = ((t ^ tr_hi) << 6) + tr_low0;
-                    const uint2 w0 = lds_read_tr16(fb + col);
-                    const uint2 w1 = lds_read_tr16(fb + 8 * L::w_pitch + (col ^ 32));
-                    const uint4 wt = make_uint4(w0.x, w0.y, w1.x, w1.y);
-                    accR[t] = mfma32(wt, rb, accR[t]);
-                    accB[t] = mfma32(wt, bb, accB[t]);
-                }
-            }
-        };
-        for (int ft = 0; ft < FT; ++ft) {
-            floatx16 u, tp;
-            issue(ft, u, tp);
-            finish(ft, u, tp);
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = ct[q];
+            u[4 * q] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
         }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            u = mfma32(*(const uint4*)(lw + 32 * ft * L::w_pitch + u_lane + ((32 * s) ^ u_xor)), cur.q[s], u);
+            const int so = l32 * L::sp_pitch + 32 * s + 16 * half;
+            tp = mfma32(*(const uint4*)(lsh + 32 * ft * L::sp_pitch + so), cur.g[s], tp);
+            tp = mfma32(*(const uint4*)(lo_rows + so), cur.g[s], tp);
+        }
+        uint32_t pr[8], pb[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float b0 = fast_exp2(fmaf(u[2 * q], LOG2E, nlam));
+            const float b1 = fast_exp2(fmaf(u[2 * q + 1], LOG2E, nlam));
+            pb[q] = pack_bf16(b0, b1);
+            pr[q] = pack_bf16(b0 * (tp[2 * q] - gh), b1 * (tp[2 * q + 1] - gh));
+            sB = add_bf16_pair(pb[q], sB);
+            sR = add_bf16_pair(pr[q], sR);
+        }
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            const uint4 rb = {pr[4 * sp], pr[4 * sp + 1], pr[4 * sp + 2], pr[4 * sp + 3]};
+            const uint4 bb = {pb[4 * sp], pb[4 * sp + 1], pb[4 * sp + 2], pb[4 * sp + 3]};
+            const unsigned char* fb = lw + (32 * ft + 16 * sp) * L::w_pitch + tr_row;
+#pragma unroll
+            for (int t = 0; t < TT; ++t) {
+                const int col = ((t ^ tr_hi) << 6) + tr_low0;
+                const uint2 w0 = lds_read_tr16(fb + col);
+                const uint2 w1 = lds_read_tr16(fb + 8 * L::w_pitch + (col ^ 32));
+                const uint4 wt = make_uint4(w0.x, w0.y, w1.x, w1.y);
+                accR[t] = mfma32(wt, rb, accR[t]);
+                accB[t] = mfma32(wt, bb, accB[t]);
+            }
+        }
+    };
+    auto end_tile = [&](int row0) {
+        const int qrow = row0 + l32;
         // this row's normaliser and the correction of ghat; both halves of the wavefront hold the same row
-        sR = half_sum(sR);
-        sB = half_sum(sB);
-        const float inv = 1.f / sB;
-        const float dg = sR * inv;
+        const float tR = half_sum(sR), tB = half_sum(sB);
+        const float inv = 1.f / tB;
+        const float dg = tR * inv;
         if (half == 0) {
             a.delta[(long)bh * a.n + qrow] = gh + dg;
-            a.lam2[(long)bh * a.n + qrow] = cur.lam + logf(sB);
+            a.lam2[(long)bh * a.n + qrow] = cur.lam + logf(tB);
         }
         // dQ rows: 16-byte pieces; head size 64 passes them through the transposition area so that whole
         // chunks leave in memory order
@@ -339,7 +351,40 @@ __global__ __launch_bounds__(BwdXLds<D>::nw * 64) void bwd_query_x_kernel(BwdXAr
             for (int u = 0; u < LPT; ++u)
                 *(uint4*)(ob + 512 * u) = *(const uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR);
         }
-        row0 = row_next;
+    };
+
+    if constexpr (!RING) {
+        for (int row0 = row_begin + 32 * wave; row0 < row_end;) {
+            int grabbed = 0;
+            if (lane == 0) grabbed = atomicAdd(next_tile, 1);
+            const int row_next = row_begin + 32 * __builtin_amdgcn_readfirstlane(grabbed);
+            begin_tile(row0);
+            for (int ft = 0; ft < FT; ++ft) feature_tile(ft, lsl + 32 * ft * L::sp_pitch);
+            end_tile(row0);
+            row0 = row_next;
+        }
+    } else {
+        // Rounds of X_NW tiles, one per wavefront; every wavefront runs every iteration (also without a
+        // tile in the last round), so the barriers match.  Iteration (round, ft) reads ring slot `slot`
+        // and fills the other one for the next iteration; the barrier at the top of an iteration makes
+        // that fill visible and separates it from the reads of the slot it will overwrite next.
+        const int ntiles = (row_end - row_begin) / 32;
+        const int fr = tid / cpr, fq = tid % cpr;            // this thread's chunk of a 32-row slot
+        int slot = 0;
+        for (int base = 0; base < ntiles; base += X_NW) {
+            const bool has = base + wave < ntiles;
+            const int row0 = row_begin + 32 * (has ? base + wave : 0);
+            if (has) begin_tile(row0);
+            for (int ft = 0; ft < FT; ++ft) {
+                if (base != 0 || ft != 0) __syncthreads();
+                uint4 nhi, nlo;
+                sp_terms(32 * (ft + 1 < FT ? ft + 1 : 0) + fr, fq, nhi, nlo);
+                if (has) feature_tile(ft, lsl + 32 * slot * L::sp_pitch);
+                *(uint4*)(lsl + (32 * (slot ^ 1) + fr) * L::sp_pitch + 16 * fq) = nlo;
+                slot ^= 1;
+            }
+            if (has) end_tile(row0);
+        }
     }
     }   // head segments
 }
@@ -843,8 +888,12 @@ __global__ __launch_bounds__(256) void sum_splits_bf16_kernel(SumSplitsArgs a) {
 // ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
+// bwd_query_x keeps all its operand images in LDS where they fit; at d = 128 the lo terms of S/z go
+// through a two-slot ring otherwise (see BwdXLds)
+static bool bwd_x_ring(const Problem& p) { return p.d == 128 && BwdXLds<128>::total(p.mf) > 160 * 1024; }
 static int bwd_x_lds_bytes(const Problem& p) {
-    return p.d == 64 ? BwdXLds<64>::total(p.mf) : BwdXLds<128>::total(p.mf);
+    if (p.d == 64) return BwdXLds<64>::total(p.mf);
+    return bwd_x_ring(p) ? BwdXLds<128, true>::total(p.mf) : BwdXLds<128>::total(p.mf);
 }
 
 bool fast_bwd_supported(const Problem& p) {
@@ -920,12 +969,12 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
 
 size_t fast_bwd_ws_bytes(const Problem& p) { return fast_bwd_ws_layout(p).total; }
 
-template <int D>
+template <int D, bool RING>
 static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
-    auto kern = bwd_query_x_kernel<D>;
+    auto kern = bwd_query_x_kernel<D, RING>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
         return FLURKA_ERR_LAUNCH;
-    constexpr int threads = BwdXLds<D>::nw * 64;
+    constexpr int threads = BwdXLds<D, RING>::nw * 64;
     const int grid = resident_grid((const void*)kern, threads, ldsb, xa.total_tiles);
     if (grid < 1) return FLURKA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), ldsb, s, xa);
@@ -952,7 +1001,8 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         xa.total_tiles = (long)p.BH * xa.tiles_per_head;
         const int ldsb = bwd_x_lds_bytes(p);
         stage_begin(s);
-        st = p.d == 64 ? launch_bwd_x<64>(xa, ldsb, s) : launch_bwd_x<128>(xa, ldsb, s);
+        st = p.d == 64 ? launch_bwd_x<64, false>(xa, ldsb, s)
+             : bwd_x_ring(p) ? launch_bwd_x<128, true>(xa, ldsb, s) : launch_bwd_x<128, false>(xa, ldsb, s);
         if (st != FLURKA_OK) return st;
         stage_end(s, STAGE_K_BWD_X);
 

@@ -58,10 +58,11 @@ WORKLOADS = {
 }
 
 # Not benchmark configurations: shapes derived from them for timing code paths the five do not reach.
-# D128T is the long-sequence shape as a training step with the largest feature count for which the
-# head-size-128 backward kernels hold their operand images in LDS (192; with C4's 256 the backward
-# pass runs on the generic kernels).
+# C4T is the long-sequence shape as a training step (head size 128 through the backward kernels; with
+# 256 features the dQ kernel streams one operand term through an LDS ring), D128T the same with 192
+# features, the most for which that kernel holds all its operand images in LDS.
 DERIVED_WORKLOADS = {
+    "C4T": Workload("C4T", 1, 16, 65536, 128, 512, 256, "bf16", PHI_PERFORMER, True),
     "D128T": Workload("D128T", 1, 16, 65536, 128, 512, 192, "bf16", PHI_PERFORMER, True),
 }
 

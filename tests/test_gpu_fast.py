@@ -100,6 +100,12 @@ BWD_SHAPES = [
     (2, 2, 1024, 128, 256, 192),
     (3, 2, 2048, 128, 512, 32),
     (4, 8, 192, 128, 40, 96),
+    # head size 128 with 256 features: the lo terms of S/z pass through a two-slot LDS ring, the
+    # wavefronts of a workgroup walk the feature tiles in step (rounds with idle wavefronts; shares that
+    # cross from one head into the next)
+    (2, 2, 1024, 128, 256, 256),
+    (1, 3, 2112, 128, 300, 256),
+    (8, 16, 128, 128, 40, 256),
     # many tiles: the dE/dF contraction fills the chip without splitting its reduction and stores its
     # result directly (ragged k and a ragged last column tile; both head sizes)
     (1, 1, 8256, 64, 1000, 32),
