@@ -45,6 +45,15 @@ def test_c5_forward_backward():
     print("C5", {k: f"{v:.2e}" for k, v in errs.items()})
 
 
+def test_training_step_at_the_long_sequence_shape():
+    """C4's shape as a training step, cut to two heads so that the fp64 oracle's backward stays within
+    seconds: n = 65536, d = 128, k = 512, m = 256 (|k'|^2 ~ 1450, attention concentrated on few
+    (key, feature) pairs; the dQ kernel's ring variant)."""
+    w = inputs.shrink(inputs.DERIVED_WORKLOADS["C4T"], H=2)
+    errs = gu.check_forward_backward(w, seed=0, algo="auto")
+    print("C4T/2 heads", {k: f"{v:.2e}" for k, v in errs.items()})
+
+
 @pytest.mark.parametrize("name", ["C3", "C4"])
 def test_every_output_row_is_a_weighted_mean_of_projected_values(name):
     """Property that holds at any size, checked on ALL rows of the sampled-parity workloads: the weights
