@@ -146,8 +146,10 @@ FLURKA_API flurka_status flurka_attn_fwd(const void* Q, const void* K, const voi
  * layer but prints no backward).  Given dOut = d loss / d out:
  *
  *   out         in   (B, H, n, d), the forward's result for the same inputs
- *                    (the row sums of dOut * out enter every gradient; the
- *                    generic kernels recompute them and only check the pointer)
+ *                    (the row sums g_i of dOut * out enter every gradient; the
+ *                    MFMA kernels take them from `out` as a first estimate and
+ *                    correct it with their own attention weights, the generic
+ *                    kernels recompute them and only check the pointer)
  *   dQ, dK, dV  out  (B, H, n, d)
  *   dE, dF      out  (k, n), summed over batch and heads (E, F are shared),
  *                    overwritten, not accumulated into
