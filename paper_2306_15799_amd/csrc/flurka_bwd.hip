@@ -650,7 +650,6 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
     const int FT = a.mf / 32;
     const int key = 32 * kt + l32;
     const bool live = key < a.k;
-    const int krow = live ? key : a.k - 1;
     const long img_plane = (long)a.BH * a.kp * D;
     const long ds_plane = (long)a.BH * a.mf * D;
     constexpr int P = BwdKeyLds<D>::pitch;
@@ -658,19 +657,39 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
     const int s16 = lane & 15;
     const int tr_off = (4 * half + (s16 >> 2)) * P + 2 * (16 * ((lane >> 4) & 1) + 4 * (s16 & 3));
 
-    // this key's k' and v' (8 consecutive coordinates per step), split into bf16 terms: B operands
+    // The tile's rows of K' and V' (32 x D fp32 each, contiguous in ctx) are fetched once per workgroup
+    // with whole-line loads into LDS (rows past k as zeros); every wavefront then takes this lane's key
+    // out of it (8 consecutive coordinates per step, split into bf16 terms: B operands) and the K'
+    // entries its part of the epilogue needs.  The area is reused by the feature tiles below.
+    constexpr int SP = D * 4 + 16;                  // staging row pitch: 16-byte reads down a column of rows
+    {
+        constexpr int CPRF = D / 4;                 // 16-byte chunks per fp32 row
+        for (int c = threadIdx.x; c < 32 * CPRF; c += 256) {
+            const int row = c / CPRF, q = c % CPRF;
+            const int r = 32 * kt + row;
+            float4 x = {0.f, 0.f, 0.f, 0.f}, y = {0.f, 0.f, 0.f, 0.f};
+            if (r < a.k) {
+                x = *(const float4*)(a.Kp + ((long)bh * a.k + r) * D + 4 * q);
+                y = *(const float4*)(a.Vp + ((long)bh * a.k + r) * D + 4 * q);
+            }
+            *(float4*)(lds + row * SP + 16 * q) = x;
+            *(float4*)(lds + 32 * SP + row * SP + 16 * q) = y;
+        }
+    }
+    __syncthreads();
     uint4 kb[3][KS], vb[2][KS];
     float nrm = 0.f;
+    float kpr[TT][4];                               // K'[32*kt + 8*wave + 4*half + i][32*tt + l32]
     {
-        const float* kg = a.Kp + ((long)bh * a.k + krow) * D + 8 * half;
-        const float* vg = a.Vp + ((long)bh * a.k + krow) * D + 8 * half;
+        const unsigned char* kg = lds + l32 * SP + 32 * half;
+        const unsigned char* vg = kg + 32 * SP;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             float kv[8], vv[8];
-            *(float4*)&kv[0] = *(const float4*)(kg + 16 * s);
-            *(float4*)&kv[4] = *(const float4*)(kg + 16 * s + 4);
-            *(float4*)&vv[0] = *(const float4*)(vg + 16 * s);
-            *(float4*)&vv[4] = *(const float4*)(vg + 16 * s + 4);
+            *(float4*)&kv[0] = *(const float4*)(kg + 64 * s);
+            *(float4*)&kv[4] = *(const float4*)(kg + 64 * s + 16);
+            *(float4*)&vv[0] = *(const float4*)(vg + 64 * s);
+            *(float4*)&vv[4] = *(const float4*)(vg + 64 * s + 16);
             uint32_t kh[4], km[4], kl[4], vh[4], vl[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -696,18 +715,28 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
         }
         nrm = half_sum(nrm);
         nrm = live ? 0.5f * nrm : INFINITY;       // padding keys: exponent -inf, PhiK = 0
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                kpr[tt][i] = *(const float*)(lds + (8 * wave + 4 * half + i) * SP + 4 * (32 * tt + l32));
     }
+    __syncthreads();                              // the staging area becomes the wavefronts' tile areas
 
     floatx16 accV[TT], accK[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) { accV[t] = zero16(); accK[t] = zero16(); }
     float rs = 0.f;
-    const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)l32 * D + 8 * half;
-    const uint16_t* dsg = a.dSimg + ((long)bh * a.mf + l32) * D + 8 * half;
     const float* cg = a.c + (long)bh * a.mf + 4 * half;
     const float* zg = a.dz + (long)bh * a.mf + 4 * half;
 
     for (int ft = wave; ft < FT; ft += 4) {
+        float4 cv4[4], zv4[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            cv4[q] = *(const float4*)(cg + 32 * ft + 8 * q);
+            zv4[q] = *(const float4*)(zg + 32 * ft + 8 * q);
+        }
         {   // this feature tile's rows of omega and dS, row-major, into the wavefront's LDS area
             constexpr int CPR = D / 8, LPT = 32 * CPR / 64;
             const uint16_t* ob = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ft) * D;
@@ -724,21 +753,23 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
                 *(uint4*)(dst + 2 * BwdKeyLds<D>::tile) = x2;
             }
         }
-        // e^T tile (features x keys) and dPhiK^T tile; element g <-> feature 32*ft + 8*(g/4) + 4*half + g%4
+        // e^T tile (features x keys) and dPhiK^T tile; element g <-> feature 32*ft + 8*(g/4) + 4*half + g%4.
+        // The A operands (this lane's feature row, 8 coordinates per step) come out of the tiles just
+        // copied; c and dz of the tile were requested together with them.
         floatx16 e = zero16(), dp;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 zv = *(const float4*)(zg + 32 * ft + 8 * q);
-            dp[4 * q] = zv.x; dp[4 * q + 1] = zv.y; dp[4 * q + 2] = zv.z; dp[4 * q + 3] = zv.w;
+            dp[4 * q] = zv4[q].x; dp[4 * q + 1] = zv4[q].y; dp[4 * q + 2] = zv4[q].z; dp[4 * q + 3] = zv4[q].w;
         }
+        const unsigned char* arow = tw + l32 * P + 16 * half;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const uint4 wa = ld16(og + (long)(32 * ft) * D + 16 * s);
+            const uint4 wa = *(const uint4*)(arow + 32 * s);
             e = mfma32(wa, kb[0][s], e);
             e = mfma32(wa, kb[1][s], e);
             e = mfma32(wa, kb[2][s], e);
-            const uint4 dh = ld16(dsg + (long)(32 * ft) * D + 16 * s);
-            const uint4 dl = ld16(dsg + ds_plane + (long)(32 * ft) * D + 16 * s);
+            const uint4 dh = *(const uint4*)(arow + BwdKeyLds<D>::tile + 32 * s);
+            const uint4 dl = *(const uint4*)(arow + 2 * BwdKeyLds<D>::tile + 32 * s);
             dp = mfma32(dh, vb[0][s], dp);
             dp = mfma32(dl, vb[0][s], dp);
             dp = mfma32(dh, vb[1][s], dp);
@@ -746,8 +777,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
         uint32_t ph[8], pl[8], uh[8], ul[8];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 cv = *(const float4*)(cg + 32 * ft + 8 * q);
-            const float cc[4] = {cv.x, cv.y, cv.z, cv.w};
+            const float cc[4] = {cv4[q].x, cv4[q].y, cv4[q].z, cv4[q].w};
             float phi[4], du[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -839,8 +869,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
                 sk += slots[w * SLOT + ((TT + tt) * 16 + 4 * q + i) * 64 + lane];
             }
             const int r = r0 + i;
-            const float kprt = r < a.k ? a.Kp[((long)bh * a.k + r) * D + t] : 0.f;
-            dk[i] = sk - rsq[i] * kprt;
+            dk[i] = sk - rsq[i] * kpr[tt][i];
             dv[i] = sv;
             imgK[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dk[i]);
             imgV[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dv[i]);

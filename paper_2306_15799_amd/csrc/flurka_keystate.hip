@@ -192,6 +192,24 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
         return e;
     };
 
+    // B operands of the second contraction for one key tile: V' columns 32*tt + l32, key pairs in the
+    // order in which the accumulator hands PhiK^T on.  They are requested a tile ahead, so that the trip
+    // to memory runs under the exponentials of the tile before (one wavefront per SIMD: nobody else
+    // would hide it).
+    struct VFrag { uint4 h[2][TT], l[2][TT]; };
+    auto load_v = [&](int kt, VFrag& f) {
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            const uint32_t* vb = vimg + (long)(16 * kt + 8 * sp + 2 * half) * D + l32;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                f.h[sp][tt].x = vb[32 * tt];           f.l[sp][tt].x = vb[vplane + 32 * tt];
+                f.h[sp][tt].y = vb[32 * tt + D];       f.l[sp][tt].y = vb[vplane + 32 * tt + D];
+                f.h[sp][tt].z = vb[32 * tt + 4 * D];   f.l[sp][tt].z = vb[vplane + 32 * tt + 4 * D];
+                f.h[sp][tt].w = vb[32 * tt + 5 * D];   f.l[sp][tt].w = vb[vplane + 32 * tt + 5 * D];
+            }
+        }
+    };
     // Up to KS_MT tiles per range (what the plan aims for) are evaluated once, all their loads in flight
     // together, and kept in registers between the maximum and the accumulation; longer ranges are
     // evaluated twice.
@@ -203,6 +221,8 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
         for (int i = 0; i < KS_MT; ++i)
             if (i < nt) ev[i] = tile_values(kt0 + i);
     }
+    VFrag vcur, vnext;
+    load_v(kt0, vcur);
     float c = 0.f;
     if (!ELU) {
         c = -INFINITY;
@@ -228,14 +248,14 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
     for (int t = 0; t < TT; ++t) accS[t] = zero16();
     float zsum = 0.f;
     constexpr float LOG2E = 1.4426950408889634f;
-    auto accumulate = [&](int kt, const floatx16& e) {
+    auto accumulate = [&](const floatx16& e, const VFrag& f) {
         uint32_t hi[8], lo[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             float p0 = e[2 * q], p1 = e[2 * q + 1];
             if (!ELU) {
-                p0 = exp2f((p0 - c) * LOG2E);
-                p1 = exp2f((p1 - c) * LOG2E);
+                p0 = fast_exp2((p0 - c) * LOG2E);
+                p1 = fast_exp2((p1 - c) * LOG2E);
             }
             zsum += p0 + p1;
             uint16_t h0, l0, h1, l1;
@@ -248,28 +268,30 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
         const uint4 ah[2] = {{hi[0], hi[1], hi[2], hi[3]}, {hi[4], hi[5], hi[6], hi[7]}};
         const uint4 al[2] = {{lo[0], lo[1], lo[2], lo[3]}, {lo[4], lo[5], lo[6], lo[7]}};
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-            // B operand: V' columns 32*tt + l32, key pairs in the matching order
-            const uint32_t* vb = vimg + (long)(16 * kt + 8 * sp + 2 * half) * D + l32;
+        for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                uint4 bh4, bl4;
-                bh4.x = vb[32 * tt];                 bl4.x = vb[vplane + 32 * tt];
-                bh4.y = vb[32 * tt + D];             bl4.y = vb[vplane + 32 * tt + D];
-                bh4.z = vb[32 * tt + 4 * D];         bl4.z = vb[vplane + 32 * tt + 4 * D];
-                bh4.w = vb[32 * tt + 5 * D];         bl4.w = vb[vplane + 32 * tt + 5 * D];
-                accS[tt] = mfma32(ah[sp], bh4, accS[tt]);
-                accS[tt] = mfma32(al[sp], bh4, accS[tt]);
-                accS[tt] = mfma32(ah[sp], bl4, accS[tt]);
+                accS[tt] = mfma32(ah[sp], f.h[sp][tt], accS[tt]);
+                accS[tt] = mfma32(al[sp], f.h[sp][tt], accS[tt]);
+                accS[tt] = mfma32(ah[sp], f.l[sp][tt], accS[tt]);
+            }
+    };
+    {
+        if (keep) {
+#pragma unroll
+            for (int i = 0; i < KS_MT; ++i)
+                if (i < nt) {
+                    if (i + 1 < nt) load_v(kt0 + i + 1, vnext);
+                    accumulate(ev[i], vcur);
+                    if (i + 1 < nt) vcur = vnext;
+                }
+        } else {
+            for (int kt = kt0; kt < kt1; ++kt) {
+                if (kt + 1 < kt1) load_v(kt + 1, vnext);
+                accumulate(tile_values(kt), vcur);
+                if (kt + 1 < kt1) vcur = vnext;
             }
         }
-    };
-    if (keep) {
-#pragma unroll
-        for (int i = 0; i < KS_MT; ++i)
-            if (i < nt) accumulate(kt0 + i, ev[i]);
-    } else {
-        for (int kt = kt0; kt < kt1; ++kt) accumulate(kt, tile_values(kt));
     }
     zsum = half_sum(zsum);
 
