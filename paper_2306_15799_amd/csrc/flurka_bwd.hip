@@ -144,11 +144,7 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
         const float v[8] = {s0.x * rz, s0.y * rz, s0.z * rz, s0.w * rz, s1.x * rz, s1.y * rz, s1.z * rz, s1.w * rz};
         uint32_t hi[4], lo[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint16_t h0 = f32_to_bf16(v[2 * e]), h1 = f32_to_bf16(v[2 * e + 1]);
-            hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            lo[e] = pack_bf16(v[2 * e] - bf16_to_f32(h0), v[2 * e + 1] - bf16_to_f32(h1));
-        }
+        for (int e = 0; e < 4; ++e) split2_pair(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
         hi4 = make_uint4(hi[0], hi[1], hi[2], hi[3]);
         lo4 = make_uint4(lo[0], lo[1], lo[2], lo[3]);
     };
@@ -563,11 +559,6 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
         }
 }
 
-// x = hi + lo, both bf16
-__device__ __forceinline__ void bsplit2(float x, uint16_t& hi, uint16_t& lo) {
-    hi = f32_to_bf16(x);
-    lo = f32_to_bf16(x - bf16_to_f32(hi));
-}
 
 // Sums the query ranges of dS, dz and writes the operand images of the key-side kernel:
 //   dSimg  2 x (BH, mf, d) bf16 (hi, lo)    A operand of dPhiK^T = dS V'^T, and (through transposing
@@ -587,9 +578,9 @@ __global__ void bwd_merge_kernel(uint16_t* dSimg, float* dz, const float* dSpart
         s0 += p[0];
         s1 += p[d];
     }
-    uint16_t h0, l0, h1, l1;
-    bsplit2(s0, h0, l0);
-    bsplit2(s1, h1, l1);
+    uint32_t hp, lp;
+    split2_pair(s0, s1, hp, lp);
+    const uint16_t h0 = (uint16_t)hp, h1 = (uint16_t)(hp >> 16), l0 = (uint16_t)lp, l1 = (uint16_t)(lp >> 16);
     const long plane = total * 2;                     // BH * mf * d
     const long i0 = (bh * mf + 2 * pr) * d + t;
     dSimg[i0] = h0; dSimg[i0 + d] = h1;
@@ -693,19 +684,10 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
             uint32_t kh[4], km[4], kl[4], vh[4], vl[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                uint16_t h0, m0, l0, h1, m1, l1;
-                h0 = f32_to_bf16(kv[2 * e]);     { const float r = kv[2 * e] - bf16_to_f32(h0);         m0 = f32_to_bf16(r); l0 = f32_to_bf16(r - bf16_to_f32(m0)); }
-                h1 = f32_to_bf16(kv[2 * e + 1]); { const float r = kv[2 * e + 1] - bf16_to_f32(h1);     m1 = f32_to_bf16(r); l1 = f32_to_bf16(r - bf16_to_f32(m1)); }
-                kh[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                km[e] = (uint32_t)m0 | ((uint32_t)m1 << 16);
-                kl[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+                split3_pair(kv[2 * e], kv[2 * e + 1], kh[e], km[e], kl[e]);
                 nrm = fmaf(kv[2 * e], kv[2 * e], nrm);
                 nrm = fmaf(kv[2 * e + 1], kv[2 * e + 1], nrm);
-                uint16_t a0, b0, a1, b1;
-                bsplit2(vv[2 * e], a0, b0);
-                bsplit2(vv[2 * e + 1], a1, b1);
-                vh[e] = (uint32_t)a0 | ((uint32_t)a1 << 16);
-                vl[e] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+                split2_pair(vv[2 * e], vv[2 * e + 1], vh[e], vl[e]);
             }
             kb[0][s] = make_uint4(kh[0], kh[1], kh[2], kh[3]);
             kb[1][s] = make_uint4(km[0], km[1], km[2], km[3]);
@@ -787,15 +769,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                uint16_t h0, l0, h1, l1;
-                bsplit2(phi[2 * i], h0, l0);
-                bsplit2(phi[2 * i + 1], h1, l1);
-                ph[2 * q + i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                pl[2 * q + i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-                bsplit2(du[2 * i], h0, l0);
-                bsplit2(du[2 * i + 1], h1, l1);
-                uh[2 * q + i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                ul[2 * q + i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+                split2_pair(phi[2 * i], phi[2 * i + 1], ph[2 * q + i], pl[2 * q + i]);
+                split2_pair(du[2 * i], du[2 * i + 1], uh[2 * q + i], ul[2 * q + i]);
             }
         }
 #pragma unroll

@@ -34,10 +34,6 @@ __device__ __forceinline__ void split3(float x, uint16_t& hi, uint16_t& mid, uin
     mid = f32_to_bf16(r1);
     lo = f32_to_bf16(r1 - bf16_to_f32(mid));
 }
-__device__ __forceinline__ void split2(float x, uint16_t& hi, uint16_t& lo) {
-    hi = f32_to_bf16(x);
-    lo = f32_to_bf16(x - bf16_to_f32(hi));
-}
 
 // ---------------------------------------------------------------------------
 // proj_finish: one wavefront per (head, four consecutive keys 4g .. 4g+3); lane = coordinate t (and
@@ -98,12 +94,11 @@ __global__ __launch_bounds__(256) void proj_finish_kernel(FinishArgs a) {
         }
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
-            uint16_t h0, l0, h1, l1;
-            split2(vv[2 * pr], h0, l0);
-            split2(vv[2 * pr + 1], h1, l1);
+            uint32_t hp, lp;
+            split2_pair(vv[2 * pr], vv[2 * pr + 1], hp, lp);
             const long vo = ((long)bh * (a.kpad / 2) + r0 / 2 + pr) * a.d + t;
-            a.Vimg[vo] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            a.Vimg[vimg_plane + vo] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            a.Vimg[vo] = hp;
+            a.Vimg[vimg_plane + vo] = lp;
         }
     }
     if (a.nrm) {
@@ -258,11 +253,7 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
                 p1 = fast_exp2((p1 - c) * LOG2E);
             }
             zsum += p0 + p1;
-            uint16_t h0, l0, h1, l1;
-            split2(p0, h0, l0);
-            split2(p1, h1, l1);
-            hi[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            lo[q] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            split2_pair(p0, p1, hi[q], lo[q]);
         }
         // PhiK^T tile as A operand: row = this lane's feature, reduction slots = keys in accumulator order
         const uint4 ah[2] = {{hi[0], hi[1], hi[2], hi[3]}, {hi[4], hi[5], hi[6], hi[7]}};

@@ -35,6 +35,21 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// Split-precision operands: x = hi + lo (+ more) with every term a bf16, two values at a time on the
+// packed hardware conversion (round to nearest even).  pair_lo/pair_hi widen the halves of a packed pair.
+__device__ __forceinline__ float pair_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float pair_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+__device__ __forceinline__ void split2_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+    hi = pack_bf16(x0, x1);
+    lo = pack_bf16(x0 - pair_lo(hi), x1 - pair_hi(hi));
+}
+__device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+    hi = pack_bf16(x0, x1);
+    const float r0 = x0 - pair_lo(hi), r1 = x1 - pair_hi(hi);
+    mid = pack_bf16(r0, r1);
+    lo = pack_bf16(r0 - pair_lo(mid), r1 - pair_hi(mid));
+}
+
 // 2^x on the transcendental unit, no denormal fix-up (inputs here are <= 0 and results that
 // underflow are meant to be 0)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
