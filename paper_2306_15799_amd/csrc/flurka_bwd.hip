@@ -843,15 +843,19 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
                 sv += slots[w * SLOT + (tt * 16 + 4 * q + i) * 64 + lane];
                 sk += slots[w * SLOT + ((TT + tt) * 16 + 4 * q + i) * 64 + lane];
             }
-            const int r = r0 + i;
             dk[i] = sk - rsq[i] * kpr[tt][i];
             dv[i] = sv;
-            imgK[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dk[i]);
-            imgV[((long)bh * a.kp + r) * D + t] = f32_to_bf16(dv[i]);
         }
         uint2 pk, pv;
         pk.x = pack_bf16(dk[0], dk[1]); pk.y = pack_bf16(dk[2], dk[3]);
         pv.x = pack_bf16(dv[0], dv[1]); pv.y = pack_bf16(dv[2], dv[3]);
+        const uint32_t pkw[2] = {pk.x, pk.y}, pvw[2] = {pv.x, pv.y};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const long io = ((long)bh * a.kp + r0 + i) * D + t;
+            imgK[io] = (uint16_t)(pkw[i >> 1] >> (16 * (i & 1)));
+            imgV[io] = (uint16_t)(pvw[i >> 1] >> (16 * (i & 1)));
+        }
         *(uint2*)(imgTK + ((long)bh * D + t) * a.kp + r0) = pk;
         *(uint2*)(imgTV + ((long)bh * D + t) * a.kp + r0) = pv;
     }

@@ -485,10 +485,12 @@ struct GradEPolicy {
         if (col >= g.n) return;
         uint16_t* o = (uint16_t*)g.C[which] + col;
         const int r0 = row + 4 * half;
+        const uint32_t pe[2] = {pack_bf16(ev[0], ev[1]), pack_bf16(ev[2], ev[3])};
+        const uint32_t po[2] = {pack_bf16(od[0], od[1]), pack_bf16(od[2], od[3])};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (r0 + e < g.k) o[(long)(r0 + e) * g.n] = f32_to_bf16(ev[e]);
-            if (r0 + 8 + e < g.k) o[(long)(r0 + 8 + e) * g.n] = f32_to_bf16(od[e]);
+            if (r0 + e < g.k) o[(long)(r0 + e) * g.n] = (uint16_t)(pe[e >> 1] >> (16 * (e & 1)));
+            if (r0 + 8 + e < g.k) o[(long)(r0 + 8 + e) * g.n] = (uint16_t)(po[e >> 1] >> (16 * (e & 1)));
         }
     }
 };

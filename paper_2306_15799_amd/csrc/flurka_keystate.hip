@@ -44,7 +44,7 @@ struct FinishArgs {
     const float* part;      // tile-ordered split partials of the projection (see flurka_gemm.h)
     float* ctx;             // K' at ctx + Kp_off, V' at ctx + Vp_off
     long Kp_off, Vp_off;
-    uint16_t* Kimg;         // 3 x (BH, kpad, d) bf16: hi, mid, lo      (nullptr for elu1)
+    uint16_t* Kimg;         // 3 x (BH, kpad * d) bf16: hi, mid, lo, in key_state's operand order (nullptr for elu1)
     uint32_t* Vimg;         // 2 x (BH, kpad/2, d) dwords: hi, lo; low half = even key
     float* nrm;             // (BH, kpad): |k'|^2/2, +inf for the padding keys (nullptr for elu1)
     int splits, tilesM, tilesN, k, kpad, d, BH;
@@ -86,7 +86,10 @@ __global__ __launch_bounds__(256) void proj_finish_kernel(FinishArgs a) {
             if (a.Kimg) {
                 uint16_t hi, mid, lo;
                 split3(kv[e], hi, mid, lo);
-                const long io = ((long)bh * a.kpad + r) * a.d + t;
+                // operand order of key_state: [32-key tile][16-coordinate step][8-coordinate half][key][8],
+                // so that a wavefront's fragment load is 1 KiB of consecutive bytes
+                const long io = (long)bh * a.kpad * a.d +
+                                ((((long)(r >> 5) * (a.d / 16) + (t >> 4)) * 2 + ((t >> 3) & 1)) * 32 + (r & 31)) * 8 + (t & 7);
                 a.Kimg[io] = hi;
                 a.Kimg[img_plane + io] = mid;
                 a.Kimg[2 * img_plane + io] = lo;
@@ -159,12 +162,12 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
     auto tile_values = [&](int kt) -> floatx16 {
         floatx16 e = zero16();
         if (!ELU) {
-            const uint16_t* kg = a.Kimg + ((long)bh * a.kpad + 32 * kt + l32) * D + 8 * half;
+            const uint16_t* kg = a.Kimg + (long)bh * a.kpad * D + ((long)kt * KS * 64 + lane) * 8;
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                e = mfma32(ld16(kg + 16 * s), wf[s], e);
-                e = mfma32(ld16(kg + plane + 16 * s), wf[s], e);
-                e = mfma32(ld16(kg + 2 * plane + 16 * s), wf[s], e);
+                e = mfma32(ld16(kg + 512 * s), wf[s], e);
+                e = mfma32(ld16(kg + plane + 512 * s), wf[s], e);
+                e = mfma32(ld16(kg + 2 * plane + 512 * s), wf[s], e);
             }
             const float* ng = a.nrm + (long)bh * a.kpad + 32 * kt + 4 * half;
 #pragma unroll
