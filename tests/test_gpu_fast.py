@@ -138,8 +138,11 @@ def test_backward_matches_generic_kernels_closely():
         assert fo.rel_l2(gu.to_host(a), gu.to_host(b)) < 2e-2, name
 
 
-def test_backward_is_deterministic():
-    w = Workload("det", 2, 2, 512, 64, 96, 64, "bf16", PHI_PERFORMER, True)
+@pytest.mark.parametrize("shape", [(2, 2, 512, 64, 96, 64), (2, 3, 512, 128, 96, 256)])
+def test_backward_is_deterministic(shape):
+    """Both head sizes (128 with 256 features: the ring variant of the dQ kernel, whose wavefronts meet
+    at a barrier per feature tile)."""
+    w = Workload("det", *shape, "bf16", PHI_PERFORMER, True)
     t = inputs.make_inputs(w, 14)
     g, out, ctx = gu.run_forward(w, t, "fast")
     a = gu.run_backward(w, g, out, ctx, "fast")
@@ -148,13 +151,20 @@ def test_backward_is_deterministic():
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("d,m", [(64, 128), (128, 256)])
+def test_backward_with_one_omega_for_all_heads(d, m):
+    w = Workload("shared", 2, 3, 512, d, 128, m, "bf16", PHI_PERFORMER, True, omega_per_head=False)
+    errs = gu.check_forward_backward(w, seed=15, algo="fast")
+    print((d, m), {k_: f"{v:.2e}" for k_, v in errs.items()})
+
+
 # ---- scratch independence ------------------------------------------------------------------
-@pytest.mark.parametrize("algo", ["fast", "generic"])
-def test_results_do_not_depend_on_what_the_scratch_buffers_held(algo):
+@pytest.mark.parametrize("algo,d,m", [("fast", 64, 96), ("generic", 64, 96), ("fast", 128, 256)])
+def test_results_do_not_depend_on_what_the_scratch_buffers_held(algo, d, m):
     """ctx, workspace and the result tensors are filled with NaN bit patterns (0xFF bytes) before the
     calls: every byte a kernel reads must have been written by an earlier kernel of the same call.
     Shape with ragged k (tile rows past k), ragged heads per projection tile and an odd step count."""
-    w = Workload("poison", 1, 3, 192, 64, 100, 96, "bf16", PHI_PERFORMER, True)
+    w = Workload("poison", 1, 3, 192, d, 100, m, "bf16", PHI_PERFORMER, True)
     t = inputs.make_inputs(w, 21)
     g = gu.to_device(t, w.dtype)
     dims = (w.B, w.H, w.n, w.d, w.k, w.m)
