@@ -70,7 +70,7 @@ KERNEL_TRACE_NAME = {
     "key_state": "key_state_kernel<{d}, false>",
     "merge_pack": "merge_pack_kernel",
     "query_stream": "query_stream_kernel<{d}, {elu}, {qs_waves}, 1, {elu}>",     # staged tiles: elu1 only
-    "bwd_query_x": "bwd_query_x_kernel<{d}>",
+    "bwd_query_x": "bwd_query_x_kernel<{d}, {ring}>",              # ring: d = 128 with more than 192 features
     "bwd_query_y": "bwd_query_y_kernel<{d}, 8>",
     "bwd_merge": "bwd_merge_kernel",
     "bwd_key": "bwd_key_kernel<{d}>",
@@ -240,7 +240,8 @@ def main():
                               "HIP events around each launch of this kernel, on the stream it runs on",
                               model=kernel_model)
         trace = KERNEL_TRACE_NAME[dominant].format(d=w.d, elu="true" if w.phi == "elu1" else "false",
-                                                   qs_waves=12 if w.d == 64 else 8)
+                                                   qs_waves=12 if w.d == 64 else 8,
+                                                   ring="true" if (w.d == 128 and m_eff > 192) else "false")
         roof["kernel_in_trace"] = trace
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
         if os.path.exists(tpath):
