@@ -71,7 +71,7 @@ KERNEL_TRACE_NAME = {
     "merge_pack": "merge_pack_kernel",
     "query_stream": "query_stream_kernel<{d}, {elu}, {qs_waves}, 1, {elu}>",     # staged tiles: elu1 only
     "bwd_query_x": "bwd_query_x_kernel<{d}, {ring}>",              # ring: d = 128 with more than 192 features
-    "bwd_query_y": "bwd_query_y_kernel<{d}, 8>",
+    "bwd_query_y": "bwd_query_y_kernel<{d}, 8, false>",
     "bwd_merge": "bwd_merge_kernel",
     "bwd_key": "bwd_key_kernel<{d}>",
     "gemm_mfma_gradx": "gemm_mfma_kernel<GradXPolicy<{d}>, true>",      # several items per workgroup

@@ -386,6 +386,219 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// bwd_query_x for phi = elu + 1 (the "RNN" feature map of Sec. 2; features = the d coordinates):
+//     P_ij = elu(q_ij) + 1,  D_i = P_i . z,  T_ij = G_i . S_j,  g_i = (P_i . T_i) / D_i  (= G_i . out_i),
+//     dQ_ij = (T_ij - g_i z_j) / D_i * phi'(q_ij),  phi'(x) = 1 (x > 0), exp(x) otherwise.
+// One contraction (T, with S as a two-term bf16 split so that T_ij - g_i z_j keeps fp32 accuracy where
+// it cancels); everything else is elementwise in the accumulator layout, so Q and dOut are both taken in
+// the accumulator's slot order (slot 8h + e of a group of 16 holds t = 8*(e/4) + 4*h + e%4).  g_i and
+// 1/D_i go to the dS kernel.
+// ---------------------------------------------------------------------------
+struct BwdXEluArgs {
+    const uint16_t* Q;
+    const uint16_t* G;         // dOut
+    const float* S;            // ctx (BH, d, d): S[j][t]
+    const float* z;            // ctx (BH, d)
+    uint16_t* dQ;
+    float* delta;              // (BH, n)  g_i
+    float* dinv;               // (BH, n)  1 / D_i
+    int n, tiles_per_head;
+    long total_tiles;
+};
+
+template <int D>
+struct BwdXEluLds {
+    static constexpr bool direct = D > 64;
+    static constexpr int nw = 8;
+    static constexpr int sp_pitch = (D + 8) * 2;
+    static constexpr int images = 2 * D * sp_pitch + D * 4;              // S hi, S lo, z
+    static constexpr int scratch = direct ? 0 : 32 * D * 2;
+    static constexpr int total = images + nw * scratch + 16;
+};
+
+__device__ __forceinline__ float elu1_of(float x) { return x > 0.f ? x + 1.f : __expf(x); }
+
+template <int D>
+__global__ __launch_bounds__(512) void bwd_query_x_elu_kernel(BwdXEluArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    using L = BwdXEluLds<D>;
+    constexpr bool DIRECT = L::direct;
+    constexpr int X_NW = L::nw;
+    constexpr int KS = D / 16, TT = D / 32;         // TT feature tiles = coordinate tiles
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    unsigned char* lsh = lds;
+    unsigned char* lsl = lsh + D * L::sp_pitch;
+    float* lz = (float*)(lsl + D * L::sp_pitch);    // z in accumulator order of a 32-feature tile
+    int* const next_tile = (int*)(lds + L::images + X_NW * L::scratch);
+
+    const long tile_begin = a.total_tiles * blockIdx.x / gridDim.x;
+    const long tile_end = a.total_tiles * (blockIdx.x + 1) / gridDim.x;
+    for (long seg = tile_begin; seg < tile_end;) {
+    const int bh = (int)(seg / a.tiles_per_head);
+    long seg_end = (long)(bh + 1) * a.tiles_per_head;
+    if (seg_end > tile_end) seg_end = tile_end;
+    if (seg != tile_begin) __syncthreads();
+    {
+        const float* Sg = a.S + (long)bh * D * D;
+        constexpr int cpr = D / 8;
+        for (int c = tid; c < D * cpr; c += X_NW * 64) {
+            const int r = c / cpr, q = c % cpr;
+            const int t0 = 16 * (q >> 1) + 4 * (q & 1);
+            const float4 s0 = *(const float4*)(Sg + (long)r * D + t0);
+            const float4 s1 = *(const float4*)(Sg + (long)r * D + t0 + 8);
+            const float v[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) split2_pair(v[2 * e], v[2 * e + 1], hi[e], lo[e]);
+            *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *(uint4*)(lsl + r * L::sp_pitch + 16 * q) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        }
+        const float* zg = a.z + (long)bh * D;
+        for (int slot = tid; slot < D; slot += X_NW * 64) {
+            const int g = slot & 15, h = (slot >> 4) & 1;
+            lz[slot] = zg[(slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3)];
+        }
+    }
+    if (tid == 0) *next_tile = X_NW;
+    __syncthreads();
+
+    const long head_off = (long)bh * a.n * D;
+    const int row_begin = (int)(seg - (long)bh * a.tiles_per_head) * 32;
+    int row_end = (int)(seg_end - (long)bh * a.tiles_per_head) * 32;
+    if (row_end > a.n) row_end = a.n;
+    seg = seg_end;
+
+    constexpr int CPR = D / 8, ROWB = D * 2, LPT = 32 * CPR / 64;
+    unsigned char* const scr = lds + L::images + wave * L::scratch;
+    auto scr_at = [&](int row, int c) -> unsigned char* { return scr + row * ROWB + 16 * (c ^ ((row >> 1) & 7)); };
+    // this lane's row of Q and of dOut in accumulator slot order (see bwd_query_x_kernel for the staging)
+    uint4 qv[KS], gv[KS];
+    auto load_tile = [&](int row0) {
+        if constexpr (DIRECT) {
+            const long off = head_off + (long)(row0 + l32) * D + 4 * half;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uint2 q0 = *(const uint2*)(a.Q + off + 16 * s), q1 = *(const uint2*)(a.Q + off + 16 * s + 8);
+                const uint2 g0 = *(const uint2*)(a.G + off + 16 * s), g1 = *(const uint2*)(a.G + off + 16 * s + 8);
+                qv[s] = make_uint4(q0.x, q0.y, q1.x, q1.y);
+                gv[s] = make_uint4(g0.x, g0.y, g1.x, g1.y);
+            }
+        } else {
+            uint4 rq[LPT], rg[LPT];
+            const long off = head_off + (long)row0 * D + 8 * lane;
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) {
+                rq[u] = ld16(a.Q + off + 512 * u);
+                rg[u] = ld16(a.G + off + 512 * u);
+            }
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = rq[u];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uint2 x0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
+                const uint2 x1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
+                qv[s] = make_uint4(x0.x, x0.y, x1.x, x1.y);
+            }
+#pragma unroll
+            for (int u = 0; u < LPT; ++u) *(uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR) = rg[u];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const uint2 x0 = *(const uint2*)(scr_at(l32, 2 * s) + 8 * half);
+                const uint2 x1 = *(const uint2*)(scr_at(l32, 2 * s + 1) + 8 * half);
+                gv[s] = make_uint4(x0.x, x0.y, x1.x, x1.y);
+            }
+        }
+    };
+
+    for (int row0 = row_begin + 32 * wave; row0 < row_end;) {
+        const int qrow = row0 + l32;
+        int grabbed = 0;
+        if (lane == 0) grabbed = atomicAdd(next_tile, 1);
+        const int row_next = row_begin + 32 * __builtin_amdgcn_readfirstlane(grabbed);
+        load_tile(row0);
+
+        // T^T tiles: rows = features j (accumulator element g <-> j = 32*ft + 8*(g/4) + 4*half + g%4)
+        floatx16 tp[TT];
+#pragma unroll
+        for (int ft = 0; ft < TT; ++ft) {
+            tp[ft] = zero16();
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int so = (32 * ft + l32) * L::sp_pitch + 32 * s + 16 * half;
+                tp[ft] = mfma32(*(const uint4*)(lsh + so), gv[s], tp[ft]);
+                tp[ft] = mfma32(*(const uint4*)(lsl + so), gv[s], tp[ft]);
+            }
+        }
+        // P, D, g in the same layout: element g of tile ft is slot g % 8 of step 2*ft + g / 8
+        float pv[TT][16], zv[TT][16];
+        float dsum = 0.f, gsum = 0.f;
+#pragma unroll
+        for (int ft = 0; ft < TT; ++ft)
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                const uint4& w4 = qv[2 * ft + (g >> 3)];
+                const uint32_t w = (g & 7) < 2 ? w4.x : (g & 7) < 4 ? w4.y : (g & 7) < 6 ? w4.z : w4.w;
+                const float q = (g & 1) ? pair_hi(w) : pair_lo(w);
+                const float p = elu1_of(q);
+                const float zz = lz[32 * ft + 16 * half + g];
+                dsum = fmaf(p, zz, dsum);
+                gsum = fmaf(p, tp[ft][g], gsum);
+                pv[ft][g] = q > 0.f ? 1.f : p;              // phi'(q)
+                zv[ft][g] = zz;
+            }
+        dsum = half_sum(dsum);
+        gsum = half_sum(gsum);
+        const float inv = 1.f / dsum;
+        const float gi = gsum * inv;
+        if (half == 0) {
+            a.delta[(long)bh * a.n + qrow] = gi;
+            a.dinv[(long)bh * a.n + qrow] = inv;
+        }
+#pragma unroll
+        for (int t = 0; t < TT; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; q += 2) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (tp[t][4 * q + e] - gi * zv[t][4 * q + e]) * inv * pv[t][4 * q + e];
+                uint2 ev, od;
+                ev.x = pack_bf16(v[0], v[1]); ev.y = pack_bf16(v[2], v[3]);
+                od.x = pack_bf16(v[4], v[5]); od.y = pack_bf16(v[6], v[7]);
+                const uint4 piece = join_halves(ev, od);
+                if constexpr (DIRECT) *(uint4*)(a.dQ + head_off + (long)qrow * D + 8 * (4 * t + q + half)) = piece;
+                else                  *(uint4*)scr_at(l32, 4 * t + q + half) = piece;
+            }
+        if constexpr (!DIRECT) {
+            uint16_t* ob = a.dQ + head_off + (long)row0 * D + 8 * lane;
+#pragma unroll
+            for (int u = 0; u < LPT; ++u)
+                *(uint4*)(ob + 512 * u) = *(const uint4*)scr_at((64 * u + lane) / CPR, (64 * u + lane) % CPR);
+        }
+        row0 = row_next;
+    }
+    }   // head segments
+}
+
+// fp32 dK', dV' (BH, k, d) of the generic key-side kernels -> the bf16 operand images of the two
+// gradient GEMMs: img (BH, kp, d) with zero rows past k, imgT (BH * d, kp).  blockIdx.y: dK' or dV'.
+__global__ void grad_images_kernel(const float* dKp, const float* dVp, uint16_t* img, uint16_t* imgT,
+                                   int k, int kp, int d, long per_tensor) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;    // (bh, r < kp, t)
+    if (idx >= per_tensor) return;
+    const int t = (int)(idx % d);
+    const long rest = idx / d;
+    const int r = (int)(rest % kp);
+    const long bh = rest / kp;
+    const float* src = blockIdx.y ? dVp : dKp;
+    const float v = r < k ? src[(bh * k + r) * d + t] : 0.f;
+    const uint16_t b = (uint16_t)pack_bf16(v, 0.f);
+    img[blockIdx.y * per_tensor + idx] = b;
+    imgT[blockIdx.y * per_tensor + (bh * d + t) * kp + r] = b;
+}
+
+// ---------------------------------------------------------------------------
 // bwd_query_y: one wavefront per (head, feature tile, query range)
 // ---------------------------------------------------------------------------
 struct BwdYArgs {
@@ -393,7 +606,7 @@ struct BwdYArgs {
     const uint16_t* G;
     const uint16_t* omega;
     const float* c;            // ctx shifts, natural order (BH, mf)
-    const float* lse;          // renormalised lambda_i from bwd_query_x
+    const float* lse;          // renormalised lambda_i from bwd_query_x; elu1: 1 / D_i
     const float* delta;
     float* dSpart;             // (BH, R, mf, d)
     float* dzpart;             // (BH, R, mf)
@@ -412,19 +625,21 @@ struct BwdYArgs {
 // The next block is requested into registers while the current one is worked on.
 constexpr int Y_ST = 4;
 
-template <int D>
+// elu1: W_ij = (elu(q_ij) + 1) / D_i needs no contraction; the Q tile is read through the same
+// transposing loads as the dOut tile (lane = feature), so it gets that tile's pitch.
+template <int D, bool ELU = false>
 struct BwdYLds {
     static constexpr int rows = 32 * Y_ST;
-    static constexpr int q_pitch = (D + 8) * 2;      // conflict-free 16-byte reads down a column of rows
     static constexpr int g_pitch = D * 2 + 64;       // 4 consecutive rows fall into 4 distinct bank groups
+    static constexpr int q_pitch = ELU ? g_pitch : (D + 8) * 2;   // plain: conflict-free 16-byte reads down a column of rows
     static constexpr int total = rows * (q_pitch + g_pitch) + 2 * rows * 4;
 };
 
 
-template <int D, int NW>
+template <int D, int NW, bool ELU>
 __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
-    using L = BwdYLds<D>;
+    using L = BwdYLds<D, ELU>;
     constexpr int QP = L::q_pitch, GP = L::g_pitch, ROWS = L::rows;
     constexpr int CPR = D / 8;                 // 16-byte chunks per row
     constexpr int NT = NW * 64;
@@ -454,12 +669,13 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
     const long vec_off = (long)bh * a.n;
 
     uint4 wf[KS];
-    {
+    float cj = 0.f;
+    if constexpr (!ELU) {
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ftc + l32) * D + 8 * half;
 #pragma unroll
         for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
+        cj = a.c[(long)bh * a.mf + 32 * ftc + l32] * LOG2E;
     }
-    const float cj = a.c[(long)bh * a.mf + 32 * ftc + l32] * LOG2E;
     floatx16 accS[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) accS[t] = zero16();
@@ -479,7 +695,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
         }
         if (tid < 2 * ROWS) {
             const int row = 32 * qt + (tid % ROWS);
-            if (tid < ROWS) rv = row <= row_last ? a.lse[vec_off + row] * LOG2E : INFINITY;
+            if (tid < ROWS) rv = row <= row_last ? a.lse[vec_off + row] * (ELU ? 1.f : LOG2E) : (ELU ? 0.f : INFINITY);
             else            rv = row <= row_last ? a.delta[vec_off + row] : 0.f;
         }
     };
@@ -498,6 +714,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
     // of the 16-column group (l32/16); see the layout note above
     const int s16 = lane & 15;
     const unsigned char* gtr = gs + (4 * half + (s16 >> 2)) * GP + 2 * (16 * ((lane >> 4) & 1) + 4 * (s16 & 3));
+    const unsigned char* qtr = qs + (4 * half + (s16 >> 2)) * QP + 2 * (16 * ((lane >> 4) & 1) + 4 * (s16 & 3));
 
     if (qt0 < qt1) load_block(qt0);
     for (int qt = qt0; qt < qt1; qt += Y_ST) {
@@ -507,20 +724,41 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
 #pragma unroll
         for (int i = 0; i < Y_ST; ++i) {
             // u tile: rows = queries of tile i, columns = this wavefront's features
+            // (elu1: the same elements of Q itself, column 32*ft + l32, through transposing reads)
             floatx16 u = zero16();
+            if constexpr (!ELU) {
 #pragma unroll
-            for (int s = 0; s < KS; ++s)
-                u = mfma32(*(const uint4*)(qs + (32 * i + l32) * QP + 32 * s + 16 * half), wf[s], u);
+                for (int s = 0; s < KS; ++s)
+                    u = mfma32(*(const uint4*)(qs + (32 * i + l32) * QP + 32 * s + 16 * half), wf[s], u);
+            } else {
+#pragma unroll
+                for (int sp = 0; sp < 2; ++sp) {
+                    const unsigned char* bp = qtr + (32 * i + 16 * sp) * QP + 64 * ftc;
+                    const uint2 b0 = lds_read_tr16(bp);
+                    const uint2 b1 = lds_read_tr16(bp + 8 * QP);
+                    const uint32_t w[4] = {b0.x, b0.y, b1.x, b1.y};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        u[8 * sp + 2 * e] = elu1_of(pair_lo(w[e]));
+                        u[8 * sp + 2 * e + 1] = elu1_of(pair_hi(w[e]));
+                    }
+                }
+            }
             // element g <-> query 32*i + 8*(g/4) + 4*half + g%4
             uint32_t wk[8];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float4 lv = *(const float4*)(ll + 32 * i + 8 * q + 4 * half);
                 const float4 dv = *(const float4*)(ld + 32 * i + 8 * q + 4 * half);
-                const float w0 = fast_exp2(fmaf(u[4 * q], LOG2E, cj - lv.x));
-                const float w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, cj - lv.y));
-                const float w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, cj - lv.z));
-                const float w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, cj - lv.w));
+                float w0, w1, w2, w3;
+                if constexpr (!ELU) {
+                    w0 = fast_exp2(fmaf(u[4 * q], LOG2E, cj - lv.x));
+                    w1 = fast_exp2(fmaf(u[4 * q + 1], LOG2E, cj - lv.y));
+                    w2 = fast_exp2(fmaf(u[4 * q + 2], LOG2E, cj - lv.z));
+                    w3 = fast_exp2(fmaf(u[4 * q + 3], LOG2E, cj - lv.w));
+                } else {
+                    w0 = u[4 * q] * lv.x; w1 = u[4 * q + 1] * lv.y; w2 = u[4 * q + 2] * lv.z; w3 = u[4 * q + 3] * lv.w;
+                }
                 wk[2 * q] = pack_bf16(w0, w1);
                 wk[2 * q + 1] = pack_bf16(w2, w3);
                 // dz from the rounded weights, the ones dS is formed with: dS_j . v'_r + dz_j then cancels
@@ -564,7 +802,8 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
 //   dSimg  2 x (BH, mf, d) bf16 (hi, lo)    A operand of dPhiK^T = dS V'^T, and (through transposing
 //                                           LDS reads) B operand of dV' = PhiK dS
 //   dz     (BH, mf) fp32
-__global__ void bwd_merge_kernel(uint16_t* dSimg, float* dz, const float* dSpart,
+// (elu1: the key side runs on the generic kernels and wants dS itself, fp32, instead of the image.)
+__global__ void bwd_merge_kernel(uint16_t* dSimg, float* dS32, float* dz, const float* dSpart,
                                  const float* dzpart, int R, int mf, int d, long total) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;    // (bh, feature pair, t)
     if (idx >= total) return;
@@ -578,13 +817,17 @@ __global__ void bwd_merge_kernel(uint16_t* dSimg, float* dz, const float* dSpart
         s0 += p[0];
         s1 += p[d];
     }
-    uint32_t hp, lp;
-    split2_pair(s0, s1, hp, lp);
-    const uint16_t h0 = (uint16_t)hp, h1 = (uint16_t)(hp >> 16), l0 = (uint16_t)lp, l1 = (uint16_t)(lp >> 16);
-    const long plane = total * 2;                     // BH * mf * d
     const long i0 = (bh * mf + 2 * pr) * d + t;
-    dSimg[i0] = h0; dSimg[i0 + d] = h1;
-    dSimg[plane + i0] = l0; dSimg[plane + i0 + d] = l1;
+    if (dS32) {
+        dS32[i0] = s0; dS32[i0 + d] = s1;
+    } else {
+        uint32_t hp, lp;
+        split2_pair(s0, s1, hp, lp);
+        const uint16_t h0 = (uint16_t)hp, h1 = (uint16_t)(hp >> 16), l0 = (uint16_t)lp, l1 = (uint16_t)(lp >> 16);
+        const long plane = total * 2;                     // BH * mf * d
+        dSimg[i0] = h0; dSimg[i0 + d] = h1;
+        dSimg[plane + i0] = l0; dSimg[plane + i0 + d] = l1;
+    }
     if (t == 0) {
         float z0 = 0.f, z1 = 0.f;
         for (int r = 0; r < R; ++r) {
@@ -905,10 +1148,10 @@ static int bwd_x_lds_bytes(const Problem& p) {
 }
 
 bool fast_bwd_supported(const Problem& p) {
-    if (!p.bf16 || p.elu) return false;
+    if (!p.bf16) return false;
     if (p.d != 64 && p.d != 128) return false;
     if (p.n % 64 != 0 || p.mf % 32 != 0) return false;
-    if (bwd_x_lds_bytes(p) > 160 * 1024) return false;
+    if (!p.elu && bwd_x_lds_bytes(p) > 160 * 1024) return false;
     // 32-bit byte offsets inside the gradient GEMMs' buffer descriptors
     if ((size_t)p.BH * p.n * p.d * 2 >= ((size_t)1 << 31)) return false;
     if (((size_t)p.k + GBM) * (size_t)p.n * 2 >= ((size_t)1 << 31)) return false;
@@ -975,7 +1218,51 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     return W;
 }
 
-size_t fast_bwd_ws_bytes(const Problem& p) { return fast_bwd_ws_layout(p).total; }
+// elu1: the key side runs on the generic kernels, whose workspace comes first
+struct EluBwdWs {
+    size_t delta, dinv, dSpart, dzpart, img, imgT, epart, total;
+    int kp;
+};
+
+static EluBwdWs elu_bwd_ws_layout(const Problem& p) {
+    EluBwdWs W{};
+    const BwdYPlan y = bwd_y_plan(p);
+    const GradEPlan e = grad_e_plan(p);
+    const size_t BH = (size_t)p.BH;
+    size_t o = round_up(generic_ws_layout(p, 1).total * sizeof(float), 256);
+    W.delta = o;  o += round_up(BH * p.n * 4, 256);
+    W.dinv = o;   o += round_up(BH * p.n * 4, 256);
+    W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
+    W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
+    W.kp = (p.k + 63) / 64 * 64;
+    W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);
+    W.imgT = o;   o += round_up(2 * BH * W.kp * p.d * 2, 256);
+    W.epart = o;  o += e.splits == 1 ? 0 : round_up((size_t)2 * e.splits * e.tilesM * e.tilesN * G_TILE_ELEMS * 4, 256);
+    W.total = o;
+    return W;
+}
+
+size_t fast_bwd_ws_bytes(const Problem& p) { return p.elu ? elu_bwd_ws_layout(p).total : fast_bwd_ws_layout(p).total; }
+
+template <int D, int NW, bool ELU>
+static flurka_status launch_bwd_y_impl(const BwdYArgs& ya, unsigned grid, hipStream_t s) {
+    auto kern = bwd_query_y_kernel<D, NW, ELU>;
+    constexpr int ldsb = BwdYLds<D, ELU>::total;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
+        return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), ldsb, s, ya);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
+}
+
+static flurka_status launch_bwd_y(const Problem& p, const BwdYArgs& ya, const BwdYPlan& y, hipStream_t s) {
+    const unsigned grid = (unsigned)((long)p.BH * y.R * ((y.FT + y.NW - 1) / y.NW));
+    if (p.elu) {        // features = the d coordinates: 2 or 4 feature tiles
+        return p.d == 64 ? launch_bwd_y_impl<64, 4, true>(ya, grid, s) : launch_bwd_y_impl<128, 4, true>(ya, grid, s);
+    }
+    if (p.d == 64) return y.NW == 8 ? launch_bwd_y_impl<64, 8, false>(ya, grid, s) : launch_bwd_y_impl<64, 4, false>(ya, grid, s);
+    return y.NW == 8 ? launch_bwd_y_impl<128, 8, false>(ya, grid, s) : launch_bwd_y_impl<128, 4, false>(ya, grid, s);
+}
 
 template <int D, bool RING>
 static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
@@ -990,7 +1277,60 @@ static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
     return FLURKA_OK;
 }
 
+// The four sequence-length GEMMs from the bf16 images of dK', dV': img (2 x BH x kp x d) and imgT
+// (2 x BH*d x kp); `part` holds the split partials of dE, dF.
+static flurka_status grad_gemms(const Problem& p, const BwdArgs& a, const uint16_t* img, const uint16_t* imgT,
+                                int kp, float* part, hipStream_t s) {
+    const size_t img_elems = (size_t)p.BH * kp * p.d;
+    flurka_status st;
+    {
+        StageScope sc(s, STAGE_K_GRAD_X);
+        GemmParams gp{};       // dK = E^T dK', dV = F^T dV'
+        gp.A[0] = imgT; gp.A[1] = imgT + img_elems;
+        gp.B[0] = (const uint16_t*)a.E; gp.B[1] = (const uint16_t*)a.F;
+        gp.C[0] = a.dK; gp.C[1] = a.dV;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = kp;
+        gp.tilesM = (p.BH * p.d + GBM - 1) / GBM; gp.tilesN = (p.n + GBN - 1) / GBN;
+        gp.splits = 1; gp.total_steps = kp / GBK; gp.steps_per_split = gp.total_steps;
+        st = p.d == 64 ? launch_gemm_mfma<GradXPolicy<64>>(gp, s) : launch_gemm_mfma<GradXPolicy<128>>(gp, s);
+        if (st != FLURKA_OK) return st;
+    }
+    {
+        stage_begin(s);
+        const GradEPlan e = grad_e_plan(p);
+        GemmParams gp{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
+        gp.A[0] = img; gp.A[1] = img + img_elems;
+        gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = kp;
+        gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
+        gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
+        if (e.splits == 1) {
+            // enough tiles to fill the chip without splitting the reduction: results leave as bf16
+            gp.C[0] = a.dE; gp.C[1] = a.dF;
+            st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64, true>>(gp, s) : launch_gemm_mfma<GradEPolicy<128, true>>(gp, s);
+            if (st != FLURKA_OK) return st;
+            stage_end(s, STAGE_K_GRAD_E);
+            return FLURKA_OK;
+        }
+        gp.C[0] = part; gp.C[1] = nullptr;
+        st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64>>(gp, s) : launch_gemm_mfma<GradEPolicy<128>>(gp, s);
+        if (st != FLURKA_OK) return st;
+        stage_end(s, STAGE_K_GRAD_E);
+        StageScope sc(s, STAGE_K_SUM_SPLITS);
+        SumSplitsArgs sa{};
+        sa.dst[0] = (uint16_t*)a.dE; sa.dst[1] = (uint16_t*)a.dF; sa.part = part;
+        sa.k = p.k; sa.n = p.n; sa.splits = e.splits; sa.tilesM = e.tilesM; sa.tilesN = e.tilesN;
+        const long threads = (long)((p.k + 3) / 4) * (p.n / 2);
+        hipLaunchKernelGGL(sum_splits_bf16_kernel, dim3((unsigned)((threads + 255) / 256), 2), dim3(256), 0, s, sa);
+        FLURKA_CHECK_LAUNCH();
+    }
+    return FLURKA_OK;
+}
+
+static flurka_status fast_backward_elu(const Problem& p, const BwdArgs& a, hipStream_t s);
+
 flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
+    if (p.elu) return fast_backward_elu(p, a, s);
     const CtxLayout L = ctx_layout(p);
     const FastBwdWs W = fast_bwd_ws_layout(p);
     const BwdYPlan y = bwd_y_plan(p);
@@ -1021,20 +1361,8 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ya.omega_head_stride = omega_stride;
         ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
         ya.tiles_per_range = y.tiles_per_range;
-        const unsigned ygrid = (unsigned)((long)p.BH * y.R * ((y.FT + y.NW - 1) / y.NW));
         stage_begin(s);
-        const int ylds = p.d == 64 ? BwdYLds<64>::total : BwdYLds<128>::total;
-        const void* yk = p.d == 64 ? (y.NW == 8 ? (const void*)bwd_query_y_kernel<64, 8> : (const void*)bwd_query_y_kernel<64, 4>)
-                                   : (y.NW == 8 ? (const void*)bwd_query_y_kernel<128, 8> : (const void*)bwd_query_y_kernel<128, 4>);
-        if (hipFuncSetAttribute(yk, hipFuncAttributeMaxDynamicSharedMemorySize, ylds) != hipSuccess)
-            return FLURKA_ERR_LAUNCH;
-        if (p.d == 64) {
-            if (y.NW == 8) hipLaunchKernelGGL((bwd_query_y_kernel<64, 8>), dim3(ygrid), dim3(512), ylds, s, ya);
-            else           hipLaunchKernelGGL((bwd_query_y_kernel<64, 4>), dim3(ygrid), dim3(256), ylds, s, ya);
-        } else {
-            if (y.NW == 8) hipLaunchKernelGGL((bwd_query_y_kernel<128, 8>), dim3(ygrid), dim3(512), ylds, s, ya);
-            else           hipLaunchKernelGGL((bwd_query_y_kernel<128, 4>), dim3(ygrid), dim3(256), ylds, s, ya);
-        }
+        if ((st = launch_bwd_y(p, ya, y, s)) != FLURKA_OK) return st;
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_Y);
     }
@@ -1045,7 +1373,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         stage_begin(s);
         const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
         hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.dSimg),
-                           (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
+                           (float*)nullptr, (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
                            (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_MERGE);
@@ -1067,49 +1395,73 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         else           hipLaunchKernelGGL(bwd_key_kernel<128>, dim3(kgrid), dim3(256), klds, s, ka);
         FLURKA_CHECK_LAUNCH();
     }
+    return grad_gemms(p, a, img, imgT, W.kp, (float*)(wsb + W.epart), s);
+}
+
+// elu1: dQ, dS, dz on MFMA kernels of their own; the small key side on the generic kernels (0.05 ms at
+// k = 256); the four sequence-length GEMMs as for the random-feature map.
+template <int D>
+static flurka_status launch_bwd_x_elu(const BwdXEluArgs& xa, hipStream_t s) {
+    auto kern = bwd_query_x_elu_kernel<D>;
+    constexpr int ldsb = BwdXEluLds<D>::total;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
+        return FLURKA_ERR_LAUNCH;
+    const int grid = resident_grid((const void*)kern, 512, ldsb, xa.total_tiles);
+    if (grid < 1) return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ldsb, s, xa);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
+}
+
+static flurka_status fast_backward_elu(const Problem& p, const BwdArgs& a, hipStream_t s) {
+    const CtxLayout L = ctx_layout(p);
+    const GenericWs GW = generic_ws_layout(p, 1);
+    const EluBwdWs W = elu_bwd_ws_layout(p);
+    const BwdYPlan y = bwd_y_plan(p);
+    unsigned char* wsb = (unsigned char*)a.ws;
+    flurka_status st;
     {
-        StageScope sc(s, STAGE_K_GRAD_X);
-        GemmParams gp{};       // dK = E^T dK', dV = F^T dV'
-        gp.A[0] = imgT; gp.A[1] = imgT + img_elems;
-        gp.B[0] = (const uint16_t*)a.E; gp.B[1] = (const uint16_t*)a.F;
-        gp.C[0] = a.dK; gp.C[1] = a.dV;
-        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
-        gp.tilesM = (p.BH * p.d + GBM - 1) / GBM; gp.tilesN = (p.n + GBN - 1) / GBN;
-        gp.splits = 1; gp.total_steps = W.kp / GBK; gp.steps_per_split = gp.total_steps;
-        st = p.d == 64 ? launch_gemm_mfma<GradXPolicy<64>>(gp, s) : launch_gemm_mfma<GradXPolicy<128>>(gp, s);
-        if (st != FLURKA_OK) return st;
-    }
-    {
+        BwdXEluArgs xa{};
+        xa.Q = (const uint16_t*)a.Q; xa.G = (const uint16_t*)a.dOut;
+        xa.S = a.ctx + L.S; xa.z = a.ctx + L.z;
+        xa.dQ = (uint16_t*)a.dQ; xa.delta = (float*)(wsb + W.delta); xa.dinv = (float*)(wsb + W.dinv);
+        xa.n = p.n; xa.tiles_per_head = (p.n + 31) / 32;
+        xa.total_tiles = (long)p.BH * xa.tiles_per_head;
         stage_begin(s);
-        const GradEPlan e = grad_e_plan(p);
-        float* part = (float*)(wsb + W.epart);
-        GemmParams gp{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
-        gp.A[0] = img; gp.A[1] = img + img_elems;
-        gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
-        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = W.kp;
-        gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
-        gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
-        if (e.splits == 1) {
-            // enough tiles to fill the chip without splitting the reduction: results leave as bf16
-            gp.C[0] = a.dE; gp.C[1] = a.dF;
-            st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64, true>>(gp, s) : launch_gemm_mfma<GradEPolicy<128, true>>(gp, s);
-            if (st != FLURKA_OK) return st;
-            stage_end(s, STAGE_K_GRAD_E);
-            return FLURKA_OK;
-        }
-        gp.C[0] = part; gp.C[1] = nullptr;
-        st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64>>(gp, s) : launch_gemm_mfma<GradEPolicy<128>>(gp, s);
+        st = p.d == 64 ? launch_bwd_x_elu<64>(xa, s) : launch_bwd_x_elu<128>(xa, s);
         if (st != FLURKA_OK) return st;
-        stage_end(s, STAGE_K_GRAD_E);
-        StageScope sc(s, STAGE_K_SUM_SPLITS);
-        SumSplitsArgs sa{};
-        sa.dst[0] = (uint16_t*)a.dE; sa.dst[1] = (uint16_t*)a.dF; sa.part = part;
-        sa.k = p.k; sa.n = p.n; sa.splits = e.splits; sa.tilesM = e.tilesM; sa.tilesN = e.tilesN;
-        const long threads = (long)((p.k + 3) / 4) * (p.n / 2);
-        hipLaunchKernelGGL(sum_splits_bf16_kernel, dim3((unsigned)((threads + 255) / 256), 2), dim3(256), 0, s, sa);
+        stage_end(s, STAGE_K_BWD_X);
+
+        BwdYArgs ya{};
+        ya.Q = xa.Q; ya.G = xa.G; ya.lse = xa.dinv; ya.delta = xa.delta;
+        ya.dSpart = (float*)(wsb + W.dSpart); ya.dzpart = (float*)(wsb + W.dzpart);
+        ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
+        ya.tiles_per_range = y.tiles_per_range;
+        stage_begin(s);
+        if ((st = launch_bwd_y(p, ya, y, s)) != FLURKA_OK) return st;
+        stage_end(s, STAGE_K_BWD_Y);
+
+        stage_begin(s);
+        const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
+        hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)nullptr,
+                           a.ws + GW.dS, a.ws + GW.dz, (const float*)(wsb + W.dSpart),
+                           (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
+        FLURKA_CHECK_LAUNCH();
+        stage_end(s, STAGE_K_BWD_MERGE);
+    }
+    // key side: dQ is written and dS, dz are in place; stop before the sequence-length GEMMs
+    if ((st = generic_backward_from(p, a, s, 3)) != FLURKA_OK) return st;
+    uint16_t* img = (uint16_t*)(wsb + W.img);
+    uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
+    {
+        StageScope sc(s, STAGE_K_BWD_KEY);
+        const long per_tensor = (long)p.BH * W.kp * p.d;
+        hipLaunchKernelGGL(grad_images_kernel, dim3((unsigned)((per_tensor + 255) / 256), 2), dim3(256), 0, s,
+                           (const float*)(a.ws + GW.dKp), (const float*)(a.ws + GW.dVp), img, imgT, p.k, W.kp, p.d,
+                           per_tensor);
         FLURKA_CHECK_LAUNCH();
     }
-    return FLURKA_OK;
+    return grad_gemms(p, a, img, imgT, W.kp, (float*)(wsb + W.epart), s);
 }
 
 }  // namespace flurka

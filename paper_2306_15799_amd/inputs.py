@@ -60,10 +60,12 @@ WORKLOADS = {
 # Not benchmark configurations: shapes derived from them for timing code paths the five do not reach.
 # C4T is the long-sequence shape as a training step (head size 128 through the backward kernels; with
 # 256 features the dQ kernel streams one operand term through an LDS ring), D128T the same with 192
-# features, the most for which that kernel holds all its operand images in LDS.
+# features, the most for which that kernel holds all its operand images in LDS; C3T is the elu1
+# workload as a training step.
 DERIVED_WORKLOADS = {
     "C4T": Workload("C4T", 1, 16, 65536, 128, 512, 256, "bf16", PHI_PERFORMER, True),
     "D128T": Workload("D128T", 1, 16, 65536, 128, 512, 192, "bf16", PHI_PERFORMER, True),
+    "C3T": Workload("C3T", 4, 16, 16384, 64, 256, 64, "bf16", PHI_ELU1, True),
 }
 
 

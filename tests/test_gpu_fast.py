@@ -126,6 +126,18 @@ def test_forward_backward_performer(shape):
     print(shape, {k_: f"{v:.2e}" for k_, v in errs.items()})
 
 
+# elu1: dQ, dS, dz on MFMA kernels of their own, the key side on the generic kernels, the four
+# sequence-length GEMMs shared with the random-feature map
+@pytest.mark.parametrize("shape", [(1, 3, 192, 64, 100), (2, 4, 1024, 64, 256), (1, 2, 320, 128, 64),
+                                   (3, 5, 1088, 64, 96), (1, 2, 16384, 64, 256), (2, 2, 2048, 128, 300)])
+def test_forward_backward_elu(shape):
+    B, H, n, d, k = shape
+    w = Workload("fastbwd_elu", B, H, n, d, k, d, "bf16", PHI_ELU1, True)
+    assert fb.fast_path_supported(B, H, n, d, k, d, fb.BF16, w.phi, fb.PASS_BWD)
+    errs = gu.check_forward_backward(w, seed=16, algo="fast")
+    print(shape, {k_: f"{v:.2e}" for k_, v in errs.items()})
+
+
 def test_backward_matches_generic_kernels_closely():
     """Same inputs through both kernel families: they differ only by bf16 rounding of operands."""
     w = Workload("cmp", 1, 2, 512, 64, 128, 64, "bf16", PHI_PERFORMER, True)
