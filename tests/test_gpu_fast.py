@@ -150,11 +150,12 @@ def test_backward_matches_generic_kernels_closely():
         assert fo.rel_l2(gu.to_host(a), gu.to_host(b)) < 2e-2, name
 
 
-@pytest.mark.parametrize("shape", [(2, 2, 512, 64, 96, 64), (2, 3, 512, 128, 96, 256)])
-def test_backward_is_deterministic(shape):
+@pytest.mark.parametrize("shape,phi", [((2, 2, 512, 64, 96, 64), PHI_PERFORMER), ((2, 3, 512, 128, 96, 256), PHI_PERFORMER),
+                                       ((2, 3, 512, 64, 96, 64), PHI_ELU1)])
+def test_backward_is_deterministic(shape, phi):
     """Both head sizes (128 with 256 features: the ring variant of the dQ kernel, whose wavefronts meet
-    at a barrier per feature tile)."""
-    w = Workload("det", *shape, "bf16", PHI_PERFORMER, True)
+    at a barrier per feature tile) and both feature maps."""
+    w = Workload("det", *shape, "bf16", phi, True)
     t = inputs.make_inputs(w, 14)
     g, out, ctx = gu.run_forward(w, t, "fast")
     a = gu.run_backward(w, g, out, ctx, "fast")
@@ -171,12 +172,13 @@ def test_backward_with_one_omega_for_all_heads(d, m):
 
 
 # ---- scratch independence ------------------------------------------------------------------
-@pytest.mark.parametrize("algo,d,m", [("fast", 64, 96), ("generic", 64, 96), ("fast", 128, 256)])
-def test_results_do_not_depend_on_what_the_scratch_buffers_held(algo, d, m):
+@pytest.mark.parametrize("algo,d,m,phi", [("fast", 64, 96, PHI_PERFORMER), ("generic", 64, 96, PHI_PERFORMER),
+                                          ("fast", 128, 256, PHI_PERFORMER), ("fast", 64, 64, PHI_ELU1)])
+def test_results_do_not_depend_on_what_the_scratch_buffers_held(algo, d, m, phi):
     """ctx, workspace and the result tensors are filled with NaN bit patterns (0xFF bytes) before the
     calls: every byte a kernel reads must have been written by an earlier kernel of the same call.
     Shape with ragged k (tile rows past k), ragged heads per projection tile and an odd step count."""
-    w = Workload("poison", 1, 3, 192, d, 100, m, "bf16", PHI_PERFORMER, True)
+    w = Workload("poison", 1, 3, 192, d, 100, m, "bf16", phi, True)
     t = inputs.make_inputs(w, 21)
     g = gu.to_device(t, w.dtype)
     dims = (w.B, w.H, w.n, w.d, w.k, w.m)
