@@ -202,3 +202,52 @@ def test_results_do_not_depend_on_what_the_scratch_buffers_held(algo, d, m, phi)
     for name, a, b in zip(["out", "dQ", "dK", "dV", "dE", "dF"], clean, dirty):
         assert torch.isfinite(b.float()).all(), name
         assert torch.equal(a, b), name
+
+
+# ---- stream capture --------------------------------------------------------------------------
+def test_forward_and_backward_replay_from_a_captured_graph():
+    """The library allocates nothing, never synchronises and clears no memory with runtime calls, so a
+    forward+backward pair can be captured into a graph.  The graph is replayed several times with eager
+    calls (and synchronisations) in between; every replay must reproduce the eager result bit for bit."""
+    w = Workload("graph", 2, 3, 512, 64, 96, 64, "bf16", PHI_PERFORMER, True)
+    t = inputs.make_inputs(w, 17)
+    g = gu.to_device(t, w.dtype)
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    dev = g["Q"].device
+    ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, fb.BF16, w.phi), dev)
+    wf = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_FWD, "auto"), dev)
+    wb = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_BWD, "auto"), dev)
+    out = torch.empty_like(g["Q"])
+    grads = tuple(torch.empty_like(x) for x in (g["Q"], g["K"], g["V"], g["E"], g["F"]))
+
+    def step():
+        fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, out=out, ctx=ctx,
+                           workspace=wf)
+        fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, g["dOut"], ctx, phi=w.phi,
+                           workspace=wb, grads=grads)
+
+    step()                                   # eager: reference values (and one-time kernel attribute calls)
+    torch.cuda.synchronize()
+    ref = [out.clone()] + [x.clone() for x in grads]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                               # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    for rep in range(3):
+        for x in [out, *grads]:
+            x.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(["out", "dQ", "dK", "dV", "dE", "dF"], [out, *grads], ref):
+            assert torch.equal(a, b), (rep, name)
+        # eager work between replays, on another shape, through the same library
+        gu.check_forward(Workload("between", 1, 2, 256, 64, 40, 32, "bf16", PHI_PERFORMER, False), seed=rep, algo="fast")
