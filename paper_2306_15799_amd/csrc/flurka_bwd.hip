@@ -27,6 +27,9 @@
 //                forms r^T and b^T tile by tile and accumulates the two parts of dQ^T
 //   bwd_query_y  one wavefront per (head, 32 features, query range), lane = feature: recomputes W with
 //                the renormalised lambda, accumulates dS and dz over its queries; a merge kernel sums ranges
+// then bwd_key (dK', dV' from dS, dz) and the four sequence-length GEMMs of flurka_gemm.h.
+// phi = elu + 1 has dQ and dS kernels of its own (bwd_query_x_elu, the ELU variant of bwd_query_y) and
+// leaves the small key side to the generic kernels.
 #include "flurka_fast.h"
 #include "flurka_gemm.h"
 

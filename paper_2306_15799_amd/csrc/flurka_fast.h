@@ -15,7 +15,7 @@ KeyStatePlan key_state_plan(const Problem& p);
 
 // Device scratch of the key-state stage (all inside the caller's workspace).
 struct KeyStateBuffers {
-    uint16_t* Kimg;        // 3 x (BH, kpad, d) bf16
+    uint16_t* Kimg;        // 3 x (BH, kpad * d) bf16, key_state's operand order (see proj_finish_kernel)
     uint32_t* Vimg;        // 2 x (BH, kpad/2, d) dwords
     float* nrm;            // (BH, kpad)
     float* Spart;          // (BH, KR, mf, d)
