@@ -1168,7 +1168,7 @@ static GradEPlan grad_e_plan(const Problem& p) {
     q.tilesM = (p.k + GBM - 1) / GBM;
     q.tilesN = (p.n + GBN - 1) / GBN;
     q.total_steps = p.BH * p.d / GBK;
-    int splits = 256 / (q.tilesM * q.tilesN * 2);
+    int splits = 128 / (q.tilesM * q.tilesN * 2);
     if (splits < 1) splits = 1;
     if (splits > q.total_steps) splits = q.total_steps;
     q.steps_per_split = (q.total_steps + splits - 1) / splits;
