@@ -113,7 +113,11 @@ FLURKA_API size_t flurka_workspace_bytes(int B, int H, int n, int d, int k, int 
                               flurka_dtype dtype, flurka_phi phi,
                               flurka_pass pass, flurka_algo algo);
 
-/* 1 if the bf16 MFMA kernels cover this problem for `pass`, else 0. */
+/* 1 if the bf16 MFMA kernels cover this problem for `pass`, else 0.  They take
+ * bf16 storage, d = 64 or 128, n a multiple of 64, m a multiple of 32 and any
+ * k, as long as the per-head operand images fit the 160 KiB of LDS of a
+ * compute unit (random features, forward: m <= 512 at d = 64, m <= 288 at
+ * d = 128; backward: m <= 288 at d = 64, m <= 256 at d = 128; ELU1: always). */
 FLURKA_API int flurka_fast_path_supported(int B, int H, int n, int d, int k, int m,
                                flurka_dtype dtype, flurka_phi phi, flurka_pass pass);
 
