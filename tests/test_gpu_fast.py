@@ -138,6 +138,18 @@ def test_forward_backward_elu(shape):
     print(shape, {k_: f"{v:.2e}" for k_, v in errs.items()})
 
 
+@pytest.mark.parametrize("phi", [PHI_PERFORMER, PHI_ELU1])
+@pytest.mark.parametrize("B,H,n,d,k,m", [(1, 1, 64, 64, 1, 32), (2, 1, 64, 128, 3, 32), (1, 2, 128, 64, 200, 32)])
+def test_degenerate_shapes_through_the_mfma_kernels(phi, B, H, n, d, k, m):
+    """Smallest sequence the path takes (one 64-row step), k = 1 (the output ignores Q and K: dQ, dK, dE are
+    exactly zero and are measured against unit scale), fewer keys than one tile, more keys than positions."""
+    mm = d if phi == PHI_ELU1 else m
+    w = Workload("tiny", B, H, n, d, k, mm, "bf16", phi, True)
+    assert fb.fast_path_supported(B, H, n, d, k, mm, fb.BF16, phi, fb.PASS_BWD)
+    errs = gu.check_forward_backward(w, seed=18, algo="fast", floor=1.0 if k == 1 else 0.0)
+    print((phi, B, H, n, d, k, mm), {k_: f"{v:.2e}" for k_, v in errs.items()})
+
+
 def test_backward_matches_generic_kernels_closely():
     """Same inputs through both kernel families: they differ only by bf16 rounding of operands."""
     w = Workload("cmp", 1, 2, 512, 64, 128, 64, "bf16", PHI_PERFORMER, True)
