@@ -150,6 +150,25 @@ def test_degenerate_shapes_through_the_mfma_kernels(phi, B, H, n, d, k, m):
     print((phi, B, H, n, d, k, mm), {k_: f"{v:.2e}" for k_, v in errs.items()})
 
 
+@pytest.mark.parametrize("qs,ks", [(3.0, 1.0), (1.0, 2.5), (0.05, 0.05)])
+def test_large_and_small_input_norms(qs, ks):
+    """Exponents far from the synthetic workloads' range: queries three times longer (u up to ~ +-60 with a
+    spread of e^40 between the features of one row), keys 2.5 times longer (|k'|^2/2 in the hundreds, key
+    weights spanning hundreds of e-folds), and nearly uniform attention (everything scaled down)."""
+    w = Workload("norms", 1, 2, 1024, 64, 128, 128, "bf16", PHI_PERFORMER, True)
+    t = inputs.make_inputs(w, 19)
+    t["Q"] = inputs.round_to_bf16(t["Q"] * qs)
+    t["K"] = inputs.round_to_bf16(t["K"] * ks)
+    g, out, ctx = gu.run_forward(w, t, "fast")
+    errs = {"out": fo.rel_l2(gu.to_host(out), gu.oracle_forward(w, t))}
+    grads = gu.run_backward(w, g, out, ctx, "fast")
+    for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], grads, gu.oracle_backward(w, t)):
+        errs[name] = gu.rel_err(gu.to_host(a), b)
+    print((qs, ks), {k_: f"{v:.2e}" for k_, v in errs.items()})
+    assert all(v <= 2e-2 for v in errs.values()), errs
+    assert all(torch.isfinite(x.float()).all() for x in (out, *grads))
+
+
 def test_backward_matches_generic_kernels_closely():
     """Same inputs through both kernel families: they differ only by bf16 rounding of operands."""
     w = Workload("cmp", 1, 2, 512, 64, 128, 64, "bf16", PHI_PERFORMER, True)
