@@ -169,6 +169,23 @@ def test_large_and_small_input_norms(qs, ks):
     assert all(torch.isfinite(x.float()).all() for x in (out, *grads))
 
 
+@pytest.mark.parametrize("phi,d,m", [(PHI_PERFORMER, 64, 96), (PHI_PERFORMER, 128, 256), (PHI_ELU1, 64, 64)])
+def test_backward_is_linear_in_the_upstream_gradient(phi, d, m):
+    """Every gradient is linear in dOut, and scaling by a power of two commutes with every rounding on
+    the way: grads(4 dOut) = 4 grads(dOut) bit for bit, and grads(0) = 0 exactly."""
+    w = Workload("lin", 2, 2, 512, d, 96, m, "bf16", phi, True)
+    t = inputs.make_inputs(w, 20)
+    g, out, ctx = gu.run_forward(w, t, "fast")
+    base = gu.run_backward(w, g, out, ctx, "fast")
+    g4 = dict(g); g4["dOut"] = g["dOut"] * 4
+    quad = gu.run_backward(w, g4, out, ctx, "fast")
+    g0 = dict(g); g0["dOut"] = torch.zeros_like(g["dOut"])
+    zero = gu.run_backward(w, g0, out, ctx, "fast")
+    for name, a, b, z in zip(["dQ", "dK", "dV", "dE", "dF"], base, quad, zero):
+        assert torch.equal(a * 4, b), name
+        assert not z.float().abs().max().item(), name
+
+
 def test_backward_matches_generic_kernels_closely():
     """Same inputs through both kernel families: they differ only by bf16 rounding of operands."""
     w = Workload("cmp", 1, 2, 512, 64, 128, 64, "bf16", PHI_PERFORMER, True)
