@@ -8,11 +8,14 @@ line.  `value` is tokens*heads per second of the whole step.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--algo auto]
 
-The `roofline` object describes the stage that takes the most time, measured
-with HIP events recorded on the stream the kernels run on (the library's
-built-in stage timer), in a second loop of the same K steps so that the
-events do not sit inside the region that `value` is computed from.
-`cpu_baseline` times the fp64 oracle on a bounded sample of the same
+Three loops of K steps each run per workload: the first, bracketed by two
+events, gives `ms_per_step` and `value`; the second has an event between the
+steps and gives the median and the minimum; the third runs with the library's
+stage timer on (HIP events recorded on the kernels' own stream around every
+launch) and gives `stages`, `kernels` and `roofline`, the entry of the kernel
+that takes the most time per step.  With the default workload the forward
+workloads C1..C4 are timed as well (`configs`; C4 is repeated as the benchmark spec).
+`cpu_baseline` times the fp64 oracle on a bounded sample of the headline
 workload on the host cores.
 """
 from __future__ import annotations
@@ -20,6 +23,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -33,111 +37,264 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0  # dense bf16, TFLOP/s
 PEAK_FP32_TFLOPS = 157.3        # vector fp32
 
 
-def stage_model(w, stage: str):
-    """Algorithmic (flops, bytes) of one stage for workload w: every caller tensor the
-    stage needs read once, every result written once, no n x k or n x m matrix in HBM."""
+def _sizes(w):
     es = 2 if w.dtype == "bf16" else 4
     BH, n, d, k = w.B * w.H, w.n, w.d, w.k
-    mf = w.d if w.phi == "elu1" else w.m
     perf = w.phi != "elu1"
+    mf = w.m if perf else w.d
     om = (w.H if w.omega_per_head else 1) * w.m * d * es if perf else 0
-    small = 4 * BH * (2 * k * d + mf * d + mf)          # K', V', S, z in fp32
+    return es, BH, n, d, k, mf, perf, om
+
+
+def stage_model(w, stage: str):
+    """Algorithmic (flops, bytes) of one stage: every caller tensor the stage needs read once, every
+    result written once; the small fp32 intermediates (K', V', S, z) and anything the library adds for
+    its own design (out read again in the backward, per-row side vectors) are not counted."""
+    es, BH, n, d, k, mf, perf, om = _sizes(w)
     if stage == "project":
-        return 4.0 * k * n * d * BH, es * (2 * BH * n * d + 2 * k * n) + 4 * BH * 2 * k * d
+        return 4.0 * k * n * d * BH, es * (2 * BH * n * d + 2 * k * n)
     if stage == "key_state":
         fl = (2 * k * d * mf + 2 * k * mf * d + k * mf) * BH if perf else (2 * k * d * d + k * d) * BH
-        return float(fl), small + om
+        return float(fl), 4 * BH * (2 * k * d + mf * d + mf) + om
     if stage == "query_stream":
         fl = (2 * n * d * mf + 2 * n * mf * d + 2 * n * mf) * BH if perf else (2 * n * d * d + 2 * n * d) * BH
-        return float(fl), es * 2 * BH * n * d + om + 4 * BH * (mf * d + mf)
+        return float(fl), es * 2 * BH * n * d + om
     if stage == "bwd_query":
-        # with the forward's log-denominators and out at hand: u, G S^T, dQ, dS (performer)
-        gemms = 4 if perf else 3
-        return 2.0 * gemms * n * mf * d * BH, es * 4 * BH * n * d + om + 4 * BH * 2 * (mf * d + mf)
+        gemms = 4 if perf else 3            # u, G S^T, dQ, dS (u is not needed for elu1)
+        return 2.0 * gemms * n * mf * d * BH, es * 3 * BH * n * d + om
     if stage == "bwd_key":
-        return float((4 * k * mf * d + (2 * k * mf * d if perf else 0)) * BH), 2 * small
+        return float((4 * k * mf * d + (2 * k * mf * d if perf else 0)) * BH), 4 * BH * 2 * (2 * k * d + mf * d + mf)
     if stage == "bwd_dk_dv":
-        return 4.0 * n * k * d * BH, es * (2 * k * n + 2 * BH * n * d) + 4 * BH * 2 * k * d
+        return 4.0 * n * k * d * BH, es * (2 * k * n + 2 * BH * n * d)
     if stage == "bwd_de_df":
-        return 4.0 * k * n * d * BH, es * (2 * BH * n * d + 2 * k * n) + 4 * BH * 2 * k * d
+        return 4.0 * k * n * d * BH, es * (2 * BH * n * d + 2 * k * n)
     raise KeyError(stage)
 
 
-# timer name of an MFMA-path kernel -> (name in rocprofv3 traces, stage it belongs to)
-KERNEL_TRACE_NAME = {
-    "gemm_mfma_proj": "gemm_mfma_kernel<ProjPolicy<{d}>, false>",        # one item per workgroup
-    "proj_finish": "proj_finish_kernel",
-    "key_state": "key_state_kernel<{d}, false>",
-    "merge_pack": "merge_pack_kernel",
-    "query_stream": "query_stream_kernel<{d}, {elu}, {qs_waves}, 1, {elu}>",     # staged tiles: elu1 only
-    "bwd_query_x": "bwd_query_x_kernel<{d}, {ring}>",              # ring: d = 128 with more than 192 features
-    "bwd_query_y": "bwd_query_y_kernel<{d}, 8, false>",
-    "bwd_merge": "bwd_merge_kernel",
-    "bwd_key": "bwd_key_kernel<{d}>",
-    "gemm_mfma_gradx": "gemm_mfma_kernel<GradXPolicy<{d}>, true>",      # several items per workgroup
-    "gemm_mfma_grade": "gemm_mfma_kernel<GradEPolicy<{d}, false>, false>",
-    "sum_splits": "sum_splits_bf16_kernel",
-}
-
-
 def kernel_model(w, kernel: str):
-    """Algorithmic (flops, bytes) of one kernel of the MFMA path (recomputation is not counted: the
-    backward's four n*m*d contractions are split 3 : 1 between bwd_query_x, which forms u, G S^T and
-    dQ, and bwd_query_y, whose second evaluation of u is not counted)."""
-    es = 2 if w.dtype == "bf16" else 4
-    BH, n, d, k = w.B * w.H, w.n, w.d, w.k
-    mf = w.d if w.phi == "elu1" else w.m
+    """(flops, algorithmic bytes, bytes the kernel moves by design) of one kernel of the MFMA path.
+    Algorithmic: the caller tensors this kernel's part of the method needs, once.  By design: what the
+    kernel as written reads and writes (side vectors per query row, split partials, the forward's out).
+    Recomputation is not counted as flops: of the backward's four n*m*d contractions three belong to
+    bwd_query_x (u, G S^T, dQ) and one to bwd_query_y (dS; its second evaluation of u is not counted)."""
+    es, BH, n, d, k, mf, perf, om = _sizes(w)
+    state = 4 * BH * (mf * d + mf)
     if kernel == "gemm_mfma_proj":
-        return stage_model(w, "project")
+        fl, by = stage_model(w, "project")
+        return fl, by, by + 2 * 4 * BH * k * d      # + one set of fp32 partials (times the split count at run time)
     if kernel == "query_stream":
-        return stage_model(w, "query_stream")
+        fl, by = stage_model(w, "query_stream")
+        return fl, by, by + 4 * BH * n + BH * mf * d * 2
     if kernel == "key_state":
-        return stage_model(w, "key_state")
+        fl, by = stage_model(w, "key_state")
+        return fl, by, by
     if kernel == "bwd_query_x":
-        return 6.0 * n * mf * d * BH, es * 4 * BH * n * d + 8 * BH * n
+        fl = (6.0 if perf else 2.0) * n * mf * d * BH
+        alg = es * 3 * BH * n * d                    # Q, dOut in; dQ out
+        return fl, alg, alg + 12 * BH * n + state    # lse in, g and the renormalised lse out, S/z/c
     if kernel == "bwd_query_y":
-        return 2.0 * n * mf * d * BH, es * 2 * BH * n * d + 8 * BH * n + 4 * BH * mf * d
+        alg = es * 2 * BH * n * d                    # Q, dOut in (dS, dz are small intermediates)
+        return 2.0 * n * mf * d * BH, alg, alg + 8 * BH * n + state
     if kernel == "bwd_key":
-        return stage_model(w, "bwd_key")
+        fl, by = stage_model(w, "bwd_key")
+        return fl, by, by
     if kernel == "gemm_mfma_gradx":
-        return stage_model(w, "bwd_dk_dv")
+        fl, by = stage_model(w, "bwd_dk_dv")
+        return fl, by, by + 2 * BH * k * d * 2
     if kernel == "gemm_mfma_grade":
-        return stage_model(w, "bwd_de_df")
+        fl, by = stage_model(w, "bwd_de_df")
+        return fl, by, by + 2 * BH * k * d * 2
     # small helper kernels: data movement only
     small = 4 * BH * (2 * k * d + mf * d + mf)
-    return 0.0, float(small)
+    return 0.0, float(small), float(small)
 
 
 def whole_model(w):
+    """Algorithmic flops and bytes of a whole step: forward reads Q, K, V, E, F, omega and writes out;
+    the backward reads Q, K, V, dOut, E, F, omega and writes dQ, dK, dV, dE, dF."""
     stages = ["project", "key_state", "query_stream"]
     if w.backward:
         stages += ["bwd_query", "bwd_key", "bwd_dk_dv", "bwd_de_df"]
     fl = sum(stage_model(w, s)[0] for s in stages)
-    es = 2 if w.dtype == "bf16" else 4
-    BH, n, d, k = w.B * w.H, w.n, w.d, w.k
-    om = (w.H if w.omega_per_head else 1) * w.m * d * es if w.phi != "elu1" else 0
-    by = es * (4 * BH * n * d + 2 * k * n) + om                       # forward: Q,K,V,E,F,omega in, out out
+    es, BH, n, d, k, mf, perf, om = _sizes(w)
+    by = es * (4 * BH * n * d + 2 * k * n) + om
     if w.backward:
-        # backward: Q, K, V, out, dOut, E, F, omega in; dQ, dK, dV, dE, dF out
-        by += es * (5 * BH * n * d + 2 * k * n) + om + es * (3 * BH * n * d + 2 * k * n)
+        by += es * (4 * BH * n * d + 2 * k * n) + om + es * (3 * BH * n * d + 2 * k * n)
     return fl, by
 
 
-def roofline_entry(w, stage, avg_ms, launches_note, model=None):
-    fl, by = (model or stage_model)(w, stage)
+def peak_flops(w):
+    return (PEAK_MFMA_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS) * 1e12
+
+
+def roofline_entry(w, name, avg_ms, note, per_kernel):
+    if per_kernel:
+        fl, by, design = kernel_model(w, name)
+    else:
+        fl, by = stage_model(w, name)
+        design = by
     sec = avg_ms * 1e-3
-    peak_fl = PEAK_MFMA_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
-    t_fl = fl / (peak_fl * 1e12)
+    t_fl = fl / peak_flops(w)
     t_by = by / (PEAK_HBM_GBS * 1e9)
     if t_fl >= t_by:
         bound = "mfma" if w.dtype == "bf16" else "alu"
-        achieved, peak, unit = fl / sec / 1e12, peak_fl, "TFLOP/s"
+        achieved, peak, unit = fl / sec / 1e12, peak_flops(w) / 1e12, "TFLOP/s"
     else:
         bound, achieved, peak, unit = "hbm", by / sec / 1e9, PEAK_HBM_GBS, "GB/s"
-    return {"kernel": stage, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+    return {"kernel": name, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
             "frac": round(achieved / peak, 4), "traffic": None, "avg_ms": round(avg_ms, 5),
-            "alg_flops": fl, "alg_bytes": by,
-            "tflops": round(fl / sec / 1e12, 3), "gbs": round(by / sec / 1e9, 2), "note": launches_note}
+            "alg_flops": fl, "alg_bytes": by, "design_bytes": design,
+            "tflops": round(fl / sec / 1e12, 3), "gbs": round(by / sec / 1e9, 2), "note": note}
+
+
+def run_workload(torch, fb, inputs, w, algo, steps, warmup, graph=False):
+    """Times `steps` steps of workload w three times over (see the module docstring)."""
+    t = inputs.make_inputs(w, seed=0)
+    td = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    dev = torch.device("cuda:0")
+    g = {k: (None if v is None else torch.from_numpy(v).to(dev).to(td).contiguous()) for k, v in t.items()}
+    code = fb.BF16 if w.dtype == "bf16" else fb.F32
+    m_eff = w.d if w.phi == "elu1" else w.m
+    dims = (w.B, w.H, w.n, w.d, w.k, m_eff)
+    ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, code, w.phi), dev)
+    ws_f = fb.alloc_buffer(fb.workspace_bytes(*dims, code, w.phi, fb.PASS_FWD, algo), dev)
+    out = torch.empty_like(g["Q"])
+    grads = ws_b = None
+    if w.backward:
+        ws_b = fb.alloc_buffer(fb.workspace_bytes(*dims, code, w.phi, fb.PASS_BWD, algo), dev)
+        grads = (torch.empty_like(g["Q"]), torch.empty_like(g["Q"]), torch.empty_like(g["Q"]),
+                 torch.empty_like(g["E"]), torch.empty_like(g["E"]))
+
+    def step():
+        fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, algo=algo,
+                           out=out, ctx=ctx, workspace=ws_f)
+        if w.backward:
+            fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, g["dOut"], ctx,
+                               phi=w.phi, algo=algo, workspace=ws_b, grads=grads)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    # loop 1: the figure `value` comes from
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms_per_step = ev0.elapsed_time(ev1) / steps
+
+    # loop 2: one event between steps -> median and minimum
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record()
+    for i in range(steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+
+    # loop 3: per-kernel times from HIP events on the kernels' own stream
+    fb.profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    rec = fb.profile_read()
+    fb.profile_enable(False)
+    # timer entries are "stage" (generic kernels) or "stage:kernel" (MFMA path, one kernel each)
+    stage_tot, kernel_tot, kernel_cnt = {}, {}, {}
+    for name, ms in rec:
+        stage, _, kern = name.partition(":")
+        stage_tot[stage] = stage_tot.get(stage, 0.0) + ms
+        if kern:
+            kernel_tot[kern] = kernel_tot.get(kern, 0.0) + ms
+            kernel_cnt[kern] = kernel_cnt.get(kern, 0) + 1
+    stage_avg = {k: v / steps for k, v in stage_tot.items()}
+    stages_out = {}
+    for name, ms in stage_avg.items():
+        fl, by = stage_model(w, name)
+        stages_out[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 2), "gbs": round(by / ms / 1e6, 1)}
+    kernels_out = {k: {"avg_ms": round(kernel_tot[k] / kernel_cnt[k], 5), "launches_per_step": kernel_cnt[k] / steps}
+                   for k in kernel_tot}
+    if kernel_tot:
+        dominant = max(kernel_tot, key=kernel_tot.get)
+        roof = roofline_entry(w, dominant, kernel_tot[dominant] / kernel_cnt[dominant],
+                              "HIP events around each launch of this kernel, on the stream it runs on", True)
+        attach_traffic(roof, w, dominant)
+    else:
+        dominant = max(stage_avg, key=stage_avg.get)
+        roof = roofline_entry(w, dominant, stage_avg[dominant],
+                              "stage time = HIP events around the stage's launches on their stream", False)
+
+    res = {"ms_per_step": ms_per_step, "wall_ms_per_step": wall_ms, "ms_median": statistics.median(per_step),
+           "ms_min": min(per_step), "stages": stages_out, "kernels": kernels_out, "roofline": roof,
+           "dims": dims, "code": code, "inputs": t, "out": out}
+
+    if graph:
+        # the same step captured once into a HIP graph and replayed: what the kernels take when the host's
+        # launch work is out of the way
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                step()
+                side.synchronize()
+                with torch.cuda.graph(gr, stream=side):
+                    step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            for _ in range(warmup):
+                gr.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                gr.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            res["graph_ms_per_step"] = e0.elapsed_time(e1) / steps
+        except Exception as exc:      # a figure beside the headline, never a reason to lose the run
+            res["graph_error"] = repr(exc)[:200]
+    return res
+
+
+def attach_traffic(roof, w, kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter runs, if they were measured on the
+    library sources that are running now."""
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(tpath):
+        return
+    from paper_2306_15799_amd import profile_summary
+    entry = json.load(open(tpath)).get(w.name, {})
+    tr = entry.get("kernels", {}).get(kernel)
+    if not tr:
+        return
+    if entry.get("source_sha256") != profile_summary.source_hash():
+        roof["traffic_stale"] = True          # the kernels changed since the counters were read
+        return
+    roof["traffic"] = tr["read_bytes"] + tr["write_bytes"]
+    roof["traffic_kernel"] = tr.get("trace_name")
+    roof["traffic_note"] = ("HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE runs "
+                            "(profiles/hbm_traffic_%s.txt)" % w.name)
+
+
+def summary(w, r):
+    """Short record of one workload for the `configs` block."""
+    fl_all, by_all = whole_model(w)
+    sec = r["ms_per_step"] * 1e-3
+    t_fl, t_by = fl_all / peak_flops(w), by_all / (PEAK_HBM_GBS * 1e9)
+    roof = r["roofline"]
+    return {"ms_per_step": round(r["ms_per_step"], 5), "ms_median": round(r["ms_median"], 5),
+            "ms_min": round(r["ms_min"], 5), "tokens_heads_per_s": round(w.tokens_heads / sec, 1),
+            "tflops": round(fl_all / sec / 1e12, 2), "gbs": round(by_all / sec / 1e9, 1),
+            "binding_roof": "mfma" if t_fl >= t_by else "hbm",
+            "roof_ms": round(max(t_fl, t_by) * 1e3, 5),
+            "frac_of_binding_roof": round(max(t_fl, t_by) / sec, 4),
+            "dominant_kernel": roof["kernel"], "dominant_kernel_ms": roof["avg_ms"],
+            "dominant_kernel_bound": roof["bound"], "dominant_kernel_frac": roof["frac"],
+            "kernels_ms": {k: v["avg_ms"] for k, v in r["kernels"].items()} or {k: v["ms"] for k, v in r["stages"].items()}}
 
 
 def main():
@@ -150,6 +307,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-measured-peaks", action="store_true",
                     help="skip the device copy and library GEMM that give the box's achievable HBM and MFMA rates")
+    ap.add_argument("--no-configs", action="store_true", help="skip the extra timing of the forward workloads C1..C4")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample")
     args = ap.parse_args()
 
@@ -169,99 +327,20 @@ def main():
         sys.exit(3)
     fb.load_library()          # raises if the HIP library has not been built: there is no fallback
 
-    w = {**inputs.WORKLOADS, **inputs.DERIVED_WORKLOADS}[args.workload]
-    t = inputs.make_inputs(w, seed=0)
-    td = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    dev = torch.device("cuda:0")
-    g = {k: (None if v is None else torch.from_numpy(v).to(dev).to(td).contiguous()) for k, v in t.items()}
-    if w.backward and "dOut" not in g:
-        raise RuntimeError("workload has a backward pass but no dOut")
-
-    code = fb.BF16 if w.dtype == "bf16" else fb.F32
-    m_eff = w.d if w.phi == "elu1" else w.m
-    dims = (w.B, w.H, w.n, w.d, w.k, m_eff)
-    ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, code, w.phi), dev)
-    ws_f = fb.alloc_buffer(fb.workspace_bytes(*dims, code, w.phi, fb.PASS_FWD, args.algo), dev)
-    out = torch.empty_like(g["Q"])
-    grads = ws_b = None
-    if w.backward:
-        ws_b = fb.alloc_buffer(fb.workspace_bytes(*dims, code, w.phi, fb.PASS_BWD, args.algo), dev)
-        grads = (torch.empty_like(g["Q"]), torch.empty_like(g["Q"]), torch.empty_like(g["Q"]),
-                 torch.empty_like(g["E"]), torch.empty_like(g["E"]))
-
-    def step():
-        fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, algo=args.algo,
-                           out=out, ctx=ctx, workspace=ws_f)
-        if w.backward:
-            fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, g["dOut"], ctx,
-                               phi=w.phi, algo=args.algo, workspace=ws_b, grads=grads)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
-
-    # per-stage times from HIP events on the kernels' own stream, same K steps again
-    fb.profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    rec = fb.profile_read()
-    fb.profile_enable(False)
-    # timer entries are "stage" (generic kernels) or "stage:kernel" (MFMA path, one kernel each)
-    steps_seen = max(1, args.steps)
-    stage_tot, kernel_tot, kernel_cnt = {}, {}, {}
-    for name, ms in rec:
-        stage, _, kern = name.partition(":")
-        stage_tot[stage] = stage_tot.get(stage, 0.0) + ms
-        if kern:
-            kernel_tot[kern] = kernel_tot.get(kern, 0.0) + ms
-            kernel_cnt[kern] = kernel_cnt.get(kern, 0) + 1
-    stage_avg = {k: v / steps_seen for k, v in stage_tot.items()}
-    stages_out = {}
-    for name, ms in stage_avg.items():
-        fl, by = stage_model(w, name)
-        stages_out[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 2), "gbs": round(by / ms / 1e6, 1)}
-    kernels_out = {k: {"avg_ms": round(kernel_tot[k] / kernel_cnt[k], 5), "launches_per_step": kernel_cnt[k] / steps_seen}
-                   for k in kernel_tot}
-    if kernel_tot:
-        # dominant kernel = largest time per step; its average launch duration from the HIP events
-        dominant = max(kernel_tot, key=kernel_tot.get)
-        avg_launch = kernel_tot[dominant] / kernel_cnt[dominant]
-        roof = roofline_entry(w, dominant, avg_launch,
-                              "HIP events around each launch of this kernel, on the stream it runs on",
-                              model=kernel_model)
-        trace = KERNEL_TRACE_NAME[dominant].format(d=w.d, elu="true" if w.phi == "elu1" else "false",
-                                                   qs_waves=12 if w.d == 64 else 8,
-                                                   ring="true" if (w.d == 128 and m_eff > 192) else "false")
-        roof["kernel_in_trace"] = trace
-        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-        if os.path.exists(tpath):
-            tr = json.load(open(tpath)).get(w.name, {}).get("kernels", {}).get(trace)
-            if tr:
-                roof["traffic"] = tr["read_bytes"] + tr["write_bytes"]
-                roof["traffic_note"] = "HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE runs (profiles/hbm_traffic_%s.txt)" % w.name
-    else:
-        dominant = max(stage_avg, key=stage_avg.get)
-        roof = roofline_entry(w, dominant, stage_avg[dominant],
-                              "stage time = HIP events around the stage's launches on their stream")
+    all_w = {**inputs.WORKLOADS, **inputs.DERIVED_WORKLOADS}
+    w = all_w[args.workload]
+    r = run_workload(torch, fb, inputs, w, args.algo, args.steps, args.warmup, graph=True)
+    t, out, dims, code = r["inputs"], r["out"], r["dims"], r["code"]
+    m_eff = dims[5]
 
     fl_all, by_all = whole_model(w)
-    sec = ms_per_step * 1e-3
-    value = w.tokens_heads / sec
-
+    sec = r["ms_per_step"] * 1e-3
     result = {
         "metric": "FLuRKA attn fwd+bwd tokens*heads/s" if w.backward else "FLuRKA attn fwd tokens*heads/s",
-        "value": round(value, 1), "unit": "tokens*heads/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "wall_ms_per_step": round(wall_ms, 5),
+        "value": round(w.tokens_heads / sec, 1), "unit": "tokens*heads/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(r["ms_per_step"], 5),
+        "ms_per_step_median": round(r["ms_median"], 5), "ms_per_step_min": round(r["ms_min"], 5),
+        "wall_ms_per_step": round(r["wall_ms_per_step"], 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} n={w.n} d={w.d} k={w.k} m={m_eff} {w.dtype} "
@@ -269,16 +348,24 @@ def main():
                    "fast_path": bool(fb.fast_path_supported(*dims, code, w.phi, fb.PASS_FWD))},
         "whole_step": {"tflops": round(fl_all / sec / 1e12, 3), "gbs": round(by_all / sec / 1e9, 2),
                        "alg_flops": fl_all, "alg_bytes": by_all,
-                       "frac_of_binding_roof": round(max(fl_all / (PEAK_MFMA_BF16_TFLOPS * 1e12 if w.dtype == "bf16" else PEAK_FP32_TFLOPS * 1e12),
-                                                         by_all / (PEAK_HBM_GBS * 1e9)) / sec, 4)},
-        "stages": stages_out,
-        "kernels": kernels_out,
-        "roofline": roof,
+                       "frac_of_binding_roof": round(max(fl_all / peak_flops(w), by_all / (PEAK_HBM_GBS * 1e9)) / sec, 4)},
+        "stages": r["stages"],
+        "kernels": r["kernels"],
+        "roofline": r["roofline"],
     }
+    if "graph_ms_per_step" in r:
+        result["hip_graph_replay"] = {"ms_per_step": round(r["graph_ms_per_step"], 5),
+                                      "note": "the same forward(+backward) calls captured once into a HIP graph and replayed; "
+                                              "not the figure `value` is computed from"}
+    elif "graph_error" in r:
+        result["hip_graph_replay"] = {"error": r["graph_error"]}
+    roof = result["roofline"]
 
     if not args.no_measured_peaks:
         # What this machine sustains, beside the published peaks: a plain device copy (read + write) and the
         # vendor library's bf16 GEMM, both through torch.  Context for the fractions above, not a target.
+        dev = torch.device("cuda:0")
+
         def timed(fn, reps):
             fn(); torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -307,30 +394,52 @@ def main():
         from oracle import flurka_oracle as fo
         import threadpoolctl
         threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+        out_host = out.float().cpu().numpy()          # before the clock starts: the copy is not the oracle's work
         # bounded sample: whole heads of the same workload, one after another, until the time target
         heads = [(b, h) for b in range(w.B) for h in range(w.H)]
-        done, t_start = 0, time.perf_counter()
-        errs = []
-        passes = 0
+        kept = {}                                      # a few references of the first pass, compared afterwards
+        done, passes, t_start = 0, 0, time.perf_counter()
         while time.perf_counter() - t_start < args.cpu_seconds and passes < 64:
-          passes += 1
-          for (b, h) in heads:
-            om = None if t["omega"] is None else np.asarray(t["omega"][h if t["omega"].shape[0] > 1 else 0], np.float64)
-            ref = fo.flurka_head(t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["E"], t["F"], om, w.phi)
-            if w.backward:
-                fo.flurka_head_bwd(t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["E"], t["F"], om,
-                                   t["dOut"][b, h], w.phi)
-            done += 1
-            if passes == 1:
-                errs.append(fo.rel_l2(out[b, h].float().cpu().numpy(), ref))
-            if time.perf_counter() - t_start >= args.cpu_seconds:
-                break
+            passes += 1
+            for (b, h) in heads:
+                om = None if t["omega"] is None else np.asarray(t["omega"][h if t["omega"].shape[0] > 1 else 0], np.float64)
+                ref = fo.flurka_head(t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["E"], t["F"], om, w.phi)
+                if w.backward:
+                    fo.flurka_head_bwd(t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["E"], t["F"], om,
+                                       t["dOut"][b, h], w.phi)
+                done += 1
+                if passes == 1 and len(kept) < 4:
+                    kept[(b, h)] = ref
+                if time.perf_counter() - t_start >= args.cpu_seconds:
+                    break
         cpu_s = time.perf_counter() - t_start
         result["cpu_baseline"] = {"value": round(done * w.n / cpu_s, 1), "unit": "tokens*heads/s",
-                                  "cores": int(threads), "kind": "oracle",
+                                  "cores": int(threads), "host_cpus": os.cpu_count(), "kind": "oracle",
                                   "sample": f"{done} (batch, head) slices ({len(heads)} distinct) of {w.name}, "
-                                            f"{'fwd+bwd' if w.backward else 'fwd'}, fp64 numpy, {cpu_s:.1f} s"}
-        result["parity_sample_rel_l2_out"] = float(max(errs))
+                                            f"{'fwd+bwd' if w.backward else 'fwd'}, fp64 numpy with {threads} BLAS threads "
+                                            f"on a host that reports {os.cpu_count()} CPUs, {cpu_s:.1f} s"}
+        result["parity_sample_rel_l2_out"] = float(max(fo.rel_l2(out_host[b, h], ref) for (b, h), ref in kept.items()))
+    del r, t, out
+
+    if args.workload == "C5" and not args.no_configs:
+        # the other four workloads (forward only), so that one default run records all five
+        configs = {"C5": summary(w, {"ms_per_step": result["ms_per_step"], "ms_median": result["ms_per_step_median"],
+                                     "ms_min": result["ms_per_step_min"], "roofline": roof,
+                                     "kernels": result["kernels"], "stages": result["stages"]})}
+        for name in ["C1", "C2", "C3", "C4"]:
+            wn = all_w[name]
+            rn = run_workload(torch, fb, inputs, wn, args.algo, min(args.steps, 20), min(args.warmup, 5))
+            configs[name] = summary(wn, rn)
+            if name == "C4":
+                c4 = configs[name]
+                result["north_star"] = {"workload": "C4 forward: B=1 H=16 n=65536 d=128 k=512 m=256 bf16 performer",
+                                        "ms": c4["ms_per_step"], "ms_median": c4["ms_median"], "ms_min": c4["ms_min"],
+                                        "tflops": c4["tflops"], "gbs": c4["gbs"], "binding_roof": c4["binding_roof"],
+                                        "roof_ms": c4["roof_ms"], "frac_of_binding_roof": c4["frac_of_binding_roof"],
+                                        "target_frac": 0.5}
+            del rn
+            torch.cuda.empty_cache()
+        result["configs"] = configs
 
     print(json.dumps(result))
 

@@ -146,7 +146,7 @@ FLURKA_API flurka_status flurka_attn_fwd(const void* Q, const void* K, const voi
                               void* stream);
 
 /*
- * Backward of the forward above (chain rule; the paper trains through this
+ * Backward of flurka_attn_fwd (chain rule; the paper trains through this
  * layer but prints no backward).  Given dOut = d loss / d out:
  *
  *   out         in   (B, H, n, d), the forward's result for the same inputs

@@ -2,6 +2,7 @@
 // The entry points are documented in include/flurka.h.
 #include "flurka_internal.h"
 
+#include <mutex>
 #include <vector>
 
 using namespace flurka;
@@ -29,11 +30,65 @@ void stage_end(hipStream_t s, Stage id) {
     g_stage_of[g_intervals] = (int)id;
     ++g_intervals;
 }
+
+void stage_abandon() { g_open = false; }
+
+// ---- launch facts ---------------------------------------------------------------
+namespace {
+struct FactsEntry { int dev; const void* kernel; int threads, lds; KernelFacts facts; };
+std::mutex g_facts_mutex;
+std::vector<FactsEntry> g_facts;         // a few dozen entries at most: linear search
+std::vector<int> g_cus;                  // compute units per device id, 0 = not asked yet
+
+// compute units of device `dev`; 0 if the runtime cannot tell (g_facts_mutex held)
+int cus_of(int dev) {
+    if (dev < 0) return 0;
+    if ((size_t)dev >= g_cus.size()) g_cus.resize((size_t)dev + 1, 0);
+    if (g_cus[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return 0;
+        g_cus[dev] = cus;
+    }
+    return g_cus[dev];
+}
+}  // namespace
+
+bool kernel_facts(const void* kernel, int threads, int lds_bytes, KernelFacts* out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(g_facts_mutex);
+    for (const FactsEntry& e : g_facts)
+        if (e.dev == dev && e.kernel == kernel && e.threads == threads && e.lds == lds_bytes) {
+            *out = e.facts;
+            return true;
+        }
+    KernelFacts f{};
+    f.cus = cus_of(dev);
+    if (f.cus < 1) return false;
+    if (lds_bytes > 0 &&
+        hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+        return false;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&f.blocks_per_cu, kernel, threads, (size_t)lds_bytes) != hipSuccess ||
+        f.blocks_per_cu < 1)
+        return false;
+    g_facts.push_back(FactsEntry{dev, kernel, threads, lds_bytes, f});
+    *out = f;
+    return true;
+}
+
+int chip_cus() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 256; }
+    std::lock_guard<std::mutex> lock(g_facts_mutex);
+    const int cus = cus_of(dev);
+    if (cus < 1) { (void)hipGetLastError(); return 256; }
+    return cus;
+}
 }  // namespace flurka
 
 namespace {
 
-constexpr int kVersion = 110;
+constexpr int kVersion = 111;
 
 flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
                            int dtype, int phi, Problem* out) {
@@ -59,6 +114,38 @@ bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
 
 bool valid_algo(int a) { return a == FLURKA_ALGO_AUTO || a == FLURKA_ALGO_GENERIC || a == FLURKA_ALGO_FAST; }
 
+}  // namespace
+
+namespace {
+// Validation and dispatch of the forward entry point.
+flurka_status forward_impl(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                           const void* omega, void* out, void* ctx, size_t ctx_bytes, void* workspace,
+                           size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                           int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo, void* stream) {
+    Problem p;
+    flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
+    if (st != FLURKA_OK) return st;
+    if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
+    if (!Q || !K || !V || !E || !F || !out || !ctx || !workspace) return FLURKA_ERR_NULL;
+    if (!p.elu && !omega) return FLURKA_ERR_NULL;
+    const size_t es = p.bf16 ? 2 : 4;
+    if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
+        misaligned(F, es) || misaligned(out, es) || (omega && misaligned(omega, es)) ||
+        misaligned(ctx, 256) || misaligned(workspace, 256))
+        return FLURKA_ERR_ALIGN;
+    const bool fast_ok = fast_supported(p, 0) && fast_pointers_ok(Q, K, V, E, F, omega, out);
+    if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
+    const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
+    if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
+    const size_t need = use_fast ? fast_ws_bytes(p, 0) : generic_ws_layout(p, 0).total * sizeof(float);
+    if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
+
+    FwdArgs a{Q, K, V, E, F, omega, out, (float*)ctx, (float*)workspace};
+    hipStream_t s = (hipStream_t)stream;
+    st = use_fast ? fast_forward(p, a, s) : generic_forward(p, a, s);
+    if (st != FLURKA_OK) stage_abandon();
+    return st;
+}
 }  // namespace
 
 extern "C" {
@@ -124,27 +211,8 @@ flurka_status flurka_attn_fwd(const void* Q, const void* K, const void* V, const
                               size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
                               int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
                               void* stream) {
-    Problem p;
-    flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
-    if (st != FLURKA_OK) return st;
-    if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
-    if (!Q || !K || !V || !E || !F || !out || !ctx || !workspace) return FLURKA_ERR_NULL;
-    if (!p.elu && !omega) return FLURKA_ERR_NULL;
-    const size_t es = p.bf16 ? 2 : 4;
-    if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
-        misaligned(F, es) || misaligned(out, es) || (omega && misaligned(omega, es)) ||
-        misaligned(ctx, 256) || misaligned(workspace, 256))
-        return FLURKA_ERR_ALIGN;
-    const bool fast_ok = fast_supported(p, 0) && fast_pointers_ok(Q, K, V, E, F, omega, out);
-    if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
-    const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
-    if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
-    const size_t need = use_fast ? fast_ws_bytes(p, 0) : generic_ws_layout(p, 0).total * sizeof(float);
-    if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
-
-    FwdArgs a{Q, K, V, E, F, omega, out, (float*)ctx, (float*)workspace};
-    hipStream_t s = (hipStream_t)stream;
-    return use_fast ? fast_forward(p, a, s) : generic_forward(p, a, s);
+    return forward_impl(Q, K, V, E, F, omega, out, ctx, ctx_bytes, workspace, workspace_bytes, B, H, n, d,
+                        k, m, omega_per_head, dtype, phi, algo, stream);
 }
 
 flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
@@ -176,7 +244,9 @@ flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const
 
     BwdArgs a{Q, K, V, E, F, omega, out, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace};
     hipStream_t s = (hipStream_t)stream;
-    return use_fast ? fast_backward(p, a, s) : generic_backward(p, a, s);
+    st = use_fast ? fast_backward(p, a, s) : generic_backward(p, a, s);
+    if (st != FLURKA_OK) stage_abandon();
+    return st;
 }
 
 flurka_status flurka_profile_enable(int on) {
@@ -228,7 +298,7 @@ const char* flurka_profile_stage_name(int id) {
         case STAGE_BWD_DKDV: return "bwd_dk_dv";
         case STAGE_BWD_DEDF: return "bwd_de_df";
         case STAGE_K_PROJ_GEMM: return "project:gemm_mfma_proj";
-        case STAGE_K_PROJ_FINISH: return "key_state:proj_finish";
+        case STAGE_K_PROJ_FINISH: return "project:proj_finish";
         case STAGE_K_KEY_STATE: return "key_state:key_state";
         case STAGE_K_MERGE_PACK: return "key_state:merge_pack";
         case STAGE_K_QUERY_STREAM: return "query_stream:query_stream";

@@ -1158,6 +1158,10 @@ bool fast_bwd_supported(const Problem& p) {
     // 32-bit byte offsets inside the gradient GEMMs' buffer descriptors
     if ((size_t)p.BH * p.n * p.d * 2 >= ((size_t)1 << 31)) return false;
     if (((size_t)p.k + GBM) * (size_t)p.n * 2 >= ((size_t)1 << 31)) return false;
+    // ... and inside the bf16 images of dK', dV' (k may exceed n): BH*d rows of kp slots each, plus the rows
+    // of a last tile that reach past the end
+    const size_t kp = ((size_t)p.k + 63) / 64 * 64;
+    if (((size_t)p.BH * p.d + GBM) * kp * 2 >= ((size_t)1 << 31)) return false;
     return true;
 }
 
@@ -1168,7 +1172,7 @@ static GradEPlan grad_e_plan(const Problem& p) {
     q.tilesM = (p.k + GBM - 1) / GBM;
     q.tilesN = (p.n + GBN - 1) / GBN;
     q.total_steps = p.BH * p.d / GBK;
-    int splits = 128 / (q.tilesM * q.tilesN * 2);
+    int splits = chip_cus() / 2 / (q.tilesM * q.tilesN * 2);     // workgroups on half of the compute units are enough
     if (splits < 1) splits = 1;
     if (splits > q.total_steps) splits = q.total_steps;
     q.steps_per_split = (q.total_steps + splits - 1) / splits;
@@ -1186,7 +1190,7 @@ static BwdYPlan bwd_y_plan(const Problem& p) {
     const int FG = (q.FT + q.NW - 1) / q.NW;
     // one round of workgroups: the chip holds one 8-wavefront or two 4-wavefront workgroups per
     // compute unit; ranges are whole staged blocks of query tiles
-    const int slots = 512;
+    const int slots = 2 * chip_cus();
     int R = slots / (p.BH * FG);
     if (R > QT / Y_ST) R = QT / Y_ST;
     if (R < 1) R = 1;
@@ -1251,8 +1255,8 @@ template <int D, int NW, bool ELU>
 static flurka_status launch_bwd_y_impl(const BwdYArgs& ya, unsigned grid, hipStream_t s) {
     auto kern = bwd_query_y_kernel<D, NW, ELU>;
     constexpr int ldsb = BwdYLds<D, ELU>::total;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
-        return FLURKA_ERR_LAUNCH;
+    KernelFacts facts;
+    if (!kernel_facts((const void*)kern, NW * 64, ldsb, &facts)) return FLURKA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), ldsb, s, ya);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
@@ -1270,8 +1274,6 @@ static flurka_status launch_bwd_y(const Problem& p, const BwdYArgs& ya, const Bw
 template <int D, bool RING>
 static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
     auto kern = bwd_query_x_kernel<D, RING>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
-        return FLURKA_ERR_LAUNCH;
     constexpr int threads = BwdXLds<D, RING>::nw * 64;
     const int grid = resident_grid((const void*)kern, threads, ldsb, xa.total_tiles);
     if (grid < 1) return FLURKA_ERR_LAUNCH;
@@ -1369,7 +1371,6 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_Y);
     }
-    const size_t img_elems = (size_t)p.BH * W.kp * p.d;
     uint16_t* img = (uint16_t*)(wsb + W.img);
     uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
     {
@@ -1392,8 +1393,8 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         const unsigned kgrid = (unsigned)(p.BH * (W.kp / 32));
         const int klds = p.d == 64 ? BwdKeyLds<64>::total : BwdKeyLds<128>::total;
         const void* kk = p.d == 64 ? (const void*)bwd_key_kernel<64> : (const void*)bwd_key_kernel<128>;
-        if (hipFuncSetAttribute(kk, hipFuncAttributeMaxDynamicSharedMemorySize, klds) != hipSuccess)
-            return FLURKA_ERR_LAUNCH;
+        KernelFacts facts;
+        if (!kernel_facts(kk, 256, klds, &facts)) return FLURKA_ERR_LAUNCH;
         if (p.d == 64) hipLaunchKernelGGL(bwd_key_kernel<64>, dim3(kgrid), dim3(256), klds, s, ka);
         else           hipLaunchKernelGGL(bwd_key_kernel<128>, dim3(kgrid), dim3(256), klds, s, ka);
         FLURKA_CHECK_LAUNCH();
@@ -1407,8 +1408,6 @@ template <int D>
 static flurka_status launch_bwd_x_elu(const BwdXEluArgs& xa, hipStream_t s) {
     auto kern = bwd_query_x_elu_kernel<D>;
     constexpr int ldsb = BwdXEluLds<D>::total;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
-        return FLURKA_ERR_LAUNCH;
     const int grid = resident_grid((const void*)kern, 512, ldsb, xa.total_tiles);
     if (grid < 1) return FLURKA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(512), ldsb, s, xa);

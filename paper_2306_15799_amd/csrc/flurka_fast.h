@@ -35,12 +35,9 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
 // device keeps resident at once for this block size and LDS use (one round, no tail), at most `items`.
 // Returns 0 if the runtime cannot place the kernel.
 inline int resident_grid(const void* kernel, int threads, int lds_bytes, long items) {
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, (size_t)lds_bytes) != hipSuccess)
-        return 0;
-    long grid = (long)cus * per_cu;
+    KernelFacts f;
+    if (!kernel_facts(kernel, threads, lds_bytes, &f)) return 0;
+    long grid = (long)f.cus * f.blocks_per_cu;
     if (grid > items) grid = items;
     return (int)grid;
 }

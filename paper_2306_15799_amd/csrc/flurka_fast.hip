@@ -40,7 +40,7 @@ static ProjPlan proj_plan(const Problem& p) {
     q.tilesN = (p.BH + heads_per_tile - 1) / heads_per_tile;
     q.total_steps = p.n / PBK;
     const int tiles = q.tilesM * q.tilesN * 2;
-    int splits = 256 / tiles;                      // one workgroup per compute unit
+    int splits = chip_cus() / tiles;               // one workgroup per compute unit
     if (splits < 1) splits = 1;
     if (splits > 8) splits = splits / 8 * 8;       // keep each XCD on its own n-ranges
     if (splits > q.total_steps) splits = q.total_steps;
@@ -337,8 +337,6 @@ template <int D, bool ELU, bool STAGED>
 static flurka_status launch_query_impl(const QueryArgs& qa, int ldsb, hipStream_t s) {
     constexpr int QS_NW = QsWaves<D>::value;
     auto kern = query_stream_kernel<D, ELU, QS_NW, QS_QT, STAGED>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb) != hipSuccess)
-        return FLURKA_ERR_LAUNCH;
     const int grid = resident_grid((const void*)kern, QS_NW * 64, ldsb, qa.total_tiles);
     if (grid < 1) return FLURKA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(QS_NW * 64), ldsb, s, qa);

@@ -498,8 +498,8 @@ struct GradEPolicy {
 template <class Pol, bool STREAM>
 static inline flurka_status launch_gemm_mfma_impl(const GemmParams& g, int grid, hipStream_t s) {
     auto kern = gemm_mfma_kernel<Pol, STREAM>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS) != hipSuccess)
-        return FLURKA_ERR_LAUNCH;
+    KernelFacts facts;
+    if (!kernel_facts((const void*)kern, 256, G_LDS, &facts)) return FLURKA_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), G_LDS, s, g);
     if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH;
     return FLURKA_OK;

@@ -126,12 +126,28 @@ enum Stage {
 // No-ops unless the timer is enabled.  begin/end pairs must not nest.
 void stage_begin(hipStream_t s);
 void stage_end(hipStream_t s, Stage id);
+// Forgets a begin that never saw its end (a call that returned early on a launch error).
+void stage_abandon();
 
 struct StageScope {
     hipStream_t s; Stage id;
     StageScope(hipStream_t s_, Stage id_) : s(s_), id(id_) { stage_begin(s); }
     ~StageScope() { stage_end(s, id); }
 };
+
+// ---- launch facts ------------------------------------------------------------
+// What the runtime reports about a kernel for one (device, block size, dynamic LDS size) does not
+// change while the process lives, so it is asked once and kept in a host-side table (no device memory).
+struct KernelFacts {
+    int cus;             // compute units of the device
+    int blocks_per_cu;   // workgroups of this kernel a compute unit holds at once
+};
+// First use on the current device raises the kernel's dynamic-LDS limit to `lds_bytes` and queries its
+// occupancy; every later call is a table lookup.  false: the runtime refused.
+bool kernel_facts(const void* kernel, int threads, int lds_bytes, KernelFacts* out);
+// Compute units of the current device; 256 (MI355X) where no device is visible, so that buffer sizes
+// can still be computed on a host without a GPU.
+int chip_cus();
 
 // ---- bf16 MFMA path ---------------------------------------------------------
 // Whether the MFMA kernels cover the problem (dtype, feature map, tile multiples).

@@ -392,7 +392,8 @@ KeyStatePlan key_state_plan(const Problem& p) {
     q.kpad = (p.k + 31) / 32 * 32;
     q.FT = p.mf / 32;
     const int KT = q.kpad / 32;
-    int KR = (1024 + p.BH * q.FT - 1) / (p.BH * q.FT);          // about 1024 wavefronts ...
+    const int waves = 4 * chip_cus();                            // about one wavefront per SIMD ...
+    int KR = (waves + p.BH * q.FT - 1) / (p.BH * q.FT);
     if (KR < (KT + KS_MT - 1) / KS_MT) KR = (KT + KS_MT - 1) / KS_MT;   // ... of at most KS_MT key tiles
     if (KR > 32) KR = 32;
     if (KR > KT) KR = KT;

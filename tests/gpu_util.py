@@ -10,6 +10,11 @@ from paper_2306_15799_amd import inputs
 # Relative-L2 bars from the benchmark definition: 1e-5 for fp32 storage,
 # 2e-2 for bf16 storage with fp32 accumulation.
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+# Bar for the worst block of a tensor (32 consecutive rows of a (.., n, d) tensor, 256 consecutive
+# columns of dE, dF): 4 x the whole-tensor bar.  A block nobody wrote, or one written from the wrong
+# rows, has a relative error near 1; rounding noise of a single block scatters around the tensor's
+# figure (observed: at most about twice it), so 4 x separates the two with room on both sides.
+BLOCK_FACTOR = 4.0
 
 
 def to_device(t: dict, dtype: str) -> dict:
@@ -62,11 +67,55 @@ def rel_err(x, ref, floor=0.0):
     return float(np.linalg.norm((x - ref).ravel())) / den if den > 0 else fo.rel_l2(x, ref)
 
 
+def block_sums(a, block, axis):
+    """Sums of squares over blocks of `block` consecutive indices of `axis` (last block may be short)
+    and over every other axis."""
+    a = np.moveaxis(np.asarray(a, np.float64), axis, -1)
+    sq = (a * a).reshape(-1, a.shape[-1]).sum(axis=0)
+    return np.add.reduceat(sq, np.arange(0, sq.size, block))
+
+
+def worst_block(x, ref, block, axis, floor=0.0):
+    """Largest relative L2 error over blocks of `block` indices along `axis` (negative: counted from the
+    last axis), each batch/head slice on
+    its own for 4-d tensors.  A block's reference norm is taken no smaller than a tenth of the
+    root-mean-square block norm of the whole tensor, so that a block whose exact value is (nearly) zero
+    is measured against the scale of its neighbours."""
+    x = np.asarray(x, np.float64)
+    ref = np.asarray(ref, np.float64)
+    if x.ndim == 4:
+        x = x.reshape(-1, *x.shape[2:])
+        ref = ref.reshape(-1, *ref.shape[2:])
+    else:
+        x, ref = x[None], ref[None]
+    num = np.stack([block_sums(a - b, block, axis) for a, b in zip(x, ref)])
+    den = np.stack([block_sums(b, block, axis) for b in ref])
+    typical = max(den.mean(), (floor ** 2) * ref[0].size / den.shape[1])
+    return float(np.sqrt((num / np.maximum(den, 0.01 * typical)).max())) if typical > 0 else 0.0
+
+
+def block_of(name):
+    """(block length, axis counted from the end) used for the worst-block figure of tensor `name`."""
+    return (256, -1) if name in ("dE", "dF") else (32, -2)
+
+
+def check_blocks(errs, name, x, ref, bar, floor=0.0):
+    block, axis = block_of(name)
+    wb = worst_block(x, ref, block, axis, floor)
+    errs[name + ":worst_block"] = wb
+    return wb <= BLOCK_FACTOR * bar
+
+
 def check_forward(w, seed=0, algo="auto", tol=None):
     t = inputs.make_inputs(w, seed)
     _, out, _ = run_forward(w, t, algo)
-    err = fo.rel_l2(to_host(out), oracle_forward(w, t))
-    assert err <= (tol or TOL[w.dtype]), f"{w.name} fwd rel-L2 {err:.3e}"
+    ref = oracle_forward(w, t)
+    got = to_host(out)
+    err = fo.rel_l2(got, ref)
+    bar = tol or TOL[w.dtype]
+    assert err <= bar, f"{w.name} fwd rel-L2 {err:.3e}"
+    wb = worst_block(got, ref, 32, -2)
+    assert wb <= BLOCK_FACTOR * bar, f"{w.name} fwd worst 32-row block rel-L2 {wb:.3e} (tensor {err:.3e})"
     return err
 
 
@@ -74,11 +123,61 @@ def check_forward_backward(w, seed=0, algo="auto", tol=None, floor=0.0):
     t = inputs.make_inputs(w, seed)
     g, out, ctx = run_forward(w, t, algo)
     bar = tol or TOL[w.dtype]
-    errs = {"out": fo.rel_l2(to_host(out), oracle_forward(w, t))}
+    ref_out = oracle_forward(w, t)
+    errs = {"out": fo.rel_l2(to_host(out), ref_out)}
+    blocks_ok = check_blocks(errs, "out", to_host(out), ref_out, bar)
     grads = run_backward(w, g, out, ctx, algo)
     ref = oracle_backward(w, t)
     for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], grads, ref):
         errs[name] = rel_err(to_host(a), b, floor)
-    bad = {k: v for k, v in errs.items() if not v <= bar}
+        blocks_ok &= check_blocks(errs, name, to_host(a), b, bar, floor)
+    bad = {k: v for k, v in errs.items() if ":" not in k and not v <= bar}
     assert not bad, f"{w.name} rel-L2 over {bar:g}: {bad} (all: {errs})"
+    assert blocks_ok, f"{w.name} worst block over {BLOCK_FACTOR * bar:g}: {errs}"
+    return errs
+
+
+def check_head_by_head(w, t, out, grads=None, bar=None):
+    """Whole-tensor and worst-block parity for workloads whose fp64 tensors should not all sit in host
+    memory at once: the oracle runs one (batch, head) slice at a time (`fo.flurka_head`,
+    `fo.flurka_head_bwd`), squared errors are accumulated per tensor and per block, dE and dF are summed
+    over the slices as the definition says.  Returns {name: rel-L2, name:worst_block: ...}."""
+    bar = bar or TOL[w.dtype]
+    names = ["out"] + (["dQ", "dK", "dV"] if grads is not None else [])
+    num = {k: 0.0 for k in names}
+    den = {k: 0.0 for k in names}
+    bnum = {k: [] for k in names}
+    bden = {k: [] for k in names}
+    k_, n = t["E"].shape
+    dE = np.zeros((k_, n)) if grads is not None else None
+    dF = np.zeros((k_, n)) if grads is not None else None
+    for b in range(w.B):
+        for h in range(w.H):
+            om = None if t["omega"] is None else np.asarray(t["omega"][h if t["omega"].shape[0] > 1 else 0], np.float64)
+            sl = (t["Q"][b, h], t["K"][b, h], t["V"][b, h], t["E"], t["F"], om)
+            ref = {"out": fo.flurka_head(*sl, w.phi)}
+            got = {"out": to_host(out[b, h])}
+            if grads is not None:
+                g = fo.flurka_head_bwd(*sl, t["dOut"][b, h], w.phi)
+                ref.update(dQ=g[0], dK=g[1], dV=g[2])
+                dE += g[3]
+                dF += g[4]
+                for name, x in zip(["dQ", "dK", "dV"], grads[:3]):
+                    got[name] = to_host(x[b, h])
+            for name in names:
+                num[name] += float(((got[name] - ref[name]) ** 2).sum())
+                den[name] += float((ref[name] ** 2).sum())
+                bnum[name].append(block_sums(got[name] - ref[name], 32, -2))
+                bden[name].append(block_sums(ref[name], 32, -2))
+    errs = {}
+    for name in names:
+        errs[name] = float(np.sqrt(num[name] / den[name]))
+        bn, bd = np.stack(bnum[name]), np.stack(bden[name])
+        errs[name + ":worst_block"] = float(np.sqrt((bn / np.maximum(bd, 0.01 * bd.mean())).max()))
+    if grads is not None:
+        for name, x, ref in (("dE", grads[3], dE), ("dF", grads[4], dF)):
+            errs[name] = fo.rel_l2(to_host(x), ref)
+            errs[name + ":worst_block"] = worst_block(to_host(x), ref, 256, -1)
+    bad = {k: v for k, v in errs.items() if not v <= (BLOCK_FACTOR * bar if ":" in k else bar)}
+    assert not bad, f"{w.name}: over the bar ({bar:g}, blocks {BLOCK_FACTOR * bar:g}): {bad} (all: {errs})"
     return errs

@@ -27,7 +27,7 @@ def test_every_declared_entry_point_is_exported(lib):
     assert declared == set(fb.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.flurka_version() == 110
+    assert lib.flurka_version() == 111
 
 
 def test_status_strings(lib):
@@ -104,6 +104,16 @@ def test_backward_rejects_bad_arguments_before_launching(lib):
     assert _bwd(lib, dE=FAKE + 1) == fb.ERR_ALIGN
     assert _bwd(lib, ctx_bytes=16) == fb.ERR_WORKSPACE
     assert _bwd(lib, ws_bytes=16) == fb.ERR_WORKSPACE
+
+
+def test_shapes_whose_byte_offsets_leave_32_bits_are_not_taken_by_the_mfma_kernels(lib):
+    # the bf16 images of dK', dV' are addressed with 32-bit byte offsets: many projected keys (k > n is
+    # allowed) times many (head, coordinate) rows must fall back to the generic kernels
+    assert fb.fast_path_supported(64, 1, 64, 128, 1 << 10, 32, fb.BF16, "performer", fb.PASS_BWD)
+    assert not fb.fast_path_supported(64, 1, 64, 128, 1 << 18, 32, fb.BF16, "performer", fb.PASS_BWD)
+    assert _bwd(lib, B=64, n=64, d=128, k=1 << 18, m=32, dtype=fb.BF16, algo=fb.ALGO_FAST) == fb.ERR_UNSUPPORTED
+    # forward: one projection tile's rows of E must stay below 2 GiB
+    assert not fb.fast_path_supported(1, 1, 1 << 22, 64, 512, 32, fb.BF16, "performer", fb.PASS_FWD)
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -1,9 +1,11 @@
 """Full-size parity on the five benchmark workloads, in the launch
 configuration bench.py times (algo = auto), against the fp64 oracle.
 
-C1, C2 and C5 are compared element by element over the whole output; for the
-two long-sequence workloads (C3, C4) the oracle evaluates a random sample of
-query rows per head (every key and value still enters through K', V')."""
+Every workload is compared element by element over its whole output (C3 and
+C4 one head at a time, so that the fp64 tensors of the oracle never sit in
+host memory all at once); a cheaper test on a random sample of query rows of
+C3 and C4 stays beside it.  Besides the whole-tensor relative L2 error, the
+worst 32-row block (256-column block for dE, dF) is held to a bar of its own."""
 import numpy as np
 import pytest
 import torch
@@ -39,6 +41,15 @@ def test_forward_sampled_rows(name):
     assert torch.isfinite(out.float()).all()
 
 
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_forward_whole_output_head_by_head(name):
+    w = inputs.WORKLOADS[name]
+    t = inputs.make_inputs(w, seed=0)
+    _, out, _ = gu.run_forward(w, t, "auto")
+    errs = gu.check_head_by_head(w, t, out)
+    print(name, {k: f"{v:.2e}" for k, v in errs.items()})
+
+
 def test_c5_forward_backward():
     w = inputs.WORKLOADS["C5"]
     errs = gu.check_forward_backward(w, seed=0, algo="auto")
@@ -46,12 +57,15 @@ def test_c5_forward_backward():
 
 
 def test_training_step_at_the_long_sequence_shape():
-    """C4's shape as a training step, cut to two heads so that the fp64 oracle's backward stays within
-    seconds: n = 65536, d = 128, k = 512, m = 256 (|k'|^2 ~ 1450, attention concentrated on few
-    (key, feature) pairs; the dQ kernel's ring variant)."""
-    w = inputs.shrink(inputs.DERIVED_WORKLOADS["C4T"], H=2)
-    errs = gu.check_forward_backward(w, seed=0, algo="auto")
-    print("C4T/2 heads", {k: f"{v:.2e}" for k, v in errs.items()})
+    """C4's shape as a training step, all 16 heads: n = 65536, d = 128, k = 512, m = 256 (|k'|^2 ~ 1450,
+    attention concentrated on few (key, feature) pairs; the dQ kernel's ring variant).  The oracle's
+    backward runs one head at a time."""
+    w = inputs.DERIVED_WORKLOADS["C4T"]
+    t = inputs.make_inputs(w, seed=0)
+    g, out, ctx = gu.run_forward(w, t, "auto")
+    grads = gu.run_backward(w, g, out, ctx, "auto")
+    errs = gu.check_head_by_head(w, t, out, grads)
+    print("C4T", {k: f"{v:.2e}" for k, v in errs.items()})
 
 
 @pytest.mark.parametrize("name", ["C3", "C4"])
@@ -92,6 +106,35 @@ def test_output_does_not_depend_on_the_order_of_the_projected_keys(name):
     rel = ((a - b).norm() / b.norm()).item()
     print(f"{name} key-permutation rel-L2 {rel:.2e}")
     assert rel < 5e-3
+
+
+def test_full_size_results_do_not_depend_on_what_the_buffers_held():
+    """C5 in the benchmark's launch configuration with ctx, both workspaces and every result tensor
+    filled with NaN bit patterns before the calls: a tile that no workgroup wrote, or a scratch byte
+    read before it was written, shows up as a NaN or as a difference from the clean run."""
+    w = inputs.WORKLOADS["C5"]
+    t = inputs.make_inputs(w, seed=0)
+    g = gu.to_device(t, w.dtype)
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    dev = g["Q"].device
+
+    def run(fill):
+        ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, fb.BF16, w.phi), dev).fill_(fill)
+        wf = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_FWD, "auto"), dev).fill_(fill)
+        wb = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_BWD, "auto"), dev).fill_(fill)
+        res = [torch.empty_like(x).view(torch.uint8).fill_(fill).view(torch.bfloat16).view(x.shape)
+               for x in (g["Q"], g["Q"], g["K"], g["V"], g["E"], g["F"])]
+        fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, out=res[0], ctx=ctx,
+                           workspace=wf)
+        fb.flurka_attn_bwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], res[0], g["dOut"], ctx,
+                           phi=w.phi, workspace=wb, grads=tuple(res[1:]))
+        torch.cuda.synchronize()
+        return res
+
+    clean, dirty = run(0), run(0xFF)
+    for name, a, b in zip(["out", "dQ", "dK", "dV", "dE", "dF"], clean, dirty):
+        assert torch.isfinite(b.float()).all(), name
+        assert torch.equal(a, b), name
 
 
 def test_full_size_results_are_bit_reproducible():

@@ -198,6 +198,28 @@ def test_backward_matches_generic_kernels_closely():
         assert fo.rel_l2(gu.to_host(a), gu.to_host(b)) < 2e-2, name
 
 
+def test_one_context_serves_both_kernel_families():
+    """What the forward leaves in ctx (K', V', S, z, c, lse) means the same to the MFMA kernels and to
+    the generic ones.  With 320 features at head size 64, algo = auto runs the MFMA forward and the
+    generic backward on one ctx; the second case forces the opposite pairing."""
+    w = Workload("cross", 1, 2, 512, 64, 96, 320, "bf16", PHI_PERFORMER, True)
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    assert fb.fast_path_supported(*dims, fb.BF16, w.phi, fb.PASS_FWD)
+    assert not fb.fast_path_supported(*dims, fb.BF16, w.phi, fb.PASS_BWD)
+    errs = gu.check_forward_backward(w, seed=22, algo="auto")
+    print("mfma fwd + generic bwd", {k_: f"{v:.2e}" for k_, v in errs.items()})
+
+    w = Workload("cross2", 1, 2, 512, 64, 96, 64, "bf16", PHI_PERFORMER, True)
+    t = inputs.make_inputs(w, 23)
+    g, out, ctx = gu.run_forward(w, t, "generic")
+    grads = gu.run_backward(w, g, out, ctx, "fast")
+    errs = {}
+    for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], grads, gu.oracle_backward(w, t)):
+        errs[name] = gu.rel_err(gu.to_host(a), b)
+    print("generic fwd + mfma bwd", {k_: f"{v:.2e}" for k_, v in errs.items()})
+    assert all(v <= 2e-2 for v in errs.values()), errs
+
+
 @pytest.mark.parametrize("shape,phi", [((2, 2, 512, 64, 96, 64), PHI_PERFORMER), ((2, 3, 512, 128, 96, 256), PHI_PERFORMER),
                                        ((2, 3, 512, 64, 96, 64), PHI_ELU1)])
 def test_backward_is_deterministic(shape, phi):

@@ -37,9 +37,11 @@ def test_degenerate_sizes(shape):
     # with k = 1 the output ignores Q and K (dQ, dK, dE are exactly zero), with m = 1 it ignores Q;
     # what the GPU returns there is fp32 cancellation noise: measure it against unit scale, not zero
     floor = 1.0 if (k == 1 or m == 1) else 0.0
-    gu.check_forward_backward(w, seed=2, algo="generic", tol=2e-5, floor=floor)
+    errs = gu.check_forward_backward(w, seed=2, algo="generic", floor=floor)
+    print(shape, "performer", {k_: f"{v:.2e}" for k_, v in errs.items()})
     w = Workload("edge", B, H, n, d, k, d, "f32", PHI_ELU1, True)
-    gu.check_forward_backward(w, seed=2, algo="generic", tol=2e-5, floor=floor)
+    errs = gu.check_forward_backward(w, seed=2, algo="generic", floor=floor)
+    print(shape, "elu1", {k_: f"{v:.2e}" for k_, v in errs.items()})
 
 
 def test_shared_omega_equals_per_head_copy():
