@@ -146,6 +146,29 @@ FLURKA_API flurka_status flurka_attn_fwd(const void* Q, const void* K, const voi
                               void* stream);
 
 /*
+ * flurka_attn_fwd for callers that cannot allocate device memory and have no scratch buffer of their
+ * own to hand over: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and error codes as flurka_attn_fwd, without `workspace`: the
+ * scratch is a fixed array of FLURKA_STATIC_WORKSPACE_BYTES inside the library's device image (each
+ * GPU the library runs on holds one copy until the process ends; its address is looked up on the first
+ * call on a device).  The call allocates and frees nothing.  A problem whose forward workspace
+ * (flurka_workspace_bytes(..., FLURKA_PASS_FWD, algo)) exceeds FLURKA_STATIC_WORKSPACE_BYTES is refused
+ * with FLURKA_ERR_WORKSPACE before anything is launched.  Every call on a GPU uses that GPU's one
+ * array: calls that overlap on one GPU (two streams, two threads) race, so order them on one stream.
+ * The array keeps the previous call's contents; nothing in it has to start at zero (every kernel reads
+ * only what an earlier kernel of the same call wrote).
+ */
+#define FLURKA_STATIC_WORKSPACE_BYTES (32u << 20)
+FLURKA_API flurka_status flurka_attn_fwd_static(const void* Q, const void* K, const void* V,
+                              const void* E, const void* F, const void* omega,
+                              void* out,
+                              void* ctx, size_t ctx_bytes,
+                              int B, int H, int n, int d, int k, int m,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              void* stream);
+
+/*
  * Backward of flurka_attn_fwd (chain rule; the paper trains through this
  * layer but prints no backward).  Given dOut = d loss / d out:
  *

@@ -29,7 +29,7 @@ _ALGO = {"auto": ALGO_AUTO, "generic": ALGO_GENERIC, "fast": ALGO_FAST,
 
 EXPORTED_SYMBOLS = (
     "flurka_version", "flurka_status_str", "flurka_ctx_bytes", "flurka_ctx_layout", "flurka_workspace_bytes",
-    "flurka_fast_path_supported", "flurka_attn_fwd", "flurka_attn_bwd",
+    "flurka_fast_path_supported", "flurka_attn_fwd", "flurka_attn_fwd_static", "flurka_attn_bwd",
     "flurka_profile_enable", "flurka_profile_read", "flurka_profile_stage_name",
 )
 
@@ -68,6 +68,9 @@ def load_library() -> ctypes.CDLL:
     lib.flurka_attn_fwd.restype = c_int
     lib.flurka_attn_fwd.argtypes = ([c_void] * 7 + [c_void, c_size, c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
+    lib.flurka_attn_fwd_static.restype = c_int
+    lib.flurka_attn_fwd_static.argtypes = ([c_void] * 7 + [c_void, c_size]
+                                           + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
     lib.flurka_attn_bwd.restype = c_int
     lib.flurka_attn_bwd.argtypes = ([c_void] * 8 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
@@ -211,6 +214,32 @@ def flurka_attn_fwd(Q, K, V, E, F, omega, phi="performer", algo="auto", out=None
                              B, H, n, d, k, m, per_head, code, _PHI[phi], _ALGO[algo], s)
     if st != OK:
         raise FlurkaError(st, "flurka_attn_fwd")
+    return out, ctx
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20       # FLURKA_STATIC_WORKSPACE_BYTES
+
+
+def flurka_attn_fwd_static(Q, K, V, E, F, omega, out, ctx, phi="performer", algo="auto", stream=None):
+    """flurka_attn_fwd with the scratch inside the library's device image: `out` and `ctx` come from
+    the caller and nothing is allocated, here or in the library."""
+    lib = load_library()
+    B, H, n, d, k, m, per_head, omega_shape = _shapes(Q, E, omega, phi)
+    dt, dev = Q.dtype, Q.device
+    code = _dtype_code(Q)
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (out, "out")):
+        _check(t, name, (B, H, n, d), dt, dev)
+    for t, name in ((E, "E"), (F, "F")):
+        _check(t, name, (k, n), dt, dev)
+    if omega_shape is not None:
+        _check(omega, "omega", omega_shape, dt, dev)
+    s = stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    st = lib.flurka_attn_fwd_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(E), _ptr(F),
+                                    _ptr(omega) if omega_shape is not None else None, _ptr(out),
+                                    _ptr(ctx), ctx.numel() * ctx.element_size(),
+                                    B, H, n, d, k, m, per_head, code, _PHI[phi], _ALGO[algo], s)
+    if st != OK:
+        raise FlurkaError(st, "flurka_attn_fwd_static")
     return out, ctx
 
 

@@ -88,7 +88,7 @@ int chip_cus() {
 
 namespace {
 
-constexpr int kVersion = 111;
+constexpr int kVersion = 120;
 
 flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
                            int dtype, int phi, Problem* out) {
@@ -116,22 +116,45 @@ bool valid_algo(int a) { return a == FLURKA_ALGO_AUTO || a == FLURKA_ALGO_GENERI
 
 }  // namespace
 
+// Scratch of flurka_attn_fwd_static: part of the library's device image, so every GPU the library runs
+// on holds its own copy at its own address until the process ends.  In host code the array's name only
+// stands for the symbol; its device address is asked from the runtime once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FLURKA_STATIC_WORKSPACE_BYTES];
+
 namespace {
-// Validation and dispatch of the forward entry point.
+std::mutex g_scratch_mutex;
+std::vector<void*> g_scratch_ptr;        // per device id, nullptr = not asked yet
+
+// device address of `scratch` on the current device, or nullptr if the runtime cannot tell
+void* static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if ((size_t)dev >= g_scratch_ptr.size()) g_scratch_ptr.resize((size_t)dev + 1, nullptr);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// Validation and dispatch shared by the two forward entry points.  `workspace == nullptr` stands for
+// the library's own scratch array (looked up only after everything else has been validated).
 flurka_status forward_impl(const void* Q, const void* K, const void* V, const void* E, const void* F,
                            const void* omega, void* out, void* ctx, size_t ctx_bytes, void* workspace,
-                           size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                           size_t workspace_bytes, bool own_scratch, int B, int H, int n, int d, int k, int m,
                            int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo, void* stream) {
     Problem p;
     flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
     if (st != FLURKA_OK) return st;
     if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
-    if (!Q || !K || !V || !E || !F || !out || !ctx || !workspace) return FLURKA_ERR_NULL;
+    if (!Q || !K || !V || !E || !F || !out || !ctx || (!own_scratch && !workspace)) return FLURKA_ERR_NULL;
     if (!p.elu && !omega) return FLURKA_ERR_NULL;
     const size_t es = p.bf16 ? 2 : 4;
     if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
         misaligned(F, es) || misaligned(out, es) || (omega && misaligned(omega, es)) ||
-        misaligned(ctx, 256) || misaligned(workspace, 256))
+        misaligned(ctx, 256) || (!own_scratch && misaligned(workspace, 256)))
         return FLURKA_ERR_ALIGN;
     const bool fast_ok = fast_supported(p, 0) && fast_pointers_ok(Q, K, V, E, F, omega, out);
     if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
@@ -139,6 +162,7 @@ flurka_status forward_impl(const void* Q, const void* K, const void* V, const vo
     if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
     const size_t need = use_fast ? fast_ws_bytes(p, 0) : generic_ws_layout(p, 0).total * sizeof(float);
     if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
+    if (own_scratch && !(workspace = static_scratch())) return FLURKA_ERR_LAUNCH;
 
     FwdArgs a{Q, K, V, E, F, omega, out, (float*)ctx, (float*)workspace};
     hipStream_t s = (hipStream_t)stream;
@@ -211,8 +235,16 @@ flurka_status flurka_attn_fwd(const void* Q, const void* K, const void* V, const
                               size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
                               int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
                               void* stream) {
-    return forward_impl(Q, K, V, E, F, omega, out, ctx, ctx_bytes, workspace, workspace_bytes, B, H, n, d,
+    return forward_impl(Q, K, V, E, F, omega, out, ctx, ctx_bytes, workspace, workspace_bytes, false, B, H, n, d,
                         k, m, omega_per_head, dtype, phi, algo, stream);
+}
+
+flurka_status flurka_attn_fwd_static(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                                     const void* omega, void* out, void* ctx, size_t ctx_bytes, int B, int H,
+                                     int n, int d, int k, int m, int omega_per_head, flurka_dtype dtype,
+                                     flurka_phi phi, flurka_algo algo, void* stream) {
+    return forward_impl(Q, K, V, E, F, omega, out, ctx, ctx_bytes, nullptr, FLURKA_STATIC_WORKSPACE_BYTES, true, B,
+                        H, n, d, k, m, omega_per_head, dtype, phi, algo, stream);
 }
 
 flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,

@@ -27,7 +27,7 @@ def test_every_declared_entry_point_is_exported(lib):
     assert declared == set(fb.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.flurka_version() == 111
+    assert lib.flurka_version() == 120
 
 
 def test_status_strings(lib):
@@ -114,6 +114,24 @@ def test_shapes_whose_byte_offsets_leave_32_bits_are_not_taken_by_the_mfma_kerne
     assert _bwd(lib, B=64, n=64, d=128, k=1 << 18, m=32, dtype=fb.BF16, algo=fb.ALGO_FAST) == fb.ERR_UNSUPPORTED
     # forward: one projection tile's rows of E must stay below 2 GiB
     assert not fb.fast_path_supported(1, 1, 1 << 22, 64, 512, 32, fb.BF16, "performer", fb.PASS_FWD)
+
+
+def test_static_scratch_entry_point_validates_like_the_forward(lib):
+    def call(**over):
+        a = dict(Q=FAKE, K=FAKE, V=FAKE, E=FAKE, F=FAKE, omega=FAKE, out=FAKE, ctx=FAKE, ctx_bytes=1 << 40,
+                 B=1, H=1, n=512, d=64, k=64, m=64, per_head=1, dtype=fb.F32, phi=fb.PHI_PERFORMER,
+                 algo=fb.ALGO_GENERIC)
+        a.update(over)
+        return lib.flurka_attn_fwd_static(a["Q"], a["K"], a["V"], a["E"], a["F"], a["omega"], a["out"], a["ctx"],
+                                          a["ctx_bytes"], a["B"], a["H"], a["n"], a["d"], a["k"], a["m"],
+                                          a["per_head"], a["dtype"], a["phi"], a["algo"], None)
+    assert call(Q=None) == fb.ERR_NULL
+    assert call(n=0) == fb.ERR_SHAPE
+    assert call(ctx=FAKE + 64) == fb.ERR_ALIGN
+    assert call(ctx_bytes=16) == fb.ERR_WORKSPACE
+    # a workspace beyond the library's own array is refused before anything is launched
+    assert fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_FWD, "generic") > fb.STATIC_WORKSPACE_BYTES
+    assert call(B=4, H=12, n=8192, d=64, k=256, m=256, dtype=fb.BF16) == fb.ERR_WORKSPACE
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -1,0 +1,61 @@
+"""flurka_attn_fwd_static (scratch inside the library's device image) against flurka_attn_fwd
+(scratch from the caller), through the C ABI."""
+import pytest
+import torch
+
+from paper_2306_15799_amd import binding as fb
+from paper_2306_15799_amd import inputs
+from paper_2306_15799_amd.inputs import Workload, PHI_ELU1, PHI_PERFORMER
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(w, seed, algo):
+    t = inputs.make_inputs(w, seed)
+    g = gu.to_device(t, w.dtype)
+    code = fb.BF16 if w.dtype == "bf16" else fb.F32
+    m_eff = w.d if w.phi == PHI_ELU1 else w.m
+    dims = (w.B, w.H, w.n, w.d, w.k, m_eff)
+    assert fb.workspace_bytes(*dims, code, w.phi, fb.PASS_FWD, algo) <= fb.STATIC_WORKSPACE_BYTES
+    out_ref, ctx_ref = fb.flurka_attn_fwd(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], phi=w.phi, algo=algo)
+    out = torch.full_like(g["Q"], float("nan"))
+    ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, code, w.phi), g["Q"].device).fill_(0xFF)
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    fb.flurka_attn_fwd_static(g["Q"], g["K"], g["V"], g["E"], g["F"], g["omega"], out, ctx, phi=w.phi, algo=algo)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    # same kernels, same scratch layout: the results agree bit for bit (the parity bar is rel-L2
+    # <= 2e-2 for bf16 storage; equality is stronger)
+    assert torch.equal(out, out_ref)
+    va = fb.ctx_views(ctx, *dims, code, w.phi)
+    vb = fb.ctx_views(ctx_ref, *dims, code, w.phi)
+    for name in va:
+        assert torch.equal(va[name], vb[name]), name
+    # and both agree with the oracle
+    from oracle import flurka_oracle as fo
+    assert fo.rel_l2(gu.to_host(out), gu.oracle_forward(w, t)) <= gu.TOL[w.dtype]
+
+
+def test_two_calls_in_a_row_the_second_smaller():
+    """The library's array keeps the first call's contents; the second, smaller problem must not see them."""
+    _both(Workload("static_a", 2, 5, 1024, 64, 256, 256, "bf16", PHI_PERFORMER, False), 31, "auto")
+    _both(Workload("static_b", 1, 3, 192, 64, 100, 96, "bf16", PHI_PERFORMER, False), 32, "auto")
+    _both(Workload("static_c", 1, 2, 320, 128, 64, 128, "bf16", PHI_ELU1, False), 33, "auto")
+    _both(Workload("static_d", 1, 2, 200, 32, 40, 48, "f32", PHI_PERFORMER, False), 34, "auto")
+
+
+def test_a_problem_beyond_the_array_is_refused():
+    w = inputs.WORKLOADS["C5"]
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    assert fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_FWD, "auto") > fb.STATIC_WORKSPACE_BYTES
+    dev = torch.device("cuda")
+    q = torch.zeros(w.B, w.H, w.n, w.d, dtype=torch.bfloat16, device=dev)
+    e = torch.zeros(w.k, w.n, dtype=torch.bfloat16, device=dev)
+    om = torch.zeros(w.H, w.m, w.d, dtype=torch.bfloat16, device=dev)
+    ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, fb.BF16, w.phi), dev)
+    with pytest.raises(fb.FlurkaError) as err:
+        fb.flurka_attn_fwd_static(q, q, q, e, e, om, torch.empty_like(q), ctx, phi=w.phi)
+    assert err.value.status == fb.ERR_WORKSPACE
