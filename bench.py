@@ -68,6 +68,8 @@ def stage_model(w, stage: str):
         return 4.0 * n * k * d * BH, es * (2 * k * n + 2 * BH * n * d)
     if stage == "bwd_de_df":
         return 4.0 * k * n * d * BH, es * (2 * BH * n * d + 2 * k * n)
+    if stage == "bwd_grad_gemms":         # dK, dV and dE, dF in one launch (MFMA path)
+        return 8.0 * k * n * d * BH, es * (4 * BH * n * d + 4 * k * n)
     raise KeyError(stage)
 
 
@@ -104,6 +106,9 @@ def kernel_model(w, kernel: str):
     if kernel == "gemm_mfma_grade":
         fl, by = stage_model(w, "bwd_de_df")
         return fl, by, by + 2 * BH * k * d * 2
+    if kernel == "gemm_mfma_grads":
+        fl, by = stage_model(w, "bwd_grad_gemms")
+        return fl, by, by + 4 * BH * k * d * 2
     # small helper kernels: data movement only
     small = 4 * BH * (2 * k * d + mf * d + mf)
     return 0.0, float(small), float(small)
@@ -114,7 +119,7 @@ def whole_model(w):
     the backward reads Q, K, V, dOut, E, F, omega and writes dQ, dK, dV, dE, dF."""
     stages = ["project", "key_state", "query_stream"]
     if w.backward:
-        stages += ["bwd_query", "bwd_key", "bwd_dk_dv", "bwd_de_df"]
+        stages += ["bwd_query", "bwd_key", "bwd_grad_gemms"]
     fl = sum(stage_model(w, s)[0] for s in stages)
     es, BH, n, d, k, mf, perf, om = _sizes(w)
     by = es * (4 * BH * n * d + 2 * k * n) + om

@@ -340,7 +340,9 @@ const char* flurka_profile_stage_name(int id) {
         case STAGE_K_BWD_KEY: return "bwd_key:bwd_key";
         case STAGE_K_GRAD_X: return "bwd_dk_dv:gemm_mfma_gradx";
         case STAGE_K_GRAD_E: return "bwd_de_df:gemm_mfma_grade";
-        case STAGE_K_SUM_SPLITS: return "bwd_de_df:sum_splits";
+        case STAGE_K_SUM_SPLITS: return "bwd_grad_gemms:sum_splits";
+        case STAGE_BWD_GRADS: return "bwd_grad_gemms";
+        case STAGE_K_GRAD_PAIR: return "bwd_grad_gemms:gemm_mfma_grads";
     }
     return "unknown";
 }

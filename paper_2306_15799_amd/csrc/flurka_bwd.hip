@@ -1283,44 +1283,40 @@ static flurka_status launch_bwd_x(const BwdXArgs& xa, int ldsb, hipStream_t s) {
 }
 
 // The four sequence-length GEMMs from the bf16 images of dK', dV': img (2 x BH x kp x d) and imgT
-// (2 x BH*d x kp); `part` holds the split partials of dE, dF.
-static flurka_status grad_gemms(const Problem& p, const BwdArgs& a, const uint16_t* img, const uint16_t* imgT,
-                                int kp, float* part, hipStream_t s) {
+// (2 x BH*d x kp); `part` holds the split partials of dE, dF.  dE/dF (few long items) and dK/dV (many
+// short items) run side by side in one launch.
+template <int D>
+static flurka_status grad_gemms_d(const Problem& p, const BwdArgs& a, const uint16_t* img, const uint16_t* imgT,
+                                  int kp, float* part, hipStream_t s) {
     const size_t img_elems = (size_t)p.BH * kp * p.d;
+    const GradEPlan e = grad_e_plan(p);
+    GemmParams gx{};       // dK = E^T dK', dV = F^T dV'
+    gx.A[0] = imgT; gx.A[1] = imgT + img_elems;
+    gx.B[0] = (const uint16_t*)a.E; gx.B[1] = (const uint16_t*)a.F;
+    gx.C[0] = a.dK; gx.C[1] = a.dV;
+    gx.n = p.n; gx.d = p.d; gx.k = p.k; gx.BH = p.BH; gx.kp = kp;
+    gx.tilesM = (p.BH * p.d + GBM - 1) / GBM; gx.tilesN = (p.n + GBN - 1) / GBN;
+    gx.splits = 1; gx.total_steps = kp / GBK; gx.steps_per_split = gx.total_steps;
+    GemmParams ge{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
+    ge.A[0] = img; ge.A[1] = img + img_elems;
+    ge.B[0] = (const uint16_t*)a.K; ge.B[1] = (const uint16_t*)a.V;
+    ge.n = p.n; ge.d = p.d; ge.k = p.k; ge.BH = p.BH; ge.kp = kp;
+    ge.tilesM = e.tilesM; ge.tilesN = e.tilesN; ge.splits = e.splits;
+    ge.total_steps = e.total_steps; ge.steps_per_split = e.steps_per_split;
     flurka_status st;
     {
-        StageScope sc(s, STAGE_K_GRAD_X);
-        GemmParams gp{};       // dK = E^T dK', dV = F^T dV'
-        gp.A[0] = imgT; gp.A[1] = imgT + img_elems;
-        gp.B[0] = (const uint16_t*)a.E; gp.B[1] = (const uint16_t*)a.F;
-        gp.C[0] = a.dK; gp.C[1] = a.dV;
-        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = kp;
-        gp.tilesM = (p.BH * p.d + GBM - 1) / GBM; gp.tilesN = (p.n + GBN - 1) / GBN;
-        gp.splits = 1; gp.total_steps = kp / GBK; gp.steps_per_split = gp.total_steps;
-        st = p.d == 64 ? launch_gemm_mfma<GradXPolicy<64>>(gp, s) : launch_gemm_mfma<GradXPolicy<128>>(gp, s);
-        if (st != FLURKA_OK) return st;
-    }
-    {
-        stage_begin(s);
-        const GradEPlan e = grad_e_plan(p);
-        GemmParams gp{};       // dE = sum_bh dK' K^T, dF = sum_bh dV' V^T
-        gp.A[0] = img; gp.A[1] = img + img_elems;
-        gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
-        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = kp;
-        gp.tilesM = e.tilesM; gp.tilesN = e.tilesN; gp.splits = e.splits;
-        gp.total_steps = e.total_steps; gp.steps_per_split = e.steps_per_split;
+        StageScope sc(s, STAGE_K_GRAD_PAIR);
         if (e.splits == 1) {
             // enough tiles to fill the chip without splitting the reduction: results leave as bf16
-            gp.C[0] = a.dE; gp.C[1] = a.dF;
-            st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64, true>>(gp, s) : launch_gemm_mfma<GradEPolicy<128, true>>(gp, s);
-            if (st != FLURKA_OK) return st;
-            stage_end(s, STAGE_K_GRAD_E);
-            return FLURKA_OK;
+            ge.C[0] = a.dE; ge.C[1] = a.dF;
+            st = launch_gemm_mfma_pair<GradEPolicy<D, true>, GradXPolicy<D>>(ge, gx, s);
+        } else {
+            ge.C[0] = part; ge.C[1] = nullptr;
+            st = launch_gemm_mfma_pair<GradEPolicy<D, false>, GradXPolicy<D>>(ge, gx, s);
         }
-        gp.C[0] = part; gp.C[1] = nullptr;
-        st = p.d == 64 ? launch_gemm_mfma<GradEPolicy<64>>(gp, s) : launch_gemm_mfma<GradEPolicy<128>>(gp, s);
         if (st != FLURKA_OK) return st;
-        stage_end(s, STAGE_K_GRAD_E);
+    }
+    if (e.splits > 1) {
         StageScope sc(s, STAGE_K_SUM_SPLITS);
         SumSplitsArgs sa{};
         sa.dst[0] = (uint16_t*)a.dE; sa.dst[1] = (uint16_t*)a.dF; sa.part = part;
@@ -1330,6 +1326,11 @@ static flurka_status grad_gemms(const Problem& p, const BwdArgs& a, const uint16
         FLURKA_CHECK_LAUNCH();
     }
     return FLURKA_OK;
+}
+
+static flurka_status grad_gemms(const Problem& p, const BwdArgs& a, const uint16_t* img, const uint16_t* imgT,
+                                int kp, float* part, hipStream_t s) {
+    return p.d == 64 ? grad_gemms_d<64>(p, a, img, imgT, kp, part, s) : grad_gemms_d<128>(p, a, img, imgT, kp, part, s);
 }
 
 static flurka_status fast_backward_elu(const Problem& p, const BwdArgs& a, hipStream_t s);

@@ -98,17 +98,19 @@ __host__ __device__ inline int gemm_item_count(const GemmParams& g) {
 
 // STREAM: a workgroup may take several work items (launched with fewer workgroups than items); the
 // one-item form keeps the step bookkeeping out of the long reductions, where it costs a few percent.
+// `block` of `nblocks`: this workgroup's place among the workgroups that run this GEMM (the whole grid,
+// or one part of a grid that runs two GEMMs side by side).
 template <class Pol, bool STREAM>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+__device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int block, const int nblocks,
+                                               unsigned char* const lds) {
     constexpr bool BT = Pol::B_TRANSPOSE;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // Work items = (split, row tile, column tile, which).  A workgroup takes items blockIdx.x,
-    // blockIdx.x + gridDim.x, ... (gridDim.x is a multiple of 8 whenever there is more than one item per
+    // Work items = (split, row tile, column tile, which).  A workgroup takes items block,
+    // block + nblocks, ... (nblocks is a multiple of 8 whenever there is more than one item per
     // workgroup, so a workgroup's items all run on one XCD = id mod 8) and runs their reduction steps as
     // ONE stream: the requests issued during the last two steps of an item already fetch the first two
     // steps of the next one, so only the first item of a workgroup pays for an empty pipeline.
@@ -145,8 +147,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
         it.send = it.step0 + ((it.step1 - it.step0 + 1) & ~1);        // steps run in pairs
         return it;
     };
-    int item_id = blockIdx.x;
-    Item cur = decode(item_id), nxt = decode(STREAM ? item_id + (int)gridDim.x : total_items);
+    int item_id = block;
+    Item cur = decode(item_id), nxt = decode(STREAM ? item_id + nblocks : total_items);
     typename Pol::Ctx pc = Pol::make(g, cur.which, cur.tm * GBM, cur.tn * GBN, tid);
     typename Pol::Ctx pn = Pol::make(g, nxt.which, nxt.tm * GBM, nxt.tn * GBN, tid);
 
@@ -361,10 +363,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc[i][j] = zero16();
-            item_id += gridDim.x;
+            item_id += nblocks;
             cur = nxt;
             pc = pn;
-            nxt = decode(item_id + gridDim.x);
+            nxt = decode(item_id + nblocks);
             pn = Pol::make(g, nxt.which, nxt.tm * GBM, nxt.tn * GBN, tid);
         }
     }
@@ -372,6 +374,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
 #undef G_MMA
 #undef G_LDA
 #undef G_LDB
+}
+
+template <class Pol, bool STREAM>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    gemm_mfma_body<Pol, STREAM>(g, (int)blockIdx.x, (int)gridDim.x, lds);
+}
+
+// Two independent GEMMs in one launch: workgroups 0 .. blocks_a - 1 run the first (launch the one with
+// the longer items first), the rest the second.  Each part alone would leave compute units idle (few
+// long items) or pay its ramp-up and tail on its own; side by side they fill the chip for the length of
+// the longer part.  Both parts stream their items; blocks_a is a multiple of 8, so id mod 8 names the
+// XCD in both parts.
+template <class PolA, class PolB>
+__global__ __launch_bounds__(256) void gemm_mfma_pair_kernel(GemmParams ga, GemmParams gb, int blocks_a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int b = (int)blockIdx.x;
+    if (b < blocks_a) gemm_mfma_body<PolA, true>(ga, b, blocks_a, lds);
+    else              gemm_mfma_body<PolB, true>(gb, b - blocks_a, (int)gridDim.x - blocks_a, lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -517,6 +538,27 @@ static inline flurka_status launch_gemm_mfma(const GemmParams& g, hipStream_t s)
     if (items > resident) resident = resident / 8 * 8;
     if (items <= resident || resident < 8) return launch_gemm_mfma_impl<Pol, false>(g, (int)items, s);
     return launch_gemm_mfma_impl<Pol, true>(g, resident, s);
+}
+
+// Both GEMMs in one launch (gemm_mfma_pair_kernel).  Falls back to two launches where a part cannot
+// stream (fewer than 8 resident workgroups).
+template <class PolA, class PolB>
+static inline flurka_status launch_gemm_mfma_pair(const GemmParams& ga, const GemmParams& gb, hipStream_t s) {
+    auto kern = gemm_mfma_pair_kernel<PolA, PolB>;
+    KernelFacts facts;
+    if (!kernel_facts((const void*)kern, 256, G_LDS, &facts)) return FLURKA_ERR_LAUNCH;
+    const long resident = (long)facts.cus * facts.blocks_per_cu / 8 * 8;
+    if (resident < 8) {
+        const flurka_status st = launch_gemm_mfma<PolA>(ga, s);
+        return st != FLURKA_OK ? st : launch_gemm_mfma<PolB>(gb, s);
+    }
+    const long items_a = gemm_item_count<PolA>(ga), items_b = gemm_item_count<PolB>(gb);
+    static_assert(PolA::SHARE_B, "the first part's item count must be a multiple of 8");
+    const int blocks_a = (int)(items_a < resident ? items_a : resident);
+    const int blocks_b = (int)(items_b < resident ? items_b : resident);
+    hipLaunchKernelGGL(kern, dim3(blocks_a + blocks_b), dim3(256), G_LDS, s, ga, gb, blocks_a);
+    if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH;
+    return FLURKA_OK;
 }
 
 }  // namespace flurka

@@ -121,7 +121,9 @@ enum Stage {
     STAGE_K_GRAD_X = 17,
     STAGE_K_GRAD_E = 18,
     STAGE_K_SUM_SPLITS = 19,
-    STAGE_COUNT = 20
+    STAGE_BWD_GRADS = 20,  // dK, dV, dE, dF together (MFMA path: one launch)
+    STAGE_K_GRAD_PAIR = 21,
+    STAGE_COUNT = 22
 };
 // No-ops unless the timer is enabled.  begin/end pairs must not nest.
 void stage_begin(hipStream_t s);

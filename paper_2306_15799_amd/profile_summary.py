@@ -28,6 +28,7 @@ ROOT = os.path.dirname(PKG_DIR)
 # kernel name in a rocprofv3 trace (template arguments vary) -> name the library's stage timer uses
 TIMER_NAME_RULES = [
     ("gemm_mfma_kernel<ProjPolicy", "gemm_mfma_proj"),
+    ("gemm_mfma_pair_kernel", "gemm_mfma_grads"),
     ("gemm_mfma_kernel<GradXPolicy", "gemm_mfma_gradx"),
     ("gemm_mfma_kernel<GradEPolicy", "gemm_mfma_grade"),
     ("proj_finish_kernel", "proj_finish"),
