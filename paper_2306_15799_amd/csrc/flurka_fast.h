@@ -8,7 +8,7 @@ namespace flurka {
 struct KeyStatePlan {
     int kpad;              // k rounded up to whole 32-key tiles
     int FT;                // 32-feature tiles
-    int KR;                // key ranges handled by separate wavefronts and merged afterwards
+    int KR;                // key ranges = wavefronts of a workgroup, merged in LDS
     int tiles_per_range;
 };
 KeyStatePlan key_state_plan(const Problem& p);
@@ -18,9 +18,6 @@ struct KeyStateBuffers {
     uint16_t* Kimg;        // 3 x (BH, kpad * d) bf16, key_state's operand order (see proj_finish_kernel)
     uint32_t* Vimg;        // 2 x (BH, kpad/2, d) dwords
     float* nrm;            // (BH, kpad)
-    float* Spart;          // (BH, KR, mf, d)
-    float* zpart;          // (BH, KR, mf)
-    float* cpart;          // (BH, KR, mf)
     uint16_t* St;          // (BH, d, mf) bf16, feature slots in operand order; performer: S_j / z_j
     float* zp;             // (BH, mf)
     uint16_t* cw;          // (BH, mf, 4) bf16: hi, mid, lo terms of c + ln z, then 0 (performer only)

@@ -301,7 +301,7 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 }
 
 struct FastWs {
-    size_t partial, Kimg, Vimg, nrm, Spart, zpart, cpart, St, zp, cw, total;    // byte offsets
+    size_t partial, Kimg, Vimg, nrm, St, zp, cw, total;    // byte offsets
 };
 
 static FastWs fast_ws_layout(const Problem& p) {
@@ -315,9 +315,6 @@ static FastWs fast_ws_layout(const Problem& p) {
     W.Kimg = o;    o += round_up(p.elu ? 0 : 3 * BH * ks.kpad * p.d * 2, 256);
     W.Vimg = o;    o += round_up(2 * BH * (ks.kpad / 2) * p.d * 4, 256);
     W.nrm = o;     o += round_up(BH * ks.kpad * 4, 256);
-    W.Spart = o;   o += round_up(BH * ks.KR * p.mf * p.d * 4, 256);
-    W.zpart = o;   o += round_up(BH * ks.KR * p.mf * 4, 256);
-    W.cpart = o;   o += round_up(BH * ks.KR * p.mf * 4, 256);
     W.St = o;      o += round_up(BH * p.d * p.mf * 2, 256);
     W.zp = o;      o += round_up(BH * p.mf * 4, 256);
     W.cw = o;      o += round_up(BH * p.mf * 8, 256);
@@ -381,7 +378,6 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     {
         KeyStateBuffers kb{};
         kb.Kimg = (uint16_t*)(wsb + W.Kimg); kb.Vimg = (uint32_t*)(wsb + W.Vimg); kb.nrm = (float*)(wsb + W.nrm);
-        kb.Spart = (float*)(wsb + W.Spart); kb.zpart = (float*)(wsb + W.zpart); kb.cpart = (float*)(wsb + W.cpart);
         kb.St = (uint16_t*)(wsb + W.St); kb.zp = (float*)(wsb + W.zp); kb.cw = (uint16_t*)(wsb + W.cw);
         const ProjPlan q = proj_plan(p);
         st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN, proj_splits, kb, s);

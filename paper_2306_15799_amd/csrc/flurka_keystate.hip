@@ -6,15 +6,15 @@
 // fp32 accuracy: K' (fp32) is split into three bf16 terms whose products with the bf16 omega are
 // exact in the fp32 accumulator.  PhiK and V' enter the second contraction as two-term bf16 splits.
 //
-// Three kernels:
+// Two kernels:
 //   proj_finish   sums the projection's split-n partials into K', V' (fp32, ctx) and writes the
 //                 operand images: K' as bf16 hi/mid/lo rows, V' as bf16 hi/lo with two consecutive
 //                 keys per dword, and |k'|^2 / 2 per key
-//   key_state     one wavefront per (head, 32 features, key range): first contraction on MFMA, column
-//                 maximum, exp, second contraction on MFMA with PhiK taken from the accumulator
-//                 registers as the A operand; writes per-range partial S, z, c
-//   merge_pack    joins the key ranges (log-sum-exp style), writes S, z, c (fp32, ctx) and the bf16
-//                 images the query-stream kernel loads into LDS
+//   key_state     one workgroup per (head, 32 features), one wavefront per key range: first
+//                 contraction on MFMA, column maximum, exp, second contraction on MFMA with PhiK taken
+//                 from the accumulator registers as the A operand; the ranges' partial S, z, c meet in
+//                 LDS, are joined there (log-sum-exp style) and leave as S, z, c (fp32, ctx) and as the
+//                 bf16 images the query-stream kernel loads into LDS
 #include "flurka_fast.h"
 #include "flurka_gemm.h"
 
@@ -123,24 +123,37 @@ struct KeyStateArgs {
     const uint32_t* Vimg;
     const float* nrm;
     const uint16_t* omega;
-    float* Spart;           // (BH, KR, mf, d)
-    float* zpart;           // (BH, KR, mf)
-    float* cpart;           // (BH, KR, mf)
+    float* S; float* z; float* c;            // ctx
+    uint16_t* St; float* zp; uint16_t* cw;   // images for the query stream (see the merge step below)
     long omega_head_stride;
     int BH, H, k, kpad, mf, FT, KR, tiles_per_range;
 };
 
-constexpr int KS_MT = 4;       // key tiles of a range that stay in registers
+// LDS of a workgroup: per key range the partial S tile (32 features x d, rows padded), z and c; then
+// the merge step's weights, 1/z and one 32 x 32 transposition tile.
+template <int D>
+struct KeyStateLds {
+    static constexpr int s_pitch = D + 4;                                   // floats
+    static __host__ __device__ int range_floats() { return 32 * s_pitch + 64; }
+    static __host__ __device__ int total(int KR) { return (KR * range_floats() + KR * 32 + 32 + 32 * 33) * 4; }
+};
+
+// key tiles of a range that stay in registers (head size 128 keeps fewer, and does without the
+// one-tile-ahead request of V' below: its eight wavefronts per workgroup share 256 registers each)
+template <int D> struct KeyStateKeep { static constexpr int value = D <= 64 ? 4 : 2; };
+
+// most wavefronts (key ranges) per workgroup: what the kernel's register need leaves room for
+template <int D> struct KeyStateMaxWaves { static constexpr int value = 8; };
 
 template <int D, bool ELU>
-__global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
+__global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_kernel(KeyStateArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
+    extern __shared__ __attribute__((aligned(16))) float ks_lds[];
+    using L = KeyStateLds<D>;
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
-    long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wid >= (long)a.BH * a.FT * a.KR) return;
-    const int kr = (int)(wid % a.KR); wid /= a.KR;
-    const int ft = (int)(wid % a.FT);
-    const int bh = (int)(wid / a.FT);
+    const int kr = threadIdx.x >> 6;                       // this wavefront's key range
+    const int ft = (int)(blockIdx.x % a.FT);
+    const int bh = (int)(blockIdx.x / a.FT);
     const int KT = a.kpad / 32;
     const int kt0 = kr * a.tiles_per_range;
     int kt1 = kt0 + a.tiles_per_range;
@@ -212,6 +225,8 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
     // together, and kept in registers between the maximum and the accumulation; longer ranges are
     // evaluated twice.
     const int nt = kt1 - kt0;
+    constexpr int KS_MT = KeyStateKeep<D>::value;
+    constexpr bool V_AHEAD = D <= 64;
     const bool keep = nt <= KS_MT;
     floatx16 ev[KS_MT];
     if (keep) {
@@ -275,112 +290,109 @@ __global__ __launch_bounds__(256) void key_state_kernel(KeyStateArgs a) {
 #pragma unroll
             for (int i = 0; i < KS_MT; ++i)
                 if (i < nt) {
-                    if (i + 1 < nt) load_v(kt0 + i + 1, vnext);
-                    accumulate(ev[i], vcur);
-                    if (i + 1 < nt) vcur = vnext;
+                    if constexpr (V_AHEAD) {
+                        if (i + 1 < nt) load_v(kt0 + i + 1, vnext);
+                        accumulate(ev[i], vcur);
+                        if (i + 1 < nt) vcur = vnext;
+                    } else {
+                        if (i > 0) load_v(kt0 + i, vcur);
+                        accumulate(ev[i], vcur);
+                    }
                 }
         } else {
             for (int kt = kt0; kt < kt1; ++kt) {
-                if (kt + 1 < kt1) load_v(kt + 1, vnext);
-                accumulate(tile_values(kt), vcur);
-                if (kt + 1 < kt1) vcur = vnext;
+                if constexpr (V_AHEAD) {
+                    if (kt + 1 < kt1) load_v(kt + 1, vnext);
+                    accumulate(tile_values(kt), vcur);
+                    if (kt + 1 < kt1) vcur = vnext;
+                } else {
+                    if (kt > kt0) load_v(kt, vcur);
+                    accumulate(tile_values(kt), vcur);
+                }
             }
         }
     }
     zsum = half_sum(zsum);
 
-    const long po = ((long)bh * a.KR + kr) * a.mf;
+    // this range's partial results into LDS: S tile [feature][t], then z[32], c[32]
+    float* const mine = ks_lds + kr * L::range_floats();
     if (half == 0) {
-        a.zpart[po + 32 * ft + l32] = zsum;
-        a.cpart[po + 32 * ft + l32] = c;
+        mine[32 * L::s_pitch + l32] = zsum;
+        mine[32 * L::s_pitch + 32 + l32] = c;
     }
-    float* sp = a.Spart + po * D;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
         for (int g = 0; g < 16; ++g) {
-            const int f = 32 * ft + 8 * (g >> 2) + 4 * half + (g & 3);
-            sp[(long)f * D + 32 * tt + l32] = accS[tt][g];
+            const int f = 8 * (g >> 2) + 4 * half + (g & 3);
+            mine[f * L::s_pitch + 32 * tt + l32] = accS[tt][g];
         }
-}
+    __syncthreads();
 
-// ---------------------------------------------------------------------------
-// merge_pack: one workgroup per (head, 32 features).
-//   c_j = max_r c_jr,  S_j = sum_r exp(c_jr - c_j) S_jr,  z_j likewise
-//   St (d x mf) bf16: St[t][slot] = S[feature(slot)][t];  zp: z in accumulator order of a tile
-// For the random-feature map the query stream works with p'_ij = p_ij z_j, so that its denominator is
-// the plain sum of p': St holds S_j / z_j, and cw the exponent shift c_j + ln z_j as three bf16 terms
-// (it enters the query kernel's first contraction as extra reduction slots against ones).
-// The slot -> feature order inside each group of 16 is the order in which the first MFMA of the
-// query-stream kernel hands P^T on as the B operand of the second:
-//   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4          (natural order for elu1)
-// ---------------------------------------------------------------------------
-struct MergeArgs {
-    const float* Spart; const float* zpart; const float* cpart;
-    float* S; float* z; float* c;        // ctx
-    uint16_t* St; float* zp; uint16_t* cw;  // images for the query stream
-    int KR, mf, d, permute;
-};
-
-// Grid: (head, 32 features) x chunks of 32 coordinates t, so that even a few heads fill the chip.
-__global__ __launch_bounds__(256) void merge_pack_kernel(MergeArgs a) {
-    __shared__ float w[32][32];          // weights exp(c_jr - c_j) per range and feature
-    __shared__ float zinv[32];           // 1 / z_j (random-feature map), 1 (elu1)
-    __shared__ float tile[32][33];       // merged S tile (features x 32 t), padded
-    const int FT = a.mf / 32;
-    const int bh = blockIdx.x / FT, ft = blockIdx.x % FT;
-    const int t0 = 32 * blockIdx.y;
-    const int tid = threadIdx.x;
-    const long pbase = (long)bh * a.KR * a.mf;
+    // Merge of the key ranges, by the whole workgroup:
+    //   c_j = max_r c_jr,  S_j = sum_r exp(c_jr - c_j) S_jr,  z_j likewise
+    //   St (d x mf) bf16: St[t][slot] = S[feature(slot)][t];  zp: z in accumulator order of a tile
+    // For the random-feature map the query stream works with p'_ij = p_ij z_j, so that its denominator
+    // is the plain sum of p': St holds S_j / z_j, and cw the exponent shift c_j + ln z_j as three bf16
+    // terms (it enters the query kernel's first contraction as extra reduction slots against ones).
+    // The slot -> feature order inside each group of 16 is the order in which the first MFMA of the
+    // query-stream kernel hands P^T on as the B operand of the second:
+    //   slot 16*q + 8*h + e  <->  feature 16*q + 8*(e/4) + 4*h + e%4          (natural order for elu1)
+    const int KR = a.KR, tid = threadIdx.x, nthreads = blockDim.x;
+    float* const wgt = ks_lds + KR * L::range_floats();      // [range][feature]
+    float* const zinv = wgt + KR * 32;
+    float* const tile = zinv + 32;                           // [32][33]
     if (tid < 32) {
         const int f = 32 * ft + tid;
         float cm = -INFINITY;
-        for (int r = 0; r < a.KR; ++r) cm = fmaxf(cm, a.cpart[pbase + (long)r * a.mf + f]);
+        for (int r = 0; r < KR; ++r) cm = fmaxf(cm, ks_lds[r * L::range_floats() + 32 * L::s_pitch + 32 + tid]);
         float zs = 0.f;
-        for (int r = 0; r < a.KR; ++r) {
-            const float wr = a.permute ? expf(a.cpart[pbase + (long)r * a.mf + f] - cm) : 1.f;
-            w[r][tid] = wr;
-            zs = fmaf(wr, a.zpart[pbase + (long)r * a.mf + f], zs);
+        for (int r = 0; r < KR; ++r) {
+            const float* pr = ks_lds + r * L::range_floats() + 32 * L::s_pitch;
+            const float wr = ELU ? 1.f : expf(pr[32 + tid] - cm);
+            wgt[r * 32 + tid] = wr;
+            zs = fmaf(wr, pr[tid], zs);
         }
-        if (blockIdx.y == 0) {
-            a.z[(long)bh * a.mf + f] = zs;
-            a.c[(long)bh * a.mf + f] = cm;
-            // accumulator order of a 32-feature tile: position 16*h + g <-> feature 8*(g/4) + 4*h + g%4
-            int pos = tid;
-            if (a.permute) {
-                const int q = tid >> 3, h = (tid >> 2) & 1, e = tid & 3;
-                pos = 16 * h + 4 * q + e;
-            }
-            a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
-            if (a.permute) {
-                uint16_t hi, mid, lo;
-                split3(cm + logf(zs), hi, mid, lo);
-                uint2 pk;
-                pk.x = (uint32_t)hi | ((uint32_t)mid << 16);
-                pk.y = (uint32_t)lo;
-                *(uint2*)(a.cw + ((long)bh * a.mf + f) * 4) = pk;
-            }
+        a.z[(long)bh * a.mf + f] = zs;
+        a.c[(long)bh * a.mf + f] = cm;
+        // accumulator order of a 32-feature tile: position 16*h + g <-> feature 8*(g/4) + 4*h + g%4
+        int pos = tid;
+        if (!ELU) {
+            const int q = tid >> 3, h = (tid >> 2) & 1, e = tid & 3;
+            pos = 16 * h + 4 * q + e;
         }
-        zinv[tid] = a.permute ? 1.f / zs : 1.f;
+        a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
+        if (!ELU) {
+            uint16_t hi, mid, lo;
+            split3(cm + logf(zs), hi, mid, lo);
+            uint2 pk;
+            pk.x = (uint32_t)hi | ((uint32_t)mid << 16);
+            pk.y = (uint32_t)lo;
+            *(uint2*)(a.cw + ((long)bh * a.mf + f) * 4) = pk;
+        }
+        zinv[tid] = ELU ? 1.f : 1.f / zs;
     }
     __syncthreads();
-    for (int i = tid; i < 32 * 32; i += 256) {
-        const int fl = i / 32, t = t0 + i % 32;
-        float s = 0.f;
-        for (int r = 0; r < a.KR; ++r)
-            s = fmaf(w[r][fl], a.Spart[(pbase + (long)r * a.mf + 32 * ft + fl) * a.d + t], s);
-        a.S[((long)bh * a.mf + 32 * ft + fl) * a.d + t] = s;
-        tile[fl][i % 32] = s;
-    }
-    __syncthreads();
-    for (int i = tid; i < 32 * 32; i += 256) {
-        const int tl = i / 32, sl = i % 32;
-        int fl = sl;
-        if (a.permute) {
-            const int e = sl & 7, h = (sl >> 3) & 1;
-            fl = (sl & 16) + 8 * (e >> 2) + 4 * h + (e & 3);
+    for (int t0 = 0; t0 < D; t0 += 32) {
+        for (int i = tid; i < 32 * 32; i += nthreads) {
+            const int fl = i / 32, t = t0 + i % 32;
+            float sv = 0.f;
+            for (int r = 0; r < KR; ++r)
+                sv = fmaf(wgt[r * 32 + fl], ks_lds[r * L::range_floats() + fl * L::s_pitch + t], sv);
+            a.S[((long)bh * a.mf + 32 * ft + fl) * D + t] = sv;
+            tile[fl * 33 + i % 32] = sv;
         }
-        a.St[((long)bh * a.d + t0 + tl) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl][tl] * zinv[fl]);
+        __syncthreads();
+        for (int i = tid; i < 32 * 32; i += nthreads) {
+            const int tl = i / 32, sl = i % 32;
+            int fl = sl;
+            if (!ELU) {
+                const int e = sl & 7, h = (sl >> 3) & 1;
+                fl = (sl & 16) + 8 * (e >> 2) + 4 * h + (e & 3);
+            }
+            a.St[((long)bh * D + t0 + tl) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl * 33 + tl] * zinv[fl]);
+        }
+        __syncthreads();
     }
 }
 
@@ -392,25 +404,34 @@ KeyStatePlan key_state_plan(const Problem& p) {
     q.kpad = (p.k + 31) / 32 * 32;
     q.FT = p.mf / 32;
     const int KT = q.kpad / 32;
-    const int waves = 4 * chip_cus();                            // about one wavefront per SIMD ...
-    int KR = (waves + p.BH * q.FT - 1) / (p.BH * q.FT);
-    if (KR < (KT + KS_MT - 1) / KS_MT) KR = (KT + KS_MT - 1) / KS_MT;   // ... of at most KS_MT key tiles
-    if (KR > 32) KR = 32;
-    if (KR > KT) KR = KT;
-    if (KR < 1) KR = 1;
+    // Key ranges = wavefronts of a workgroup: about two key tiles per wavefront (measured best at the
+    // benchmark shapes: fewer wavefronts leave the latency of the operand loads exposed, more of them
+    // make the merge longer), at most KeyStateMaxWaves (the ranges' partial tiles meet in LDS).  Ranges
+    // of more than KeyStateKeep tiles are evaluated twice (maximum, then accumulation).
+    const int max_kr = p.d <= 64 ? KeyStateMaxWaves<64>::value : KeyStateMaxWaves<128>::value;
+    const int want = (KT + 1) / 2;
+    int KR = 1;
+    while (KR < want && KR < max_kr) KR *= 2;
+    while (KR > KT && KR > 1) KR /= 2;
     q.tiles_per_range = (KT + KR - 1) / KR;
     q.KR = (KT + q.tiles_per_range - 1) / q.tiles_per_range;
     return q;
 }
 
-template <int D>
-static flurka_status launch_key_state(const Problem& p, const KeyStateArgs& ka, hipStream_t s) {
-    const long waves = (long)p.BH * ka.FT * ka.KR;
-    const dim3 grid((unsigned)((waves + 3) / 4));
-    if (p.elu) hipLaunchKernelGGL((key_state_kernel<D, true>), grid, dim3(256), 0, s, ka);
-    else       hipLaunchKernelGGL((key_state_kernel<D, false>), grid, dim3(256), 0, s, ka);
+template <int D, bool ELU>
+static flurka_status launch_key_state_impl(const Problem& p, const KeyStateArgs& ka, hipStream_t s) {
+    auto kern = key_state_kernel<D, ELU>;
+    const int ldsb = KeyStateLds<D>::total(ka.KR);
+    KernelFacts facts;
+    if (!kernel_facts((const void*)kern, ka.KR * 64, ldsb, &facts)) return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(p.BH * ka.FT)), dim3(ka.KR * 64), ldsb, s, ka);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
+}
+
+template <int D>
+static flurka_status launch_key_state(const Problem& p, const KeyStateArgs& ka, hipStream_t s) {
+    return p.elu ? launch_key_state_impl<D, true>(p, ka, s) : launch_key_state_impl<D, false>(p, ka, s);
 }
 
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
@@ -433,22 +454,13 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         KeyStateArgs ka{};
         ka.Kimg = b.Kimg; ka.Kp = ctx + L.Kp; ka.Vimg = b.Vimg; ka.nrm = b.nrm;
         ka.omega = (const uint16_t*)omega;
-        ka.Spart = b.Spart; ka.zpart = b.zpart; ka.cpart = b.cpart;
+        ka.S = ctx + L.S; ka.z = ctx + L.z; ka.c = ctx + L.c;
+        ka.St = b.St; ka.zp = b.zp; ka.cw = b.cw;
         ka.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
         ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf;
         ka.FT = q.FT; ka.KR = q.KR; ka.tiles_per_range = q.tiles_per_range;
         flurka_status st = p.d == 64 ? launch_key_state<64>(p, ka, s) : launch_key_state<128>(p, ka, s);
         if (st != FLURKA_OK) return st;
-    }
-    {
-        StageScope sc(s, STAGE_K_MERGE_PACK);
-        MergeArgs ma{};
-        ma.Spart = b.Spart; ma.zpart = b.zpart; ma.cpart = b.cpart;
-        ma.S = ctx + L.S; ma.z = ctx + L.z; ma.c = ctx + L.c;
-        ma.St = b.St; ma.zp = b.zp; ma.cw = b.cw;
-        ma.KR = q.KR; ma.mf = p.mf; ma.d = p.d; ma.permute = p.elu ? 0 : 1;
-        hipLaunchKernelGGL(merge_pack_kernel, dim3(p.BH * q.FT, p.d / 32), dim3(256), 0, s, ma);
-        FLURKA_CHECK_LAUNCH();
     }
     return FLURKA_OK;
 }

@@ -142,7 +142,7 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
     };
     auto maybe_rescale = [&](int i, float tmax) {
         if (tmax > mu[i] + FLURKA_LAZY_MAX) {
-            const float sc = fast_exp2((mu[i] - tmax) * FLURKA_LOG2E);     // 0 on the first tile
+            const float sc = fast_exp2((mu[i] - tmax) * FLURKA_LOG2E);
             mu[i] = tmax;
             den[i] *= sc;
 #pragma unroll
@@ -163,8 +163,10 @@ __device__ __forceinline__ void forward_feature_pass(const unsigned char* lw, in
 #pragma unroll
             for (int i = 0; i < QT; ++i) u[i] = mfma32(wa, s < KS ? qf[i][s] : qone, u[i]);
         }
+        // the first tile's maximum simply becomes the running maximum: nothing has been accumulated
+        // yet, so there is nothing to rescale
 #pragma unroll
-        for (int i = 0; i < QT; ++i) maybe_rescale(i, tile_max(u[i]));
+        for (int i = 0; i < QT; ++i) mu[i] = tile_max(u[i]);
     }
 
     auto iteration = [&](int ft, auto last_tag) {
