@@ -265,6 +265,62 @@ def run_workload(torch, fb, inputs, w, algo, steps, warmup, graph=False):
     return res
 
 
+def run_paper_order(torch, fb, inputs, w, dm, steps, warmup):
+    """Forward in the order Eq. 2 prints (projection of the model-wide input, then the per-head transform
+    of its k rows) next to the transform-first route on the same data: K = X_K W^K, V = X_V W^V over all n
+    positions by the vendor GEMM (torch.matmul), then flurka_attn_fwd."""
+    t = inputs.make_paper_order_inputs(w, dm, seed=0)
+    dev = torch.device("cuda:0")
+    g = {k: (None if v is None else torch.from_numpy(v).to(dev).to(torch.bfloat16).contiguous()) for k, v in t.items()}
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    ctx = fb.alloc_buffer(fb.ctx_bytes(*dims, fb.BF16, w.phi), dev)
+    ws = fb.alloc_buffer(fb.load_library().flurka_fused_w_workspace_bytes(*dims, dm, fb.BF16, 0 if w.phi == "performer" else 1), dev)
+    ws2 = fb.alloc_buffer(fb.workspace_bytes(*dims, fb.BF16, w.phi, fb.PASS_FWD, "auto"), dev)
+    out = torch.empty_like(g["Q"])
+    wk2 = g["WK"].reshape(w.H * w.d, dm).t().contiguous()       # (dm, H*d) for the vendor GEMM
+    wv2 = g["WV"].reshape(w.H * w.d, dm).t().contiguous()
+
+    def fused():
+        fb.flurka_attn_fwd_fused_w(g["Q"], g["XK"], g["XV"], g["E"], g["F"], g["WK"], g["WV"], g["omega"], phi=w.phi,
+                                   out=out, ctx=ctx, workspace=ws)
+
+    def transform_first():
+        K = torch.matmul(g["XK"], wk2).view(w.B, w.n, w.H, w.d).permute(0, 2, 1, 3).contiguous()
+        V = torch.matmul(g["XV"], wv2).view(w.B, w.n, w.H, w.d).permute(0, 2, 1, 3).contiguous()
+        fb.flurka_attn_fwd(g["Q"], K, V, g["E"], g["F"], g["omega"], phi=w.phi, out=out, ctx=ctx, workspace=ws2)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms_fused, ms_first = timed(fused), timed(transform_first)
+    fb.profile_enable(True)
+    for _ in range(steps):
+        fused()
+    torch.cuda.synchronize()
+    acc = {}
+    for name, ms in fb.profile_read():
+        acc.setdefault(name.split(":")[-1], []).append(ms)
+    fb.profile_enable(False)
+    BH = w.B * w.H
+    fl = 4.0 * w.k * w.n * dm * w.B + 4.0 * w.k * dm * w.H * w.d * w.B + stage_model(w, "key_state")[0] + stage_model(w, "query_stream")[0]
+    return {"workload": f"B={w.B} H={w.H} n={w.n} d={w.d} k={w.k} m={w.m} dm={dm} bf16 {w.phi} fwd",
+            "ms_paper_order": round(ms_fused, 5), "ms_transform_first": round(ms_first, 5),
+            "speedup": round(ms_first / ms_fused, 3), "tokens_heads_per_s": round(BH * w.n / ms_fused * 1e3, 1),
+            "tflops": round(fl / ms_fused / 1e9, 2),
+            "kernels_ms": {k: round(sum(v) / len(v), 5) for k, v in acc.items()},
+            "note": "transform first = torch.matmul for X W over all n positions (plus the head-major copy "
+                    "flurka_attn_fwd's layout needs) + flurka_attn_fwd"}
+
+
 def attach_traffic(roof, w, kernel):
     """HBM bytes per launch from the committed rocprofv3 counter runs, if they were measured on the
     library sources that are running now."""
@@ -445,6 +501,9 @@ def main():
             del rn
             torch.cuda.empty_cache()
         result["configs"] = configs
+        # Eq. 2 in the paper's own order at C4's shape (model width = H * d)
+        c4 = all_w["C4"]
+        result["paper_order"] = run_paper_order(torch, fb, inputs, c4, c4.H * c4.d, min(args.steps, 20), 5)
 
     print(json.dumps(result))
 

@@ -169,6 +169,42 @@ FLURKA_API flurka_status flurka_attn_fwd_static(const void* Q, const void* K, co
                               void* stream);
 
 /*
+ * Forward with the linear transforms fused in the order Eq. 2 prints them:
+ *
+ *     K' = (E X_K) W^K_h,   V' = (F X_V) W^V_h,   out as in flurka_attn_fwd
+ *
+ * The sequence projection is applied once to the model-wide layer inputs X_K, X_V (before the split into
+ * heads), and each head's transform to the k projected rows instead of the n sequence positions (App. B,
+ * steps "downsampling" then "linear transformation": d_k d_m^2 instead of N d_m^2 products per
+ * transform).  The result equals flurka_attn_fwd on K = X_K W^K_h, V = X_V W^V_h (the products
+ * re-associate), up to rounding: here X W is never rounded to the storage type.
+ *
+ *   Q         in   (B, H, n, d)    per-head queries (already transformed)
+ *   XK, XV    in   (B, n, dm)      layer inputs of the key and value branches, dm = model width
+ *   WK, WV    in   (H, d, dm)      head h's transform stored transposed: row t holds column t of W_h
+ *   E, F, omega, out, ctx           as in flurka_attn_fwd; ctx holds the same state afterwards
+ *   workspace      flurka_fused_w_workspace_bytes(...) bytes, 256-byte aligned
+ *
+ * Only the bf16 MFMA kernels implement this order: bf16 storage, d = 64 or 128, n a multiple of 64, m a
+ * multiple of 32, dm a multiple of 64, H*d a multiple of 256; anything else returns
+ * FLURKA_ERR_UNSUPPORTED (flurka_fused_w_supported tells beforehand).  No backward pass is provided for
+ * this entry point.
+ */
+FLURKA_API int flurka_fused_w_supported(int B, int H, int n, int d, int k, int m, int dm,
+                             flurka_dtype dtype, flurka_phi phi);
+FLURKA_API size_t flurka_fused_w_workspace_bytes(int B, int H, int n, int d, int k, int m, int dm,
+                                      flurka_dtype dtype, flurka_phi phi);
+FLURKA_API flurka_status flurka_attn_fwd_fused_w(const void* Q, const void* XK, const void* XV,
+                              const void* E, const void* F, const void* WK, const void* WV,
+                              const void* omega, void* out,
+                              void* ctx, size_t ctx_bytes,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int H, int n, int d, int k, int m, int dm,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi,
+                              void* stream);
+
+/*
  * Backward of flurka_attn_fwd (chain rule; the paper trains through this
  * layer but prints no backward).  Given dOut = d loss / d out:
  *

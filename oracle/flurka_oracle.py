@@ -193,6 +193,35 @@ def flurka_attention(Q, K, V, E, F, omega, phi, rows=None):
 
 
 # --------------------------------------------------------------------------
+# forward with the linear transforms in the order Eq. 2 prints them
+# --------------------------------------------------------------------------
+def flurka_attention_paper_order(Q, XK, XV, E, F, WK, WV, omega, phi):
+    """Eq. 2 read literally: phi(Q W^Q) (phi((E_1 K) W^K)^T ((E_2 V) W^V)), row-normalised.
+
+    The sequence projection acts on the model-wide layer inputs, the per-head
+    transform on the k projected rows (App. B lists the steps in this order:
+    "low-rank downsampling products E_1 K & E_2 V", then the linear
+    transformations).  Q: (B, H, n, d), already transformed; XK, XV: (B, n, dm);
+    WK, WV: (H, d, dm), head h's (dm x d) transform stored transposed;
+    E, F: (k, n).  Returns out (B, H, n, d).
+    """
+    Q = np.asarray(Q, np.float64)
+    B, H, n, d = Q.shape
+    out = np.empty_like(Q)
+    for b in range(B):
+        YK = sequence_projection(E, XK[b])          # (k, dm)
+        YV = sequence_projection(F, XV[b])
+        for h in range(H):
+            Kp = YK @ np.asarray(WK[h], np.float64).T    # (k, d)
+            Vp = YV @ np.asarray(WV[h], np.float64).T
+            om = _head_omega(omega, h)
+            _, S, z, _ = key_state(Kp, Vp, om, phi)
+            P = query_features(Q[b, h], om, phi)
+            out[b, h] = (P @ S) / (P @ z)[:, None]
+    return out
+
+
+# --------------------------------------------------------------------------
 # backward (chain rule of the forward above)
 # --------------------------------------------------------------------------
 def flurka_head_bwd(Q, K, V, E, F, omega, G, phi):

@@ -30,6 +30,7 @@ _ALGO = {"auto": ALGO_AUTO, "generic": ALGO_GENERIC, "fast": ALGO_FAST,
 EXPORTED_SYMBOLS = (
     "flurka_version", "flurka_status_str", "flurka_ctx_bytes", "flurka_ctx_layout", "flurka_workspace_bytes",
     "flurka_fast_path_supported", "flurka_attn_fwd", "flurka_attn_fwd_static", "flurka_attn_bwd",
+    "flurka_fused_w_supported", "flurka_fused_w_workspace_bytes", "flurka_attn_fwd_fused_w",
     "flurka_profile_enable", "flurka_profile_read", "flurka_profile_stage_name",
 )
 
@@ -71,6 +72,13 @@ def load_library() -> ctypes.CDLL:
     lib.flurka_attn_fwd_static.restype = c_int
     lib.flurka_attn_fwd_static.argtypes = ([c_void] * 7 + [c_void, c_size]
                                            + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
+    lib.flurka_fused_w_supported.restype = c_int
+    lib.flurka_fused_w_supported.argtypes = [c_int] * 9
+    lib.flurka_fused_w_workspace_bytes.restype = c_size
+    lib.flurka_fused_w_workspace_bytes.argtypes = [c_int] * 9
+    lib.flurka_attn_fwd_fused_w.restype = c_int
+    lib.flurka_attn_fwd_fused_w.argtypes = ([c_void] * 9 + [c_void, c_size, c_void, c_size]
+                                            + [c_int] * 7 + [c_int] + [c_int] * 2 + [c_void])
     lib.flurka_attn_bwd.restype = c_int
     lib.flurka_attn_bwd.argtypes = ([c_void] * 8 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
@@ -214,6 +222,47 @@ def flurka_attn_fwd(Q, K, V, E, F, omega, phi="performer", algo="auto", out=None
                              B, H, n, d, k, m, per_head, code, _PHI[phi], _ALGO[algo], s)
     if st != OK:
         raise FlurkaError(st, "flurka_attn_fwd")
+    return out, ctx
+
+
+def fused_w_supported(B, H, n, d, k, m, dm, dtype, phi) -> bool:
+    return bool(load_library().flurka_fused_w_supported(B, H, n, d, k, m, dm, dtype, _PHI[phi]))
+
+
+def flurka_attn_fwd_fused_w(Q, XK, XV, E, F, WK, WV, omega, phi="performer", out=None, ctx=None, workspace=None,
+                            stream=None):
+    """out, ctx = forward in the paper's order: K' = (E X_K) W^K, V' = (F X_V) W^V (Eq. 2).
+
+    Q: (B,H,n,d); XK, XV: (B,n,dm); WK, WV: (H,d,dm) (each head's transform, transposed); E, F: (k,n)."""
+    lib = load_library()
+    B, H, n, d, k, m, per_head, omega_shape = _shapes(Q, E, omega, phi)
+    dt, dev = Q.dtype, Q.device
+    code = _dtype_code(Q)
+    dm = XK.shape[-1]
+    _check(Q, "Q", (B, H, n, d), dt, dev)
+    for t, name in ((XK, "XK"), (XV, "XV")):
+        _check(t, name, (B, n, dm), dt, dev)
+    for t, name in ((WK, "WK"), (WV, "WV")):
+        _check(t, name, (H, d, dm), dt, dev)
+    for t, name in ((E, "E"), (F, "F")):
+        _check(t, name, (k, n), dt, dev)
+    if omega_shape is not None:
+        _check(omega, "omega", omega_shape, dt, dev)
+    if out is None:
+        out = torch.empty_like(Q)
+    _check(out, "out", (B, H, n, d), dt, dev)
+    if ctx is None:
+        ctx = alloc_buffer(lib.flurka_ctx_bytes(B, H, n, d, k, m, code, _PHI[phi]), dev)
+    if workspace is None:
+        workspace = alloc_buffer(lib.flurka_fused_w_workspace_bytes(B, H, n, d, k, m, dm, code, _PHI[phi]), dev)
+    s = stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    st = lib.flurka_attn_fwd_fused_w(_ptr(Q), _ptr(XK), _ptr(XV), _ptr(E), _ptr(F), _ptr(WK), _ptr(WV),
+                                     _ptr(omega) if omega_shape is not None else None, _ptr(out),
+                                     _ptr(ctx), ctx.numel() * ctx.element_size(),
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     B, H, n, d, k, m, dm, per_head, code, _PHI[phi], s)
+    if st != OK:
+        raise FlurkaError(st, "flurka_attn_fwd_fused_w")
     return out, ctx
 
 

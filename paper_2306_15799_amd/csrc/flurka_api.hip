@@ -88,7 +88,7 @@ int chip_cus() {
 
 namespace {
 
-constexpr int kVersion = 120;
+constexpr int kVersion = 130;
 
 flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
                            int dtype, int phi, Problem* out) {
@@ -247,6 +247,48 @@ flurka_status flurka_attn_fwd_static(const void* Q, const void* K, const void* V
                         H, n, d, k, m, omega_per_head, dtype, phi, algo, stream);
 }
 
+int flurka_fused_w_supported(int B, int H, int n, int d, int k, int m, int dm, flurka_dtype dtype, flurka_phi phi) {
+    Problem p;
+    if (make_problem(B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    if (dm < 1 || dm > (1 << 20)) return 0;
+    return fast_fusedw_supported(p, dm) ? 1 : 0;
+}
+
+size_t flurka_fused_w_workspace_bytes(int B, int H, int n, int d, int k, int m, int dm, flurka_dtype dtype,
+                                      flurka_phi phi) {
+    Problem p;
+    if (make_problem(B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    if (dm < 1 || dm > (1 << 20) || !fast_fusedw_supported(p, dm)) return 0;
+    return fast_fusedw_ws_bytes(p, dm);
+}
+
+flurka_status flurka_attn_fwd_fused_w(const void* Q, const void* XK, const void* XV, const void* E, const void* F,
+                                      const void* WK, const void* WV, const void* omega, void* out, void* ctx,
+                                      size_t ctx_bytes, void* workspace, size_t workspace_bytes, int B, int H, int n,
+                                      int d, int k, int m, int dm, int omega_per_head, flurka_dtype dtype,
+                                      flurka_phi phi, void* stream) {
+    Problem p;
+    flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
+    if (st != FLURKA_OK) return st;
+    if (dm < 1 || dm > (1 << 20)) return FLURKA_ERR_SHAPE;
+    if (!Q || !XK || !XV || !E || !F || !WK || !WV || !out || !ctx || !workspace) return FLURKA_ERR_NULL;
+    if (!p.elu && !omega) return FLURKA_ERR_NULL;
+    if (misaligned(ctx, 256) || misaligned(workspace, 256)) return FLURKA_ERR_ALIGN;
+    const size_t es = p.bf16 ? 2 : 4;
+    if (misaligned(Q, es) || misaligned(XK, es) || misaligned(XV, es) || misaligned(E, es) || misaligned(F, es) ||
+        misaligned(WK, es) || misaligned(WV, es) || misaligned(out, es) || (omega && misaligned(omega, es)))
+        return FLURKA_ERR_ALIGN;
+    if (!fast_fusedw_supported(p, dm) || !fast_pointers_ok(Q, XK, XV, E, F, omega, out) ||
+        !fast_pointers_ok(WK, WV, nullptr, nullptr, nullptr, nullptr, nullptr))
+        return FLURKA_ERR_UNSUPPORTED;
+    if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
+    if (workspace_bytes < fast_fusedw_ws_bytes(p, dm)) return FLURKA_ERR_WORKSPACE;
+    FusedWArgs a{Q, XK, XV, E, F, WK, WV, omega, out, (float*)ctx, (float*)workspace, dm};
+    st = fast_forward_fusedw(p, a, (hipStream_t)stream);
+    if (st != FLURKA_OK) stage_abandon();
+    return st;
+}
+
 flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
                               const void* omega, const void* out, const void* dOut, const void* ctx,
                               size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
@@ -343,6 +385,9 @@ const char* flurka_profile_stage_name(int id) {
         case STAGE_K_SUM_SPLITS: return "bwd_grad_gemms:sum_splits";
         case STAGE_BWD_GRADS: return "bwd_grad_gemms";
         case STAGE_K_GRAD_PAIR: return "bwd_grad_gemms:gemm_mfma_grads";
+        case STAGE_K_WIDE_GEMM: return "project:gemm_mfma_wide";
+        case STAGE_K_WIDE_FINISH: return "project:wide_finish";
+        case STAGE_K_TRANSFORM_GEMM: return "project:gemm_mfma_transform";
     }
     return "unknown";
 }

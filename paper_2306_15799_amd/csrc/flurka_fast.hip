@@ -354,8 +354,30 @@ static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int lds
     return launch_query_impl<D, ELU, false>(qa, ldsb, s);
 }
 
-flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
+// Query stream over the St / zp / cw images the key-state stage left in the workspace.
+static flurka_status run_query_stream(const Problem& p, const void* Q, const void* omega, void* out, float* ctx,
+                                      const uint16_t* St, const float* zp, const uint16_t* cw, hipStream_t s) {
     const CtxLayout L = ctx_layout(p);
+    StageScope sc(s, STAGE_K_QUERY_STREAM);
+    QueryArgs qa{};
+    qa.Q = (const uint16_t*)Q;
+    qa.omega = (const uint16_t*)omega;
+    qa.St = St;
+    qa.zp = zp;
+    qa.cw = cw;
+    qa.out = (uint16_t*)out;
+    qa.lse = ctx + L.lse;
+    qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
+    qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
+    qa.tiles_per_head = (p.n + 32 * QS_QT - 1) / (32 * QS_QT);
+    qa.total_tiles = (long)p.BH * qa.tiles_per_head;
+    const int ldsb = query_lds_bytes(p);
+    if (p.d == 64)
+        return p.elu ? launch_query<64, true>(p, qa, ldsb, s) : launch_query<64, false>(p, qa, ldsb, s);
+    return p.elu ? launch_query<128, true>(p, qa, ldsb, s) : launch_query<128, false>(p, qa, ldsb, s);
+}
+
+flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
     const FastWs W = fast_ws_layout(p);
     unsigned char* wsb = (unsigned char*)a.ws;
     flurka_status st;
@@ -383,29 +405,163 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN, proj_splits, kb, s);
         if (st != FLURKA_OK) return st;
     }
-    {
-        StageScope sc(s, STAGE_K_QUERY_STREAM);
-        QueryArgs qa{};
-        qa.Q = (const uint16_t*)a.Q;
-        qa.omega = (const uint16_t*)a.omega;
-        qa.St = (const uint16_t*)(wsb + W.St);
-        qa.zp = (const float*)(wsb + W.zp);
-        qa.cw = (const uint16_t*)(wsb + W.cw);
-        qa.out = (uint16_t*)a.out;
-        qa.lse = a.ctx + L.lse;
-        qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
-        qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
-        qa.tiles_per_head = (p.n + 32 * QS_QT - 1) / (32 * QS_QT);
-        qa.total_tiles = (long)p.BH * qa.tiles_per_head;
-        const int ldsb = query_lds_bytes(p);
-        if (p.d == 64)
-            st = p.elu ? launch_query<64, true>(p, qa, ldsb, s) : launch_query<64, false>(p, qa, ldsb, s);
-        else
-            st = p.elu ? launch_query<128, true>(p, qa, ldsb, s) : launch_query<128, false>(p, qa, ldsb, s);
-        if (st != FLURKA_OK) return st;
-    }
-    return FLURKA_OK;
+    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx, (const uint16_t*)(wsb + W.St), (const float*)(wsb + W.zp),
+                            (const uint16_t*)(wsb + W.cw), s);
 }
 
+// ===========================================================================
+// Paper-order path: K' = (E X_K) W^K, V' = (F X_V) W^V  (Eq. 2 read literally: the sequence projection
+// is applied to the model-wide layer input, the per-head transform to its k projected rows)
+// ===========================================================================
+// Y = E X from the first product's split partials -> the three-term bf16 image of Y that the second
+// product reads as its A operand: image[which][batch][row][term][column], term = hi, mid, lo.
+// One wavefront per (which, batch, four rows, 64 columns); a lane's four rows are the four floats of
+// one 16-byte element of the tile-ordered partials.
+struct WideFinishArgs {
+    const float* part;
+    uint16_t* img;
+    int splits, tilesM, tilesN, tiles_per_batch, k, dm, B;
+};
 
+__global__ __launch_bounds__(256) void wide_finish_kernel(WideFinishArgs a) {
+    const int lane = threadIdx.x & 63;
+    long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int col_chunks = (a.dm + 63) / 64, row_groups = (a.k + 3) / 4;
+    if (wid >= (long)2 * a.B * row_groups * col_chunks) return;
+    const int cc = (int)(wid % col_chunks); wid /= col_chunks;
+    const int rg = (int)(wid % row_groups); wid /= row_groups;
+    const int b = (int)(wid % a.B);
+    const int which = (int)(wid / a.B);
+    const int c = 64 * cc + lane, r0 = 4 * rg;
+    if (c >= a.dm) return;
+    const int tn = b * a.tiles_per_batch + c / GBN, tm = r0 / GBM;
+    const int eo = partial_elem_offset(r0 % GBM, c % GBN);
+    float4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < a.splits; ++s) {
+        const float4 x = *(const float4*)(a.part + partial_tile_index(which, s, tn, tm, a.splits, a.tilesN, a.tilesM) * G_TILE_ELEMS + eo);
+        sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+    }
+    const float v[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (r0 + e >= a.k) break;
+        uint32_t hi, mid, lo;
+        split3_pair(v[e], 0.f, hi, mid, lo);
+        uint16_t* row = a.img + (((long)(which * a.B + b) * a.k + r0 + e) * 3) * a.dm + c;
+        row[0] = (uint16_t)hi;
+        row[a.dm] = (uint16_t)mid;
+        row[2 * a.dm] = (uint16_t)lo;
+    }
+}
+
+struct SplitPlan { int splits, steps_per_split; };
+// split of a reduction of `total_steps` steps so that `tiles` output tiles give about one workgroup per
+// compute unit (the rule of proj_plan)
+static SplitPlan split_plan(int tiles, int total_steps) {
+    int splits = chip_cus() / tiles;
+    if (splits < 1) splits = 1;
+    if (splits > 8) splits = splits / 8 * 8;
+    if (splits > total_steps) splits = total_steps;
+    SplitPlan q;
+    q.steps_per_split = (total_steps + splits - 1) / splits;
+    q.splits = (total_steps + q.steps_per_split - 1) / q.steps_per_split;
+    return q;
+}
+
+struct FusedWPlan {
+    int tilesM, tpb1, tilesN1, steps1, tpb2, tilesN2, steps2;
+    SplitPlan s1, s2;
+};
+
+static FusedWPlan fusedw_plan(const Problem& p, int dm) {
+    FusedWPlan q;
+    q.tilesM = (p.k + GBM - 1) / GBM;
+    q.tpb1 = (dm + GBN - 1) / GBN;
+    q.tilesN1 = p.B * q.tpb1;
+    q.steps1 = p.n / GBK;
+    q.s1 = split_plan(q.tilesM * q.tilesN1 * 2, q.steps1);
+    q.tpb2 = p.H * p.d / GBN;
+    q.tilesN2 = p.B * q.tpb2;
+    q.steps2 = 3 * dm / GBK;
+    q.s2 = split_plan(q.tilesM * q.tilesN2 * 2, q.steps2);
+    return q;
+}
+
+bool fast_fusedw_supported(const Problem& p, int dm) {
+    if (!fast_supported(p, 0)) return false;
+    if (dm < GBK || dm % GBK != 0) return false;             // whole reduction steps of the second product
+    if ((p.H * p.d) % GBN != 0) return false;                // column tiles of the second product inside one batch
+    // 32-bit byte offsets inside the buffer descriptors of the two products
+    if ((size_t)p.n * dm * 2 >= ((size_t)1 << 31)) return false;
+    if (((size_t)p.k + GBM) * 3 * dm * 2 >= ((size_t)1 << 31)) return false;
+    if (((size_t)p.H * p.d + GBN) * dm * 2 >= ((size_t)1 << 31)) return false;
+    return true;
+}
+
+struct FusedWWs { size_t partial, img, rest, total; };
+
+static FusedWWs fusedw_ws_layout(const Problem& p, int dm) {
+    const FusedWPlan q = fusedw_plan(p, dm);
+    FusedWWs W{};
+    const size_t p1 = (size_t)2 * q.s1.splits * q.tilesM * q.tilesN1 * G_TILE_ELEMS * 4;
+    const size_t p2 = (size_t)2 * q.s2.splits * q.tilesM * q.tilesN2 * G_TILE_ELEMS * 4;
+    size_t o = 0;
+    W.partial = o; o += round_up(p1 > p2 ? p1 : p2, 256);    // the second product reuses the first one's room
+    W.img = o;     o += round_up((size_t)2 * p.B * p.k * 3 * dm * 2, 256);
+    W.rest = o;    o += fast_ws_layout(p).total;             // key-state and query-stream images (its `partial` part unused)
+    W.total = o;
+    return W;
+}
+
+size_t fast_fusedw_ws_bytes(const Problem& p, int dm) { return fusedw_ws_layout(p, dm).total; }
+
+flurka_status fast_forward_fusedw(const Problem& p, const FusedWArgs& a, hipStream_t s) {
+    const FusedWPlan q = fusedw_plan(p, a.dm);
+    const FusedWWs W = fusedw_ws_layout(p, a.dm);
+    const FastWs R = fast_ws_layout(p);
+    unsigned char* wsb = (unsigned char*)a.ws;
+    unsigned char* rest = wsb + W.rest;
+    flurka_status st;
+    {
+        StageScope sc(s, STAGE_K_WIDE_GEMM);
+        GemmParams gp{};
+        gp.A[0] = (const uint16_t*)a.E; gp.A[1] = (const uint16_t*)a.F;
+        gp.B[0] = (const uint16_t*)a.XK; gp.B[1] = (const uint16_t*)a.XV;
+        gp.C[0] = wsb + W.partial;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = p.k;
+        gp.dm = a.dm; gp.tiles_per_batch = q.tpb1;
+        gp.tilesM = q.tilesM; gp.tilesN = q.tilesN1; gp.splits = q.s1.splits;
+        gp.steps_per_split = q.s1.steps_per_split; gp.total_steps = q.steps1;
+        if ((st = launch_gemm_mfma<ProjWidePolicy>(gp, s)) != FLURKA_OK) return st;
+    }
+    {
+        StageScope sc(s, STAGE_K_WIDE_FINISH);
+        WideFinishArgs fa{};
+        fa.part = (const float*)(wsb + W.partial); fa.img = (uint16_t*)(wsb + W.img);
+        fa.splits = q.s1.splits; fa.tilesM = q.tilesM; fa.tilesN = q.tilesN1; fa.tiles_per_batch = q.tpb1;
+        fa.k = p.k; fa.dm = a.dm; fa.B = p.B;
+        const long waves = (long)2 * p.B * ((p.k + 3) / 4) * ((a.dm + 63) / 64);
+        hipLaunchKernelGGL(wide_finish_kernel, grid1d(waves, 4), dim3(256), 0, s, fa);
+        FLURKA_CHECK_LAUNCH();
+    }
+    {
+        StageScope sc(s, STAGE_K_TRANSFORM_GEMM);
+        const size_t img_elems = (size_t)p.B * p.k * 3 * a.dm;
+        GemmParams gp{};
+        gp.A[0] = (const uint16_t*)(wsb + W.img); gp.A[1] = gp.A[0] + img_elems;
+        gp.B[0] = (const uint16_t*)a.WK; gp.B[1] = (const uint16_t*)a.WV;
+        gp.C[0] = wsb + W.partial;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = p.k;
+        gp.dm = a.dm; gp.tiles_per_batch = q.tpb2;
+        gp.tilesM = q.tilesM; gp.tilesN = q.tilesN2; gp.splits = q.s2.splits;
+        gp.steps_per_split = q.s2.steps_per_split; gp.total_steps = q.steps2;
+        if ((st = launch_gemm_mfma<TransformPolicy>(gp, s)) != FLURKA_OK) return st;
+    }
+    KeyStateBuffers kb{};
+    kb.Kimg = (uint16_t*)(rest + R.Kimg); kb.Vimg = (uint32_t*)(rest + R.Vimg); kb.nrm = (float*)(rest + R.nrm);
+    kb.St = (uint16_t*)(rest + R.St); kb.zp = (float*)(rest + R.zp); kb.cw = (uint16_t*)(rest + R.cw);
+    st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN2, q.s2.splits, kb, s);
+    if (st != FLURKA_OK) return st;
+    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx, kb.St, kb.zp, kb.cw, s);
+}
 }  // namespace flurka

@@ -64,6 +64,7 @@ struct GemmParams {
                              // for policies with PARTIAL_TILES
     int tilesM, tilesN, splits, steps_per_split, total_steps;
     int n, d, k, BH, kp;     // problem sizes the policies need (kp: padded k of an image)
+    int dm, tiles_per_batch; // model width and 256-column tiles per batch (policies of the paper-order path)
 };
 
 template <int N>
@@ -437,6 +438,61 @@ struct ProjPolicy {
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
     static __device__ __forceinline__ int b_soff(const Ctx&, int step) { return step * (GBK * D * 2); }
+};
+
+// Paper-order path, first product: Y = E X for the model-wide layer input X (B, n, dm) before any
+// per-head transform (Eq. 2: the sequence projection comes first).  Rows = k projected slots, columns =
+// (batch, model coordinate), reduction = sequence positions; like ProjPolicy with row stride dm.
+struct ProjWidePolicy {
+    static constexpr bool B_TRANSPOSE = true;
+    static constexpr bool PARTIAL_TILES = true;
+    static constexpr bool TRANSPOSED_STORE = false;
+    static constexpr bool SHARE_B = false;
+    struct Ctx : PolicyCtxBase {};
+    static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
+        Ctx c;
+        const int tn = n0 / GBN, b = tn / g.tiles_per_batch, c0 = (tn % g.tiles_per_batch) * GBN;
+        c.rsA = make_rsrc(g.A[which], (unsigned)g.k * (unsigned)g.n * 2u);
+        c.rsB = make_rsrc(g.B[which] + (long)b * g.n * g.dm, (unsigned)g.n * (unsigned)g.dm * 2u);
+        c.voffA = ((m0 + (tid >> 3)) * g.n + 8 * (tid & 7)) * 2;
+        c.a_qstride = 64 * g.n;
+        // columns past dm (a ragged last tile) read the next position's values or zero: finite, and nobody
+        // uses those columns of the result
+        c.voffB = ((8 * (tid >> 5)) * g.dm + c0 + 8 * (tid & 31)) * 2;
+        c.b_qstride = g.dm * 2;
+        return c;
+    }
+    static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
+    static __device__ __forceinline__ int b_soff(const Ctx& c, int step) { return step * GBK * c.b_qstride; }
+};
+
+// Paper-order path, second product: K' = Y W^K per head (Eq. 2: (E_1 K) W^K), all heads of a batch at
+// once.  Rows = k projected slots of the three-term bf16 image of Y (row = [hi | mid | lo], 3*dm
+// reduction slots, so that the products with the bf16 transform are exact in the fp32 accumulator),
+// columns = (batch, head, t), B = the transform stored as (H*d, dm) rows (reduction contiguous), the
+// reduction index wrapping around dm once per term.  Results leave as split partials in the projection's
+// tile order, so the same finishing kernel takes over.
+struct TransformPolicy {
+    static constexpr bool B_TRANSPOSE = false;
+    static constexpr bool PARTIAL_TILES = true;
+    static constexpr bool TRANSPOSED_STORE = false;
+    static constexpr bool SHARE_B = false;
+    struct Ctx : PolicyCtxBase { int steps_per_term; };
+    static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
+        Ctx c;
+        const int tn = n0 / GBN, b = tn / g.tiles_per_batch, c0 = (tn % g.tiles_per_batch) * GBN;
+        const int row_bytes = 3 * g.dm * 2;
+        c.rsA = make_rsrc(g.A[which] + (long)b * g.k * 3 * g.dm, (unsigned)g.k * (unsigned)row_bytes);
+        c.rsB = make_rsrc(g.B[which], (unsigned)(g.tiles_per_batch * GBN) * (unsigned)g.dm * 2u);
+        c.voffA = (m0 + (tid >> 3)) * row_bytes + 16 * (tid & 7);
+        c.a_qstride = 32 * row_bytes;
+        c.voffB = ((c0 + (tid >> 3)) * g.dm + 8 * (tid & 7)) * 2;
+        c.b_qstride = 32 * g.dm * 2;
+        c.steps_per_term = g.dm / GBK;
+        return c;
+    }
+    static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
+    static __device__ __forceinline__ int b_soff(const Ctx& c, int step) { return (step % c.steps_per_term) * (GBK * 2); }
 };
 
 // dX = E^T dX': rows = (head, t) of the (BH*D x kp) image of (dX')^T, columns = sequence positions,

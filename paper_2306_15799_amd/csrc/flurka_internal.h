@@ -123,7 +123,10 @@ enum Stage {
     STAGE_K_SUM_SPLITS = 19,
     STAGE_BWD_GRADS = 20,  // dK, dV, dE, dF together (MFMA path: one launch)
     STAGE_K_GRAD_PAIR = 21,
-    STAGE_COUNT = 22
+    STAGE_K_WIDE_GEMM = 22,        // paper-order path: Y = E X on the model-wide input
+    STAGE_K_WIDE_FINISH = 23,
+    STAGE_K_TRANSFORM_GEMM = 24,   // K' = Y W^K, V' = Y W^V
+    STAGE_COUNT = 25
 };
 // No-ops unless the timer is enabled.  begin/end pairs must not nest.
 void stage_begin(hipStream_t s);
@@ -160,6 +163,17 @@ bool fast_pointers_ok(const void* a, const void* b, const void* c, const void* d
 size_t fast_ws_bytes(const Problem& p, int bwd);
 flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
 flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s);
+// Paper-order forward: K' = (E X_K) W^K, V' = (F X_V) W^V from the model-wide inputs.
+struct FusedWArgs {
+    const void *Q, *XK, *XV, *E, *F, *WK, *WV, *omega;
+    void* out;
+    float* ctx;
+    float* ws;
+    int dm;
+};
+bool fast_fusedw_supported(const Problem& p, int dm);
+size_t fast_fusedw_ws_bytes(const Problem& p, int dm);
+flurka_status fast_forward_fusedw(const Problem& p, const FusedWArgs& a, hipStream_t s);
 // Key-side state from K', V' already in ctx: PhiK (scratch, BH*k*mf floats), S, z and the shifts c.
 flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, float* PhiK, hipStream_t s);
 

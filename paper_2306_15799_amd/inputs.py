@@ -134,6 +134,33 @@ def make_inputs(w: Workload, seed: int = 0) -> dict:
     return t
 
 
+def make_paper_order_inputs(w: Workload, dm: int, seed: int = 0) -> dict:
+    """Inputs of the forward in the paper's order (projection before the per-head transform).
+
+    As `make_inputs`, with K, V replaced by the model-wide layer inputs XK, XV (B, n, dm) ~ N(0, 1) and
+    the per-head transforms WK, WV (H, d, dm) ~ N(0, 1 / dm) * d^(-1/4), stored transposed, so that
+    X W has the scale K and V have in the other workloads.  Draw order: Q, XK, XV, E, F, omega, WK, WV.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    qkv_scale = float(w.d) ** -0.25
+    t = {}
+    t["Q"] = _normal(rng, (w.B, w.H, w.n, w.d), qkv_scale)
+    t["XK"] = _normal(rng, (w.B, w.n, dm), 1.0)
+    t["XV"] = _normal(rng, (w.B, w.n, dm), 1.0)
+    t["E"] = _normal(rng, (w.k, w.n), float(w.k) ** -0.5)
+    t["F"] = _normal(rng, (w.k, w.n), float(w.k) ** -0.5)
+    t["omega"] = _normal(rng, (w.H if w.omega_per_head else 1, w.m, w.d), 1.0) if w.phi == PHI_PERFORMER else None
+    t["WK"] = _normal(rng, (w.H, w.d, dm), qkv_scale * float(dm) ** -0.5)
+    t["WV"] = _normal(rng, (w.H, w.d, dm), qkv_scale * float(dm) ** -0.5)
+    if w.dtype == "bf16":
+        for key, val in t.items():
+            if val is not None:
+                t[key] = round_to_bf16(val)
+    elif w.dtype != "f32":
+        raise ValueError(f"unknown dtype {w.dtype!r}")
+    return t
+
+
 def shrink(w: Workload, **over) -> Workload:
     """A copy of `w` with some fields replaced (used for small parity cases)."""
     d = w.as_dict()

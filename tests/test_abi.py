@@ -27,7 +27,7 @@ def test_every_declared_entry_point_is_exported(lib):
     assert declared == set(fb.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.flurka_version() == 120
+    assert lib.flurka_version() == 130
 
 
 def test_status_strings(lib):
@@ -132,6 +132,31 @@ def test_static_scratch_entry_point_validates_like_the_forward(lib):
     # a workspace beyond the library's own array is refused before anything is launched
     assert fb.workspace_bytes(4, 12, 8192, 64, 256, 256, fb.BF16, "performer", fb.PASS_FWD, "generic") > fb.STATIC_WORKSPACE_BYTES
     assert call(B=4, H=12, n=8192, d=64, k=256, m=256, dtype=fb.BF16) == fb.ERR_WORKSPACE
+
+
+def test_paper_order_entry_point_validates_before_launching(lib):
+    def call(**over):
+        a = dict(Q=FAKE, XK=FAKE, XV=FAKE, E=FAKE, F=FAKE, WK=FAKE, WV=FAKE, omega=FAKE, out=FAKE, ctx=FAKE,
+                 ctx_bytes=1 << 40, ws=FAKE, ws_bytes=1 << 40, B=1, H=4, n=512, d=64, k=64, m=64, dm=256,
+                 per_head=1, dtype=fb.BF16, phi=fb.PHI_PERFORMER)
+        a.update(over)
+        return lib.flurka_attn_fwd_fused_w(a["Q"], a["XK"], a["XV"], a["E"], a["F"], a["WK"], a["WV"], a["omega"],
+                                           a["out"], a["ctx"], a["ctx_bytes"], a["ws"], a["ws_bytes"], a["B"],
+                                           a["H"], a["n"], a["d"], a["k"], a["m"], a["dm"], a["per_head"],
+                                           a["dtype"], a["phi"], None)
+    for name in ["Q", "XK", "XV", "E", "F", "WK", "WV", "omega", "out", "ctx", "ws"]:
+        assert call(**{name: None}) == fb.ERR_NULL, name
+    assert call(dm=0) == fb.ERR_SHAPE
+    assert call(n=0) == fb.ERR_SHAPE
+    assert call(dm=100) == fb.ERR_UNSUPPORTED              # not whole 64-deep reduction steps
+    assert call(H=3) == fb.ERR_UNSUPPORTED                 # H*d not a multiple of the 256-column tile
+    assert call(dtype=fb.F32) == fb.ERR_UNSUPPORTED
+    assert call(WK=FAKE + 2) == fb.ERR_UNSUPPORTED         # vector loads need 16-byte alignment
+    assert call(ws_bytes=1000) == fb.ERR_WORKSPACE
+    assert call(ctx_bytes=1000) == fb.ERR_WORKSPACE
+    assert lib.flurka_fused_w_supported(1, 4, 512, 64, 64, 64, 256, fb.BF16, 0) == 1
+    assert lib.flurka_fused_w_workspace_bytes(1, 4, 512, 64, 64, 64, 256, fb.BF16, 0) > 0
+    assert lib.flurka_fused_w_workspace_bytes(1, 3, 512, 64, 64, 64, 256, fb.BF16, 0) == 0
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -294,3 +294,68 @@ def test_rel_l2_metric():
     ref = np.array([3.0, 4.0])
     assert fo.rel_l2(ref, ref) == 0.0
     assert abs(fo.rel_l2(ref + np.array([0.3, 0.4]), ref) - 0.1) < 1e-15
+
+
+# --- the products in the order Eq. 2 prints them ------------------------------------------------
+def _paper_order_case(phi, seed=40, B=2, H=3, n=11, d=4, k=5, m=6, dm=7):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((B, H, n, d)) * 0.6
+    XK = rng.standard_normal((B, n, dm))
+    XV = rng.standard_normal((B, n, dm))
+    E = rng.standard_normal((k, n)) / np.sqrt(k)
+    F = rng.standard_normal((k, n)) / np.sqrt(k)
+    WK = rng.standard_normal((H, d, dm)) * 0.3
+    WV = rng.standard_normal((H, d, dm)) * 0.3
+    om = rng.standard_normal((H, m, d)) if phi == fo.PHI_PERFORMER else None
+    return Q, XK, XV, E, F, WK, WV, om
+
+
+@pytest.mark.parametrize("phi", [fo.PHI_PERFORMER, fo.PHI_ELU1])
+def test_paper_order_equals_transform_first(phi):
+    """(E X) W = E (X W): projecting the layer input first and transforming its k rows gives the same
+    attention as transforming all n positions first (the order the other entry point assumes)."""
+    Q, XK, XV, E, F, WK, WV, om = _paper_order_case(phi)
+    got = fo.flurka_attention_paper_order(Q, XK, XV, E, F, WK, WV, om, phi)
+    K = np.einsum("bnc,hdc->bhnd", XK, WK)
+    V = np.einsum("bnc,hdc->bhnd", XV, WV)
+    ref = fo.flurka_attention_definition(Q, K, V, E, F, om, phi)
+    assert np.max(np.abs(got - ref)) < 1e-12
+
+
+def test_paper_order_projected_keys_by_explicit_loops():
+    """K'[r, t] = sum_c (sum_i E[r, i] X[i, c]) W[t, c] with W stored (d, dm): a transposed transform, or
+    E applied on the wrong axis, changes the result."""
+    Q, XK, XV, E, F, WK, WV, om = _paper_order_case(fo.PHI_ELU1, B=1, H=2, n=6, d=3, k=4, dm=5)
+    k, n = E.shape
+    H, d, dm = WK.shape
+    out = np.empty_like(Q)
+    for h in range(H):
+        Kp = np.zeros((k, d)); Vp = np.zeros((k, d))
+        for r in range(k):
+            for t in range(d):
+                for c in range(dm):
+                    yk = sum(E[r, i] * XK[0, i, c] for i in range(n))
+                    yv = sum(F[r, i] * XV[0, i, c] for i in range(n))
+                    Kp[r, t] += yk * WK[h, t, c]
+                    Vp[r, t] += yv * WV[h, t, c]
+        PQ, PK = fo.phi_elu1(Q[0, h]), fo.phi_elu1(Kp)
+        A = PQ @ PK.T
+        out[0, h] = (A / A.sum(axis=1, keepdims=True)) @ Vp
+    got = fo.flurka_attention_paper_order(Q, XK, XV, E, F, WK, WV, None, fo.PHI_ELU1)
+    assert np.max(np.abs(got - out)) < 1e-12
+
+
+def test_paper_order_with_selector_transforms_is_plain_attention():
+    """W_h that picks d coordinates of the layer input: the paper-order forward is the plain forward on
+    those coordinates as per-head K, V."""
+    Q, XK, XV, E, F, _, _, om = _paper_order_case(fo.PHI_PERFORMER, H=2, d=3, dm=6)
+    H, d, dm = 2, 3, 6
+    W = np.zeros((H, d, dm))
+    for h in range(H):
+        for t in range(d):
+            W[h, t, h * d + t] = 1.0
+    got = fo.flurka_attention_paper_order(Q, XK, XV, E, F, W, W, om, fo.PHI_PERFORMER)
+    K = np.stack([XK[:, :, h * d:(h + 1) * d] for h in range(H)], axis=1)
+    V = np.stack([XV[:, :, h * d:(h + 1) * d] for h in range(H)], axis=1)
+    ref = fo.flurka_attention(Q, K, V, E, F, om, fo.PHI_PERFORMER)
+    assert np.max(np.abs(got - ref)) < 1e-12
