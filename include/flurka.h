@@ -205,6 +205,42 @@ FLURKA_API flurka_status flurka_attn_fwd_fused_w(const void* Q, const void* XK, 
                               void* stream);
 
 /*
+ * The method's two constituents as attention-level baselines, for the speed comparisons of Sec. 4.1
+ * ("Model speed") and Sec. 4.3 (ablations over d_k and d_m) on this hardware.  Forward only, bf16 MFMA
+ * kernels only (d = 64 or 128, n a multiple of 64); anything else returns FLURKA_ERR_UNSUPPORTED.
+ *
+ *   FLURKA_BASELINE_KERNEL_ATTN   kernel attention (Sec. 2, "Kernel Methods"):
+ *                                 out = phi(Q)(phi(K)^T V) / phi(Q)(phi(K)^T 1), i.e. the forward above
+ *                                 with E = F = I computed without any n x n product.  E, F and k are
+ *                                 ignored (pass NULL, anything); m a multiple of 32.
+ *   FLURKA_BASELINE_LINFORMER     low-rank attention (Sec. 2, "Low-rank Methods"):
+ *                                 out = softmax(Q (E K)^T) (F V), softmax over the k projected keys, no
+ *                                 temperature.  omega, m and phi are ignored.  The k projected keys and
+ *                                 values of a head are kept in LDS as bf16: k <= 512 at d = 64,
+ *                                 k <= 256 at d = 128 (rounded up to a multiple of 32).
+ *
+ * ctx (flurka_baseline_ctx_bytes) holds lse afterwards (and S, z, c resp. K', V'); workspace as
+ * flurka_baseline_workspace_bytes says.  Conventions as for flurka_attn_fwd.
+ */
+typedef enum { FLURKA_BASELINE_KERNEL_ATTN = 0, FLURKA_BASELINE_LINFORMER = 1 } flurka_baseline;
+FLURKA_API int flurka_baseline_supported(flurka_baseline which, int B, int H, int n, int d, int k, int m,
+                              flurka_dtype dtype, flurka_phi phi);
+FLURKA_API size_t flurka_baseline_ctx_bytes(flurka_baseline which, int B, int H, int n, int d, int k, int m,
+                                 flurka_dtype dtype, flurka_phi phi);
+FLURKA_API size_t flurka_baseline_workspace_bytes(flurka_baseline which, int B, int H, int n, int d, int k, int m,
+                                       flurka_dtype dtype, flurka_phi phi);
+FLURKA_API flurka_status flurka_baseline_fwd(flurka_baseline which,
+                              const void* Q, const void* K, const void* V,
+                              const void* E, const void* F, const void* omega,
+                              void* out,
+                              void* ctx, size_t ctx_bytes,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int H, int n, int d, int k, int m,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi,
+                              void* stream);
+
+/*
  * Backward of flurka_attn_fwd (chain rule; the paper trains through this
  * layer but prints no backward).  Given dOut = d loss / d out:
  *

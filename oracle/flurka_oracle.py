@@ -222,6 +222,40 @@ def flurka_attention_paper_order(Q, XK, XV, E, F, WK, WV, omega, phi):
 
 
 # --------------------------------------------------------------------------
+# the two constituents (comparison baselines)
+# --------------------------------------------------------------------------
+def kernel_attention(Q, K, V, omega, phi):
+    """Kernel attention of Sec. 2, "Kernel Methods": phi(Q) (phi(K)^T V), each row divided by
+    phi(Q) (phi(K)^T 1) -- the method without a sequence projection.  Q, K, V: (B, H, n, d)."""
+    Q = np.asarray(Q, np.float64)
+    B, H = Q.shape[:2]
+    out = np.empty_like(Q)
+    for b in range(B):
+        for h in range(H):
+            om = _head_omega(omega, h)
+            _, S, z, _ = key_state(K[b, h], V[b, h], om, phi)
+            P = query_features(Q[b, h], om, phi)
+            out[b, h] = (P @ S) / (P @ z)[:, None]
+    return out
+
+
+def linformer_attention(Q, K, V, E, F):
+    """Low-rank attention of Sec. 2, "Low-rank Methods": softmax(Q (E K)^T) (F V), the softmax taken
+    over the k projected keys, no temperature.  Q, K, V: (B, H, n, d); E, F: (k, n)."""
+    Q = np.asarray(Q, np.float64)
+    B, H = Q.shape[:2]
+    out = np.empty_like(Q)
+    for b in range(B):
+        for h in range(H):
+            Kp = sequence_projection(E, K[b, h])
+            Vp = sequence_projection(F, V[b, h])
+            s = Q[b, h] @ Kp.T
+            a = np.exp(s - s.max(axis=1, keepdims=True))
+            out[b, h] = (a / a.sum(axis=1, keepdims=True)) @ Vp
+    return out
+
+
+# --------------------------------------------------------------------------
 # backward (chain rule of the forward above)
 # --------------------------------------------------------------------------
 def flurka_head_bwd(Q, K, V, E, F, omega, G, phi):

@@ -31,6 +31,7 @@ EXPORTED_SYMBOLS = (
     "flurka_version", "flurka_status_str", "flurka_ctx_bytes", "flurka_ctx_layout", "flurka_workspace_bytes",
     "flurka_fast_path_supported", "flurka_attn_fwd", "flurka_attn_fwd_static", "flurka_attn_bwd",
     "flurka_fused_w_supported", "flurka_fused_w_workspace_bytes", "flurka_attn_fwd_fused_w",
+    "flurka_baseline_supported", "flurka_baseline_ctx_bytes", "flurka_baseline_workspace_bytes", "flurka_baseline_fwd",
     "flurka_profile_enable", "flurka_profile_read", "flurka_profile_stage_name",
 )
 
@@ -79,6 +80,15 @@ def load_library() -> ctypes.CDLL:
     lib.flurka_attn_fwd_fused_w.restype = c_int
     lib.flurka_attn_fwd_fused_w.argtypes = ([c_void] * 9 + [c_void, c_size, c_void, c_size]
                                             + [c_int] * 7 + [c_int] + [c_int] * 2 + [c_void])
+    lib.flurka_baseline_supported.restype = c_int
+    lib.flurka_baseline_supported.argtypes = [c_int] * 9
+    lib.flurka_baseline_ctx_bytes.restype = c_size
+    lib.flurka_baseline_ctx_bytes.argtypes = [c_int] * 9
+    lib.flurka_baseline_workspace_bytes.restype = c_size
+    lib.flurka_baseline_workspace_bytes.argtypes = [c_int] * 9
+    lib.flurka_baseline_fwd.restype = c_int
+    lib.flurka_baseline_fwd.argtypes = ([c_int] + [c_void] * 7 + [c_void, c_size, c_void, c_size]
+                                        + [c_int] * 6 + [c_int] + [c_int] * 2 + [c_void])
     lib.flurka_attn_bwd.restype = c_int
     lib.flurka_attn_bwd.argtypes = ([c_void] * 8 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
@@ -263,6 +273,54 @@ def flurka_attn_fwd_fused_w(Q, XK, XV, E, F, WK, WV, omega, phi="performer", out
                                      B, H, n, d, k, m, dm, per_head, code, _PHI[phi], s)
     if st != OK:
         raise FlurkaError(st, "flurka_attn_fwd_fused_w")
+    return out, ctx
+
+
+BASELINE_KERNEL_ATTN, BASELINE_LINFORMER = 0, 1
+
+
+def baseline_supported(which, B, H, n, d, k, m, dtype, phi) -> bool:
+    return bool(load_library().flurka_baseline_supported(which, B, H, n, d, k, m, dtype, _PHI[phi]))
+
+
+def flurka_baseline_fwd(which, Q, K, V, E=None, F=None, omega=None, phi="performer", out=None, ctx=None,
+                        workspace=None, stream=None):
+    """The paper's constituents at the attention level: BASELINE_KERNEL_ATTN (E, F unused) or
+    BASELINE_LINFORMER (omega unused; softmax over the projected keys).  Returns out, ctx."""
+    lib = load_library()
+    if Q.dim() != 4:
+        raise ValueError("Q must be (B,H,n,d)")
+    B, H, n, d = Q.shape
+    dt, dev = Q.dtype, Q.device
+    code = _dtype_code(Q)
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
+        _check(t, name, (B, H, n, d), dt, dev)
+    k, m, per_head = n, d, 0
+    if which == BASELINE_LINFORMER:
+        k = E.shape[0]
+        for t, name in ((E, "E"), (F, "F")):
+            _check(t, name, (k, n), dt, dev)
+        m, omega = 32, None
+    elif _PHI[phi] == PHI_PERFORMER:
+        m = omega.shape[1]
+        per_head = 1 if (omega.shape[0] == H and H > 1) else 0
+        _check(omega, "omega", (omega.shape[0], m, d), dt, dev)
+    else:
+        omega = None
+    if out is None:
+        out = torch.empty_like(Q)
+    _check(out, "out", (B, H, n, d), dt, dev)
+    if ctx is None:
+        ctx = alloc_buffer(lib.flurka_baseline_ctx_bytes(which, B, H, n, d, k, m, code, _PHI[phi]), dev)
+    if workspace is None:
+        workspace = alloc_buffer(lib.flurka_baseline_workspace_bytes(which, B, H, n, d, k, m, code, _PHI[phi]), dev)
+    s = stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    st = lib.flurka_baseline_fwd(which, _ptr(Q), _ptr(K), _ptr(V), _ptr(E), _ptr(F), _ptr(omega), _ptr(out),
+                                 _ptr(ctx), ctx.numel() * ctx.element_size(),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 B, H, n, d, k, m, per_head, code, _PHI[phi], s)
+    if st != OK:
+        raise FlurkaError(st, "flurka_baseline_fwd")
     return out, ctx
 
 

@@ -88,7 +88,7 @@ int chip_cus() {
 
 namespace {
 
-constexpr int kVersion = 130;
+constexpr int kVersion = 140;
 
 flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
                            int dtype, int phi, Problem* out) {
@@ -289,6 +289,62 @@ flurka_status flurka_attn_fwd_fused_w(const void* Q, const void* XK, const void*
     return st;
 }
 
+namespace {
+// Problem of a baseline call: kernel attention has every position as a key; Linformer has one "feature"
+// per key and no feature map of its own.
+flurka_status baseline_problem(int which, int B, int H, int n, int d, int k, int m, int omega_per_head, int dtype,
+                               int phi, Problem* p) {
+    if (which == FLURKA_BASELINE_KERNEL_ATTN) return make_problem(B, H, n, d, n, m, omega_per_head, dtype, phi, p);
+    if (which == FLURKA_BASELINE_LINFORMER) return make_problem(B, H, n, d, k, 32, 1, dtype, FLURKA_PHI_PERFORMER, p);
+    return FLURKA_ERR_DTYPE;
+}
+}  // namespace
+
+int flurka_baseline_supported(flurka_baseline which, int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
+                              flurka_phi phi) {
+    Problem p;
+    if (baseline_problem(which, B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    return fast_baseline_supported(which, p) ? 1 : 0;
+}
+
+size_t flurka_baseline_ctx_bytes(flurka_baseline which, int B, int H, int n, int d, int k, int m, flurka_dtype dtype,
+                                 flurka_phi phi) {
+    Problem p;
+    if (baseline_problem(which, B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    return fast_baseline_ctx_floats(which, p) * sizeof(float);
+}
+
+size_t flurka_baseline_workspace_bytes(flurka_baseline which, int B, int H, int n, int d, int k, int m,
+                                       flurka_dtype dtype, flurka_phi phi) {
+    Problem p;
+    if (baseline_problem(which, B, H, n, d, k, m, 1, dtype, phi, &p) != FLURKA_OK) return 0;
+    if (!fast_baseline_supported(which, p)) return 0;
+    return fast_baseline_ws_bytes(which, p);
+}
+
+flurka_status flurka_baseline_fwd(flurka_baseline which, const void* Q, const void* K, const void* V, const void* E,
+                                  const void* F, const void* omega, void* out, void* ctx, size_t ctx_bytes,
+                                  void* workspace, size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                                  int omega_per_head, flurka_dtype dtype, flurka_phi phi, void* stream) {
+    Problem p;
+    flurka_status st = baseline_problem(which, B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
+    if (st != FLURKA_OK) return st;
+    const bool lin = which == FLURKA_BASELINE_LINFORMER;
+    if (!Q || !K || !V || !out || !ctx || !workspace) return FLURKA_ERR_NULL;
+    if (lin && (!E || !F)) return FLURKA_ERR_NULL;
+    if (!lin && !p.elu && !omega) return FLURKA_ERR_NULL;
+    if (misaligned(ctx, 256) || misaligned(workspace, 256)) return FLURKA_ERR_ALIGN;
+    if (!fast_baseline_supported(which, p) ||
+        !fast_pointers_ok(Q, K, V, lin ? E : nullptr, lin ? F : nullptr, lin ? nullptr : omega, out))
+        return FLURKA_ERR_UNSUPPORTED;
+    if (ctx_bytes < fast_baseline_ctx_floats(which, p) * sizeof(float)) return FLURKA_ERR_WORKSPACE;
+    if (workspace_bytes < fast_baseline_ws_bytes(which, p)) return FLURKA_ERR_WORKSPACE;
+    FwdArgs a{Q, K, V, E, F, omega, out, (float*)ctx, (float*)workspace};
+    st = lin ? fast_linformer_forward(p, a, (hipStream_t)stream) : fast_kernel_attn_forward(p, a, (hipStream_t)stream);
+    if (st != FLURKA_OK) stage_abandon();
+    return st;
+}
+
 flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
                               const void* omega, const void* out, const void* dOut, const void* ctx,
                               size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
@@ -388,6 +444,8 @@ const char* flurka_profile_stage_name(int id) {
         case STAGE_K_WIDE_GEMM: return "project:gemm_mfma_wide";
         case STAGE_K_WIDE_FINISH: return "project:wide_finish";
         case STAGE_K_TRANSFORM_GEMM: return "project:gemm_mfma_transform";
+        case STAGE_K_IDENTITY_PACK: return "key_state:identity_pack";
+        case STAGE_K_LINFORMER_PACK: return "key_state:linformer_pack";
     }
     return "unknown";
 }

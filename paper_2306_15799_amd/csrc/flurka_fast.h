@@ -28,6 +28,15 @@ struct KeyStateBuffers {
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
                              int tilesM, int tilesN, int splits, const KeyStateBuffers& b, hipStream_t s);
 
+// Kernel attention without a sequence projection (p.k == p.n, K' = K, V' = V): packs the caller's bf16
+// K, V into the key-state operand images and fills S, z, c in ctx and the St/zp/cw images.
+flurka_status fast_identity_key_state(const Problem& p, const void* K, const void* V, const void* omega, float* S,
+                                      float* z, float* c, const KeyStateBuffers& b, hipStream_t s);
+// The projection's second stage alone: sums the split partials into K', V' (ctx) and, with `images`,
+// writes the key-state operand images.
+flurka_status fast_proj_finish(const Problem& p, float* ctx, const float* partials, int tilesM, int tilesN,
+                               int splits, bool images, const KeyStateBuffers& b, hipStream_t s);
+
 // Grid of a kernel whose workgroups split `items` evenly among themselves: as many workgroups as the
 // device keeps resident at once for this block size and LDS use (one round, no tail), at most `items`.
 // Returns 0 if the runtime cannot place the kernel.

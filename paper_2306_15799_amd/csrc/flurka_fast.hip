@@ -78,6 +78,11 @@ struct QueryLds {
     }
 };
 
+// Slot of feature f (0..31) inside a 32-feature tile of the S'^T image: the order in which the first
+// contraction's accumulator hands P'^T on as the B operand of the second (slot 8h + e of a group of 16
+// holds feature 8*(e/4) + 4*h + e%4; the map is its own inverse).
+__host__ __device__ inline int slot_of_feature_tile(int f) { return (f & 16) + 8 * ((f >> 2) & 1) + 4 * ((f >> 3) & 1) + (f & 3); }
+
 // One workgroup = NW wavefronts sharing the LDS image of omega, S^T and z of one head; each wavefront
 // streams QT tiles of 32 query rows at a time.  (QT = 2 would feed two MFMAs per operand fragment read
 // from LDS, but needs more than the 256 architectural VGPRs of a wavefront; the register allocator then
@@ -355,9 +360,8 @@ static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int lds
 }
 
 // Query stream over the St / zp / cw images the key-state stage left in the workspace.
-static flurka_status run_query_stream(const Problem& p, const void* Q, const void* omega, void* out, float* ctx,
+static flurka_status run_query_stream(const Problem& p, const void* Q, const void* omega, void* out, float* lse,
                                       const uint16_t* St, const float* zp, const uint16_t* cw, hipStream_t s) {
-    const CtxLayout L = ctx_layout(p);
     StageScope sc(s, STAGE_K_QUERY_STREAM);
     QueryArgs qa{};
     qa.Q = (const uint16_t*)Q;
@@ -366,7 +370,7 @@ static flurka_status run_query_stream(const Problem& p, const void* Q, const voi
     qa.zp = zp;
     qa.cw = cw;
     qa.out = (uint16_t*)out;
-    qa.lse = ctx + L.lse;
+    qa.lse = lse;
     qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
     qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
     qa.tiles_per_head = (p.n + 32 * QS_QT - 1) / (32 * QS_QT);
@@ -405,8 +409,8 @@ flurka_status fast_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
         st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN, proj_splits, kb, s);
         if (st != FLURKA_OK) return st;
     }
-    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx, (const uint16_t*)(wsb + W.St), (const float*)(wsb + W.zp),
-                            (const uint16_t*)(wsb + W.cw), s);
+    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx + ctx_layout(p).lse, (const uint16_t*)(wsb + W.St),
+                            (const float*)(wsb + W.zp), (const uint16_t*)(wsb + W.cw), s);
 }
 
 // ===========================================================================
@@ -562,6 +566,144 @@ flurka_status fast_forward_fusedw(const Problem& p, const FusedWArgs& a, hipStre
     kb.St = (uint16_t*)(rest + R.St); kb.zp = (float*)(rest + R.zp); kb.cw = (uint16_t*)(rest + R.cw);
     st = fast_key_state(p, a.omega, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN2, q.s2.splits, kb, s);
     if (st != FLURKA_OK) return st;
-    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx, kb.St, kb.zp, kb.cw, s);
+    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx + ctx_layout(p).lse, kb.St, kb.zp, kb.cw, s);
 }
+
+// ===========================================================================
+// Comparison baselines at the attention level (the paper's constituents, Sec. 2): kernel attention
+// without a sequence projection, and Linformer's softmax over the k projected keys.  Both reuse the
+// kernels above; they exist so that the speed comparisons of Sec. 4.1 / 4.3 can be run on this hardware.
+// ===========================================================================
+// Kernel attention phi(Q)(phi(K)^T V) / phi(Q)(phi(K)^T 1): FLuRKA with E = F = I, computed without the
+// n x n product.  `p` has k == n.  ctx: S, z, c, lse at the offsets of the same problem with k = 1.
+static Problem ctx_problem_kernel_attn(const Problem& p) { Problem q = p; q.k = 1; return q; }
+
+struct KernelAttnWs { size_t Kimg, Vimg, nrm, St, zp, cw, total; };
+static KernelAttnWs kernel_attn_ws_layout(const Problem& p) {
+    KernelAttnWs W{};
+    const size_t BH = (size_t)p.BH;
+    size_t o = 0;
+    W.Kimg = o; o += round_up(p.elu ? 0 : BH * p.n * p.d * 2, 256);
+    W.Vimg = o; o += round_up(BH * (p.n / 2) * p.d * 4, 256);
+    W.nrm = o;  o += round_up(BH * p.n * 4, 256);
+    W.St = o;   o += round_up(BH * p.d * p.mf * 2, 256);
+    W.zp = o;   o += round_up(BH * p.mf * 4, 256);
+    W.cw = o;   o += round_up(BH * p.mf * 8, 256);
+    W.total = o;
+    return W;
+}
+
+// Linformer: softmax(Q K'^T) V' over the k projected keys.  With omega := K' (one "feature" per key, rounded
+// to bf16), S' := V' and zero shifts the query stream computes exactly that: u = K' q, running row maximum,
+// exp, P V' / sum P.  linformer_pack writes those images from K', V' in ctx; keys past k (k is padded to
+// whole 32-key tiles) get the shift -inf, i.e. weight 0.
+__global__ void linformer_pack_kernel(const float* Kp, const float* Vp, uint16_t* Wimg, uint16_t* St, uint16_t* cw,
+                                      int k, int kpad, int d, long total) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;        // (bh, r < kpad, t)
+    if (idx >= total) return;
+    const int t = (int)(idx % d);
+    const long rest = idx / d;
+    const int r = (int)(rest % kpad);
+    const long bh = rest / kpad;
+    const bool live = r < k;
+    const float kv = live ? Kp[(bh * k + r) * d + t] : 0.f;
+    const float vv = live ? Vp[(bh * k + r) * d + t] : 0.f;
+    Wimg[(bh * kpad + r) * d + t] = f32_to_bf16(kv);
+    St[(bh * d + t) * kpad + (r & ~31) + slot_of_feature_tile(r & 31)] = f32_to_bf16(vv);
+    if (t < 4) cw[(bh * kpad + r) * 4 + t] = (t == 0 && !live) ? (uint16_t)0xff80u : (uint16_t)0;
+}
+
+static Problem query_problem_linformer(const Problem& p) {
+    Problem q = p;
+    q.m = q.mf = (p.k + 31) / 32 * 32;     // one feature per projected key
+    q.H = p.BH; q.B = 1;                   // every (batch, head) has its own K'
+    q.omega_per_head = 1;
+    q.elu = 0;
+    return q;
+}
+
+struct LinformerWs { size_t partial, Wimg, St, zp, cw, total; };
+static LinformerWs linformer_ws_layout(const Problem& p) {
+    LinformerWs W{};
+    const ProjPlan q = proj_plan(p);
+    const size_t BH = (size_t)p.BH, kpad = (size_t)(p.k + 31) / 32 * 32;
+    size_t o = 0;
+    W.partial = o; o += round_up((size_t)2 * q.splits * q.tilesM * q.tilesN * G_TILE_ELEMS * 4, 256);
+    W.Wimg = o;    o += round_up(BH * kpad * p.d * 2, 256);
+    W.St = o;      o += round_up(BH * p.d * kpad * 2, 256);
+    W.zp = o;      o += round_up(BH * kpad * 4, 256);
+    W.cw = o;      o += round_up(BH * kpad * 8, 256);
+    W.total = o;
+    return W;
+}
+
+bool fast_baseline_supported(int which, const Problem& p) {
+    if (!p.bf16 || (p.d != 64 && p.d != 128) || p.n % PBK != 0) return false;
+    if (which == FLURKA_BASELINE_KERNEL_ATTN) {
+        if (p.k != p.n || p.mf % 32 != 0) return false;
+        if (query_lds_bytes(p) > 160 * 1024) return false;
+        return (size_t)p.BH * p.n * p.d * 2 < ((size_t)1 << 40);
+    }
+    if (which == FLURKA_BASELINE_LINFORMER) {
+        if (p.elu) return false;
+        if (!fast_supported(p, 0)) return false;                       // the projection's limits
+        return query_lds_bytes(query_problem_linformer(p)) <= 160 * 1024;   // K', V' of a head in LDS
+    }
+    return false;
+}
+
+size_t fast_baseline_ws_bytes(int which, const Problem& p) {
+    return which == FLURKA_BASELINE_KERNEL_ATTN ? kernel_attn_ws_layout(p).total : linformer_ws_layout(p).total;
+}
+
+size_t fast_baseline_ctx_floats(int which, const Problem& p) {
+    return which == FLURKA_BASELINE_KERNEL_ATTN ? ctx_layout(ctx_problem_kernel_attn(p)).total : ctx_layout(p).total;
+}
+
+flurka_status fast_kernel_attn_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
+    const KernelAttnWs W = kernel_attn_ws_layout(p);
+    const CtxLayout L = ctx_layout(ctx_problem_kernel_attn(p));
+    unsigned char* wsb = (unsigned char*)a.ws;
+    KeyStateBuffers kb{};
+    kb.Kimg = (uint16_t*)(wsb + W.Kimg); kb.Vimg = (uint32_t*)(wsb + W.Vimg); kb.nrm = (float*)(wsb + W.nrm);
+    kb.St = (uint16_t*)(wsb + W.St); kb.zp = (float*)(wsb + W.zp); kb.cw = (uint16_t*)(wsb + W.cw);
+    const flurka_status st = fast_identity_key_state(p, a.K, a.V, a.omega, a.ctx + L.S, a.ctx + L.z, a.ctx + L.c, kb, s);
+    if (st != FLURKA_OK) return st;
+    return run_query_stream(p, a.Q, a.omega, a.out, a.ctx + L.lse, kb.St, kb.zp, kb.cw, s);
+}
+
+flurka_status fast_linformer_forward(const Problem& p, const FwdArgs& a, hipStream_t s) {
+    const LinformerWs W = linformer_ws_layout(p);
+    const CtxLayout L = ctx_layout(p);
+    const ProjPlan q = proj_plan(p);
+    unsigned char* wsb = (unsigned char*)a.ws;
+    flurka_status st;
+    {
+        StageScope sc(s, STAGE_K_PROJ_GEMM);
+        GemmParams gp{};
+        gp.A[0] = (const uint16_t*)a.E; gp.A[1] = (const uint16_t*)a.F;
+        gp.B[0] = (const uint16_t*)a.K; gp.B[1] = (const uint16_t*)a.V;
+        gp.C[0] = wsb + W.partial;
+        gp.n = p.n; gp.d = p.d; gp.k = p.k; gp.BH = p.BH; gp.kp = p.k;
+        gp.tilesM = q.tilesM; gp.tilesN = q.tilesN; gp.splits = q.splits;
+        gp.steps_per_split = q.steps_per_split; gp.total_steps = q.total_steps;
+        st = p.d == 64 ? launch_gemm_mfma<ProjPolicy<64>>(gp, s) : launch_gemm_mfma<ProjPolicy<128>>(gp, s);
+        if (st != FLURKA_OK) return st;
+    }
+    KeyStateBuffers none{};
+    if ((st = fast_proj_finish(p, a.ctx, (const float*)(wsb + W.partial), q.tilesM, q.tilesN, q.splits, false, none, s)) != FLURKA_OK)
+        return st;
+    const Problem pq = query_problem_linformer(p);
+    {
+        StageScope sc(s, STAGE_K_LINFORMER_PACK);
+        const long total = (long)p.BH * pq.mf * p.d;
+        hipLaunchKernelGGL(linformer_pack_kernel, grid1d(total, 256), dim3(256), 0, s, (const float*)(a.ctx + L.Kp),
+                           (const float*)(a.ctx + L.Vp), (uint16_t*)(wsb + W.Wimg), (uint16_t*)(wsb + W.St),
+                           (uint16_t*)(wsb + W.cw), p.k, pq.mf, p.d, total);
+        FLURKA_CHECK_LAUNCH();
+    }
+    return run_query_stream(pq, a.Q, wsb + W.Wimg, a.out, a.ctx + L.lse, (const uint16_t*)(wsb + W.St),
+                            (const float*)(wsb + W.zp), (const uint16_t*)(wsb + W.cw), s);
+}
+
 }  // namespace flurka

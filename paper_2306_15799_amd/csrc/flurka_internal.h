@@ -126,7 +126,9 @@ enum Stage {
     STAGE_K_WIDE_GEMM = 22,        // paper-order path: Y = E X on the model-wide input
     STAGE_K_WIDE_FINISH = 23,
     STAGE_K_TRANSFORM_GEMM = 24,   // K' = Y W^K, V' = Y W^V
-    STAGE_COUNT = 25
+    STAGE_K_IDENTITY_PACK = 25,    // baselines: operand images of K, V without a projection
+    STAGE_K_LINFORMER_PACK = 26,   // baselines: K', V' as the query stream's images
+    STAGE_COUNT = 27
 };
 // No-ops unless the timer is enabled.  begin/end pairs must not nest.
 void stage_begin(hipStream_t s);
@@ -174,6 +176,12 @@ struct FusedWArgs {
 bool fast_fusedw_supported(const Problem& p, int dm);
 size_t fast_fusedw_ws_bytes(const Problem& p, int dm);
 flurka_status fast_forward_fusedw(const Problem& p, const FusedWArgs& a, hipStream_t s);
+// Comparison baselines (flurka_baseline_* entry points); `which` is a flurka_baseline value.
+bool fast_baseline_supported(int which, const Problem& p);
+size_t fast_baseline_ws_bytes(int which, const Problem& p);
+size_t fast_baseline_ctx_floats(int which, const Problem& p);
+flurka_status fast_kernel_attn_forward(const Problem& p, const FwdArgs& a, hipStream_t s);   // p.k == p.n
+flurka_status fast_linformer_forward(const Problem& p, const FwdArgs& a, hipStream_t s);
 // Key-side state from K', V' already in ctx: PhiK (scratch, BH*k*mf floats), S, z and the shifts c.
 flurka_status generic_key_state(const Problem& p, const void* omega, float* ctx, float* PhiK, hipStream_t s);
 

@@ -45,7 +45,7 @@ struct FinishArgs {
     float* ctx;             // K' at ctx + Kp_off, V' at ctx + Vp_off
     long Kp_off, Vp_off;
     uint16_t* Kimg;         // 3 x (BH, kpad * d) bf16: hi, mid, lo, in key_state's operand order (nullptr for elu1)
-    uint32_t* Vimg;         // 2 x (BH, kpad/2, d) dwords: hi, lo; low half = even key
+    uint32_t* Vimg;         // 2 x (BH, kpad/2, d) dwords: hi, lo; low half = even key (nullptr: K', V' only)
     float* nrm;             // (BH, kpad): |k'|^2/2, +inf for the padding keys (nullptr for elu1)
     int splits, tilesM, tilesN, k, kpad, d, BH;
 };
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void proj_finish_kernel(FinishArgs a) {
             }
         }
 #pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
+        for (int pr = 0; pr < 2 && a.Vimg; ++pr) {
             uint32_t hp, lp;
             split2_pair(vv[2 * pr], vv[2 * pr + 1], hp, lp);
             const long vo = ((long)bh * (a.kpad / 2) + r0 / 2 + pr) * a.d + t;
@@ -120,6 +120,7 @@ __global__ __launch_bounds__(256) void proj_finish_kernel(FinishArgs a) {
 struct KeyStateArgs {
     const uint16_t* Kimg;   // performer
     const float* Kp;        // elu1: K' fp32 (BH, k, d)
+    const uint16_t* Kb;     // elu1, EXACT: the keys themselves, bf16 (BH, k, d)
     const uint32_t* Vimg;
     const float* nrm;
     const uint16_t* omega;
@@ -145,7 +146,9 @@ template <int D> struct KeyStateKeep { static constexpr int value = D <= 64 ? 4 
 // most wavefronts (key ranges) per workgroup: what the kernel's register need leaves room for
 template <int D> struct KeyStateMaxWaves { static constexpr int value = 8; };
 
-template <int D, bool ELU>
+// EXACT: the keys and values are bf16 numbers to begin with (kernel attention without a sequence
+// projection): one term of K and one of V carry everything, the other operand terms are skipped.
+template <int D, bool ELU, bool EXACT>
 __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_kernel(KeyStateArgs a) {
     constexpr int KS = D / 16, TT = D / 32;
     extern __shared__ __attribute__((aligned(16))) float ks_lds[];
@@ -179,8 +182,10 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 e = mfma32(ld16(kg + 512 * s), wf[s], e);
-                e = mfma32(ld16(kg + plane + 512 * s), wf[s], e);
-                e = mfma32(ld16(kg + 2 * plane + 512 * s), wf[s], e);
+                if constexpr (!EXACT) {
+                    e = mfma32(ld16(kg + plane + 512 * s), wf[s], e);
+                    e = mfma32(ld16(kg + 2 * plane + 512 * s), wf[s], e);
+                }
             }
             const float* ng = a.nrm + (long)bh * a.kpad + 32 * kt + 4 * half;
 #pragma unroll
@@ -194,7 +199,8 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
                 const int r = 32 * kt + 8 * (g >> 2) + 4 * half + (g & 3);
                 float v = 0.f;                                    // padding keys contribute nothing
                 if (r < a.k) {
-                    const float x = a.Kp[((long)bh * a.k + r) * D + 32 * ft + l32];
+                    const long idx = ((long)bh * a.k + r) * D + 32 * ft + l32;
+                    const float x = EXACT ? bf16_to_f32(a.Kb[idx]) : a.Kp[idx];
                     v = x > 0.f ? x + 1.f : __expf(x);
                 }
                 e[g] = v;
@@ -214,10 +220,16 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
             const uint32_t* vb = vimg + (long)(16 * kt + 8 * sp + 2 * half) * D + l32;
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                f.h[sp][tt].x = vb[32 * tt];           f.l[sp][tt].x = vb[vplane + 32 * tt];
-                f.h[sp][tt].y = vb[32 * tt + D];       f.l[sp][tt].y = vb[vplane + 32 * tt + D];
-                f.h[sp][tt].z = vb[32 * tt + 4 * D];   f.l[sp][tt].z = vb[vplane + 32 * tt + 4 * D];
-                f.h[sp][tt].w = vb[32 * tt + 5 * D];   f.l[sp][tt].w = vb[vplane + 32 * tt + 5 * D];
+                f.h[sp][tt].x = vb[32 * tt];
+                f.h[sp][tt].y = vb[32 * tt + D];
+                f.h[sp][tt].z = vb[32 * tt + 4 * D];
+                f.h[sp][tt].w = vb[32 * tt + 5 * D];
+                if constexpr (!EXACT) {
+                    f.l[sp][tt].x = vb[vplane + 32 * tt];
+                    f.l[sp][tt].y = vb[vplane + 32 * tt + D];
+                    f.l[sp][tt].z = vb[vplane + 32 * tt + 4 * D];
+                    f.l[sp][tt].w = vb[vplane + 32 * tt + 5 * D];
+                }
             }
         }
     };
@@ -282,7 +294,7 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
             for (int tt = 0; tt < TT; ++tt) {
                 accS[tt] = mfma32(ah[sp], f.h[sp][tt], accS[tt]);
                 accS[tt] = mfma32(al[sp], f.h[sp][tt], accS[tt]);
-                accS[tt] = mfma32(ah[sp], f.l[sp][tt], accS[tt]);
+                if constexpr (!EXACT) accS[tt] = mfma32(ah[sp], f.l[sp][tt], accS[tt]);
             }
     };
     {
@@ -418,9 +430,9 @@ KeyStatePlan key_state_plan(const Problem& p) {
     return q;
 }
 
-template <int D, bool ELU>
+template <int D, bool ELU, bool EXACT>
 static flurka_status launch_key_state_impl(const Problem& p, const KeyStateArgs& ka, hipStream_t s) {
-    auto kern = key_state_kernel<D, ELU>;
+    auto kern = key_state_kernel<D, ELU, EXACT>;
     const int ldsb = KeyStateLds<D>::total(ka.KR);
     KernelFacts facts;
     if (!kernel_facts((const void*)kern, ka.KR * 64, ldsb, &facts)) return FLURKA_ERR_LAUNCH;
@@ -430,8 +442,26 @@ static flurka_status launch_key_state_impl(const Problem& p, const KeyStateArgs&
 }
 
 template <int D>
-static flurka_status launch_key_state(const Problem& p, const KeyStateArgs& ka, hipStream_t s) {
-    return p.elu ? launch_key_state_impl<D, true>(p, ka, s) : launch_key_state_impl<D, false>(p, ka, s);
+static flurka_status launch_key_state(const Problem& p, const KeyStateArgs& ka, bool exact, hipStream_t s) {
+    if (exact) return p.elu ? launch_key_state_impl<D, true, true>(p, ka, s) : launch_key_state_impl<D, false, true>(p, ka, s);
+    return p.elu ? launch_key_state_impl<D, true, false>(p, ka, s) : launch_key_state_impl<D, false, false>(p, ka, s);
+}
+
+flurka_status fast_proj_finish(const Problem& p, float* ctx, const float* partials, int tilesM, int tilesN,
+                               int splits, bool images, const KeyStateBuffers& b, hipStream_t s) {
+    const CtxLayout L = ctx_layout(p);
+    const KeyStatePlan q = key_state_plan(p);
+    StageScope sc(s, STAGE_K_PROJ_FINISH);
+    FinishArgs fa{};
+    fa.part = partials; fa.ctx = ctx; fa.tilesM = tilesM; fa.tilesN = tilesN;
+    fa.Kp_off = (long)L.Kp; fa.Vp_off = (long)L.Vp;
+    fa.Kimg = (p.elu || !images) ? nullptr : b.Kimg; fa.Vimg = images ? b.Vimg : nullptr;
+    fa.nrm = (p.elu || !images) ? nullptr : b.nrm;
+    fa.splits = splits; fa.k = p.k; fa.kpad = q.kpad; fa.d = p.d; fa.BH = p.BH;
+    const long waves = (long)p.BH * (q.kpad / 4);
+    hipLaunchKernelGGL(proj_finish_kernel, grid1d(waves, 4), dim3(256), 0, s, fa);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
 }
 
 flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, const float* partials,
@@ -439,15 +469,8 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
     const CtxLayout L = ctx_layout(p);
     const KeyStatePlan q = key_state_plan(p);
     {
-        StageScope sc(s, STAGE_K_PROJ_FINISH);
-        FinishArgs fa{};
-        fa.part = partials; fa.ctx = ctx; fa.tilesM = tilesM; fa.tilesN = tilesN;
-        fa.Kp_off = (long)L.Kp; fa.Vp_off = (long)L.Vp;
-        fa.Kimg = p.elu ? nullptr : b.Kimg; fa.Vimg = b.Vimg; fa.nrm = p.elu ? nullptr : b.nrm;
-        fa.splits = splits; fa.k = p.k; fa.kpad = q.kpad; fa.d = p.d; fa.BH = p.BH;
-        const long waves = (long)p.BH * (q.kpad / 4);
-        hipLaunchKernelGGL(proj_finish_kernel, grid1d(waves, 4), dim3(256), 0, s, fa);
-        FLURKA_CHECK_LAUNCH();
+        const flurka_status st = fast_proj_finish(p, ctx, partials, tilesM, tilesN, splits, true, b, s);
+        if (st != FLURKA_OK) return st;
     }
     {
         StageScope sc(s, STAGE_K_KEY_STATE);
@@ -459,10 +482,76 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         ka.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
         ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf;
         ka.FT = q.FT; ka.KR = q.KR; ka.tiles_per_range = q.tiles_per_range;
-        flurka_status st = p.d == 64 ? launch_key_state<64>(p, ka, s) : launch_key_state<128>(p, ka, s);
+        flurka_status st = p.d == 64 ? launch_key_state<64>(p, ka, false, s) : launch_key_state<128>(p, ka, false, s);
         if (st != FLURKA_OK) return st;
     }
     return FLURKA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Kernel attention without a sequence projection (K' = K, V' = V): the keys and values are the caller's
+// bf16 tensors.  identity_pack writes what key_state reads -- K in its operand order (one term), V with
+// two consecutive keys per dword (one term), |k|^2 / 2 -- one wavefront per four keys, lane = coordinate.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void identity_pack_kernel(const uint16_t* K, const uint16_t* V, uint16_t* Kimg,
+                                                            uint32_t* Vimg, float* nrm, int n, int d, int BH) {
+    const int lane = threadIdx.x & 63;
+    const long wid = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int groups_per_head = n / 4;
+    if (wid >= (long)BH * groups_per_head) return;
+    const int bh = (int)(wid / groups_per_head);
+    const int r0 = 4 * (int)(wid % groups_per_head);
+    float sq[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int t = lane; t < d; t += 64) {
+        uint16_t kv[4], vv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const long off = ((long)bh * n + r0 + e) * d + t;
+            kv[e] = K[off];
+            vv[e] = V[off];
+            const float x = bf16_to_f32(kv[e]);
+            sq[e] = fmaf(x, x, sq[e]);
+            const int r = r0 + e;
+            if (Kimg) {
+                const long io = (long)bh * n * d +
+                                ((((long)(r >> 5) * (d / 16) + (t >> 4)) * 2 + ((t >> 3) & 1)) * 32 + (r & 31)) * 8 + (t & 7);
+                Kimg[io] = kv[e];
+            }
+        }
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr)
+            Vimg[((long)bh * (n / 2) + r0 / 2 + pr) * d + t] = (uint32_t)vv[2 * pr] | ((uint32_t)vv[2 * pr + 1] << 16);
+    }
+    if (nrm) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float tot = wave_sum(sq[e]);
+            if (lane == 0) nrm[(long)bh * n + r0 + e] = 0.5f * tot;
+        }
+    }
+}
+
+// p.k == p.n here: every position is a key.  Fills S, z, c in ctx and the St/zp/cw images.
+flurka_status fast_identity_key_state(const Problem& p, const void* K, const void* V, const void* omega, float* S,
+                                      float* z, float* c, const KeyStateBuffers& b, hipStream_t s) {
+    const KeyStatePlan q = key_state_plan(p);
+    {
+        StageScope sc(s, STAGE_K_IDENTITY_PACK);
+        const long waves = (long)p.BH * (p.n / 4);
+        hipLaunchKernelGGL(identity_pack_kernel, grid1d(waves, 4), dim3(256), 0, s, (const uint16_t*)K, (const uint16_t*)V,
+                           p.elu ? (uint16_t*)nullptr : b.Kimg, b.Vimg, p.elu ? (float*)nullptr : b.nrm, p.n, p.d, p.BH);
+        FLURKA_CHECK_LAUNCH();
+    }
+    StageScope sc(s, STAGE_K_KEY_STATE);
+    KeyStateArgs ka{};
+    ka.Kimg = b.Kimg; ka.Kp = nullptr; ka.Kb = (const uint16_t*)K; ka.Vimg = b.Vimg; ka.nrm = b.nrm;
+    ka.omega = (const uint16_t*)omega;
+    ka.S = S; ka.z = z; ka.c = c;
+    ka.St = b.St; ka.zp = b.zp; ka.cw = b.cw;
+    ka.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
+    ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf;
+    ka.FT = q.FT; ka.KR = q.KR; ka.tiles_per_range = q.tiles_per_range;
+    return p.d == 64 ? launch_key_state<64>(p, ka, true, s) : launch_key_state<128>(p, ka, true, s);
 }
 
 }  // namespace flurka

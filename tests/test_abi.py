@@ -27,7 +27,7 @@ def test_every_declared_entry_point_is_exported(lib):
     assert declared == set(fb.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.flurka_version() == 130
+    assert lib.flurka_version() == 140
 
 
 def test_status_strings(lib):

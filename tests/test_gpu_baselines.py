@@ -1,0 +1,64 @@
+"""GPU parity of the two attention-level baselines (flurka_baseline_fwd) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flurka_oracle as fo
+from paper_2306_15799_amd import binding as fb
+from paper_2306_15799_amd import inputs
+from paper_2306_15799_amd.inputs import Workload, PHI_ELU1, PHI_PERFORMER
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("shape,phi", [((1, 3, 192, 64, 96), PHI_PERFORMER), ((2, 2, 4096, 64, 256), PHI_PERFORMER),
+                                       ((1, 2, 2048, 128, 160), PHI_PERFORMER), ((2, 3, 1024, 64, 64), PHI_ELU1),
+                                       ((1, 2, 1088, 128, 128), PHI_ELU1)])
+def test_kernel_attention(shape, phi):
+    """Every position is a key: key ranges of hundreds of tiles per wavefront (evaluated twice: maximum,
+    then accumulation), operands exact in one bf16 term."""
+    B, H, n, d, m = shape
+    w = Workload("kattn", B, H, n, d, 8, m, "bf16", phi, False)
+    t = inputs.make_inputs(w, 60)
+    g = gu.to_device(t, "bf16")
+    assert fb.baseline_supported(fb.BASELINE_KERNEL_ATTN, B, H, n, d, n, m, fb.BF16, phi)
+    out, _ = fb.flurka_baseline_fwd(fb.BASELINE_KERNEL_ATTN, g["Q"], g["K"], g["V"], omega=g["omega"], phi=phi)
+    torch.cuda.synchronize()
+    ref = fo.kernel_attention(t["Q"], t["K"], t["V"], t["omega"], phi)
+    err = fo.rel_l2(gu.to_host(out), ref)
+    wb = gu.worst_block(gu.to_host(out), ref, 32, -2)
+    print(shape, phi, f"rel-L2 {err:.3e} worst block {wb:.3e}")
+    assert err <= gu.TOL["bf16"] and wb <= gu.BLOCK_FACTOR * gu.TOL["bf16"]
+
+
+# The projected keys enter the scores rounded to bf16 (they are the query stream's "omega"): with
+# |k'|^2 in the hundreds that alone moves a score by a few hundredths, i.e. a weight by a few percent.
+# The baseline exists for timing; its bar is the looser 5e-2 and the scores are kept moderate here.
+LINFORMER_TOL = 5e-2
+
+
+@pytest.mark.parametrize("shape", [(1, 3, 192, 64, 100), (2, 2, 2048, 64, 256), (1, 2, 4096, 64, 512),
+                                   (1, 2, 1024, 128, 256), (2, 2, 640, 128, 40)])
+def test_linformer(shape):
+    B, H, n, d, k = shape
+    w = Workload("linf", B, H, n, d, k, 32, "bf16", PHI_PERFORMER, False)
+    t = inputs.make_inputs(w, 61)
+    t["Q"] = inputs.round_to_bf16(t["Q"] * 0.5)
+    g = gu.to_device(t, "bf16")
+    assert fb.baseline_supported(fb.BASELINE_LINFORMER, B, H, n, d, k, 32, fb.BF16, PHI_PERFORMER)
+    out, ctx = fb.flurka_baseline_fwd(fb.BASELINE_LINFORMER, g["Q"], g["K"], g["V"], E=g["E"], F=g["F"])
+    torch.cuda.synchronize()
+    ref = fo.linformer_attention(t["Q"], t["K"], t["V"], t["E"], t["F"])
+    err = fo.rel_l2(gu.to_host(out), ref)
+    print(shape, f"rel-L2 {err:.3e}")
+    assert err <= LINFORMER_TOL
+    assert torch.isfinite(out.float()).all()
+
+
+def test_limits_are_refused():
+    # more projected keys than LDS holds; fp32 storage; sequence not a multiple of 64
+    assert not fb.baseline_supported(fb.BASELINE_LINFORMER, 1, 1, 4096, 128, 512, 32, fb.BF16, PHI_PERFORMER)
+    assert not fb.baseline_supported(fb.BASELINE_LINFORMER, 1, 1, 4096, 64, 256, 32, fb.F32, PHI_PERFORMER)
+    assert not fb.baseline_supported(fb.BASELINE_KERNEL_ATTN, 1, 1, 100, 64, 100, 32, fb.BF16, PHI_PERFORMER)

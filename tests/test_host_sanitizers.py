@@ -17,7 +17,12 @@ def test_host_side_is_clean_under_asan_and_ubsan():
     # the HIP runtime keeps process-lifetime allocations: leak reports at exit are not this library's
     env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=0"
     env["UBSAN_OPTIONS"] = "halt_on_error=1:print_stacktrace=1"
-    res = subprocess.run([driver], capture_output=True, text=True, env=env, timeout=300)
+    try:
+        res = subprocess.run([driver], capture_output=True, text=True, env=env, timeout=300)
+    finally:
+        for f in (lib, driver):          # 20 MB of instrumented code nobody else needs
+            if os.path.exists(f):
+                os.remove(f)
     assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-4000:]
     assert "all expectations held" in res.stdout
     assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr

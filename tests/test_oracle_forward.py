@@ -359,3 +359,36 @@ def test_paper_order_with_selector_transforms_is_plain_attention():
     V = np.stack([XV[:, :, h * d:(h + 1) * d] for h in range(H)], axis=1)
     ref = fo.flurka_attention(Q, K, V, E, F, om, fo.PHI_PERFORMER)
     assert np.max(np.abs(got - ref)) < 1e-12
+
+
+# --- the constituents used as comparison baselines ------------------------------------------------
+@pytest.mark.parametrize("phi", [fo.PHI_PERFORMER, fo.PHI_ELU1])
+def test_kernel_attention_is_the_method_with_identity_projections(phi):
+    rng = np.random.default_rng(50)
+    B, H, n, d, m = 2, 2, 9, 4, 5
+    Q, K, V = (rng.standard_normal((B, H, n, d)) * 0.7 for _ in range(3))
+    om = rng.standard_normal((H, m, d)) if phi == fo.PHI_PERFORMER else None
+    got = fo.kernel_attention(Q, K, V, om, phi)
+    ref = fo.flurka_attention_definition(Q, K, V, np.eye(n), np.eye(n), om, phi)
+    assert np.max(np.abs(got - ref)) < 1e-12
+    # and the n x n matrix written out, one head
+    pq = fo.phi_elu1(Q[0, 1]) if phi == fo.PHI_ELU1 else fo.phi_performer(Q[0, 1], om[1])
+    pk = fo.phi_elu1(K[0, 1]) if phi == fo.PHI_ELU1 else fo.phi_performer(K[0, 1], om[1])
+    A = np.array([[sum(pq[i, j] * pk[r, j] for j in range(pq.shape[1])) for r in range(n)] for i in range(n)])
+    assert np.max(np.abs(got[0, 1] - (A / A.sum(axis=1, keepdims=True)) @ V[0, 1])) < 1e-12
+
+
+def test_linformer_attention_against_library_softmax():
+    rng = np.random.default_rng(51)
+    B, H, n, d, k = 1, 2, 10, 4, 3
+    Q, K, V = (rng.standard_normal((B, H, n, d)) for _ in range(3))
+    E, F = rng.standard_normal((k, n)), rng.standard_normal((k, n))
+    got = fo.linformer_attention(Q, K, V, E, F)
+    for h in range(H):
+        Kp = np.array([[sum(E[r, i] * K[0, h, i, t] for i in range(n)) for t in range(d)] for r in range(k)])
+        Vp = np.array([[sum(F[r, i] * V[0, h, i, t] for i in range(n)) for t in range(d)] for r in range(k)])
+        w = scipy.special.softmax(Q[0, h] @ Kp.T, axis=1)
+        assert np.max(np.abs(got[0, h] - w @ Vp)) < 1e-12
+    # k = 1: every row is the one projected value; shifting all scores of a row changes nothing
+    one = fo.linformer_attention(Q, K, V, E[:1], F[:1])
+    assert np.max(np.abs(one - (F[:1] @ V)[:, :, :1, :].repeat(n, axis=2))) < 1e-12
