@@ -269,6 +269,51 @@ FLURKA_API flurka_status flurka_attn_bwd(const void* Q, const void* K, const voi
                               void* stream);
 
 /*
+ * Extended entry points: flurka_attn_fwd / flurka_attn_bwd with the variants of the method that the plain
+ * ones leave out.  `options` == NULL, or all fields zero, is exactly the plain call (both kernel families).
+ * Any option set runs on the generic (fp32-arithmetic) kernels: algo must be AUTO or GENERIC
+ * (FAST returns FLURKA_ERR_UNSUPPORTED), and the workspace is the GENERIC one
+ * (flurka_workspace_bytes(..., FLURKA_ALGO_GENERIC)).
+ *
+ *   ef_per_head   E, F are (H, k, n): one projection pair per head, as the statement of Thm. 1 writes them
+ *                 (E_i, F_i); dE, dF are then (H, k, n) too, summed over the batch only.
+ *   grad_ef_f32   backward: dE, dF are written as float32 whatever `dtype` is (they are sums over every
+ *                 batch element, head and coordinate).
+ *   d_omega       backward: if not NULL, receives d loss / d omega as float32, (H, m, d) or (m, d) like
+ *                 omega itself (summed over the batch, and over the heads when omega is shared).  The
+ *                 paper draws omega once and does not train it; this is for callers that do.  Must be
+ *                 NULL for FLURKA_PHI_ELU1.
+ * The forward uses ef_per_head only.
+ */
+typedef struct {
+    int ef_per_head;
+    int grad_ef_f32;
+    void* d_omega;
+} flurka_options;
+
+FLURKA_API flurka_status flurka_attn_fwd_ex(const void* Q, const void* K, const void* V,
+                              const void* E, const void* F, const void* omega,
+                              void* out,
+                              void* ctx, size_t ctx_bytes,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int H, int n, int d, int k, int m,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              const flurka_options* options,
+                              void* stream);
+FLURKA_API flurka_status flurka_attn_bwd_ex(const void* Q, const void* K, const void* V,
+                              const void* E, const void* F, const void* omega,
+                              const void* out, const void* dOut,
+                              const void* ctx, size_t ctx_bytes,
+                              void* dQ, void* dK, void* dV, void* dE, void* dF,
+                              void* workspace, size_t workspace_bytes,
+                              int B, int H, int n, int d, int k, int m,
+                              int omega_per_head,
+                              flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              const flurka_options* options,
+                              void* stream);
+
+/*
  * Built-in stage timer (for benchmarks; off by default, not thread-safe).
  * While enabled, every forward/backward call brackets each of its stages with
  * HIP events recorded on the call's own stream.  flurka_profile_read waits

@@ -334,6 +334,76 @@ def flurka_attention_bwd(Q, K, V, E, F, omega, dOut, phi):
 
 
 # --------------------------------------------------------------------------
+# variants: one projection pair per head (Thm. 1 writes E_i, F_i), gradient for omega
+# --------------------------------------------------------------------------
+def flurka_attention_per_head(Q, K, V, E, F, omega, phi):
+    """Forward with E, F of shape (H, k, n): head h projects with its own pair E[h], F[h]."""
+    Q = np.asarray(Q, np.float64)
+    B, H = Q.shape[:2]
+    out = np.empty_like(Q)
+    for b in range(B):
+        for h in range(H):
+            out[b, h] = flurka_head(Q[b, h], K[b, h], V[b, h], E[h], F[h], _head_omega(omega, h), phi)
+    return out
+
+
+def flurka_attention_per_head_bwd(Q, K, V, E, F, omega, dOut, phi):
+    """Backward of `flurka_attention_per_head`: dE, dF are (H, k, n), summed over the batch only."""
+    Q = np.asarray(Q, np.float64)
+    B, H = Q.shape[:2]
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dE = np.zeros(np.asarray(E).shape, np.float64)
+    dF = np.zeros(np.asarray(F).shape, np.float64)
+    for b in range(B):
+        for h in range(H):
+            g = flurka_head_bwd(Q[b, h], K[b, h], V[b, h], E[h], F[h], _head_omega(omega, h), dOut[b, h], phi)
+            dQ[b, h], dK[b, h], dV[b, h] = g[0], g[1], g[2]
+            dE[h] += g[3]
+            dF[h] += g[4]
+    return dQ, dK, dV, dE, dF
+
+
+def flurka_head_bwd_omega(Q, K, V, E, F, omega, G):
+    """d sum(out * G) / d omega for one head of the random-feature map, (m, d).
+
+    omega enters through the exponents u_ij = omega_j . q_i - |q_i|^2/2 of phi(Q) and
+    e_rj = omega_j . k'_r - |k'_r|^2/2 of phi(K'):  d omega_j = sum_i dU^Q_ij q_i + sum_r dU^K_rj k'_r,
+    with dU = dphi * phi on either side (notation of `flurka_head_bwd`)."""
+    Q = np.asarray(Q, np.float64)
+    G = np.asarray(G, np.float64)
+    omega = np.asarray(omega, np.float64)
+    Kp = sequence_projection(E, K)
+    Vp = sequence_projection(F, V)
+    PhiK, S, z, _ = key_state(Kp, Vp, omega, PHI_PERFORMER)
+    P = query_features(Q, omega, PHI_PERFORMER)
+    D = P @ z
+    out = (P @ S) / D[:, None]
+    dN = G / D[:, None]
+    dD = -np.sum(G * out, axis=1) / D
+    dUq = (dN @ S.T + np.outer(dD, z)) * P
+    dS = P.T @ dN
+    dz = P.T @ dD
+    dUk = (Vp @ dS.T + dz[None, :]) * PhiK
+    return dUq.T @ Q + dUk.T @ Kp
+
+
+def flurka_attention_bwd_omega(Q, K, V, E, F, omega, dOut):
+    """Gradient for omega over all heads: (H, m, d), or (1, m, d) summed over heads when omega is shared.
+    E, F: (k, n) shared or (H, k, n) per head."""
+    Q = np.asarray(Q, np.float64)
+    B, H = Q.shape[:2]
+    omega = np.asarray(omega, np.float64)
+    per_head_ef = np.asarray(E).ndim == 3
+    dW = np.zeros_like(omega)
+    for b in range(B):
+        for h in range(H):
+            Eh, Fh = (E[h], F[h]) if per_head_ef else (E, F)
+            g = flurka_head_bwd_omega(Q[b, h], K[b, h], V[b, h], Eh, Fh, _head_omega(omega, h), dOut[b, h])
+            dW[h if omega.shape[0] > 1 else 0] += g
+    return dW
+
+
+# --------------------------------------------------------------------------
 # error metric
 # --------------------------------------------------------------------------
 def rel_l2(x, ref) -> float:

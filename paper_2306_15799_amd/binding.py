@@ -31,9 +31,15 @@ EXPORTED_SYMBOLS = (
     "flurka_version", "flurka_status_str", "flurka_ctx_bytes", "flurka_ctx_layout", "flurka_workspace_bytes",
     "flurka_fast_path_supported", "flurka_attn_fwd", "flurka_attn_fwd_static", "flurka_attn_bwd",
     "flurka_fused_w_supported", "flurka_fused_w_workspace_bytes", "flurka_attn_fwd_fused_w",
+    "flurka_attn_fwd_ex", "flurka_attn_bwd_ex",
     "flurka_baseline_supported", "flurka_baseline_ctx_bytes", "flurka_baseline_workspace_bytes", "flurka_baseline_fwd",
     "flurka_profile_enable", "flurka_profile_read", "flurka_profile_stage_name",
 )
+
+class FlurkaOptions(ctypes.Structure):
+    """flurka_options of include/flurka.h."""
+    _fields_ = [("ef_per_head", ctypes.c_int), ("grad_ef_f32", ctypes.c_int), ("d_omega", ctypes.c_void_p)]
+
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -89,6 +95,12 @@ def load_library() -> ctypes.CDLL:
     lib.flurka_baseline_fwd.restype = c_int
     lib.flurka_baseline_fwd.argtypes = ([c_int] + [c_void] * 7 + [c_void, c_size, c_void, c_size]
                                         + [c_int] * 6 + [c_int] + [c_int] * 2 + [c_void])
+    lib.flurka_attn_fwd_ex.restype = c_int
+    lib.flurka_attn_fwd_ex.argtypes = ([c_void] * 7 + [c_void, c_size, c_void, c_size]
+                                       + [c_int] * 6 + [c_int] + [c_int] * 3 + [ctypes.POINTER(FlurkaOptions), c_void])
+    lib.flurka_attn_bwd_ex.restype = c_int
+    lib.flurka_attn_bwd_ex.argtypes = ([c_void] * 8 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
+                                       + [c_int] * 6 + [c_int] + [c_int] * 3 + [ctypes.POINTER(FlurkaOptions), c_void])
     lib.flurka_attn_bwd.restype = c_int
     lib.flurka_attn_bwd.argtypes = ([c_void] * 8 + [c_void, c_size] + [c_void] * 5 + [c_void, c_size]
                                     + [c_int] * 6 + [c_int] + [c_int] * 3 + [c_void])
@@ -274,6 +286,66 @@ def flurka_attn_fwd_fused_w(Q, XK, XV, E, F, WK, WV, omega, phi="performer", out
     if st != OK:
         raise FlurkaError(st, "flurka_attn_fwd_fused_w")
     return out, ctx
+
+
+def flurka_attn_fwd_ex(Q, K, V, E, F, omega, phi="performer", algo="auto", ef_per_head=False, stream=None):
+    """flurka_attn_fwd with options (include/flurka.h: flurka_options).  With ef_per_head E, F are (H,k,n).
+    Returns out, ctx."""
+    lib = load_library()
+    Eh = E[0] if ef_per_head else E
+    B, H, n, d, k, m, per_head, omega_shape = _shapes(Q, Eh, omega, phi)
+    dt, dev = Q.dtype, Q.device
+    code = _dtype_code(Q)
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
+        _check(t, name, (B, H, n, d), dt, dev)
+    for t, name in ((E, "E"), (F, "F")):
+        _check(t, name, (H, k, n) if ef_per_head else (k, n), dt, dev)
+    if omega_shape is not None:
+        _check(omega, "omega", omega_shape, dt, dev)
+    out = torch.empty_like(Q)
+    ctx = alloc_buffer(lib.flurka_ctx_bytes(B, H, n, d, k, m, code, _PHI[phi]), dev)
+    a = ALGO_GENERIC if ef_per_head else _ALGO[algo]
+    ws = alloc_buffer(lib.flurka_workspace_bytes(B, H, n, d, k, m, code, _PHI[phi], PASS_FWD, a), dev)
+    opt = FlurkaOptions(1 if ef_per_head else 0, 0, None)
+    s = stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    st = lib.flurka_attn_fwd_ex(_ptr(Q), _ptr(K), _ptr(V), _ptr(E), _ptr(F),
+                                _ptr(omega) if omega_shape is not None else None, _ptr(out),
+                                _ptr(ctx), ctx.numel(), _ptr(ws), ws.numel(),
+                                B, H, n, d, k, m, per_head, code, _PHI[phi], _ALGO[algo], ctypes.byref(opt), s)
+    if st != OK:
+        raise FlurkaError(st, "flurka_attn_fwd_ex")
+    return out, ctx
+
+
+def flurka_attn_bwd_ex(Q, K, V, E, F, omega, out, dOut, ctx, phi="performer", algo="auto", ef_per_head=False,
+                       grad_ef_f32=False, want_d_omega=False, stream=None):
+    """flurka_attn_bwd with options.  Returns dQ, dK, dV, dE, dF and, with want_d_omega, d_omega (float32)."""
+    lib = load_library()
+    Eh = E[0] if ef_per_head else E
+    B, H, n, d, k, m, per_head, omega_shape = _shapes(Q, Eh, omega, phi)
+    dt, dev = Q.dtype, Q.device
+    code = _dtype_code(Q)
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (out, "out"), (dOut, "dOut")):
+        _check(t, name, (B, H, n, d), dt, dev)
+    for t, name in ((E, "E"), (F, "F")):
+        _check(t, name, (H, k, n) if ef_per_head else (k, n), dt, dev)
+    gdt = torch.float32 if grad_ef_f32 else dt
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dE, dF = torch.empty(E.shape, dtype=gdt, device=dev), torch.empty(F.shape, dtype=gdt, device=dev)
+    d_omega = torch.empty(omega.shape, dtype=torch.float32, device=dev) if want_d_omega else None
+    plain = not (ef_per_head or grad_ef_f32 or want_d_omega)
+    a = _ALGO[algo] if plain else ALGO_GENERIC
+    ws = alloc_buffer(lib.flurka_workspace_bytes(B, H, n, d, k, m, code, _PHI[phi], PASS_BWD, a), dev)
+    opt = FlurkaOptions(1 if ef_per_head else 0, 1 if grad_ef_f32 else 0, _ptr(d_omega))
+    s = stream if stream is not None else torch.cuda.current_stream(dev).cuda_stream
+    st = lib.flurka_attn_bwd_ex(_ptr(Q), _ptr(K), _ptr(V), _ptr(E), _ptr(F),
+                                _ptr(omega) if omega_shape is not None else None, _ptr(out), _ptr(dOut),
+                                _ptr(ctx), ctx.numel(), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dE), _ptr(dF),
+                                _ptr(ws), ws.numel(), B, H, n, d, k, m, per_head, code, _PHI[phi], _ALGO[algo],
+                                ctypes.byref(opt), s)
+    if st != OK:
+        raise FlurkaError(st, "flurka_attn_bwd_ex")
+    return (dQ, dK, dV, dE, dF) + ((d_omega,) if want_d_omega else ())
 
 
 BASELINE_KERNEL_ATTN, BASELINE_LINFORMER = 0, 1

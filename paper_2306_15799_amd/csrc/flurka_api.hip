@@ -88,7 +88,7 @@ int chip_cus() {
 
 namespace {
 
-constexpr int kVersion = 140;
+constexpr int kVersion = 150;
 
 flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_per_head,
                            int dtype, int phi, Problem* out) {
@@ -106,6 +106,8 @@ flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_p
     p.BH = B * H;
     p.omega_per_head = omega_per_head ? 1 : 0;
     p.bf16 = (dtype == FLURKA_BF16);
+    p.ef_per_head = 0;
+    p.grad_ef_f32 = 0;
     *out = p;
     return FLURKA_OK;
 }
@@ -144,11 +146,13 @@ void* static_scratch() {
 flurka_status forward_impl(const void* Q, const void* K, const void* V, const void* E, const void* F,
                            const void* omega, void* out, void* ctx, size_t ctx_bytes, void* workspace,
                            size_t workspace_bytes, bool own_scratch, int B, int H, int n, int d, int k, int m,
-                           int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo, void* stream) {
+                           int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo, void* stream,
+                           const flurka_options* opt = nullptr) {
     Problem p;
     flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
     if (st != FLURKA_OK) return st;
     if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
+    if (opt) p.ef_per_head = opt->ef_per_head ? 1 : 0;      // the other options concern the backward only
     if (!Q || !K || !V || !E || !F || !out || !ctx || (!own_scratch && !workspace)) return FLURKA_ERR_NULL;
     if (!p.elu && !omega) return FLURKA_ERR_NULL;
     const size_t es = p.bf16 ? 2 : 4;
@@ -156,7 +160,7 @@ flurka_status forward_impl(const void* Q, const void* K, const void* V, const vo
         misaligned(F, es) || misaligned(out, es) || (omega && misaligned(omega, es)) ||
         misaligned(ctx, 256) || (!own_scratch && misaligned(workspace, 256)))
         return FLURKA_ERR_ALIGN;
-    const bool fast_ok = fast_supported(p, 0) && fast_pointers_ok(Q, K, V, E, F, omega, out);
+    const bool fast_ok = !p.ef_per_head && fast_supported(p, 0) && fast_pointers_ok(Q, K, V, E, F, omega, out);
     if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
     const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
     if (ctx_bytes < ctx_layout(p).total * sizeof(float)) return FLURKA_ERR_WORKSPACE;
@@ -345,26 +349,36 @@ flurka_status flurka_baseline_fwd(flurka_baseline which, const void* Q, const vo
     return st;
 }
 
-flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
-                              const void* omega, const void* out, const void* dOut, const void* ctx,
-                              size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
-                              size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
-                              int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
-                              void* stream) {
+namespace {
+flurka_status backward_impl(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                            const void* omega, const void* out, const void* dOut, const void* ctx,
+                            size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
+                            size_t workspace_bytes, int B, int H, int n, int d, int k, int m, int omega_per_head,
+                            flurka_dtype dtype, flurka_phi phi, flurka_algo algo, void* stream,
+                            const flurka_options* opt) {
     Problem p;
     flurka_status st = make_problem(B, H, n, d, k, m, omega_per_head, dtype, phi, &p);
     if (st != FLURKA_OK) return st;
     if (!valid_algo(algo)) return FLURKA_ERR_DTYPE;
+    void* d_omega = nullptr;
+    if (opt) {
+        p.ef_per_head = opt->ef_per_head ? 1 : 0;
+        p.grad_ef_f32 = opt->grad_ef_f32 ? 1 : 0;
+        d_omega = opt->d_omega;
+    }
     if (!Q || !K || !V || !E || !F || !out || !dOut || !ctx || !dQ || !dK || !dV || !dE || !dF || !workspace)
         return FLURKA_ERR_NULL;
     if (!p.elu && !omega) return FLURKA_ERR_NULL;
+    if (d_omega && p.elu) return FLURKA_ERR_SHAPE;            // the elu1 map has no omega
     const size_t es = p.bf16 ? 2 : 4;
+    const size_t ges = p.grad_ef_f32 ? 4 : es;
     if (misaligned(Q, es) || misaligned(K, es) || misaligned(V, es) || misaligned(E, es) ||
         misaligned(F, es) || misaligned(out, es) || misaligned(dOut, es) || (omega && misaligned(omega, es)) ||
-        misaligned(dQ, es) || misaligned(dK, es) || misaligned(dV, es) || misaligned(dE, es) ||
-        misaligned(dF, es) || misaligned(ctx, 256) || misaligned(workspace, 256))
+        misaligned(dQ, es) || misaligned(dK, es) || misaligned(dV, es) || misaligned(dE, ges) ||
+        misaligned(dF, ges) || misaligned(d_omega, 4) || misaligned(ctx, 256) || misaligned(workspace, 256))
         return FLURKA_ERR_ALIGN;
-    const bool fast_ok = fast_supported(p, 1) && fast_pointers_ok(Q, K, V, E, F, omega, dOut) &&
+    const bool plain = !p.ef_per_head && !p.grad_ef_f32 && !d_omega;      // the options run on the generic kernels
+    const bool fast_ok = plain && fast_supported(p, 1) && fast_pointers_ok(Q, K, V, E, F, omega, dOut) &&
                          fast_pointers_ok(dQ, dK, dV, dE, dF, nullptr, out);
     if (algo == FLURKA_ALGO_FAST && !fast_ok) return FLURKA_ERR_UNSUPPORTED;
     const bool use_fast = (algo != FLURKA_ALGO_GENERIC) && fast_ok;
@@ -372,11 +386,41 @@ flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const
     const size_t need = use_fast ? fast_ws_bytes(p, 1) : generic_ws_layout(p, 1).total * sizeof(float);
     if (workspace_bytes < need) return FLURKA_ERR_WORKSPACE;
 
-    BwdArgs a{Q, K, V, E, F, omega, out, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace};
+    BwdArgs a{Q, K, V, E, F, omega, out, dOut, (const float*)ctx, dQ, dK, dV, dE, dF, (float*)workspace, (float*)d_omega};
     hipStream_t s = (hipStream_t)stream;
     st = use_fast ? fast_backward(p, a, s) : generic_backward(p, a, s);
     if (st != FLURKA_OK) stage_abandon();
     return st;
+}
+}  // namespace
+
+flurka_status flurka_attn_bwd(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                              const void* omega, const void* out, const void* dOut, const void* ctx,
+                              size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
+                              size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                              int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                              void* stream) {
+    return backward_impl(Q, K, V, E, F, omega, out, dOut, ctx, ctx_bytes, dQ, dK, dV, dE, dF, workspace, workspace_bytes,
+                         B, H, n, d, k, m, omega_per_head, dtype, phi, algo, stream, nullptr);
+}
+
+flurka_status flurka_attn_fwd_ex(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                                 const void* omega, void* out, void* ctx, size_t ctx_bytes, void* workspace,
+                                 size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                                 int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                                 const flurka_options* options, void* stream) {
+    return forward_impl(Q, K, V, E, F, omega, out, ctx, ctx_bytes, workspace, workspace_bytes, false, B, H, n, d,
+                        k, m, omega_per_head, dtype, phi, algo, stream, options);
+}
+
+flurka_status flurka_attn_bwd_ex(const void* Q, const void* K, const void* V, const void* E, const void* F,
+                                 const void* omega, const void* out, const void* dOut, const void* ctx,
+                                 size_t ctx_bytes, void* dQ, void* dK, void* dV, void* dE, void* dF, void* workspace,
+                                 size_t workspace_bytes, int B, int H, int n, int d, int k, int m,
+                                 int omega_per_head, flurka_dtype dtype, flurka_phi phi, flurka_algo algo,
+                                 const flurka_options* options, void* stream) {
+    return backward_impl(Q, K, V, E, F, omega, out, dOut, ctx, ctx_bytes, dQ, dK, dV, dE, dF, workspace, workspace_bytes,
+                         B, H, n, d, k, m, omega_per_head, dtype, phi, algo, stream, options);
 }
 
 flurka_status flurka_profile_enable(int on) {

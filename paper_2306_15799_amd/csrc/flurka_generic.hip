@@ -374,7 +374,7 @@ static flurka_status project(const Problem& p, const void* E, const void* X, flo
     GemmArgs g{};
     g.A = E; g.B = X; g.C = Xp;
     g.M = p.k; g.N = p.d; g.K = p.n; g.Kin = p.n;
-    g.sAm = p.n; g.sAki = 1; g.sAb = 0; g.sAh = 0;
+    g.sAm = p.n; g.sAki = 1; g.sAb = 0; g.sAh = p.ef_per_head ? (long)p.k * p.n : 0;
     g.sBn = 1; g.sBki = p.d; g.sBb = (long)p.H * p.n * p.d; g.sBh = (long)p.n * p.d;
     g.sCm = p.d; g.sCn = 1; g.sCb = (long)p.H * p.k * p.d; g.sCh = (long)p.k * p.d;
     g.H = p.H; g.a_bf16 = p.bf16; g.b_bf16 = p.bf16;
@@ -548,6 +548,22 @@ flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStrea
             g.sCm = p.d; g.sCn = 1; g.sCb = (long)p.H * p.n * p.d; g.sCh = (long)p.n * p.d;
             g.H = p.H; g.b_bf16 = p.bf16; g.c_bf16 = p.bf16;
             if ((st = launch_gemm(g, p.BH, s)) != FLURKA_OK) return st;
+            if (a.dOmega) {
+                // d omega_j (+)= sum over (batch[, head], i) of dU_ij q_i   (u_ij = omega_j . q_i - |q_i|^2/2)
+                GemmArgs w{};
+                w.A = T; w.B = (const char*)a.Q + (size_t)row0 * p.d * es; w.C = a.dOmega;
+                w.M = p.m; w.N = p.d; w.Kin = nr;
+                w.sAm = 1; w.sAki = p.m; w.sBn = 1; w.sBki = p.d; w.sCm = p.d; w.sCn = 1;
+                w.b_bf16 = p.bf16; w.accumulate = row0 > 0;
+                if (p.omega_per_head) {      // one result per head, reduction over (batch, i)
+                    w.K = p.B * nr; w.sAko = (long)p.H * nr * p.m; w.sAh = (long)nr * p.m;
+                    w.sBko = (long)p.H * p.n * p.d; w.sBh = (long)p.n * p.d; w.sCh = (long)p.m * p.d; w.H = p.H;
+                    if ((st = launch_gemm(w, p.H, s)) != FLURKA_OK) return st;
+                } else {                      // one result, reduction over (batch, head, i)
+                    w.K = p.BH * nr; w.sAko = (long)nr * p.m; w.sBko = (long)p.n * p.d; w.H = 1;
+                    if ((st = launch_gemm(w, 1, s)) != FLURKA_OK) return st;
+                }
+            }
         } else {
             const long total = rows * p.d;
             hipLaunchKernelGGL(bwd_dq_elu_kernel, grid1d(total, 256), dim3(256), 0, s, T, dD, z, a.Q, a.dQ,
@@ -614,6 +630,22 @@ flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStrea
         g.sCm = p.d; g.sCn = 1; g.sCb = (long)p.H * p.k * p.d; g.sCh = (long)p.k * p.d;
         g.H = p.H; g.b_bf16 = p.bf16;
         if ((st = launch_gemm(g, p.BH, s)) != FLURKA_OK) return st;
+        if (a.dOmega) {
+            // d omega_j += sum over (batch[, head], r) of dUk_rj k'_r
+            GemmArgs w{};
+            w.A = dPhi; w.B = Kp; w.C = a.dOmega;
+            w.M = p.m; w.N = p.d; w.Kin = p.k;
+            w.sAm = 1; w.sAki = p.m; w.sBn = 1; w.sBki = p.d; w.sCm = p.d; w.sCn = 1;
+            w.accumulate = 1;
+            if (p.omega_per_head) {
+                w.K = p.B * p.k; w.sAko = (long)p.H * p.k * p.m; w.sAh = (long)p.k * p.m;
+                w.sBko = (long)p.H * p.k * p.d; w.sBh = (long)p.k * p.d; w.sCh = (long)p.m * p.d; w.H = p.H;
+                if ((st = launch_gemm(w, p.H, s)) != FLURKA_OK) return st;
+            } else {
+                w.K = p.BH * p.k; w.sAko = (long)p.k * p.m; w.sBko = (long)p.k * p.d; w.H = 1;
+                if ((st = launch_gemm(w, 1, s)) != FLURKA_OK) return st;
+            }
+        }
         const long total = krows * p.d;
         hipLaunchKernelGGL(bwd_key_norm_kernel, grid1d(total, 256), dim3(256), 0, s, dKp, Kp, rs, total, p.d);
         FLURKA_CHECK_LAUNCH();
@@ -633,7 +665,7 @@ flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStrea
         GemmArgs g{};
         g.A = which ? a.F : a.E; g.B = which ? dVp : dKp; g.C = which ? a.dV : a.dK;
         g.M = p.n; g.N = p.d; g.K = p.k; g.Kin = p.k;
-        g.sAm = 1; g.sAki = p.n; g.sAb = 0; g.sAh = 0;
+        g.sAm = 1; g.sAki = p.n; g.sAb = 0; g.sAh = p.ef_per_head ? (long)p.k * p.n : 0;
         g.sBn = 1; g.sBki = p.d; g.sBb = (long)p.H * p.k * p.d; g.sBh = (long)p.k * p.d;
         g.sCm = p.d; g.sCn = 1; g.sCb = (long)p.H * p.n * p.d; g.sCh = (long)p.n * p.d;
         g.H = p.H; g.a_bf16 = p.bf16; g.c_bf16 = p.bf16;
@@ -645,12 +677,17 @@ flurka_status generic_backward_from(const Problem& p, const BwdArgs& a, hipStrea
     for (int which = 0; which < 2; ++which) {
         GemmArgs g{};
         g.A = which ? dVp : dKp; g.B = which ? a.V : a.K; g.C = which ? a.dF : a.dE;
-        g.M = p.k; g.N = p.n; g.K = p.BH * p.d; g.Kin = p.d;
-        g.sAm = p.d; g.sAki = 1; g.sAko = (long)p.k * p.d;
-        g.sBn = p.d; g.sBki = 1; g.sBko = (long)p.n * p.d;
-        g.sCm = p.n; g.sCn = 1;
-        g.H = 1; g.b_bf16 = p.bf16; g.c_bf16 = p.bf16;
-        if ((st = launch_gemm(g, 1, s)) != FLURKA_OK) return st;
+        g.M = p.k; g.N = p.n; g.Kin = p.d;
+        g.sAm = p.d; g.sAki = 1; g.sBn = p.d; g.sBki = 1; g.sCm = p.n; g.sCn = 1;
+        g.b_bf16 = p.bf16; g.c_bf16 = p.bf16 && !p.grad_ef_f32;
+        if (p.ef_per_head) {     // one (k x n) gradient per head, reduction index = (batch, t)
+            g.K = p.B * p.d; g.sAko = (long)p.H * p.k * p.d; g.sAh = (long)p.k * p.d;
+            g.sBko = (long)p.H * p.n * p.d; g.sBh = (long)p.n * p.d; g.sCh = (long)p.k * p.n; g.H = p.H;
+            if ((st = launch_gemm(g, p.H, s)) != FLURKA_OK) return st;
+        } else {                  // E, F shared: reduction index = (batch, head, t)
+            g.K = p.BH * p.d; g.sAko = (long)p.k * p.d; g.sBko = (long)p.n * p.d; g.H = 1;
+            if ((st = launch_gemm(g, 1, s)) != FLURKA_OK) return st;
+        }
     }
     stage_end(s, STAGE_BWD_DEDF);
     return FLURKA_OK;

@@ -18,6 +18,9 @@ struct Problem {
     int omega_per_head;
     int bf16;            // storage type of caller tensors
     int elu;             // feature map
+    // options of the extended entry points (generic kernels only)
+    int ef_per_head;     // E, F (and dE, dF) are (H, k, n): one pair per head
+    int grad_ef_f32;     // dE, dF are written as float32 whatever the storage type
 };
 
 static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -92,6 +95,7 @@ struct BwdArgs {
     const float* ctx;
     void *dQ, *dK, *dV, *dE, *dF;
     float* ws;
+    float* dOmega;       // optional (extended entry point): d loss / d omega, (H|1, m, d) float32
 };
 
 // Each returns FLURKA_OK or FLURKA_ERR_LAUNCH.

@@ -59,6 +59,17 @@ int main() {
     EXPECT(flurka_attn_bwd(fake, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 30, fake, fake, fake, fake, fake, fake,
                            16, 1, 1, 512, 64, 64, 64, 1, FLURKA_F32, FLURKA_PHI_PERFORMER, FLURKA_ALGO_GENERIC,
                            nullptr) == FLURKA_ERR_WORKSPACE);
+    {   // extended entry points: options are read before anything is launched
+        flurka_options opt = {1, 1, fake};
+        EXPECT(flurka_attn_bwd_ex(fake, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 30, fake, fake, fake, fake, fake,
+                                  fake, 16, 1, 2, 512, 64, 64, 64, 1, FLURKA_BF16, FLURKA_PHI_PERFORMER, FLURKA_ALGO_AUTO,
+                                  &opt, nullptr) == FLURKA_ERR_WORKSPACE);
+        EXPECT(flurka_attn_fwd_ex(fake, fake, fake, fake, fake, fake, fake, fake, 1 << 30, fake, 16, 1, 2, 512, 64, 64, 64, 1,
+                                  FLURKA_BF16, FLURKA_PHI_PERFORMER, FLURKA_ALGO_FAST, &opt, nullptr) == FLURKA_ERR_UNSUPPORTED);
+        EXPECT(flurka_baseline_fwd(FLURKA_BASELINE_LINFORMER, fake, fake, fake, fake, fake, nullptr, fake, fake, 16, fake,
+                                   1 << 30, 1, 2, 512, 64, 64, 64, 1, FLURKA_BF16, FLURKA_PHI_PERFORMER,
+                                   nullptr) == FLURKA_ERR_WORKSPACE);
+    }
     // stage timer: read while disabled, enable/disable cycles (without a GPU enabling fails cleanly)
     std::vector<int> ids(8);
     std::vector<float> ms_(8);

@@ -27,7 +27,7 @@ def test_every_declared_entry_point_is_exported(lib):
     assert declared == set(fb.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.flurka_version() == 140
+    assert lib.flurka_version() == 150
 
 
 def test_status_strings(lib):
@@ -157,6 +157,26 @@ def test_paper_order_entry_point_validates_before_launching(lib):
     assert lib.flurka_fused_w_supported(1, 4, 512, 64, 64, 64, 256, fb.BF16, 0) == 1
     assert lib.flurka_fused_w_workspace_bytes(1, 4, 512, 64, 64, 64, 256, fb.BF16, 0) > 0
     assert lib.flurka_fused_w_workspace_bytes(1, 3, 512, 64, 64, 64, 256, fb.BF16, 0) == 0
+
+
+def test_extended_entry_points_validate_their_options(lib):
+    def bwd(opt, **over):
+        a = dict(algo=fb.ALGO_GENERIC, dtype=fb.F32, phi=fb.PHI_PERFORMER, ws_bytes=1 << 40, dE=FAKE)
+        a.update(over)
+        return lib.flurka_attn_bwd_ex(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, FAKE, FAKE, FAKE,
+                                      a["dE"], FAKE, FAKE, a["ws_bytes"], 1, 1, 512, 64, 64, 64, 1, a["dtype"],
+                                      a["phi"], a["algo"], opt, None)
+    import ctypes as ct
+    none = fb.FlurkaOptions(0, 0, None)
+    assert bwd(None, ws_bytes=16) == fb.ERR_WORKSPACE                 # NULL options = the plain call
+    assert bwd(ct.byref(none), ws_bytes=16) == fb.ERR_WORKSPACE
+    f32ef = fb.FlurkaOptions(0, 1, None)
+    assert bwd(ct.byref(f32ef), dtype=fb.BF16, algo=fb.ALGO_FAST, n=512) == fb.ERR_UNSUPPORTED
+    assert bwd(ct.byref(f32ef), dtype=fb.BF16, dE=FAKE + 2) == fb.ERR_ALIGN     # float32 dE needs 4-byte alignment
+    dom = fb.FlurkaOptions(0, 0, FAKE)
+    assert bwd(ct.byref(dom), phi=fb.PHI_ELU1) == fb.ERR_SHAPE       # the elu1 map has no omega
+    assert bwd(ct.byref(fb.FlurkaOptions(0, 0, FAKE + 2))) == fb.ERR_ALIGN
+    assert bwd(ct.byref(dom), ws_bytes=16) == fb.ERR_WORKSPACE
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -158,3 +158,71 @@ def test_backward_permutation_equivariance(phi):
     assert np.max(np.abs(perm[2] - base[2][:, :, p])) < 1e-12
     assert np.max(np.abs(perm[3] - base[3][:, p])) < 1e-12      # dE columns follow
     assert np.max(np.abs(perm[4] - base[4][:, p])) < 1e-12
+
+
+# --- variants: per-head projection pairs, gradient for omega --------------------------------------
+def _variant_case(seed=70, B=2, H=3, n=7, d=3, k=4, m=5):
+    rng = np.random.default_rng(seed)
+    Q, K, V, G = (rng.standard_normal((B, H, n, d)) * 0.6 for _ in range(4))
+    E = rng.standard_normal((H, k, n)) / np.sqrt(k)
+    F = rng.standard_normal((H, k, n)) / np.sqrt(k)
+    om = rng.standard_normal((H, m, d))
+    return Q, K, V, E, F, om, G
+
+
+def test_per_head_pairs_reduce_to_the_shared_pair():
+    """H copies of one (E, F) pair give the shared-pair forward and backward; the per-head dE, dF then
+    add up to the shared ones (which are sums over batch AND heads)."""
+    Q, K, V, E, F, om, G = _variant_case()
+    H = Q.shape[1]
+    Ec, Fc = np.repeat(E[:1], H, axis=0), np.repeat(F[:1], H, axis=0)
+    for phi, w in ((fo.PHI_PERFORMER, om), (fo.PHI_ELU1, None)):
+        assert np.max(np.abs(fo.flurka_attention_per_head(Q, K, V, Ec, Fc, w, phi)
+                             - fo.flurka_attention(Q, K, V, E[0], F[0], w, phi))) < 1e-13
+        a = fo.flurka_attention_per_head_bwd(Q, K, V, Ec, Fc, w, G, phi)
+        b = fo.flurka_attention_bwd(Q, K, V, E[0], F[0], w, G, phi)
+        for x, y in zip(a[:3], b[:3]):
+            assert np.max(np.abs(x - y)) < 1e-12
+        assert np.max(np.abs(a[3].sum(axis=0) - b[3])) < 1e-12
+        assert np.max(np.abs(a[4].sum(axis=0) - b[4])) < 1e-12
+
+
+def test_per_head_pairs_by_central_differences():
+    """Different pairs per head: dE[h], dF[h] against central differences of sum(out * G)."""
+    Q, K, V, E, F, om, G = _variant_case(seed=71)
+    phi = fo.PHI_PERFORMER
+    g = fo.flurka_attention_per_head_bwd(Q, K, V, E, F, om, G, phi)
+    loss = lambda E_, F_: float(np.sum(fo.flurka_attention_per_head(Q, K, V, E_, F_, om, phi) * G))
+    rng = np.random.default_rng(1)
+    h_ = 1e-6
+    for _ in range(12):
+        idx = tuple(rng.integers(0, s) for s in E.shape)
+        for which, grad in ((0, g[3]), (1, g[4])):
+            Ep, Em, Fp, Fm = E.copy(), E.copy(), F.copy(), F.copy()
+            (Ep if which == 0 else Fp)[idx] += h_
+            (Em if which == 0 else Fm)[idx] -= h_
+            num = (loss(Ep, Fp) - loss(Em, Fm)) / (2 * h_)
+            assert abs(num - grad[idx]) <= 2e-7 * max(1.0, abs(grad[idx])), (which, idx, num, grad[idx])
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_omega_gradient_by_central_differences(shared):
+    """Every entry of d omega against central differences; with one omega for all heads the gradient is
+    the sum of the per-head ones."""
+    Q, K, V, E, F, om, G = _variant_case(seed=72, B=2, H=2, n=6, d=3, k=3, m=4)
+    if shared:
+        om = om[:1]
+    E0, F0 = E[0], F[0]
+    dW = fo.flurka_attention_bwd_omega(Q, K, V, E0, F0, om, G)
+    assert dW.shape == om.shape
+    loss = lambda w: float(np.sum(fo.flurka_attention(Q, K, V, E0, F0, w, fo.PHI_PERFORMER) * G))
+    h_ = 1e-6
+    for idx in np.ndindex(*om.shape):
+        wp, wm = om.copy(), om.copy()
+        wp[idx] += h_
+        wm[idx] -= h_
+        num = (loss(wp) - loss(wm)) / (2 * h_)
+        assert abs(num - dW[idx]) <= 2e-7 * max(1.0, abs(dW[idx])), (idx, num, dW[idx])
+    if shared:
+        per = fo.flurka_attention_bwd_omega(Q, K, V, E0, F0, np.repeat(om, Q.shape[1], axis=0), G)
+        assert np.max(np.abs(per.sum(axis=0, keepdims=True) - dW)) < 1e-12
