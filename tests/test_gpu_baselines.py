@@ -62,3 +62,26 @@ def test_limits_are_refused():
     assert not fb.baseline_supported(fb.BASELINE_LINFORMER, 1, 1, 4096, 128, 512, 32, fb.BF16, PHI_PERFORMER)
     assert not fb.baseline_supported(fb.BASELINE_LINFORMER, 1, 1, 4096, 64, 256, 32, fb.F32, PHI_PERFORMER)
     assert not fb.baseline_supported(fb.BASELINE_KERNEL_ATTN, 1, 1, 100, 64, 100, 32, fb.BF16, PHI_PERFORMER)
+
+
+@pytest.mark.parametrize("which", [fb.BASELINE_KERNEL_ATTN, fb.BASELINE_LINFORMER])
+def test_results_do_not_depend_on_what_the_buffers_held(which):
+    B, H, n, d, k, m = 1, 3, 704, 64, 100, 96
+    w = Workload("poison", B, H, n, d, k, m, "bf16", PHI_PERFORMER, False)
+    t = inputs.make_inputs(w, 62)
+    g = gu.to_device(t, "bf16")
+    lib = fb.load_library()
+    kk, mm = (n, m) if which == fb.BASELINE_KERNEL_ATTN else (k, 32)
+
+    def run(fill):
+        ctx = fb.alloc_buffer(lib.flurka_baseline_ctx_bytes(which, B, H, n, d, kk, mm, fb.BF16, 0), g["Q"].device).fill_(fill)
+        ws = fb.alloc_buffer(lib.flurka_baseline_workspace_bytes(which, B, H, n, d, kk, mm, fb.BF16, 0), g["Q"].device).fill_(fill)
+        out = torch.empty_like(g["Q"]).view(torch.uint8).fill_(fill).view(torch.bfloat16).view(g["Q"].shape)
+        fb.flurka_baseline_fwd(which, g["Q"], g["K"], g["V"], E=g["E"], F=g["F"], omega=g["omega"], phi=w.phi, out=out,
+                               ctx=ctx, workspace=ws)
+        torch.cuda.synchronize()
+        return out
+
+    clean, dirty = run(0), run(0xFF)
+    assert torch.isfinite(dirty.float()).all()
+    assert torch.equal(clean, dirty)

@@ -88,3 +88,26 @@ def test_unsupported_shapes_are_refused():
         fb.flurka_attn_fwd_fused_w(g["Q"], g["XK"], g["XV"], g["E"], g["F"], g["WK"], g["WV"], g["omega"],
                                    workspace=fb.alloc_buffer(1 << 20, g["Q"].device))
     assert e.value.status == fb.ERR_UNSUPPORTED
+
+
+def test_results_do_not_depend_on_what_the_buffers_held():
+    """ctx, workspace and out filled with NaN bit patterns before the call (ragged k, a model width that
+    leaves the last 256-column tile of the first product half empty, an odd number of reduction steps)."""
+    B, H, n, d, k, m, dm = 2, 4, 704, 64, 100, 96, 320
+    w = Workload("poison", B, H, n, d, k, m, "bf16", PHI_PERFORMER, False)
+    t = inputs.make_paper_order_inputs(w, dm, 45)
+    g = gu.to_device(t, "bf16")
+    lib = fb.load_library()
+
+    def run(fill):
+        ctx = fb.alloc_buffer(fb.ctx_bytes(B, H, n, d, k, m, fb.BF16, w.phi), g["Q"].device).fill_(fill)
+        ws = fb.alloc_buffer(lib.flurka_fused_w_workspace_bytes(B, H, n, d, k, m, dm, fb.BF16, 0), g["Q"].device).fill_(fill)
+        out = torch.empty_like(g["Q"]).view(torch.uint8).fill_(fill).view(torch.bfloat16).view(g["Q"].shape)
+        fb.flurka_attn_fwd_fused_w(g["Q"], g["XK"], g["XV"], g["E"], g["F"], g["WK"], g["WV"], g["omega"], phi=w.phi,
+                                   out=out, ctx=ctx, workspace=ws)
+        torch.cuda.synchronize()
+        return out
+
+    clean, dirty = run(0), run(0xFF)
+    assert torch.isfinite(dirty.float()).all()
+    assert torch.equal(clean, dirty)
