@@ -38,7 +38,7 @@ static ProjPlan proj_plan(const Problem& p) {
     q.tilesM = (p.k + PBM - 1) / PBM;
     const int heads_per_tile = PBN / p.d;
     q.tilesN = (p.BH + heads_per_tile - 1) / heads_per_tile;
-    q.total_steps = p.n / PBK;
+    q.total_steps = (p.n + PBK - 1) / PBK;        // a ragged last step reads the missing positions as zero
     const int tiles = q.tilesM * q.tilesN * 2;
     int splits = chip_cus() / tiles;               // one workgroup per compute unit
     if (splits < 1) splits = 1;
@@ -288,7 +288,7 @@ bool fast_supported(const Problem& p, int bwd) {
     if (bwd) return fast_bwd_supported(p);
     if (!p.bf16) return false;
     if (p.d != 64 && p.d != 128) return false;
-    if (p.n % PBK != 0) return false;
+    if (p.n % 8 != 0) return false;                // rows of E and F start on 16-byte boundaries
     if (p.mf % 32 != 0) return false;
     if (query_lds_bytes(p) > 160 * 1024) return false;
     // 32-bit byte offsets inside the projection's buffer descriptors
@@ -354,7 +354,7 @@ template <int D, bool ELU>
 static flurka_status launch_query(const Problem& p, const QueryArgs& qa, int ldsb, hipStream_t s) {
     if constexpr (ELU && QS_QT == 1) {
         const int staged = ldsb + QsWaves<D>::value * 32 * D * 2;
-        if (staged <= 160 * 1024) return launch_query_impl<D, ELU, true>(qa, staged, s);
+        if (p.n % 32 == 0 && staged <= 160 * 1024) return launch_query_impl<D, ELU, true>(qa, staged, s);
     }
     return launch_query_impl<D, ELU, false>(qa, ldsb, s);
 }
@@ -482,7 +482,7 @@ static FusedWPlan fusedw_plan(const Problem& p, int dm) {
     q.tilesM = (p.k + GBM - 1) / GBM;
     q.tpb1 = (dm + GBN - 1) / GBN;
     q.tilesN1 = p.B * q.tpb1;
-    q.steps1 = p.n / GBK;
+    q.steps1 = (p.n + GBK - 1) / GBK;
     q.s1 = split_plan(q.tilesM * q.tilesN1 * 2, q.steps1);
     q.tpb2 = p.H * p.d / GBN;
     q.tilesN2 = p.B * q.tpb2;

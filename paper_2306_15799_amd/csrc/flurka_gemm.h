@@ -213,6 +213,10 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
         const __amdgpu_buffer_rsrc_t rsA = sc.rsA, rsB = sc.rsB;
         const int voffA = sc.voffA, aq = sc.a_qstride, bq = sc.b_qstride;
         const int vB = real ? sc.voffB : G_OOB;                 // past the range: B reads as zero
+        // B_ROW_LIMIT: rows of B are reduction positions of which only b_rows exist (a ragged last
+        // step); this thread's row q of the step exists if q < b_left
+        int b_left = 8;
+        if constexpr (Pol::B_ROW_LIMIT) b_left = sc.b_rows - (sl * GBK + 8 * b_kg);
 #define G_CHUNK(PH, q, i0, j0, i1, j1, LD)                                                      \
         {                                                                                       \
             constexpr int cur = (PH) & 1, nxt = cur ^ 1, ns = ((PH) + 1) & 3;                   \
@@ -226,7 +230,8 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
             /* chunks 1..23 of the next step finish the other buffer before that step's barrier  */ \
             if ((pos & 1) == 0) {                                                               \
                 constexpr int j = pos / 2;                                                      \
-                if (j & 1) RB[j / 2] = buf_ld16(rsB, vB, sB + (j / 2) * bq);                    \
+                if (j & 1) RB[j / 2] = buf_ld16(rsB, (!Pol::B_ROW_LIMIT || j / 2 < b_left) ? vB : G_OOB, \
+                                                sB + (j / 2) * bq);                             \
                 else       RA[j / 2] = buf_ld16(rsA, voffA, sA + (j / 2) * aq);                 \
             } else {                                                                            \
                 constexpr int j = ((pos + 7) & 31) / 2;                                         \
@@ -329,10 +334,12 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
         // into buffer 1
         {
             const int sA = Pol::a_soff(pc, cur.step0), sB = Pol::b_soff(pc, cur.step0);
+            int b_left = 8;
+            if constexpr (Pol::B_ROW_LIMIT) b_left = pc.b_rows - (cur.step0 * GBK + 8 * b_kg);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 RA[q] = buf_ld16(pc.rsA, pc.voffA, sA + q * pc.a_qstride);
-                RB[q] = buf_ld16(pc.rsB, pc.voffB, sB + q * pc.b_qstride);
+                RB[q] = buf_ld16(pc.rsB, q < b_left ? pc.voffB : G_OOB, sB + q * pc.b_qstride);
             }
         }
 #pragma unroll
@@ -340,10 +347,12 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
         {
             const int sA = Pol::a_soff(pc, cur.step0 + 1), sB = Pol::b_soff(pc, cur.step0 + 1);
             const int vB = cur.step0 + 1 < cur.step1 ? pc.voffB : G_OOB;
+            int b_left = 8;
+            if constexpr (Pol::B_ROW_LIMIT) b_left = pc.b_rows - ((cur.step0 + 1) * GBK + 8 * b_kg);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 RA[q] = buf_ld16(pc.rsA, pc.voffA, sA + q * pc.a_qstride);
-                RB[q] = buf_ld16(pc.rsB, vB, sB + q * pc.b_qstride);
+                RB[q] = buf_ld16(pc.rsB, q < b_left ? vB : G_OOB, sB + q * pc.b_qstride);
             }
         }
         store_a(1, 0); store_b(1, 0); store_a(1, 1); store_b(1, 1);
@@ -411,6 +420,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_pair_kernel(GemmParams ga, Gemm
 struct PolicyCtxBase {
     __amdgpu_buffer_rsrc_t rsA, rsB;
     int voffA, voffB, a_qstride, b_qstride;
+    int b_rows;          // B_ROW_LIMIT policies: number of reduction positions that exist
 };
 
 // K' = E K: rows = k projected slots, columns = (head, t), reduction = sequence positions.
@@ -420,6 +430,7 @@ struct ProjPolicy {
     static constexpr bool PARTIAL_TILES = true;
     static constexpr bool TRANSPOSED_STORE = false;
     static constexpr bool SHARE_B = false;
+    static constexpr bool B_ROW_LIMIT = true; 
     struct Ctx : PolicyCtxBase { int bh0; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -434,6 +445,7 @@ struct ProjPolicy {
         const int b_col = 8 * (tid & 31), b_kg = tid >> 5;
         c.voffB = (((b_col / D) * g.n + 8 * b_kg) * D + (b_col % D)) * 2;
         c.b_qstride = D * 2;
+        c.b_rows = g.n;
         return c;
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
@@ -448,6 +460,7 @@ struct ProjWidePolicy {
     static constexpr bool PARTIAL_TILES = true;
     static constexpr bool TRANSPOSED_STORE = false;
     static constexpr bool SHARE_B = false;
+    static constexpr bool B_ROW_LIMIT = true; 
     struct Ctx : PolicyCtxBase {};
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -460,6 +473,7 @@ struct ProjWidePolicy {
         // uses those columns of the result
         c.voffB = ((8 * (tid >> 5)) * g.dm + c0 + 8 * (tid & 31)) * 2;
         c.b_qstride = g.dm * 2;
+        c.b_rows = g.n;
         return c;
     }
     static __device__ __forceinline__ int a_soff(const Ctx&, int step) { return step * (GBK * 2); }
@@ -477,6 +491,7 @@ struct TransformPolicy {
     static constexpr bool PARTIAL_TILES = true;
     static constexpr bool TRANSPOSED_STORE = false;
     static constexpr bool SHARE_B = false;
+    static constexpr bool B_ROW_LIMIT = false;
     struct Ctx : PolicyCtxBase { int steps_per_term; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -503,6 +518,7 @@ struct GradXPolicy {
     static constexpr bool PARTIAL_TILES = false;
     static constexpr bool TRANSPOSED_STORE = true;
     static constexpr bool SHARE_B = true;
+    static constexpr bool B_ROW_LIMIT = false;
     struct Ctx : PolicyCtxBase {};
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;
@@ -534,6 +550,7 @@ struct GradEPolicy {
     static constexpr bool PARTIAL_TILES = !FINAL;
     static constexpr bool TRANSPOSED_STORE = false;
     static constexpr bool SHARE_B = true;
+    static constexpr bool B_ROW_LIMIT = false;
     struct Ctx : PolicyCtxBase { int a_batch, b_batch; };
     static __device__ __forceinline__ Ctx make(const GemmParams& g, int which, int m0, int n0, int tid) {
         Ctx c;

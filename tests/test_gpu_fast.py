@@ -24,6 +24,13 @@ FWD_SHAPES = [
     (1, 1, 64, 64, 1, 32),
     (3, 5, 1088, 64, 96, 128),
     (8, 16, 128, 128, 40, 64),
+    # sequence lengths that are multiples of 8 only: a ragged last reduction step of the projection (whose
+    # missing positions would otherwise read the next head's rows), a ragged last query tile
+    (1, 3, 200, 64, 100, 96),
+    (2, 5, 1000, 64, 256, 256),
+    (2, 2, 72, 128, 8, 32),
+    (1, 3, 1048, 128, 300, 160),
+    (2, 3, 8, 64, 4, 32),
 ]
 
 
@@ -36,7 +43,8 @@ def test_forward_performer(shape):
     print(shape, f"rel-L2 {err:.3e}")
 
 
-@pytest.mark.parametrize("shape", [(1, 3, 192, 64, 100), (2, 4, 1024, 64, 256), (1, 2, 320, 128, 64)])
+@pytest.mark.parametrize("shape", [(1, 3, 192, 64, 100), (2, 4, 1024, 64, 256), (1, 2, 320, 128, 64),
+                                   (1, 3, 200, 64, 100), (2, 2, 328, 128, 64)])
 def test_forward_elu(shape):
     B, H, n, d, k = shape
     w = Workload("fast", B, H, n, d, k, d, "bf16", PHI_ELU1, False)
@@ -44,8 +52,9 @@ def test_forward_elu(shape):
     print(shape, f"rel-L2 {err:.3e}")
 
 
-def test_fast_projection_matches_oracle_projection():
-    w = Workload("proj", 1, 6, 4096, 64, 256, 64, "bf16", PHI_PERFORMER, False)
+@pytest.mark.parametrize("n", [4096, 4120])
+def test_fast_projection_matches_oracle_projection(n):
+    w = Workload("proj", 1, 6, n, 64, 256, 64, "bf16", PHI_PERFORMER, False)
     t = inputs.make_inputs(w, 9)
     _, _, ctx = gu.run_forward(w, t, "fast")
     v = fb.ctx_views(ctx, w.B, w.H, w.n, w.d, w.k, w.m, fb.BF16, w.phi)
@@ -72,7 +81,7 @@ def test_shared_omega_and_determinism():
 
 
 def test_unsupported_shapes_are_refused_not_miscomputed():
-    # n not a multiple of 64, head size other than 64/128, fp32 storage
+    # n not a multiple of 8, head size other than 64/128, fp32 storage
     assert not fb.fast_path_supported(1, 1, 100, 64, 8, 32, fb.BF16, "performer")
     assert not fb.fast_path_supported(1, 1, 128, 48, 8, 32, fb.BF16, "performer")
     assert not fb.fast_path_supported(1, 1, 128, 64, 8, 32, fb.F32, "performer")

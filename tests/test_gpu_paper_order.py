@@ -30,6 +30,8 @@ SHAPES = [
     (2, 8, 1024, 64, 256, 128, 320),
     (2, 2, 640, 128, 300, 160, 192),
     (1, 4, 2048, 128, 512, 64, 512),
+    # a sequence length that is a multiple of 8 only (ragged last reduction step of the first product)
+    (2, 4, 712, 64, 100, 96, 256),
 ]
 
 
