@@ -882,8 +882,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
     const int wave = threadIdx.x >> 6;
     const int KT = a.kp / 32;
-    const int kt = blockIdx.x % KT;
-    const int bh = blockIdx.x / KT;
+    // the KT workgroups of one head read the same omega and dS images: ids equal mod 8 = one XCD, one L2
+    const int slot = (int)(blockIdx.x >> 3);
+    const int kt = slot % KT;
+    const int bh = (slot / KT) * 8 + (int)(blockIdx.x & 7);
+    if (bh >= a.BH) return;                                // head count rounded up to whole groups of 8
     const int FT = a.mf / 32;
     const int key = 32 * kt + l32;
     const bool live = key < a.k;
@@ -1395,7 +1398,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ka.img = img; ka.imgT = imgT;
         ka.omega_head_stride = omega_stride;
         ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kp = W.kp; ka.mf = p.mf;
-        const unsigned kgrid = (unsigned)(p.BH * (W.kp / 32));
+        const unsigned kgrid = (unsigned)((p.BH + 7) / 8 * 8 * (W.kp / 32));
         const int klds = p.d == 64 ? BwdKeyLds<64>::total : BwdKeyLds<128>::total;
         const void* kk = p.d == 64 ? (const void*)bwd_key_kernel<64> : (const void*)bwd_key_kernel<128>;
         KernelFacts facts;

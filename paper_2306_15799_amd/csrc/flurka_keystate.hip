@@ -155,8 +155,12 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
     using L = KeyStateLds<D>;
     const int lane = threadIdx.x & 63, half = lane >> 5, l32 = lane & 31;
     const int kr = threadIdx.x >> 6;                       // this wavefront's key range
-    const int ft = (int)(blockIdx.x % a.FT);
-    const int bh = (int)(blockIdx.x / a.FT);
+    // Workgroup ids go round the 8 XCDs; the FT workgroups of one head all read that head's K' and V'
+    // images, so they take ids that are equal mod 8 and share one L2.
+    const int slot = (int)(blockIdx.x >> 3);
+    const int ft = slot % a.FT;
+    const int bh = (slot / a.FT) * 8 + (int)(blockIdx.x & 7);
+    if (bh >= a.BH) return;                                // head count rounded up to whole groups of 8
     const int KT = a.kpad / 32;
     const int kt0 = kr * a.tiles_per_range;
     int kt1 = kt0 + a.tiles_per_range;
@@ -436,7 +440,7 @@ static flurka_status launch_key_state_impl(const Problem& p, const KeyStateArgs&
     const int ldsb = KeyStateLds<D>::total(ka.KR);
     KernelFacts facts;
     if (!kernel_facts((const void*)kern, ka.KR * 64, ldsb, &facts)) return FLURKA_ERR_LAUNCH;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(p.BH * ka.FT)), dim3(ka.KR * 64), ldsb, s, ka);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((p.BH + 7) / 8 * 8 * ka.FT)), dim3(ka.KR * 64), ldsb, s, ka);
     FLURKA_CHECK_LAUNCH();
     return FLURKA_OK;
 }
