@@ -1168,22 +1168,46 @@ bool fast_bwd_supported(const Problem& p) {
     return true;
 }
 
-struct GradEPlan { int tilesM, tilesN, total_steps, splits, steps_per_split; };
+struct GradEPlan {
+    int tilesM, tilesN, total_steps, splits, steps_per_split;
+    int resident;          // workgroups of the launch dE/dF share with dK/dV
+    PairPlan pair;
+};
 
+// dE/dF (few items with a reduction over all B*H*d/64 steps) share their launch with dK/dV (many items of
+// kp/64 steps).  Unsplit, the long items are the critical path whenever there are fewer of them than
+// compute units (64 at the headline size: 89 us, the short items done after 46); split s ways they
+// finish sooner, their workgroups go on with short items, and a second pass sums the s partial results.
+// The split that the cost model (plan_pair, plus the traffic of the second pass) expects to finish first
+// wins.
 static GradEPlan grad_e_plan(const Problem& p) {
     GradEPlan q;
     q.tilesM = (p.k + GBM - 1) / GBM;
     q.tilesN = (p.n + GBN - 1) / GBN;
     q.total_steps = p.BH * p.d / GBK;
-    // dE/dF share their launch with dK/dV, whose many short items fill whatever this part leaves free:
-    // workgroups on a quarter of the compute units are enough, and from 64 tiles on (the headline size)
-    // the reduction is not split at all -- no partials, no second pass (measured: 88.7 us against
-    // 80.0 + 9.6 us with two splits)
-    int splits = chip_cus() / 4 / (q.tilesM * q.tilesN * 2);
-    if (splits < 1) splits = 1;
-    if (splits > q.total_steps) splits = q.total_steps;
-    q.steps_per_split = (q.total_steps + splits - 1) / splits;
-    q.splits = (q.total_steps + q.steps_per_split - 1) / q.steps_per_split;
+    q.resident = chip_cus() / 8 * 8;
+    const int kp = (p.k + 63) / 64 * 64;
+    const int items_b = 8 * ((p.BH * p.d + GBM - 1) / GBM) * ((q.tilesN * 2 + 7) / 8);
+    const int steps_b = kp / GBK;
+    double best = -1.0;
+    for (int want = 1; want <= 8; ++want) {
+        if (want > q.total_steps) break;
+        const int sps = (q.total_steps + want - 1) / want;
+        const int splits = (q.total_steps + sps - 1) / sps;
+        if (splits != want) continue;
+        const int items_a = 8 * q.tilesM * ((splits * q.tilesN * 2 + 7) / 8);
+        double t = 0.0;
+        const PairPlan pl = plan_pair(items_a, sps, items_b, steps_b, q.resident, &t);
+        if (splits > 1) {
+            // second pass: reads the fp32 partials, writes bf16; about 4 TB/s plus a launch
+            const double bytes = 2.0 * q.tilesM * q.tilesN * G_TILE_ELEMS * 4.0 * splits + 4.0 * p.k * (double)p.n;
+            t += 4.0 + bytes / 4.0e6;
+        }
+        if (best < 0.0 || t < best) {
+            best = t;
+            q.splits = splits; q.steps_per_split = sps; q.pair = pl;
+        }
+    }
     return q;
 }
 
@@ -1316,10 +1340,10 @@ static flurka_status grad_gemms_d(const Problem& p, const BwdArgs& a, const uint
         if (e.splits == 1) {
             // enough tiles to fill the chip without splitting the reduction: results leave as bf16
             ge.C[0] = a.dE; ge.C[1] = a.dF;
-            st = launch_gemm_mfma_pair<GradEPolicy<D, true>, GradXPolicy<D>>(ge, gx, s);
+            st = launch_gemm_mfma_pair<GradEPolicy<D, true>, GradXPolicy<D>>(ge, gx, e.pair, e.resident, s);
         } else {
             ge.C[0] = part; ge.C[1] = nullptr;
-            st = launch_gemm_mfma_pair<GradEPolicy<D, false>, GradXPolicy<D>>(ge, gx, s);
+            st = launch_gemm_mfma_pair<GradEPolicy<D, false>, GradXPolicy<D>>(ge, gx, e.pair, e.resident, s);
         }
         if (st != FLURKA_OK) return st;
     }

@@ -99,11 +99,12 @@ __host__ __device__ inline int gemm_item_count(const GemmParams& g) {
 
 // STREAM: a workgroup may take several work items (launched with fewer workgroups than items); the
 // one-item form keeps the step bookkeeping out of the long reductions, where it costs a few percent.
-// `block` of `nblocks`: this workgroup's place among the workgroups that run this GEMM (the whole grid,
-// or one part of a grid that runs two GEMMs side by side).
+// `block` of `nblocks`: this workgroup's place among the workgroups that share the items
+// item_lo .. item_hi - 1 of this GEMM (the whole grid and all items, or one part of a grid that runs two
+// GEMMs side by side; item_lo a multiple of 8, item_hi at most the item count).
 template <class Pol, bool STREAM>
 __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int block, const int nblocks,
-                                               unsigned char* const lds) {
+                                               unsigned char* const lds, const int item_lo, const int item_hi) {
     constexpr bool BT = Pol::B_TRANSPOSE;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -122,10 +123,9 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
     //     (split, column tile, which) index and the row tiles follow, so all row tiles that read one B
     //     tile run on the same XCD at about the same time and that tile leaves HBM once.
     struct Item { int split, tm, tn, which, step0, step1, send; bool valid; };
-    const int total_items = gemm_item_count<Pol>(g);
     auto decode = [&](int id) -> Item {
         Item it;
-        it.valid = id < total_items;
+        it.valid = id < item_hi;
         if (!it.valid) id = 0;
         if constexpr (Pol::SHARE_B) {
             const int xcd = id & 7; id >>= 3;
@@ -148,8 +148,8 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
         it.send = it.step0 + ((it.step1 - it.step0 + 1) & ~1);        // steps run in pairs
         return it;
     };
-    int item_id = block;
-    Item cur = decode(item_id), nxt = decode(STREAM ? item_id + nblocks : total_items);
+    int item_id = item_lo + block;
+    Item cur = decode(item_id), nxt = decode(STREAM ? item_id + nblocks : item_hi);
     typename Pol::Ctx pc = Pol::make(g, cur.which, cur.tm * GBM, cur.tn * GBN, tid);
     typename Pol::Ctx pn = Pol::make(g, nxt.which, nxt.tm * GBM, nxt.tn * GBN, tid);
 
@@ -389,20 +389,34 @@ __device__ __forceinline__ void gemm_mfma_body(const GemmParams& g, const int bl
 template <class Pol, bool STREAM>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmParams g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    gemm_mfma_body<Pol, STREAM>(g, (int)blockIdx.x, (int)gridDim.x, lds);
+    gemm_mfma_body<Pol, STREAM>(g, (int)blockIdx.x, (int)gridDim.x, lds, 0, gemm_item_count<Pol>(g));
 }
 
-// Two independent GEMMs in one launch: workgroups 0 .. blocks_a - 1 run the first (launch the one with
-// the longer items first), the rest the second.  Each part alone would leave compute units idle (few
-// long items) or pay its ramp-up and tail on its own; side by side they fill the chip for the length of
-// the longer part.  Both parts stream their items; blocks_a is a multiple of 8, so id mod 8 names the
-// XCD in both parts.
+// Two independent GEMMs in one launch, a few long items (first) and many short ones (second).  Each
+// alone would leave compute units idle or pay its ramp-up and tail on its own.  The grid is one resident
+// round: workgroups 0 .. blocks_a - 1 stream the first GEMM's items and then the last
+// items_b - main_b items of the second; the others stream items 0 .. main_b - 1 of the second.  The
+// host picks blocks_a and main_b so that both kinds of workgroup finish together.  blocks_a and main_b
+// are multiples of 8, so id mod 8 names the XCD in every part.
+struct PairPlan {
+    int blocks_a;      // workgroups that start with the first GEMM
+    int main_b;        // items of the second GEMM that the other workgroups share
+    int items_a, items_b;
+};
+
 template <class PolA, class PolB>
-__global__ __launch_bounds__(256) void gemm_mfma_pair_kernel(GemmParams ga, GemmParams gb, int blocks_a) {
+__global__ __launch_bounds__(256) void gemm_mfma_pair_kernel(GemmParams ga, GemmParams gb, PairPlan pl) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int b = (int)blockIdx.x;
-    if (b < blocks_a) gemm_mfma_body<PolA, true>(ga, b, blocks_a, lds);
-    else              gemm_mfma_body<PolB, true>(gb, b - blocks_a, (int)gridDim.x - blocks_a, lds);
+    if (b < pl.blocks_a) {
+        gemm_mfma_body<PolA, true>(ga, b, pl.blocks_a, lds, 0, pl.items_a);
+        if (pl.main_b < pl.items_b) {
+            __syncthreads();           // every wavefront is done with the stage buffers of the first part
+            gemm_mfma_body<PolB, true>(gb, b, pl.blocks_a, lds, pl.main_b, pl.items_b);
+        }
+    } else {
+        gemm_mfma_body<PolB, true>(gb, b - pl.blocks_a, (int)gridDim.x - pl.blocks_a, lds, 0, pl.main_b);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -613,23 +627,57 @@ static inline flurka_status launch_gemm_mfma(const GemmParams& g, hipStream_t s)
     return launch_gemm_mfma_impl<Pol, true>(g, resident, s);
 }
 
-// Both GEMMs in one launch (gemm_mfma_pair_kernel).  Falls back to two launches where a part cannot
-// stream (fewer than 8 resident workgroups).
+// Split of one resident round of `resident` workgroups between two GEMMs of items_a items of steps_a
+// reduction steps (items_a a multiple of 8) and items_b items of steps_b steps; `us` receives the time
+// the model expects.  Measured on MI355X with operands from HBM: 1.8 us per reduction step of a
+// workgroup that has a compute unit to itself, about 3 us for an epilogue that stores its accumulators
+// as they are, 4.4 us for the transposing epilogue of dK, dV.
+constexpr double G_STEP_US = 1.8, G_EPILOGUE_US = 3.0, G_EPILOGUE_T_US = 4.4;
+
+inline PairPlan plan_pair(int items_a, int steps_a, int items_b, int steps_b, int resident, double* us) {
+    const double ta = ((steps_a + 1) & ~1) * G_STEP_US + G_EPILOGUE_US;
+    const double tb = ((steps_b + 1) & ~1) * G_STEP_US + G_EPILOGUE_T_US;
+    PairPlan best{};
+    double best_t = -1.0;
+    for (int ba = 8; ba <= resident - 8; ba += 8) {
+        if (ba > items_a && ba > 8) break;                      // more starters than first-part items
+        const int bb = resident - ba;
+        const double t_first = ((items_a + ba - 1) / ba) * ta;
+        // items per workgroup of the second kind near the point where both kinds finish together
+        const int x0 = (int)((t_first / tb * ba + items_b) / resident);
+        for (int xb = x0 > 0 ? x0 : 1; xb <= x0 + 1; ++xb) {
+            long main_b = (long)bb * xb / 8 * 8;
+            if (main_b > items_b) main_b = items_b;
+            const int xa = (int)((items_b - main_b + ba - 1) / ba);
+            const double t_a = t_first + xa * tb, t_b = (double)((main_b + bb - 1) / bb) * tb;
+            const double t = t_a > t_b ? t_a : t_b;
+            if (best_t < 0.0 || t < best_t) {
+                best_t = t;
+                best.blocks_a = ba; best.main_b = (int)main_b; best.items_a = items_a; best.items_b = items_b;
+            }
+        }
+    }
+    if (us) *us = best_t;
+    return best;
+}
+
+// Both GEMMs in one launch (gemm_mfma_pair_kernel) with the split `pl` of a resident round of
+// `resident` workgroups (plan_pair).  Falls back to two launches where the kernel cannot keep 16
+// workgroups resident.
 template <class PolA, class PolB>
-static inline flurka_status launch_gemm_mfma_pair(const GemmParams& ga, const GemmParams& gb, hipStream_t s) {
+static inline flurka_status launch_gemm_mfma_pair(const GemmParams& ga, const GemmParams& gb, const PairPlan& pl,
+                                                  int resident, hipStream_t s) {
+    static_assert(PolA::SHARE_B && PolB::SHARE_B, "item counts and ranges in multiples of 8");
     auto kern = gemm_mfma_pair_kernel<PolA, PolB>;
     KernelFacts facts;
     if (!kernel_facts((const void*)kern, 256, G_LDS, &facts)) return FLURKA_ERR_LAUNCH;
-    const long resident = (long)facts.cus * facts.blocks_per_cu / 8 * 8;
-    if (resident < 8) {
+    if ((long)facts.cus * facts.blocks_per_cu < resident || pl.blocks_a < 8 || pl.blocks_a > resident - 8) {
         const flurka_status st = launch_gemm_mfma<PolA>(ga, s);
         return st != FLURKA_OK ? st : launch_gemm_mfma<PolB>(gb, s);
     }
-    const long items_a = gemm_item_count<PolA>(ga), items_b = gemm_item_count<PolB>(gb);
-    static_assert(PolA::SHARE_B, "the first part's item count must be a multiple of 8");
-    const int blocks_a = (int)(items_a < resident ? items_a : resident);
-    const int blocks_b = (int)(items_b < resident ? items_b : resident);
-    hipLaunchKernelGGL(kern, dim3(blocks_a + blocks_b), dim3(256), G_LDS, s, ga, gb, blocks_a);
+    int blocks_b = resident - pl.blocks_a;
+    if (blocks_b > pl.main_b) blocks_b = pl.main_b > 0 ? pl.main_b : 0;
+    hipLaunchKernelGGL(kern, dim3(pl.blocks_a + blocks_b), dim3(256), G_LDS, s, ga, gb, pl);
     if (hipGetLastError() != hipSuccess) return FLURKA_ERR_LAUNCH;
     return FLURKA_OK;
 }
