@@ -114,7 +114,7 @@ FLURKA_API size_t flurka_workspace_bytes(int B, int H, int n, int d, int k, int 
                               flurka_pass pass, flurka_algo algo);
 
 /* 1 if the bf16 MFMA kernels cover this problem for `pass`, else 0.  They take
- * bf16 storage, d = 64 or 128, n a multiple of 8 (forward) or of 64
+ * bf16 storage, d = 64 or 128, n a multiple of 8 (forward) or of 32
  * (backward), m a multiple of 32 and any
  * k, as long as the per-head operand images fit the 160 KiB of LDS of a
  * compute unit (random features, forward: m <= 512 at d = 64, m <= 288 at

@@ -1156,7 +1156,7 @@ static int bwd_x_lds_bytes(const Problem& p) {
 bool fast_bwd_supported(const Problem& p) {
     if (!p.bf16) return false;
     if (p.d != 64 && p.d != 128) return false;
-    if (p.n % 64 != 0 || p.mf % 32 != 0) return false;
+    if (p.n % 32 != 0 || p.mf % 32 != 0) return false;       // whole 32-row query tiles, whole feature tiles
     if (!p.elu && bwd_x_lds_bytes(p) > 160 * 1024) return false;
     // 32-bit byte offsets inside the gradient GEMMs' buffer descriptors
     if ((size_t)p.BH * p.n * p.d * 2 >= ((size_t)1 << 31)) return false;

@@ -123,6 +123,12 @@ BWD_SHAPES = [
     # sums of the chain rule cancel almost completely; a g_i taken from the rounded output alone, or S
     # rounded to a single bf16 term, puts tens of percent of error on dK here
     (1, 1, 32832, 64, 500, 32),
+    # sequence lengths that are odd multiples of 32: a last reduction step of the projection and last
+    # position tiles of the gradient GEMMs that are only partly there (both head sizes, the ring variant)
+    (1, 3, 96, 64, 40, 64),
+    (2, 2, 1056, 64, 100, 96),
+    (1, 2, 2080, 128, 300, 160),
+    (2, 2, 1056, 128, 256, 256),
 ]
 
 
@@ -138,7 +144,8 @@ def test_forward_backward_performer(shape):
 # elu1: dQ, dS, dz on MFMA kernels of their own, the key side on the generic kernels, the four
 # sequence-length GEMMs shared with the random-feature map
 @pytest.mark.parametrize("shape", [(1, 3, 192, 64, 100), (2, 4, 1024, 64, 256), (1, 2, 320, 128, 64),
-                                   (3, 5, 1088, 64, 96), (1, 2, 16384, 64, 256), (2, 2, 2048, 128, 300)])
+                                   (3, 5, 1088, 64, 96), (1, 2, 16384, 64, 256), (2, 2, 2048, 128, 300),
+                                   (2, 3, 160, 64, 100), (1, 2, 1056, 128, 300)])
 def test_forward_backward_elu(shape):
     B, H, n, d, k = shape
     w = Workload("fastbwd_elu", B, H, n, d, k, d, "bf16", PHI_ELU1, True)
@@ -205,6 +212,16 @@ def test_backward_matches_generic_kernels_closely():
     gen = gu.run_backward(w, g2, out2, ctx2, "generic")
     for name, a, b in zip(["dQ", "dK", "dV", "dE", "dF"], fast, gen):
         assert fo.rel_l2(gu.to_host(a), gu.to_host(b)) < 2e-2, name
+
+
+def test_sequence_length_that_only_the_forward_kernels_take():
+    """n = 200 is a multiple of 8 but not of 32: algo = auto runs the MFMA forward and the generic backward."""
+    w = Workload("ragged_n", 2, 3, 200, 64, 100, 96, "bf16", PHI_PERFORMER, True)
+    dims = (w.B, w.H, w.n, w.d, w.k, w.m)
+    assert fb.fast_path_supported(*dims, fb.BF16, w.phi, fb.PASS_FWD)
+    assert not fb.fast_path_supported(*dims, fb.BF16, w.phi, fb.PASS_BWD)
+    errs = gu.check_forward_backward(w, seed=24, algo="auto")
+    print({k_: f"{v:.2e}" for k_, v in errs.items()})
 
 
 def test_one_context_serves_both_kernel_families():
