@@ -31,6 +31,10 @@ FWD_SHAPES = [
     (2, 2, 72, 128, 8, 32),
     (1, 3, 1048, 128, 300, 160),
     (2, 3, 8, 64, 4, 32),
+    # more projection tiles than one resident round of workgroups: every workgroup streams several tiles,
+    # the requests for a tile's first steps being issued during the previous tile's last ones (with a
+    # ragged last step in each)
+    (8, 40, 200, 128, 40, 32),
 ]
 
 
