@@ -584,23 +584,6 @@ __global__ __launch_bounds__(512) void bwd_query_x_elu_kernel(BwdXEluArgs a) {
     }   // head segments
 }
 
-// fp32 dK', dV' (BH, k, d) of the generic key-side kernels -> the bf16 operand images of the two
-// gradient GEMMs: img (BH, kp, d) with zero rows past k, imgT (BH * d, kp).  blockIdx.y: dK' or dV'.
-__global__ void grad_images_kernel(const float* dKp, const float* dVp, uint16_t* img, uint16_t* imgT,
-                                   int k, int kp, int d, long per_tensor) {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;    // (bh, r < kp, t)
-    if (idx >= per_tensor) return;
-    const int t = (int)(idx % d);
-    const long rest = idx / d;
-    const int r = (int)(rest % kp);
-    const long bh = rest / kp;
-    const float* src = blockIdx.y ? dVp : dKp;
-    const float v = r < k ? src[(bh * k + r) * d + t] : 0.f;
-    const uint16_t b = (uint16_t)pack_bf16(v, 0.f);
-    img[blockIdx.y * per_tensor + idx] = b;
-    imgT[blockIdx.y * per_tensor + (bh * d + t) * kp + r] = b;
-}
-
 // ---------------------------------------------------------------------------
 // bwd_query_y: one wavefront per (head, feature tile, query range)
 // ---------------------------------------------------------------------------
@@ -1447,6 +1430,100 @@ static flurka_status launch_bwd_x_elu(const BwdXEluArgs& xa, hipStream_t s) {
     return FLURKA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// elu1 key side in one kernel (features = the d coordinates, so dS is d x d per head and everything a
+// key needs fits one workgroup): Phi = elu(K') + 1,
+//     dPhi_rj = sum_t V'_rt dS_jt + dz_j,   dK'_rj = dPhi_rj phi'(K'_rj),   dV'_rt = sum_j Phi_rj dS_jt,
+// all in fp32, results written straight as the bf16 operand images of the gradient GEMMs (img
+// (BH, kp, d) with zero rows past k, imgT (BH * d, kp); dV' follows dK' in both).  One workgroup per
+// (head, 32 keys); thread = (key, 8 columns).  The work is 4 d^2 flop per key: what matters is that it
+// is one launch.
+// ---------------------------------------------------------------------------
+template <int D>
+struct BwdKeyEluLds {
+    static constexpr int P = D + 1;                                        // padded row, floats
+    static constexpr int total = (D * P + 3 * 32 * P + D) * 4;            // dS, K', V', Phi tiles, dz
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_key_elu_fused_kernel(const float* Kp, const float* Vp, const float* dS,
+                                                                const float* dz, uint16_t* img, uint16_t* imgT,
+                                                                int BH, int k, int kp) {
+    extern __shared__ __attribute__((aligned(16))) float elu_key_lds[];
+    constexpr int P = BwdKeyEluLds<D>::P;
+    float* sdS = elu_key_lds;                   // [D][P]: dS[j][t]
+    float* sK = sdS + D * P;           // [32][P]: K' tile, later dK'
+    float* sV = sK + 32 * P;           // [32][P]: V' tile, later dV'
+    float* sPhi = sV + 32 * P;         // [32][P]
+    float* sdz = sPhi + 32 * P;        // [D]
+    const int tid = threadIdx.x;
+    const int KT = kp / 32;
+    const int kt = (int)(blockIdx.x % KT);
+    const long bh = blockIdx.x / KT;
+    for (int i = tid; i < D * D; i += 256) sdS[(i / D) * P + i % D] = dS[bh * D * D + i];
+    for (int i = tid; i < D; i += 256) sdz[i] = dz[bh * D + i];
+    for (int i = tid; i < 32 * D; i += 256) {
+        const int r = i / D, t = i % D, key = 32 * kt + r;
+        const float kv = key < k ? Kp[(bh * k + key) * D + t] : 0.f;
+        sK[r * P + t] = kv;
+        sV[r * P + t] = key < k ? Vp[(bh * k + key) * D + t] : 0.f;
+        sPhi[r * P + t] = elu1_of(kv);
+    }
+    __syncthreads();
+    const int r = tid >> 3, g = tid & 7;
+    const bool live = 32 * kt + r < k;
+    float rk[D / 8], rv[D / 8];
+#pragma unroll
+    for (int i = 0; i < D / 8; ++i) { rk[i] = sdz[g + 8 * i]; rv[i] = 0.f; }
+    for (int t = 0; t < D; ++t) {
+        const float v = sV[r * P + t], ph = sPhi[r * P + t];
+#pragma unroll
+        for (int i = 0; i < D / 8; ++i) {
+            rk[i] = fmaf(v, sdS[(g + 8 * i) * P + t], rk[i]);        // dPhi_rc, c = g + 8i
+            rv[i] = fmaf(ph, sdS[t * P + g + 8 * i], rv[i]);         // dV'_rc
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < D / 8; ++i) {
+        const float x = sK[r * P + g + 8 * i];
+        rk[i] = live ? rk[i] * (x > 0.f ? 1.f : __expf(x)) : 0.f;
+        rv[i] = live ? rv[i] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < D / 8; ++i) {
+        sK[r * P + g + 8 * i] = rk[i];
+        sV[r * P + g + 8 * i] = rv[i];
+    }
+    __syncthreads();
+    const long per_tensor = (long)BH * kp * D;
+    for (int i = tid; i < 32 * D; i += 256) {             // rows of the images: D consecutive columns
+        const int rr = i / D, c = i % D;
+        const long o = (bh * kp + 32 * kt + rr) * D + c;
+        img[o] = (uint16_t)pack_bf16(sK[rr * P + c], 0.f);
+        img[per_tensor + o] = (uint16_t)pack_bf16(sV[rr * P + c], 0.f);
+    }
+    for (int i = tid; i < 32 * D; i += 256) {             // transposed images: 32 consecutive keys
+        const int c = i / 32, rr = i % 32;
+        const long o = (bh * D + c) * kp + 32 * kt + rr;
+        imgT[o] = (uint16_t)pack_bf16(sK[rr * P + c], 0.f);
+        imgT[per_tensor + o] = (uint16_t)pack_bf16(sV[rr * P + c], 0.f);
+    }
+}
+
+template <int D>
+static flurka_status launch_bwd_key_elu(const Problem& p, const float* Kp, const float* Vp, const float* dS,
+                                        const float* dz, uint16_t* img, uint16_t* imgT, int kp, hipStream_t s) {
+    auto kern = bwd_key_elu_fused_kernel<D>;
+    constexpr int ldsb = BwdKeyEluLds<D>::total;
+    KernelFacts facts;
+    if (!kernel_facts((const void*)kern, 256, ldsb, &facts)) return FLURKA_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(p.BH * (kp / 32))), dim3(256), ldsb, s, Kp, Vp, dS, dz, img, imgT, p.BH,
+                       p.k, kp);
+    FLURKA_CHECK_LAUNCH();
+    return FLURKA_OK;
+}
+
 static flurka_status fast_backward_elu(const Problem& p, const BwdArgs& a, hipStream_t s) {
     const CtxLayout L = ctx_layout(p);
     const GenericWs GW = generic_ws_layout(p, 1);
@@ -1483,17 +1560,16 @@ static flurka_status fast_backward_elu(const Problem& p, const BwdArgs& a, hipSt
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_MERGE);
     }
-    // key side: dQ is written and dS, dz are in place; stop before the sequence-length GEMMs
-    if ((st = generic_backward_from(p, a, s, 3)) != FLURKA_OK) return st;
+    // key side: dQ is written and dS, dz are in place
     uint16_t* img = (uint16_t*)(wsb + W.img);
     uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
     {
         StageScope sc(s, STAGE_K_BWD_KEY);
-        const long per_tensor = (long)p.BH * W.kp * p.d;
-        hipLaunchKernelGGL(grad_images_kernel, dim3((unsigned)((per_tensor + 255) / 256), 2), dim3(256), 0, s,
-                           (const float*)(a.ws + GW.dKp), (const float*)(a.ws + GW.dVp), img, imgT, p.k, W.kp, p.d,
-                           per_tensor);
-        FLURKA_CHECK_LAUNCH();
+        const float* Kp = a.ctx + L.Kp;
+        const float* Vp = a.ctx + L.Vp;
+        st = p.d == 64 ? launch_bwd_key_elu<64>(p, Kp, Vp, a.ws + GW.dS, a.ws + GW.dz, img, imgT, W.kp, s)
+                       : launch_bwd_key_elu<128>(p, Kp, Vp, a.ws + GW.dS, a.ws + GW.dz, img, imgT, W.kp, s);
+        if (st != FLURKA_OK) return st;
     }
     return grad_gemms(p, a, img, imgT, W.kp, (float*)(wsb + W.epart), s);
 }
