@@ -55,34 +55,67 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
-    for (int k0 = 0; k0 < g.K; k0 += GK) {
+    // this thread's four elements of the A tile and of the B tile: LDS positions (fixed) and the loads of
+    // one reduction step; the loads of step k0 + GK are in flight while step k0 is being multiplied
+    int a_mm[4], a_kk[4], b_nn[4], b_kk[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (g.a_kfast) { a_kk[i] = tid & 15; a_mm[i] = (tid >> 4) + 16 * i; }
+        else           { a_mm[i] = tid & 63; a_kk[i] = (tid >> 6) + 4 * i; }
+        if (g.b_kfast) { b_kk[i] = tid & 15; b_nn[i] = (tid >> 4) + 16 * i; }
+        else           { b_nn[i] = tid & 63; b_kk[i] = (tid >> 6) + 4 * i; }
+    }
+    const bool one_level = g.Kin >= g.K;        // the reduction index is not a (outer, inner) pair
+    // element offsets of reduction step 0 (one-level index: a step adds GK * stride)
+    long pa[4], pb[4];
+    bool va[4], vb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        va[i] = m0 + a_mm[i] < g.M;
+        vb[i] = n0 + b_nn[i] < g.N;
+        pa[i] = aoff + (long)(m0 + a_mm[i]) * g.sAm + (long)a_kk[i] * g.sAki;
+        pb[i] = boff + (long)(n0 + b_nn[i]) * g.sBn + (long)b_kk[i] * g.sBki;
+    }
+    float ra[4], rb[4];
+    auto fetch = [&](int k0) {
+        if (one_level) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ra[i] = (va[i] && k0 + a_kk[i] < g.K) ? load_elem(g.A, pa[i] + (long)k0 * g.sAki, g.a_bf16) : 0.f;
+                rb[i] = (vb[i] && k0 + b_kk[i] < g.K) ? load_elem(g.B, pb[i] + (long)k0 * g.sBki, g.b_bf16) : 0.f;
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int mm, kk;
-            if (g.a_kfast) { kk = tid & 15; mm = (tid >> 4) + 16 * i; }
-            else           { mm = tid & 63; kk = (tid >> 6) + 4 * i; }
-            const int gm = m0 + mm, gk = k0 + kk;
+            const int gm = m0 + a_mm[i], gk = k0 + a_kk[i];
             float v = 0.f;
             if (gm < g.M && gk < g.K) {
                 const int ko = gk / g.Kin, ki = gk - ko * g.Kin;
                 v = load_elem(g.A, aoff + (long)gm * g.sAm + (long)ki * g.sAki + (long)ko * g.sAko, g.a_bf16);
             }
-            As[kk][mm] = v;
+            ra[i] = v;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int nn, kk;
-            if (g.b_kfast) { kk = tid & 15; nn = (tid >> 4) + 16 * i; }
-            else           { nn = tid & 63; kk = (tid >> 6) + 4 * i; }
-            const int gn = n0 + nn, gk = k0 + kk;
+            const int gn = n0 + b_nn[i], gk = k0 + b_kk[i];
             float v = 0.f;
             if (gn < g.N && gk < g.K) {
                 const int ko = gk / g.Kin, ki = gk - ko * g.Kin;
                 v = load_elem(g.B, boff + (long)gn * g.sBn + (long)ki * g.sBki + (long)ko * g.sBko, g.b_bf16);
             }
-            Bs[kk][nn] = v;
+            rb[i] = v;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < g.K; k0 += GK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            As[a_kk[i]][a_mm[i]] = ra[i];
+            Bs[b_kk[i]][b_nn[i]] = rb[i];
         }
         __syncthreads();
+        if (k0 + GK < g.K) fetch(k0 + GK);
         // two-level summation: a 16-term partial, then one add into the running sum
         float part[4][4];
 #pragma unroll
