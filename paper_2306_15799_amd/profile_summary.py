@@ -1,12 +1,12 @@
 """Turns rocprofv3 CSV output into the short text summaries kept under profiles/.
 
     python -m paper_2306_15799_amd.profile_summary trace   <r_kernel_stats.csv> <out.txt> "<command>"
-    python -m paper_2306_15799_amd.profile_summary traffic <workload> [<workload> ...]
+    python -m paper_2306_15799_amd.profile_summary traffic <raw_dir> <workload> [<workload> ...]
     python -m paper_2306_15799_amd.profile_summary pmc     <out.txt> "<command>" <r_counter_collection.csv> [...]
 
-`traffic` reads gpurun_out/pmc_fetch_<W>/r_counter_collection.csv and
-gpurun_out/pmc_write_<W>/r_counter_collection.csv (one counter per rocprofv3
-run), scales both counters by what they report for a copy of known size in the
+`traffic` reads <raw_dir>/pmc_fetch_<W>/r_counter_collection.csv and
+<raw_dir>/pmc_write_<W>/r_counter_collection.csv (one counter per rocprofv3
+run, raw_dir relative to the repository root), scales both counters by what they report for a copy of known size in the
 same run (torch's fp32 -> bf16 conversion of Q when bench.py uploads the
 inputs) and writes profiles/hbm_traffic_<W>.txt plus the machine-readable
 profiles/hbm_traffic.json that bench.py reads.  The JSON is stamped with a hash
@@ -78,7 +78,7 @@ def trace(path: str, out: str, cmd: str) -> None:
     print(open(out).read())
 
 
-def traffic(workloads) -> None:
+def traffic(raw_dir, workloads) -> None:
     from paper_2306_15799_amd import inputs
     jpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     out_json = json.load(open(jpath)) if os.path.exists(jpath) else {}
@@ -87,7 +87,7 @@ def traffic(workloads) -> None:
         wl = {**inputs.WORKLOADS, **inputs.DERIVED_WORKLOADS}[w]
         vals = {}
         for f in ["fetch", "write"]:
-            p = os.path.join(ROOT, f"gpurun_out/pmc_{f}_{w}/r_counter_collection.csv")
+            p = os.path.join(ROOT, raw_dir, f"pmc_{f}_{w}/r_counter_collection.csv")
             d = collections.defaultdict(list)
             for r in csv.DictReader(open(p)):
                 d[short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
@@ -97,7 +97,7 @@ def traffic(workloads) -> None:
         elems = wl.B * wl.H * wl.n * wl.d
         ffac = elems * 4 / 1024 / vals["fetch"][copy][0]
         wfac = elems * 2 / 1024 / vals["write"][copy][0]
-        cmd = ("rocprofv3 --pmc {c} --output-format csv -d gpurun_out/pmc_{f}_{w} -o r -- python3 bench.py "
+        cmd = ("rocprofv3 --pmc {c} --output-format csv -d " + raw_dir.rstrip("/") + "/pmc_{f}_{w} -o r -- python3 bench.py "
                "--workload {w} --steps 3 --warmup 1 --no-cpu-baseline --no-measured-peaks --no-configs")
         lines = [f"HBM traffic per dispatch, workload {w} (rocprofv3 --pmc, KiB per dispatch, mean over dispatches)",
                  "commands (run from the repository root on the GPU box, one counter per run):",
@@ -151,7 +151,7 @@ if __name__ == "__main__":
     if sys.argv[1] == "trace":
         trace(*sys.argv[2:5])
     elif sys.argv[1] == "traffic":
-        traffic(sys.argv[2:])
+        traffic(sys.argv[2], sys.argv[3:])
     elif sys.argv[1] == "pmc":
         pmc(sys.argv[2], sys.argv[3], sys.argv[4:])
     else:
