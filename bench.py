@@ -506,6 +506,40 @@ def main():
                                         "tflops": c4["tflops"], "gbs": c4["gbs"], "binding_roof": c4["binding_roof"],
                                         "roof_ms": c4["roof_ms"], "frac_of_binding_roof": c4["frac_of_binding_roof"],
                                         "target_frac": 0.5}
+                if not args.no_measured_peaks:
+                    # the vendor library on the projection's own shape (context for the kernel that takes half
+                    # of this step): K' = E K alone, as one GEMM on a position-major copy of K and as a GEMM
+                    # batched over the heads; the library's kernel computes K' and V' (twice the flops)
+                    dev = torch.device("cuda:0")
+                    e_ = torch.randn(wn.k, wn.n, device=dev, dtype=torch.bfloat16)
+                    k_ = torch.randn(wn.B * wn.H, wn.n, wn.d, device=dev, dtype=torch.bfloat16)
+                    kw_ = k_.permute(1, 0, 2).reshape(wn.n, wn.B * wn.H * wn.d).contiguous()
+
+                    def timed_ms(fn, reps=20):
+                        t_end = time.perf_counter() + 0.2
+                        while time.perf_counter() < t_end:
+                            fn()
+                        torch.cuda.synchronize()
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        for _ in range(reps):
+                            fn()
+                        e1.record(); torch.cuda.synchronize()
+                        return e0.elapsed_time(e1) / reps
+                    flop_one = 2.0 * wn.k * wn.n * wn.B * wn.H * wn.d
+                    ms_flat = timed_ms(lambda: torch.matmul(e_, kw_))
+                    ms_bat = timed_ms(lambda: torch.matmul(e_.unsqueeze(0), k_))
+                    proj_ms = c4.get("kernels_ms", {}).get("gemm_mfma_proj")
+                    result["north_star"]["projection_vs_vendor_gemm"] = {
+                        "this_library_ms_for_K_and_V": proj_ms,
+                        "this_library_tflops": round(2 * flop_one / (proj_ms * 1e-3) / 1e12, 1) if proj_ms else None,
+                        "vendor_one_gemm_ms_for_K_only": round(ms_flat, 4),
+                        "vendor_one_gemm_tflops": round(flop_one / (ms_flat * 1e-3) / 1e12, 1),
+                        "vendor_batched_over_heads_ms_for_K_only": round(ms_bat, 4),
+                        "vendor_batched_tflops": round(flop_one / (ms_bat * 1e-3) / 1e12, 1),
+                        "how": "torch.matmul, bf16, (k x n)(n x B*H*d) on a position-major copy of K, and (k x n)(n x d) "
+                               "batched over the B*H heads in the library's own layout"}
+                    del e_, k_, kw_
             del rn
             torch.cuda.empty_cache()
         result["configs"] = configs
