@@ -27,10 +27,7 @@ def _shapes(count, seed, backward):
         # fp32 ones included, returns rounding noise for them
         k = int(rng.integers(max(2, n // 40), 600)) if n // 40 < 600 else 600
         m = d if phi == PHI_ELU1 else 32 * int(rng.integers(1, 9))
-        pass_ = fb.PASS_BWD if backward else fb.PASS_FWD
-        if not fb.fast_path_supported(B, H, n, d, k, m, fb.BF16, phi, pass_):
-            continue
-        out.append((B, H, n, d, k, m, phi))
+        out.append((B, H, n, d, k, m, phi))     # within the MFMA kernels' limits by construction (asserted below)
     return out
 
 
@@ -38,6 +35,7 @@ def _shapes(count, seed, backward):
 def test_forward(shape):
     B, H, n, d, k, m, phi = shape
     w = Workload("random_fwd", B, H, n, d, k, m, "bf16", phi, False)
+    assert fb.fast_path_supported(B, H, n, d, k, m, fb.BF16, phi, fb.PASS_FWD)
     err = gu.check_forward(w, seed=n + k, algo="fast")
     print(shape, f"rel-L2 {err:.3e}")
 
@@ -46,5 +44,6 @@ def test_forward(shape):
 def test_forward_backward(shape):
     B, H, n, d, k, m, phi = shape
     w = Workload("random_bwd", B, H, n, d, k, m, "bf16", phi, True)
+    assert fb.fast_path_supported(B, H, n, d, k, m, fb.BF16, phi, fb.PASS_BWD)
     errs = gu.check_forward_backward(w, seed=n + k, algo="fast")
     print(shape, {k_: f"{v:.2e}" for k_, v in errs.items() if ":" not in k_})
