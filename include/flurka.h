@@ -115,7 +115,7 @@ FLURKA_API size_t flurka_workspace_bytes(int B, int H, int n, int d, int k, int 
 
 /* 1 if the bf16 MFMA kernels cover this problem for `pass`, else 0.  They take
  * bf16 storage, d = 64 or 128, n a multiple of 8 (forward) or of 32
- * (backward), m a multiple of 32 and any
+ * (backward), any m and any
  * k, as long as the per-head operand images fit the 160 KiB of LDS of a
  * compute unit (random features, forward: m <= 512 at d = 64, m <= 288 at
  * d = 128; backward: m <= 288 at d = 64, m <= 256 at d = 128; ELU1: always). */
@@ -186,8 +186,8 @@ FLURKA_API flurka_status flurka_attn_fwd_static(const void* Q, const void* K, co
  *   E, F, omega, out, ctx           as in flurka_attn_fwd; ctx holds the same state afterwards
  *   workspace      flurka_fused_w_workspace_bytes(...) bytes, 256-byte aligned
  *
- * Only the bf16 MFMA kernels implement this order: bf16 storage, d = 64 or 128, n a multiple of 8, m a
- * multiple of 32, dm a multiple of 64, H*d a multiple of 256; anything else returns
+ * Only the bf16 MFMA kernels implement this order: bf16 storage, d = 64 or 128, n a multiple of 8, m within
+ * the forward's limit, dm a multiple of 64, H*d a multiple of 256; anything else returns
  * FLURKA_ERR_UNSUPPORTED (flurka_fused_w_supported tells beforehand).  No backward pass is provided for
  * this entry point.
  */

@@ -103,6 +103,7 @@ flurka_status make_problem(int B, int H, int n, int d, int k, int m, int omega_p
     p.B = B; p.H = H; p.n = n; p.d = d; p.k = k; p.m = m;
     p.elu = (phi == FLURKA_PHI_ELU1);
     p.mf = p.elu ? d : m;
+    p.mfp = (p.mf + 31) / 32 * 32;
     p.BH = B * H;
     p.omega_per_head = omega_per_head ? 1 : 0;
     p.bf16 = (dtype == FLURKA_BF16);

@@ -65,7 +65,8 @@ struct BwdXArgs {
     uint16_t* dQ;
     float* delta;              // (BH, n)  g_i
     float* lam2;               // (BH, n)  lambda_i + ln sB_i: the normaliser the dS kernel uses
-    int n, H, mf, tiles_per_head;   // tiles of 32 rows
+    int n, H, mf, tiles_per_head;   // mf: features incl. the padding of a ragged last tile; tiles of 32 rows
+    int mr;                         // features that exist (rows of omega, strides of S, z, c in ctx)
     long total_tiles;               // BH * tiles_per_head
     long omega_head_stride;    // 0 if shared
 };
@@ -136,10 +137,14 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
     // omega as it lies; S_j / z_j as two bf16 terms (hi + lo), 8 slots per chunk: the slots of dOut's
     // operand order (head size 64: slot 8h + e of a group of 16 holds t = 8*(e/4) + 4*h + e%4; direct:
     // t = slot); c + ln z in the accumulator order of a 32-feature tile
-    const float* Sg = a.S + (long)bh * mf * D;
-    const float* zg = a.z + (long)bh * mf;
+    // Features past mr (the padding of a ragged last tile) get omega = 0, S/z = 0 and c' = -inf: their
+    // weights b are exactly 0 and nothing of them reaches dQ, g or lambda.
+    const int mr = a.mr;
+    const float* Sg = a.S + (long)bh * mr * D;
+    const float* zg = a.z + (long)bh * mr;
     constexpr int cpr = D / 8;
     auto sp_terms = [&](int r, int q, uint4& hi4, uint4& lo4) {      // chunk q of feature row r
+        if (r >= mr) { hi4 = make_uint4(0u, 0u, 0u, 0u); lo4 = hi4; return; }
         const int t0 = DIRECT ? 8 * q : 16 * (q >> 1) + 4 * (q & 1);
         const float4 s0 = *(const float4*)(Sg + (long)r * D + t0);
         const float4 s1 = *(const float4*)(Sg + (long)r * D + t0 + (DIRECT ? 4 : 8));
@@ -155,7 +160,7 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
         for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
-            *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = ld16(og + (long)r * D + 8 * q);
+            *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = r < mr ? ld16(og + (long)r * D + 8 * q) : make_uint4(0u, 0u, 0u, 0u);
             uint4 hi, lo;
             sp_terms(r, q, hi, lo);
             *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = hi;
@@ -166,11 +171,11 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
             sp_terms(tid / cpr, tid % cpr, hi, lo);
             *(uint4*)(lsl + (tid / cpr) * L::sp_pitch + 16 * (tid % cpr)) = lo;
         }
-        const float* cg = a.c + (long)bh * mf;
+        const float* cg = a.c + (long)bh * mr;
         for (int slot = tid; slot < mf; slot += X_NW * 64) {
             const int g = slot & 15, h = (slot >> 4) & 1;
             const int f = (slot & ~31) + 8 * (g >> 2) + 4 * h + (g & 3);
-            lc[slot] = cg[f] + logf(zg[f]);
+            lc[slot] = f < mr ? cg[f] + logf(zg[f]) : -INFINITY;
         }
     }
     // tiles of the segment are handed out on demand (see query_stream_kernel): wavefront w starts with
@@ -597,7 +602,8 @@ struct BwdYArgs {
     float* dSpart;             // (BH, R, mf, d)
     float* dzpart;             // (BH, R, mf)
     long omega_head_stride;
-    int BH, H, n, mf, FT, R, tiles_per_range;
+    int BH, H, n, mf, FT, R, tiles_per_range;   // mf incl. the padding of a ragged last feature tile
+    int mr;                                     // features that exist (rows of omega, stride of c)
 };
 
 // A workgroup is NW wavefronts = NW feature tiles of one (head, query range).  They need the same
@@ -657,10 +663,12 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
     uint4 wf[KS];
     float cj = 0.f;
     if constexpr (!ELU) {
-        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ftc + l32) * D + 8 * half;
+        // a feature of the padding: omega = 0 and c = -inf, so its weights and its rows of dS, dz are 0
+        const bool real = 32 * ftc + l32 < a.mr;
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(real ? 32 * ftc + l32 : 0) * D + 8 * half;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
-        cj = a.c[(long)bh * a.mf + 32 * ftc + l32] * LOG2E;
+        for (int s = 0; s < KS; ++s) wf[s] = real ? ld16(og + 16 * s) : make_uint4(0u, 0u, 0u, 0u);
+        cj = real ? a.c[(long)bh * a.mr + 32 * ftc + l32] * LOG2E : -INFINITY;
     }
     floatx16 accS[TT];
 #pragma unroll
@@ -841,7 +849,8 @@ struct BwdKeyArgs {
     uint16_t* img;     // 2 x (BH, kp, d): dK' then dV'
     uint16_t* imgT;    // 2 x (BH * d, kp)
     long omega_head_stride;
-    int BH, H, k, kp, mf;
+    int BH, H, k, kp, mf;   // mf incl. the padding of a ragged last feature tile (strides of dSimg, dz)
+    int mr;                 // features that exist (rows of omega, stride of c)
 };
 
 // One workgroup per (head, 32 keys); its four wavefronts take every fourth feature tile and add their
@@ -941,14 +950,19 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
 #pragma unroll
     for (int t = 0; t < TT; ++t) { accV[t] = zero16(); accK[t] = zero16(); }
     float rs = 0.f;
-    const float* cg = a.c + (long)bh * a.mf + 4 * half;
+    const float* cg = a.c + (long)bh * a.mr + 4 * half;
     const float* zg = a.dz + (long)bh * a.mf + 4 * half;
 
     for (int ft = wave; ft < FT; ft += 4) {
         float4 cv4[4], zv4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            cv4[q] = *(const float4*)(cg + 32 * ft + 8 * q);
+            // c of a padding feature = +inf: PhiK = exp(-inf) = 0 (ctx rows are mr long: scalar loads)
+            const int f0 = 32 * ft + 8 * q + 4 * half;
+            cv4[q].x = f0 < a.mr ? cg[32 * ft + 8 * q] : INFINITY;
+            cv4[q].y = f0 + 1 < a.mr ? cg[32 * ft + 8 * q + 1] : INFINITY;
+            cv4[q].z = f0 + 2 < a.mr ? cg[32 * ft + 8 * q + 2] : INFINITY;
+            cv4[q].w = f0 + 3 < a.mr ? cg[32 * ft + 8 * q + 3] : INFINITY;
             zv4[q] = *(const float4*)(zg + 32 * ft + 8 * q);
         }
         {   // this feature tile's rows of omega and dS, row-major, into the wavefront's LDS area
@@ -958,7 +972,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
 #pragma unroll
             for (int u = 0; u < LPT; ++u) {
                 const int chunk = lane + 64 * u, row = chunk / CPR, c = chunk % CPR;
-                const uint4 x0 = ld16(ob + row * D + 8 * c);
+                const uint4 x0 = 32 * ft + row < a.mr ? ld16(ob + row * D + 8 * c) : make_uint4(0u, 0u, 0u, 0u);
                 const uint4 x1 = ld16(sb + row * D + 8 * c);
                 const uint4 x2 = ld16(sb + ds_plane + row * D + 8 * c);
                 unsigned char* dst = tw + row * P + 16 * c;
@@ -1130,16 +1144,16 @@ __global__ __launch_bounds__(256) void sum_splits_bf16_kernel(SumSplitsArgs a) {
 // ---------------------------------------------------------------------------
 // bwd_query_x keeps all its operand images in LDS where they fit; at d = 128 the lo terms of S/z go
 // through a two-slot ring otherwise (see BwdXLds)
-static bool bwd_x_ring(const Problem& p) { return p.d == 128 && BwdXLds<128>::total(p.mf) > 160 * 1024; }
+static bool bwd_x_ring(const Problem& p) { return p.d == 128 && BwdXLds<128>::total(p.mfp) > 160 * 1024; }
 static int bwd_x_lds_bytes(const Problem& p) {
-    if (p.d == 64) return BwdXLds<64>::total(p.mf);
-    return bwd_x_ring(p) ? BwdXLds<128, true>::total(p.mf) : BwdXLds<128>::total(p.mf);
+    if (p.d == 64) return BwdXLds<64>::total(p.mfp);
+    return bwd_x_ring(p) ? BwdXLds<128, true>::total(p.mfp) : BwdXLds<128>::total(p.mfp);
 }
 
 bool fast_bwd_supported(const Problem& p) {
     if (!p.bf16) return false;
     if (p.d != 64 && p.d != 128) return false;
-    if (p.n % 32 != 0 || p.mf % 32 != 0) return false;       // whole 32-row query tiles, whole feature tiles
+    if (p.n % 32 != 0) return false;                         // whole 32-row query tiles
     if (!p.elu && bwd_x_lds_bytes(p) > 160 * 1024) return false;
     // 32-bit byte offsets inside the gradient GEMMs' buffer descriptors
     if ((size_t)p.BH * p.n * p.d * 2 >= ((size_t)1 << 31)) return false;
@@ -1198,7 +1212,7 @@ struct BwdYPlan { int FT, NW, R, tiles_per_range; };
 
 static BwdYPlan bwd_y_plan(const Problem& p) {
     BwdYPlan q;
-    q.FT = p.mf / 32;
+    q.FT = p.mfp / 32;
     q.NW = q.FT > 4 ? 8 : 4;                      // wavefronts (= feature tiles) per workgroup
     const int QT = p.n / 32;
     const int FG = (q.FT + q.NW - 1) / q.NW;
@@ -1225,10 +1239,10 @@ static FastBwdWs fast_bwd_ws_layout(const Problem& p) {
     size_t o = 0;
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.lam2 = o;   o += round_up(BH * p.n * 4, 256);
-    W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
-    W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
-    W.dSimg = o;  o += round_up(2 * BH * p.mf * p.d * 2, 256);
-    W.dz = o;     o += round_up(BH * p.mf * 4, 256);
+    W.dSpart = o; o += round_up(BH * y.R * p.mfp * p.d * 4, 256);
+    W.dzpart = o; o += round_up(BH * y.R * p.mfp * 4, 256);
+    W.dSimg = o;  o += round_up(2 * BH * p.mfp * p.d * 2, 256);
+    W.dz = o;     o += round_up(BH * p.mfp * 4, 256);
     W.kp = (p.k + 63) / 64 * 64;
     const GradEPlan e = grad_e_plan(p);
     W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);        // dK' then dV'
@@ -1253,8 +1267,8 @@ static EluBwdWs elu_bwd_ws_layout(const Problem& p) {
     size_t o = round_up(generic_ws_layout(p, 1).total * sizeof(float), 256);
     W.delta = o;  o += round_up(BH * p.n * 4, 256);
     W.dinv = o;   o += round_up(BH * p.n * 4, 256);
-    W.dSpart = o; o += round_up(BH * y.R * p.mf * p.d * 4, 256);
-    W.dzpart = o; o += round_up(BH * y.R * p.mf * 4, 256);
+    W.dSpart = o; o += round_up(BH * y.R * p.mfp * p.d * 4, 256);
+    W.dzpart = o; o += round_up(BH * y.R * p.mfp * 4, 256);
     W.kp = (p.k + 63) / 64 * 64;
     W.img = o;    o += round_up(2 * BH * W.kp * p.d * 2, 256);
     W.imgT = o;   o += round_up(2 * BH * W.kp * p.d * 2, 256);
@@ -1364,7 +1378,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         xa.S = a.ctx + L.S; xa.z = a.ctx + L.z; xa.c = a.ctx + L.c;
         xa.dQ = (uint16_t*)a.dQ; xa.lse = a.ctx + L.lse; xa.delta = (float*)(wsb + W.delta);
         xa.lam2 = (float*)(wsb + W.lam2);
-        xa.n = p.n; xa.H = p.H; xa.mf = p.mf; xa.omega_head_stride = omega_stride;
+        xa.n = p.n; xa.H = p.H; xa.mf = p.mfp; xa.mr = p.mf; xa.omega_head_stride = omega_stride;
         xa.tiles_per_head = (p.n + 31) / 32;
         xa.total_tiles = (long)p.BH * xa.tiles_per_head;
         const int ldsb = bwd_x_lds_bytes(p);
@@ -1379,7 +1393,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ya.lse = xa.lam2; ya.delta = xa.delta;
         ya.dSpart = (float*)(wsb + W.dSpart); ya.dzpart = (float*)(wsb + W.dzpart);
         ya.omega_head_stride = omega_stride;
-        ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
+        ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mfp; ya.mr = p.mf; ya.FT = y.FT; ya.R = y.R;
         ya.tiles_per_range = y.tiles_per_range;
         stage_begin(s);
         if ((st = launch_bwd_y(p, ya, y, s)) != FLURKA_OK) return st;
@@ -1390,10 +1404,10 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
     uint16_t* imgT = (uint16_t*)(wsb + W.imgT);
     {
         stage_begin(s);
-        const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
+        const long mtotal = (long)p.BH * (p.mfp / 2) * p.d;
         hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)(wsb + W.dSimg),
                            (float*)nullptr, (float*)(wsb + W.dz), (const float*)(wsb + W.dSpart),
-                           (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
+                           (const float*)(wsb + W.dzpart), y.R, p.mfp, p.d, mtotal);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_MERGE);
         StageScope sc(s, STAGE_K_BWD_KEY);
@@ -1404,7 +1418,7 @@ flurka_status fast_backward(const Problem& p, const BwdArgs& a, hipStream_t s) {
         ka.dz = (const float*)(wsb + W.dz);
         ka.img = img; ka.imgT = imgT;
         ka.omega_head_stride = omega_stride;
-        ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kp = W.kp; ka.mf = p.mf;
+        ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kp = W.kp; ka.mf = p.mfp; ka.mr = p.mf;
         const unsigned kgrid = (unsigned)((p.BH + 7) / 8 * 8 * (W.kp / 32));
         const int klds = p.d == 64 ? BwdKeyLds<64>::total : BwdKeyLds<128>::total;
         const void* kk = p.d == 64 ? (const void*)bwd_key_kernel<64> : (const void*)bwd_key_kernel<128>;
@@ -1546,17 +1560,17 @@ static flurka_status fast_backward_elu(const Problem& p, const BwdArgs& a, hipSt
         BwdYArgs ya{};
         ya.Q = xa.Q; ya.G = xa.G; ya.lse = xa.dinv; ya.delta = xa.delta;
         ya.dSpart = (float*)(wsb + W.dSpart); ya.dzpart = (float*)(wsb + W.dzpart);
-        ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mf; ya.FT = y.FT; ya.R = y.R;
+        ya.BH = p.BH; ya.H = p.H; ya.n = p.n; ya.mf = p.mfp; ya.mr = p.mf; ya.FT = y.FT; ya.R = y.R;
         ya.tiles_per_range = y.tiles_per_range;
         stage_begin(s);
         if ((st = launch_bwd_y(p, ya, y, s)) != FLURKA_OK) return st;
         stage_end(s, STAGE_K_BWD_Y);
 
         stage_begin(s);
-        const long mtotal = (long)p.BH * (p.mf / 2) * p.d;
+        const long mtotal = (long)p.BH * (p.mfp / 2) * p.d;
         hipLaunchKernelGGL(bwd_merge_kernel, grid1d(mtotal, 256), dim3(256), 0, s, (uint16_t*)nullptr,
                            a.ws + GW.dS, a.ws + GW.dz, (const float*)(wsb + W.dSpart),
-                           (const float*)(wsb + W.dzpart), y.R, p.mf, p.d, mtotal);
+                           (const float*)(wsb + W.dzpart), y.R, p.mfp, p.d, mtotal);
         FLURKA_CHECK_LAUNCH();
         stage_end(s, STAGE_K_BWD_MERGE);
     }

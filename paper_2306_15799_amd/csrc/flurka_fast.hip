@@ -60,7 +60,8 @@ struct QueryArgs {
     const uint16_t* cw;        // (BH, mf, 4) bf16 terms of c + ln z (performer)
     uint16_t* out;
     float* lse;                // (BH, n) log of the denominator, kept for the backward pass
-    int n, H, mf, tiles_per_head;   // tiles of 32*QT rows
+    int n, H, mf, tiles_per_head;   // mf: features incl. the padding of a ragged last tile; tiles of 32*QT rows
+    int m_rows;                     // rows of omega that exist
     long total_tiles;               // BH * tiles_per_head
     long omega_head_stride;    // 0 if shared
 };
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
         constexpr int cpr = D / 8;                      // chunks per row
         for (int c = tid; c < mf * cpr; c += NW * 64) {
             const int r = c / cpr, q = c % cpr;
-            *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)r * D + 8 * q);
+            *(uint4*)(lw + r * L::w_pitch + 16 * q) = r < a.m_rows ? ld16(og + (long)r * D + 8 * q) : make_uint4(0u, 0u, 0u, 0u);
         }
         const uint16_t* cwg = a.cw + (long)bh * mf * 4;
         for (int r = tid; r < mf; r += NW * 64) {
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
 // Host side
 // ===========================================================================
 static int query_lds_bytes(const Problem& p) {
-    return p.d == 64 ? QueryLds<64>::total(p.mf, p.elu) : QueryLds<128>::total(p.mf, p.elu);
+    return p.d == 64 ? QueryLds<64>::total(p.mfp, p.elu) : QueryLds<128>::total(p.mfp, p.elu);
 }
 
 bool fast_supported(const Problem& p, int bwd) {
@@ -289,7 +290,6 @@ bool fast_supported(const Problem& p, int bwd) {
     if (!p.bf16) return false;
     if (p.d != 64 && p.d != 128) return false;
     if (p.n % 8 != 0) return false;                // rows of E and F start on 16-byte boundaries
-    if (p.mf % 32 != 0) return false;
     if (query_lds_bytes(p) > 160 * 1024) return false;
     // 32-bit byte offsets inside the projection's buffer descriptors
     if (((size_t)p.k + PBM) * (size_t)p.n * 2 >= ((size_t)1 << 31)) return false;
@@ -320,9 +320,9 @@ static FastWs fast_ws_layout(const Problem& p) {
     W.Kimg = o;    o += round_up(p.elu ? 0 : 3 * BH * ks.kpad * p.d * 2, 256);
     W.Vimg = o;    o += round_up(2 * BH * (ks.kpad / 2) * p.d * 4, 256);
     W.nrm = o;     o += round_up(BH * ks.kpad * 4, 256);
-    W.St = o;      o += round_up(BH * p.d * p.mf * 2, 256);
-    W.zp = o;      o += round_up(BH * p.mf * 4, 256);
-    W.cw = o;      o += round_up(BH * p.mf * 8, 256);
+    W.St = o;      o += round_up(BH * p.d * p.mfp * 2, 256);
+    W.zp = o;      o += round_up(BH * p.mfp * 4, 256);
+    W.cw = o;      o += round_up(BH * p.mfp * 8, 256);
     W.total = o;
     return W;
 }
@@ -371,7 +371,7 @@ static flurka_status run_query_stream(const Problem& p, const void* Q, const voi
     qa.cw = cw;
     qa.out = (uint16_t*)out;
     qa.lse = lse;
-    qa.n = p.n; qa.H = p.H; qa.mf = p.mf;
+    qa.n = p.n; qa.H = p.H; qa.mf = p.mfp; qa.m_rows = p.mf;
     qa.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
     qa.tiles_per_head = (p.n + 32 * QS_QT - 1) / (32 * QS_QT);
     qa.total_tiles = (long)p.BH * qa.tiles_per_head;
@@ -586,9 +586,9 @@ static KernelAttnWs kernel_attn_ws_layout(const Problem& p) {
     W.Kimg = o; o += round_up(p.elu ? 0 : BH * p.n * p.d * 2, 256);
     W.Vimg = o; o += round_up(BH * (p.n / 2) * p.d * 4, 256);
     W.nrm = o;  o += round_up(BH * p.n * 4, 256);
-    W.St = o;   o += round_up(BH * p.d * p.mf * 2, 256);
-    W.zp = o;   o += round_up(BH * p.mf * 4, 256);
-    W.cw = o;   o += round_up(BH * p.mf * 8, 256);
+    W.St = o;   o += round_up(BH * p.d * p.mfp * 2, 256);
+    W.zp = o;   o += round_up(BH * p.mfp * 4, 256);
+    W.cw = o;   o += round_up(BH * p.mfp * 8, 256);
     W.total = o;
     return W;
 }
@@ -615,7 +615,7 @@ __global__ void linformer_pack_kernel(const float* Kp, const float* Vp, uint16_t
 
 static Problem query_problem_linformer(const Problem& p) {
     Problem q = p;
-    q.m = q.mf = (p.k + 31) / 32 * 32;     // one feature per projected key
+    q.m = q.mf = q.mfp = (p.k + 31) / 32 * 32;     // one feature per projected key
     q.H = p.BH; q.B = 1;                   // every (batch, head) has its own K'
     q.omega_per_head = 1;
     q.elu = 0;

@@ -14,6 +14,7 @@ namespace flurka {
 struct Problem {
     int B, H, n, d, k, m;
     int mf;              // feature count: m (performer) or d (elu1)
+    int mfp;             // mf rounded up to whole 32-feature tiles (image strides of the MFMA forward)
     int BH;
     int omega_per_head;
     int bf16;            // storage type of caller tensors

@@ -127,7 +127,7 @@ struct KeyStateArgs {
     float* S; float* z; float* c;            // ctx
     uint16_t* St; float* zp; uint16_t* cw;   // images for the query stream (see the merge step below)
     long omega_head_stride;
-    int BH, H, k, kpad, mf, FT, KR, tiles_per_range;
+    int BH, H, k, kpad, mf, mfp, FT, KR, tiles_per_range;   // mf features (ctx strides), mfp = mf rounded up to whole tiles (image strides)
 };
 
 // LDS of a workgroup: per key range the partial S tile (32 features x d, rows padded), z and c; then
@@ -172,9 +172,11 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
     // B operand of the first contraction: omega rows of this feature tile
     uint4 wf[KS];
     if (!ELU) {
-        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(32 * ft + l32) * D + 8 * half;
+        // features past mf (a ragged last tile) get a zero row; their results are replaced below
+        const int fr = 32 * ft + l32 < a.mf ? 32 * ft + l32 : 0;
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)fr * D + 8 * half;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
+        for (int s = 0; s < KS; ++s) wf[s] = 32 * ft + l32 < a.mf ? ld16(og + 16 * s) : make_uint4(0u, 0u, 0u, 0u);
     }
 
     // exponents (performer) or features (elu1) of one 32-key tile: lane = feature 32*ft + l32,
@@ -369,24 +371,27 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
             wgt[r * 32 + tid] = wr;
             zs = fmaf(wr, pr[tid], zs);
         }
-        a.z[(long)bh * a.mf + f] = zs;
-        a.c[(long)bh * a.mf + f] = cm;
+        const bool real = f < a.mf;              // a feature of the padding: weight exp(-1e30) = 0 in the query stream
+        if (real) {
+            a.z[(long)bh * a.mf + f] = zs;
+            a.c[(long)bh * a.mf + f] = cm;
+        }
         // accumulator order of a 32-feature tile: position 16*h + g <-> feature 8*(g/4) + 4*h + g%4
         int pos = tid;
         if (!ELU) {
             const int q = tid >> 3, h = (tid >> 2) & 1, e = tid & 3;
             pos = 16 * h + 4 * q + e;
         }
-        a.zp[(long)bh * a.mf + 32 * ft + pos] = zs;
+        a.zp[(long)bh * a.mfp + 32 * ft + pos] = zs;
         if (!ELU) {
             uint16_t hi, mid, lo;
-            split3(cm + logf(zs), hi, mid, lo);
+            split3(real ? cm + logf(zs) : -1e30f, hi, mid, lo);
             uint2 pk;
             pk.x = (uint32_t)hi | ((uint32_t)mid << 16);
             pk.y = (uint32_t)lo;
-            *(uint2*)(a.cw + ((long)bh * a.mf + f) * 4) = pk;
+            *(uint2*)(a.cw + ((long)bh * a.mfp + f) * 4) = pk;
         }
-        zinv[tid] = ELU ? 1.f : 1.f / zs;
+        zinv[tid] = ELU ? 1.f : (real ? 1.f / zs : 0.f);
     }
     __syncthreads();
     for (int t0 = 0; t0 < D; t0 += 32) {
@@ -395,7 +400,7 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
             float sv = 0.f;
             for (int r = 0; r < KR; ++r)
                 sv = fmaf(wgt[r * 32 + fl], ks_lds[r * L::range_floats() + fl * L::s_pitch + t], sv);
-            a.S[((long)bh * a.mf + 32 * ft + fl) * D + t] = sv;
+            if (32 * ft + fl < a.mf) a.S[((long)bh * a.mf + 32 * ft + fl) * D + t] = sv;
             tile[fl * 33 + i % 32] = sv;
         }
         __syncthreads();
@@ -406,7 +411,7 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
                 const int e = sl & 7, h = (sl >> 3) & 1;
                 fl = (sl & 16) + 8 * (e >> 2) + 4 * h + (e & 3);
             }
-            a.St[((long)bh * D + t0 + tl) * a.mf + 32 * ft + sl] = f32_to_bf16(tile[fl * 33 + tl] * zinv[fl]);
+            a.St[((long)bh * D + t0 + tl) * a.mfp + 32 * ft + sl] = f32_to_bf16(tile[fl * 33 + tl] * zinv[fl]);
         }
         __syncthreads();
     }
@@ -418,7 +423,7 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
 KeyStatePlan key_state_plan(const Problem& p) {
     KeyStatePlan q;
     q.kpad = (p.k + 31) / 32 * 32;
-    q.FT = p.mf / 32;
+    q.FT = p.mfp / 32;
     const int KT = q.kpad / 32;
     // Key ranges = wavefronts of a workgroup: about two key tiles per wavefront (measured best at the
     // benchmark shapes: fewer wavefronts leave the latency of the operand loads exposed, more of them
@@ -484,7 +489,7 @@ flurka_status fast_key_state(const Problem& p, const void* omega, float* ctx, co
         ka.S = ctx + L.S; ka.z = ctx + L.z; ka.c = ctx + L.c;
         ka.St = b.St; ka.zp = b.zp; ka.cw = b.cw;
         ka.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
-        ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf;
+        ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf; ka.mfp = p.mfp;
         ka.FT = q.FT; ka.KR = q.KR; ka.tiles_per_range = q.tiles_per_range;
         flurka_status st = p.d == 64 ? launch_key_state<64>(p, ka, false, s) : launch_key_state<128>(p, ka, false, s);
         if (st != FLURKA_OK) return st;
@@ -553,7 +558,7 @@ flurka_status fast_identity_key_state(const Problem& p, const void* K, const voi
     ka.S = S; ka.z = z; ka.c = c;
     ka.St = b.St; ka.zp = b.zp; ka.cw = b.cw;
     ka.omega_head_stride = p.omega_per_head ? (long)p.m * p.d : 0;
-    ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf;
+    ka.BH = p.BH; ka.H = p.H; ka.k = p.k; ka.kpad = q.kpad; ka.mf = p.mf; ka.mfp = p.mfp;
     ka.FT = q.FT; ka.KR = q.KR; ka.tiles_per_range = q.tiles_per_range;
     return p.d == 64 ? launch_key_state<64>(p, ka, true, s) : launch_key_state<128>(p, ka, true, s);
 }

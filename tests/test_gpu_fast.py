@@ -35,6 +35,12 @@ FWD_SHAPES = [
     # the requests for a tile's first steps being issued during the previous tile's last ones (with a
     # ragged last step in each)
     (8, 40, 200, 128, 40, 32),
+    # feature counts that are not multiples of 32: the last feature tile is padded with features of weight 0
+    (1, 3, 192, 64, 100, 72),
+    (2, 2, 1000, 128, 300, 200),
+    (1, 2, 256, 64, 64, 8),
+    (2, 3, 640, 128, 96, 250),
+    (1, 2, 512, 64, 200, 500),
 ]
 
 
@@ -133,6 +139,13 @@ BWD_SHAPES = [
     (2, 2, 1056, 64, 100, 96),
     (1, 2, 2080, 128, 300, 160),
     (2, 2, 1056, 128, 256, 256),
+    # feature counts that are not multiples of 32 (the last feature tile padded with features of weight 0);
+    # 250 features at head size 128 run the ring variant
+    (1, 3, 192, 64, 100, 72),
+    (2, 2, 1056, 128, 300, 200),
+    (1, 2, 256, 64, 64, 8),
+    (2, 2, 640, 128, 96, 250),
+    (1, 2, 512, 64, 200, 280),
 ]
 
 

@@ -32,6 +32,8 @@ SHAPES = [
     (1, 4, 2048, 128, 512, 64, 512),
     # a sequence length that is a multiple of 8 only (ragged last reduction step of the first product)
     (2, 4, 712, 64, 100, 96, 256),
+    # a feature count that is not a multiple of 32
+    (1, 4, 512, 64, 100, 100, 256),
 ]
 
 

@@ -26,7 +26,7 @@ def _shapes(count, seed, backward):
         # (key, feature) pair; dQ, dK, dE then vanish (1e-13 against dV of order 10) and any kernel, the
         # fp32 ones included, returns rounding noise for them
         k = int(rng.integers(max(2, n // 40), 600)) if n // 40 < 600 else 600
-        m = d if phi == PHI_ELU1 else 32 * int(rng.integers(1, 9))
+        m = d if phi == PHI_ELU1 else int(rng.integers(8, 257))       # any count: the last feature tile may be ragged
         out.append((B, H, n, d, k, m, phi))     # within the MFMA kernels' limits by construction (asserted below)
     return out
 
