@@ -137,14 +137,15 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
     // omega as it lies; S_j / z_j as two bf16 terms (hi + lo), 8 slots per chunk: the slots of dOut's
     // operand order (head size 64: slot 8h + e of a group of 16 holds t = 8*(e/4) + 4*h + e%4; direct:
     // t = slot); c + ln z in the accumulator order of a 32-feature tile
-    // Features past mr (the padding of a ragged last tile) get omega = 0, S/z = 0 and c' = -inf: their
-    // weights b are exactly 0 and nothing of them reaches dQ, g or lambda.
+    // Features past mr (the padding of a ragged last tile) get c' = -inf: their weights b are exactly 0
+    // and nothing of them reaches dQ, g or lambda; their rows of omega and S/z are those of the last
+    // real feature (any finite values do: they only ever multiply that 0).
     const int mr = a.mr;
     const float* Sg = a.S + (long)bh * mr * D;
     const float* zg = a.z + (long)bh * mr;
     constexpr int cpr = D / 8;
     auto sp_terms = [&](int r, int q, uint4& hi4, uint4& lo4) {      // chunk q of feature row r
-        if (r >= mr) { hi4 = make_uint4(0u, 0u, 0u, 0u); lo4 = hi4; return; }
+        if (r >= mr) r = mr - 1;
         const int t0 = DIRECT ? 8 * q : 16 * (q >> 1) + 4 * (q & 1);
         const float4 s0 = *(const float4*)(Sg + (long)r * D + t0);
         const float4 s1 = *(const float4*)(Sg + (long)r * D + t0 + (DIRECT ? 4 : 8));
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(X_THREADS) void bwd_query_x_kernel(BwdXArgs a) {
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride;
         for (int c = tid; c < mf * cpr; c += X_NW * 64) {
             const int r = c / cpr, q = c % cpr;
-            *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = r < mr ? ld16(og + (long)r * D + 8 * q) : make_uint4(0u, 0u, 0u, 0u);
+            *(uint4*)(lw + r * L::w_pitch + 16 * (q ^ L::swz(r))) = ld16(og + (long)(r < mr ? r : mr - 1) * D + 8 * q);
             uint4 hi, lo;
             sp_terms(r, q, hi, lo);
             *(uint4*)(lsh + r * L::sp_pitch + 16 * q) = hi;
@@ -663,12 +664,13 @@ __global__ __launch_bounds__(NW * 64) void bwd_query_y_kernel(BwdYArgs a) {
     uint4 wf[KS];
     float cj = 0.f;
     if constexpr (!ELU) {
-        // a feature of the padding: omega = 0 and c = -inf, so its weights and its rows of dS, dz are 0
-        const bool real = 32 * ftc + l32 < a.mr;
-        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)(real ? 32 * ftc + l32 : 0) * D + 8 * half;
+        // a feature of the padding (ragged last tile): c = -inf, so its weights and its rows of dS, dz are
+        // exactly 0; its omega row is the last real feature's (any finite row does)
+        const int f = 32 * ftc + l32, fr = f < a.mr ? f : a.mr - 1;
+        const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)fr * D + 8 * half;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wf[s] = real ? ld16(og + 16 * s) : make_uint4(0u, 0u, 0u, 0u);
-        cj = real ? a.c[(long)bh * a.mr + 32 * ftc + l32] * LOG2E : -INFINITY;
+        for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
+        cj = f < a.mr ? a.c[(long)bh * a.mr + fr] * LOG2E : -INFINITY;
     }
     floatx16 accS[TT];
 #pragma unroll
@@ -950,19 +952,20 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
 #pragma unroll
     for (int t = 0; t < TT; ++t) { accV[t] = zero16(); accK[t] = zero16(); }
     float rs = 0.f;
-    const float* cg = a.c + (long)bh * a.mr + 4 * half;
+    // A feature of the padding (ragged last tile) has dS = 0 and dz = 0 by construction; it takes the
+    // omega row and the shift of the last real feature, so that its PhiK is finite and multiplies those 0.
+    const float* cg = a.c + (long)bh * a.mr;
     const float* zg = a.dz + (long)bh * a.mf + 4 * half;
 
     for (int ft = wave; ft < FT; ft += 4) {
         float4 cv4[4], zv4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            // c of a padding feature = +inf: PhiK = exp(-inf) = 0 (ctx rows are mr long: scalar loads)
-            const int f0 = 32 * ft + 8 * q + 4 * half;
-            cv4[q].x = f0 < a.mr ? cg[32 * ft + 8 * q] : INFINITY;
-            cv4[q].y = f0 + 1 < a.mr ? cg[32 * ft + 8 * q + 1] : INFINITY;
-            cv4[q].z = f0 + 2 < a.mr ? cg[32 * ft + 8 * q + 2] : INFINITY;
-            cv4[q].w = f0 + 3 < a.mr ? cg[32 * ft + 8 * q + 3] : INFINITY;
+            const int f0 = 32 * ft + 8 * q + 4 * half, last = a.mr - 1;     // ctx rows are mr long: scalar loads
+            cv4[q].x = cg[f0 < last ? f0 : last];
+            cv4[q].y = cg[f0 + 1 < last ? f0 + 1 : last];
+            cv4[q].z = cg[f0 + 2 < last ? f0 + 2 : last];
+            cv4[q].w = cg[f0 + 3 < last ? f0 + 3 : last];
             zv4[q] = *(const float4*)(zg + 32 * ft + 8 * q);
         }
         {   // this feature tile's rows of omega and dS, row-major, into the wavefront's LDS area
@@ -972,7 +975,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_key_kernel(BwdKeyArg
 #pragma unroll
             for (int u = 0; u < LPT; ++u) {
                 const int chunk = lane + 64 * u, row = chunk / CPR, c = chunk % CPR;
-                const uint4 x0 = 32 * ft + row < a.mr ? ld16(ob + row * D + 8 * c) : make_uint4(0u, 0u, 0u, 0u);
+                const uint4 x0 = ld16(ob + (32 * ft + row < a.mr ? row : a.mr - 1 - 32 * ft) * D + 8 * c);
                 const uint4 x1 = ld16(sb + row * D + 8 * c);
                 const uint4 x2 = ld16(sb + ds_plane + row * D + 8 * c);
                 unsigned char* dst = tw + row * P + 16 * c;

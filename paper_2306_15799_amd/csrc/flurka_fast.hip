@@ -125,7 +125,8 @@ __global__ __launch_bounds__(NW * 64) void query_stream_kernel(QueryArgs a) {
         constexpr int cpr = D / 8;                      // chunks per row
         for (int c = tid; c < mf * cpr; c += NW * 64) {
             const int r = c / cpr, q = c % cpr;
-            *(uint4*)(lw + r * L::w_pitch + 16 * q) = r < a.m_rows ? ld16(og + (long)r * D + 8 * q) : make_uint4(0u, 0u, 0u, 0u);
+            // rows of the padding: any finite row does, their shift c' of -1e30 makes the weights 0
+            *(uint4*)(lw + r * L::w_pitch + 16 * q) = ld16(og + (long)(r < a.m_rows ? r : a.m_rows - 1) * D + 8 * q);
         }
         const uint16_t* cwg = a.cw + (long)bh * mf * 4;
         for (int r = tid; r < mf; r += NW * 64) {

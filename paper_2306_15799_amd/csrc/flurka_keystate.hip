@@ -172,11 +172,11 @@ __global__ __launch_bounds__(KeyStateMaxWaves<D>::value * 64) void key_state_ker
     // B operand of the first contraction: omega rows of this feature tile
     uint4 wf[KS];
     if (!ELU) {
-        // features past mf (a ragged last tile) get a zero row; their results are replaced below
-        const int fr = 32 * ft + l32 < a.mf ? 32 * ft + l32 : 0;
+        // features past mf (a ragged last tile) take the last real row; their results are replaced below
+        const int fr = 32 * ft + l32 < a.mf ? 32 * ft + l32 : a.mf - 1;
         const uint16_t* og = a.omega + (long)(bh % a.H) * a.omega_head_stride + (long)fr * D + 8 * half;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) wf[s] = 32 * ft + l32 < a.mf ? ld16(og + 16 * s) : make_uint4(0u, 0u, 0u, 0u);
+        for (int s = 0; s < KS; ++s) wf[s] = ld16(og + 16 * s);
     }
 
     // exponents (performer) or features (elu1) of one 32-key tile: lane = feature 32*ft + l32,
